@@ -1,0 +1,222 @@
+"""ctypes front end of the float64 CPU oracle (``vecinfer_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg call this; the GPU library never does, and nothing here
+imports the GPU package.
+
+Inputs arrive as the same fp16 / fp32 / uint8 arrays the GPU path receives and
+are widened to float64 (exactly) before the C code sees them.  Shapes follow
+the paper's notation: D = head dim, d = sub-vector dim, M = D / d sub-spaces,
+C = 2^b centroids per sub-space (Sec. 2.2), N tokens in the cache.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vecinfer_oracle.c")
+_LIB = os.path.join(_HERE, "libvecinfer_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (``-O2``, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+               "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = C.CDLL(_LIB)
+        dp, u8p, i64p = C.POINTER(C.c_double), C.POINTER(C.c_uint8), C.POINTER(C.c_int64)
+        lib.vo_num_threads.restype = C.c_int
+        lib.vo_set_num_threads.argtypes = [C.c_int]
+        lib.vo_hadamard.argtypes = [C.c_int, dp]
+        lib.vo_hadamard.restype = C.c_int
+        lib.vo_smoothing_factors.argtypes = [dp, C.c_int64, C.c_int, dp]
+        lib.vo_transform_keys.argtypes = [dp, C.c_int64, C.c_int, dp, dp, dp]
+        lib.vo_transform_query.argtypes = [dp, C.c_int, dp, dp, dp]
+        lib.vo_vq_encode.argtypes = [dp, C.c_int64, C.c_int, C.c_int, C.c_int, dp, u8p, dp]
+        lib.vo_vq_dequantize.argtypes = [u8p, C.c_int64, C.c_int, C.c_int, C.c_int, dp, dp]
+        lib.vo_merge_splits.argtypes = [dp, dp, C.c_int, C.c_int, dp, dp]
+        lib.vo_encode_batch.argtypes = [dp, dp, dp, C.c_int, C.c_int, C.c_int64, C.c_int,
+                                        C.c_int, C.c_int, C.c_int, u8p, dp]
+        lib.vo_encode_batch.restype = C.c_int
+        lib.vo_decode_batch.argtypes = [dp, dp, dp, dp, u8p, u8p, i64p, C.c_int, C.c_int,
+                                        C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_int, C.c_int64, dp, dp]
+        lib.vo_decode_batch.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _dp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def _u8p(a):
+    return a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def num_threads() -> int:
+    return int(_load().vo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().vo_set_num_threads(int(n))
+
+
+def hadamard(D: int) -> np.ndarray:
+    """Orthonormal Walsh-Hadamard matrix H_D of Eq. 5 (Sylvester order)."""
+    H = np.empty((D, D), dtype=np.float64)
+    if _load().vo_hadamard(D, _dp(H)) != 0:
+        raise ValueError("D must be a power of two")
+    return H
+
+
+def smoothing_factors(K) -> np.ndarray:
+    """Eq. 4: lambda_i = sqrt(max_n |K[n, i]|) over all rows of K [..., D]."""
+    K = _f64(K)
+    D = K.shape[-1]
+    K2 = K.reshape(-1, D)
+    lam = np.empty(D, dtype=np.float64)
+    _load().vo_smoothing_factors(_dp(K2), K2.shape[0], D, _dp(lam))
+    return lam
+
+
+def transform_keys(K, lam) -> np.ndarray:
+    """K diag(lam)^-1 H_D for K [N, D] (Eq. 3 and Eq. 6, key side)."""
+    K = _f64(K)
+    lam = _f64(lam)
+    N, D = K.shape
+    H = hadamard(D)
+    out = np.empty_like(K)
+    _load().vo_transform_keys(_dp(K), N, D, _dp(lam), _dp(H), _dp(out))
+    return out
+
+
+def transform_query(q, lam) -> np.ndarray:
+    """q diag(lam) H_D for one query row q [D] (Eq. 3 and Eq. 6, query side)."""
+    q = _f64(q)
+    lam = _f64(lam)
+    D = q.shape[0]
+    H = hadamard(D)
+    out = np.empty_like(q)
+    _load().vo_transform_query(_dp(q), D, _dp(lam), _dp(H), _dp(out))
+    return out
+
+
+def vq_encode(X, cb, want_gap: bool = False):
+    """Eq. 2 on rows X [N, D] with per-sub-space codebooks cb [M, C, d]."""
+    X = _f64(X)
+    cb = _f64(cb)
+    N, D = X.shape
+    M, Cn, d = cb.shape
+    assert M * d == D
+    idx = np.empty((N, M), dtype=np.uint8)
+    gap = np.empty((N, M), dtype=np.float64) if want_gap else None
+    _load().vo_vq_encode(_dp(X), N, D, d, Cn, _dp(cb), _u8p(idx), _dp(gap) if want_gap else None)
+    return (idx, gap) if want_gap else idx
+
+
+def vq_dequantize(idx, cb) -> np.ndarray:
+    """VQ^{-1}: rows of concatenated centroids, idx [N, M], cb [M, C, d] -> [N, D]."""
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    cb = _f64(cb)
+    N, M = idx.shape
+    M2, Cn, d = cb.shape
+    assert M == M2
+    out = np.empty((N, M * d), dtype=np.float64)
+    _load().vo_vq_dequantize(_u8p(idx), N, M * d, d, Cn, _dp(cb), _dp(out))
+    return out
+
+
+def merge_splits(o_parts, L_parts):
+    """LSE merge of S partial (o, L) pairs of one query row."""
+    o_parts = _f64(o_parts)
+    L_parts = _f64(L_parts)
+    S, D = o_parts.shape
+    out = np.empty(D, dtype=np.float64)
+    lse = C.c_double()
+    _load().vo_merge_splits(_dp(o_parts), _dp(L_parts), S, D, _dp(out), C.byref(lse))
+    return out, float(lse.value)
+
+
+def encode_keys(k_f16, lam, cb_k, want_gap: bool = False):
+    """Smooth + Hadamard + VQ of keys (Alg. 1 steps 2-3, Eq. 8).
+
+    k_f16 [B, Hkv, T, D], lam [Hkv, D], cb_k [Hkv, M, C, d] -> uint8 [B, Hkv, T, M].
+    """
+    return _encode(k_f16, lam, cb_k, 1, want_gap)
+
+
+def encode_values(v_f16, cb_v, want_gap: bool = False):
+    """VQ of the untransformed values (Eq. 8): [B, Hkv, T, D] -> uint8 [B, Hkv, T, M]."""
+    return _encode(v_f16, None, cb_v, 0, want_gap)
+
+
+def _encode(x, lam, cb, transform, want_gap):
+    x = _f64(x)
+    cb = _f64(cb)
+    B, Hkv, T, D = x.shape
+    Hc, M, Cn, d = cb.shape
+    assert Hc == Hkv and M * d == D
+    lam64 = _f64(lam) if transform else np.ones((Hkv, D), dtype=np.float64)
+    assert lam64.shape == (Hkv, D)
+    idx = np.empty((B, Hkv, T, M), dtype=np.uint8)
+    gap = np.empty((B, Hkv, T, M), dtype=np.float64) if want_gap else None
+    rc = _load().vo_encode_batch(_dp(x), _dp(lam64), _dp(cb), B, Hkv, T, D, d, Cn, transform,
+                                 _u8p(idx), _dp(gap) if want_gap else None)
+    if rc != 0:
+        raise ValueError("vo_encode_batch rejected the shapes")
+    return (idx, gap) if want_gap else idx
+
+
+def decode_attention(q_f16, lam, cb_k, cb_v, k_idx, v_idx, seq_lens=None, *,
+                     path: str = "eq10", tile: int = 64):
+    """One decode step of VQ attention for a batch (Eq. 10; GQA by consecutive groups).
+
+    q_f16 [B, Hq, D]; lam [Hkv, D]; cb_k [Hkv, Mk, C, d_k]; cb_v [Hkv, Mv, C, d_v];
+    k_idx [B, Hkv, n_cap, Mk]; v_idx [B, Hkv, n_cap, Mv]; seq_lens [B] or None (= n_cap).
+    path "eq10": explicit dequantize-then-attend; "alg1": lookup table + online softmax
+    over tiles of `tile` tokens.  Returns (out [B, Hq, D] f64, lse [B, Hq] f64).
+    """
+    q = _f64(q_f16)
+    lam = _f64(lam)
+    cb_k = _f64(cb_k)
+    cb_v = _f64(cb_v)
+    k_idx = np.ascontiguousarray(k_idx, dtype=np.uint8)
+    v_idx = np.ascontiguousarray(v_idx, dtype=np.uint8)
+    B, Hq, D = q.shape
+    Hkv, Mk, Cn, d_k = cb_k.shape
+    _, Mv, Cv, d_v = cb_v.shape
+    assert Cn == Cv and k_idx.shape[:2] == (B, Hkv) and v_idx.shape[:2] == (B, Hkv)
+    assert k_idx.shape[3] == Mk and v_idx.shape[3] == Mv and k_idx.shape[2] == v_idx.shape[2]
+    n_cap = k_idx.shape[2]
+    if seq_lens is None:
+        sl = np.full(B, n_cap, dtype=np.int64)
+    else:
+        sl = np.ascontiguousarray(seq_lens, dtype=np.int64)
+    assert sl.shape == (B,) and int(sl.max()) <= n_cap
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    rc = _load().vo_decode_batch(_dp(q), _dp(lam), _dp(cb_k), _dp(cb_v), _u8p(k_idx), _u8p(v_idx),
+                                 sl.ctypes.data_as(C.POINTER(C.c_int64)), B, Hq, Hkv, n_cap, D,
+                                 d_k, d_v, Cn, {"eq10": 0, "alg1": 1}[path], int(tile),
+                                 _dp(out), _dp(lse))
+    if rc != 0:
+        raise ValueError("vo_decode_batch rejected the inputs (empty sequence or bad shapes)")
+    return out, lse

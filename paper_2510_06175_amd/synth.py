@@ -1,0 +1,127 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the GPU path.
+
+This module only draws random tensors of the right shape, dtype and value
+structure; it contains none of the method's arithmetic (no transform, no
+quantization, no attention) and imports neither the oracle nor the GPU
+library.  Everything comes from ``numpy.random.Generator(PCG64(seed))``.
+
+The tensors stand in for Llama-3.1-8B KV caches (32 query heads, 8 KV heads,
+head dim 128; kernel sweep shapes of App. B.2), which would need model weights
+and long-context text that are not available here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+NUM_CENTROIDS = 256  # 8-bit codes: one uint8 index per sub-vector (Sec. 2.2)
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Problem shape in the paper's notation."""
+    B: int            # batch
+    Hq: int           # query heads
+    Hkv: int          # KV heads
+    D: int            # head dim
+    N: int            # tokens in the cache
+    d_k: int          # key sub-vector dim
+    d_v: int          # value sub-vector dim
+
+    @property
+    def Mk(self) -> int:
+        return self.D // self.d_k
+
+    @property
+    def Mv(self) -> int:
+        return self.D // self.d_v
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+    def index_bytes(self) -> int:
+        """Compressed-KV bytes one decode step has to read."""
+        return self.B * self.Hkv * self.N * (self.Mk + self.Mv)
+
+
+# BASELINE configurations (b2d4 = d 4, b4d2 = d 2; 8-bit codes in both)
+TINY = Shape(B=1, Hq=1, Hkv=1, D=128, N=4096, d_k=4, d_v=4)
+LLAMA8B_32K = Shape(B=1, Hq=32, Hkv=8, D=128, N=32768, d_k=4, d_v=4)
+LLAMA8B_BATCH32 = Shape(B=32, Hq=32, Hkv=8, D=128, N=8192, d_k=4, d_v=4)
+LLAMA8B_196K = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=4, d_v=4)
+LLAMA8B_196K_B4D2 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=2)
+ENCODE_64K = Shape(B=1, Hq=32, Hkv=8, D=128, N=65536, d_k=4, d_v=4)
+
+
+def rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def codebooks(g: np.random.Generator, Hkv: int, M: int, d: int) -> np.ndarray:
+    """Per-(KV head, sub-space) codebooks [Hkv, M, 256, d], fp16, centroids ~ N(0, 1)."""
+    return g.standard_normal((Hkv, M, NUM_CENTROIDS, d), dtype=np.float32).astype(np.float16)
+
+
+def queries(g: np.random.Generator, B: int, Hq: int, D: int) -> np.ndarray:
+    """Decode-step queries [B, Hq, D], fp16 ~ N(0, 1)."""
+    return g.standard_normal((B, Hq, D), dtype=np.float32).astype(np.float16)
+
+
+def lognormal_lambda(g: np.random.Generator, Hkv: int, D: int, sigma: float = 0.5) -> np.ndarray:
+    """Per-channel smoothing factors [Hkv, D], fp32 ~ LogNormal(0, sigma)."""
+    return np.exp(sigma * g.standard_normal((Hkv, D))).astype(np.float32)
+
+
+def random_indices(g: np.random.Generator, B: int, Hkv: int, n_cap: int, M: int) -> np.ndarray:
+    """Uniform random uint8 codes [B, Hkv, n_cap, M]."""
+    return g.integers(0, NUM_CENTROIDS, size=(B, Hkv, n_cap, M), dtype=np.uint8)
+
+
+def keys_with_outlier_channels(g: np.random.Generator, B: int, Hkv: int, T: int, D: int,
+                               n_outlier: int, factor: float = 20.0):
+    """Keys [B, Hkv, T, D] fp16 ~ N(0, 1) with `n_outlier` seeded channels per KV
+    head scaled by `factor` (the few-large-channels structure of real key caches,
+    Fig. 1 / Fig. 8).  Returns (keys, outlier_channels [Hkv, n_outlier])."""
+    k = g.standard_normal((B, Hkv, T, D), dtype=np.float32)
+    ch = np.stack([np.sort(g.choice(D, size=n_outlier, replace=False)) for _ in range(Hkv)])
+    for h in range(Hkv):
+        k[:, h, :, ch[h]] *= factor
+    return k.astype(np.float16), ch
+
+
+def values(g: np.random.Generator, B: int, Hkv: int, T: int, D: int) -> np.ndarray:
+    """Values [B, Hkv, T, D] fp16 ~ N(0, 1)."""
+    return g.standard_normal((B, Hkv, T, D), dtype=np.float32).astype(np.float16)
+
+
+def decode_inputs(shape: Shape, seed: int, n_cap: int | None = None) -> dict:
+    """Inputs of one decode step over a cache of uniform random codes
+    (the 8B-shaped configurations): q, lam, cb_k, cb_v, k_idx, v_idx."""
+    g = rng(seed)
+    n_cap = shape.N if n_cap is None else n_cap
+    return {
+        "q": queries(g, shape.B, shape.Hq, shape.D),
+        "lam": lognormal_lambda(g, shape.Hkv, shape.D),
+        "cb_k": codebooks(g, shape.Hkv, shape.Mk, shape.d_k),
+        "cb_v": codebooks(g, shape.Hkv, shape.Mv, shape.d_v),
+        "k_idx": random_indices(g, shape.B, shape.Hkv, n_cap, shape.Mk),
+        "v_idx": random_indices(g, shape.B, shape.Hkv, n_cap, shape.Mv),
+    }
+
+
+def encode_inputs(shape: Shape, seed: int, n_outlier: int) -> dict:
+    """Inputs of a cache fill: raw keys (with outlier channels), raw values, codebooks,
+    and the decode-step query.  The smoothing factors are NOT drawn here: where a
+    configuration derives them from the keys (Eq. 4) the caller computes them."""
+    g = rng(seed)
+    k, ch = keys_with_outlier_channels(g, shape.B, shape.Hkv, shape.N, shape.D, n_outlier)
+    return {
+        "k": k,
+        "outlier_channels": ch,
+        "v": values(g, shape.B, shape.Hkv, shape.N, shape.D),
+        "cb_k": codebooks(g, shape.Hkv, shape.Mk, shape.d_k),
+        "cb_v": codebooks(g, shape.Hkv, shape.Mv, shape.d_v),
+        "q": queries(rng(0), shape.B, shape.Hq, shape.D),
+    }

@@ -1,0 +1,378 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests re-types an oracle formula and compares it with itself: each
+one checks the oracle against a closed form, a hand-worked value, an invariant,
+a textbook special case, a library routine (scipy / torch, float64) or a brute
+force written in a different way (vectorised numpy instead of C loops).
+"""
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg
+import scipy.spatial.distance
+import scipy.special
+import torch
+
+from paper_2510_06175_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _blocks(path):
+    blocks, cur = [], []
+    for line in open(path):
+        s = line.strip()
+        if s.startswith("#"):
+            continue
+        if not s:
+            if cur:
+                blocks.append(np.array(cur, dtype=np.float64))
+                cur = []
+            continue
+        cur.append([float(t) for t in s.split()])
+    if cur:
+        blocks.append(np.array(cur, dtype=np.float64))
+    return blocks
+
+
+# --------------------------------------------------------------------------- Hadamard (Eq. 5)
+
+def test_hadamard_h4_golden(oracle):
+    (h4x2,) = _blocks(os.path.join(GOLDEN, "hadamard_h4.txt"))
+    np.testing.assert_allclose(oracle.hadamard(4) * 2.0, h4x2, rtol=0, atol=1e-15)
+
+
+def test_hadamard_h2_closed_form(oracle):
+    r = 1.0 / np.sqrt(2.0)
+    np.testing.assert_allclose(oracle.hadamard(2), [[r, r], [r, -r]], rtol=0, atol=1e-16)
+    np.testing.assert_array_equal(oracle.hadamard(1), [[1.0]])
+
+
+@pytest.mark.parametrize("D", [2, 8, 64, 128])
+def test_hadamard_properties(oracle, D):
+    H = oracle.hadamard(D)
+    # orthonormal (Sec. 3.2: H H^T = I); the un-normalised butterfly matrix gives D * I
+    np.testing.assert_allclose(H @ H.T, np.eye(D), atol=1e-13)
+    U = H * np.sqrt(D)
+    np.testing.assert_allclose(U @ U.T, D * np.eye(D), atol=1e-10)
+    # entries are +-1/sqrt(D) (proof of Lemma 1) with the Sylvester sign (-1)^popcount(i & j)
+    i, j = np.meshgrid(np.arange(D), np.arange(D), indexing="ij")
+    sign = 1.0 - 2.0 * (np.array([[bin(a & b).count("1") & 1 for b in range(D)] for a in range(D)]))
+    np.testing.assert_allclose(H, sign / np.sqrt(D), atol=1e-15)
+    # library construction of the same (Sylvester) matrix
+    np.testing.assert_allclose(H, scipy.linalg.hadamard(D) / np.sqrt(D), atol=1e-15)
+    np.testing.assert_array_equal(H, H.T)
+    # first unit vector maps to the constant row; the transform is an involution and an isometry
+    np.testing.assert_allclose(np.eye(D)[0] @ H, np.full(D, 1 / np.sqrt(D)), atol=1e-15)
+    x = synth.rng(D).standard_normal(D)
+    np.testing.assert_allclose((x @ H) @ H, x, atol=1e-13)
+    np.testing.assert_allclose(np.linalg.norm(x @ H), np.linalg.norm(x), rtol=1e-13)
+
+
+def test_hadamard_rejects_non_power_of_two(oracle):
+    with pytest.raises(ValueError):
+        oracle.hadamard(96)
+
+
+# --------------------------------------------------------------------------- smoothing (Eq. 3, Eq. 4)
+
+def test_smoothing_factors_golden(oracle):
+    K, lam = _blocks(os.path.join(GOLDEN, "smoothing_example.txt"))
+    np.testing.assert_array_equal(oracle.smoothing_factors(K), lam[0])
+
+
+def test_transform_direction_on_unit_vectors(oracle):
+    """Keys are divided by lambda and queries multiplied (Eq. 3), each then times H (Eq. 6)."""
+    D = 16
+    lam = np.linspace(0.5, 4.0, D)
+    H = scipy.linalg.hadamard(D) / np.sqrt(D)
+    for i in (0, 3, 15):
+        e = np.zeros(D)
+        e[i] = 1.0
+        np.testing.assert_allclose(oracle.transform_keys(e[None, :], lam)[0], H[i] / lam[i], atol=1e-15)
+        np.testing.assert_allclose(oracle.transform_query(e, lam), H[i] * lam[i], atol=1e-15)
+
+
+def test_transform_matches_library_matmul(oracle):
+    g = synth.rng(11)
+    D = 128
+    K = g.standard_normal((37, D))
+    lam = np.exp(0.5 * g.standard_normal(D))
+    H = scipy.linalg.hadamard(D) / np.sqrt(D)
+    np.testing.assert_allclose(oracle.transform_keys(K, lam), (K / lam) @ H, atol=1e-12)
+    np.testing.assert_allclose(oracle.transform_query(K[0], lam), (K[0] * lam) @ H, atol=1e-12)
+
+
+def test_score_invariance_under_dual_transform(oracle):
+    """Eq. 7: (q diag(lam) H)(K diag(lam)^-1 H)^T = q K^T for any lam > 0."""
+    g = synth.rng(7)
+    D = 128
+    K = g.standard_normal((64, D)) * np.where(g.random(D) < 0.05, 20.0, 1.0)
+    q = g.standard_normal(D)
+    lam = np.exp(0.5 * g.standard_normal(D))
+    qt = oracle.transform_query(q, lam)
+    Kt = oracle.transform_keys(K, lam)
+    np.testing.assert_allclose(Kt @ qt, K @ q, rtol=1e-11, atol=1e-11)
+    # with Eq. 4's lambda as well
+    lam4 = oracle.smoothing_factors(K)
+    np.testing.assert_allclose(oracle.transform_keys(K, lam4) @ oracle.transform_query(q, lam4),
+                               K @ q, rtol=1e-11, atol=1e-11)
+
+
+def test_lemma1_row_energy_and_outlier_suppression(oracle):
+    """Lemma 1: each transformed entry has variance (1/D) sum_l K_il^2; as H is orthonormal the
+    row's mean square equals exactly that.  Smooth + Hadamard flattens the outlier channels."""
+    e = synth.encode_inputs(synth.TINY, seed=1, n_outlier=4)
+    K = e["k"][0, 0].astype(np.float64)
+    lam = oracle.smoothing_factors(K)
+    Kt = oracle.transform_keys(K, lam)
+    np.testing.assert_allclose((Kt ** 2).mean(axis=1), ((K / lam) ** 2).sum(axis=1) / K.shape[1], rtol=1e-12)
+    spread = lambda X: np.abs(X).max(axis=0).max() / np.abs(X).max(axis=0).min()
+    assert spread(K) > 10.0 and spread(Kt) < 2.5
+
+
+# --------------------------------------------------------------------------- VQ encode (Eq. 2, Eq. 8)
+
+@pytest.mark.parametrize("d", [2, 4, 8])
+def test_vq_encode_vs_cdist_brute_force(oracle, d):
+    g = synth.rng(100 + d)
+    D, N, C = 32, 50, 256
+    M = D // d
+    X = g.standard_normal((N, D))
+    cb = g.standard_normal((M, C, d))
+    idx = oracle.vq_encode(X, cb)
+    assert idx.dtype == np.uint8 and idx.shape == (N, M)
+    for m in range(M):
+        dist = scipy.spatial.distance.cdist(X[:, m * d:(m + 1) * d], cb[m], metric="sqeuclidean")
+        np.testing.assert_array_equal(idx[:, m], dist.argmin(axis=1))
+
+
+def test_vq_encode_ties_take_lowest_index_and_gap_is_zero(oracle):
+    g = synth.rng(5)
+    cb = g.standard_normal((2, 256, 4))
+    cb[:, 200] = cb[:, 17]          # exact duplicates
+    X = np.concatenate([cb[0, 17], cb[1, 200]])[None, :]
+    idx, gap = oracle.vq_encode(X, cb, want_gap=True)
+    np.testing.assert_array_equal(idx, [[17, 17]])
+    np.testing.assert_array_equal(gap, [[0.0, 0.0]])
+
+
+def test_vq_encode_gap_is_relative_distance_gap(oracle):
+    cb = np.zeros((1, 256, 2))
+    cb[0, :, 0] = 10.0 + np.arange(256)
+    cb[0, 3] = [1.0, 0.0]           # distance^2 to origin 1
+    cb[0, 9] = [0.0, 2.0]           # distance^2 to origin 4
+    idx, gap = oracle.vq_encode(np.zeros((1, 2)), cb, want_gap=True)
+    assert idx[0, 0] == 3 and gap[0, 0] == pytest.approx(3.0)
+
+
+def test_vq_encode_centroid_in_index_out_and_permutation(oracle):
+    g = synth.rng(6)
+    M, C, d = 8, 256, 4
+    cb = g.standard_normal((M, C, d))
+    want = g.integers(0, C, size=(40, M), dtype=np.uint8)
+    X = oracle.vq_dequantize(want, cb)
+    np.testing.assert_array_equal(X[3, 4:8], cb[1, want[3, 1]])     # dequantize = centroid lookup
+    np.testing.assert_array_equal(oracle.vq_encode(X, cb), want)
+    # permuting every codebook permutes the indices the same way
+    perm = g.permutation(C)
+    inv = np.argsort(perm)
+    Y = g.standard_normal((40, M * d))
+    np.testing.assert_array_equal(oracle.vq_encode(Y, cb[:, perm]), inv[oracle.vq_encode(Y, cb)])
+
+
+def test_code_and_codebook_sizes():
+    """Sec. 2.2: (d_h/d)(b/8) index bytes per vector and 2^b d 2 codebook bytes."""
+    s = synth.LLAMA8B_196K
+    assert s.Mk == 32 and s.Mk * 8 // 8 == 32 and synth.NUM_CENTROIDS * s.d_k * 2 == 2048
+    s2 = synth.LLAMA8B_196K_B4D2
+    assert s2.Mk == 64 and synth.NUM_CENTROIDS * s2.d_k * 2 == 1024
+    assert s.index_bytes() == 100663296 and s2.index_bytes() == 201326592
+
+
+def test_encode_keys_recovers_planted_codes(oracle):
+    """K = (concatenated centroids) H^T diag(lam) must encode to exactly the planted codes,
+    for per-head codebooks and smoothing factors (Alg. 1 steps 2-3)."""
+    g = synth.rng(8)
+    B, Hkv, T, D, d = 2, 3, 9, 128, 4
+    M = D // d
+    cb = synth.codebooks(g, Hkv, M, d)
+    lam = synth.lognormal_lambda(g, Hkv, D)
+    want = g.integers(0, 256, size=(B, Hkv, T, M), dtype=np.uint8)
+    H = scipy.linalg.hadamard(D) / np.sqrt(D)
+    K = np.empty((B, Hkv, T, D))
+    for b in range(B):
+        for h in range(Hkv):
+            Khat = cb[h].astype(np.float64)[np.arange(M)[None, :], want[b, h]].reshape(T, D)
+            K[b, h] = (Khat @ H.T) * lam[h].astype(np.float64)
+    got = oracle.encode_keys(K, lam, cb)
+    # distinct fp16 centroids ~N(0,1) are separated by far more than float64 rounding
+    np.testing.assert_array_equal(got, want)
+    # values: no transform at all
+    V = np.stack([[cb[h].astype(np.float64)[np.arange(M)[None, :], want[b, h]].reshape(T, D)
+                   for h in range(Hkv)] for b in range(B)])
+    np.testing.assert_array_equal(oracle.encode_values(V, cb), want)
+
+
+def test_encode_keys_vs_numpy_pipeline(oracle):
+    e = synth.encode_inputs(synth.Shape(B=1, Hq=2, Hkv=2, D=128, N=33, d_k=4, d_v=2), seed=3, n_outlier=3)
+    lam = np.stack([oracle.smoothing_factors(e["k"][:, h]) for h in range(2)]).astype(np.float32)
+    H = scipy.linalg.hadamard(128) / np.sqrt(128)
+    got, gap = oracle.encode_keys(e["k"], lam, e["cb_k"], want_gap=True)
+    gotv = oracle.encode_values(e["v"], e["cb_v"])
+    assert got.shape == (1, 2, 33, 32) and gotv.shape == (1, 2, 33, 64)
+    for h in range(2):
+        Kt = (e["k"][0, h].astype(np.float64) / lam[h].astype(np.float64)) @ H
+        for m in range(32):
+            dist = scipy.spatial.distance.cdist(Kt[:, 4 * m:4 * m + 4], e["cb_k"][h, m].astype(np.float64),
+                                                "sqeuclidean")
+            ok = (dist.argmin(axis=1) == got[0, h, :, m]) | (gap[0, h, :, m] < 1e-9)
+            assert ok.all()
+        V = e["v"][0, h].astype(np.float64)
+        for m in range(64):
+            dist = scipy.spatial.distance.cdist(V[:, 2 * m:2 * m + 2], e["cb_v"][h, m].astype(np.float64),
+                                                "sqeuclidean")
+            np.testing.assert_array_equal(dist.argmin(axis=1), gotv[0, h, :, m])
+
+
+# --------------------------------------------------------------------------- VQ attention (Eq. 10, Alg. 1)
+
+def _dequant_np(idx, cb):
+    """idx [N, M], cb [M, C, d] -> [N, M*d] by numpy fancy indexing (not the oracle's loop)."""
+    M = cb.shape[0]
+    return cb.astype(np.float64)[np.arange(M)[None, :], idx].reshape(idx.shape[0], -1)
+
+
+def _small_decode_case(seed, B=2, Hq=4, Hkv=2, D=64, N=75, d_k=4, d_v=2):
+    return synth.Shape(B, Hq, Hkv, D, N, d_k, d_v), synth.decode_inputs(
+        synth.Shape(B, Hq, Hkv, D, N, d_k, d_v), seed)
+
+
+def test_decode_matches_torch_sdpa_on_dequantized_cache(oracle):
+    """Eq. 10 is textbook attention (Eq. 1) on the dequantized cache with the transformed query."""
+    s, x = _small_decode_case(21)
+    seq = np.array([75, 41])
+    out, lse = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"], seq)
+    H = scipy.linalg.hadamard(s.D) / np.sqrt(s.D)
+    for b in range(s.B):
+        n = seq[b]
+        Kh = np.stack([_dequant_np(x["k_idx"][b, g, :n], x["cb_k"][g]) for g in range(s.Hkv)])
+        Vh = np.stack([_dequant_np(x["v_idx"][b, g, :n], x["cb_v"][g]) for g in range(s.Hkv)])
+        lam_q = np.repeat(x["lam"].astype(np.float64), s.G, axis=0)           # head h -> KV head h // G
+        qt = (x["q"][b].astype(np.float64) * lam_q) @ H
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qt)[None, :, None, :],
+            torch.from_numpy(Kh).repeat_interleave(s.G, dim=0)[None],
+            torch.from_numpy(Vh).repeat_interleave(s.G, dim=0)[None])[0, :, 0].numpy()
+        np.testing.assert_allclose(out[b], ref, rtol=1e-11, atol=1e-13)
+        scores = np.einsum("hd,hnd->hn", qt, np.repeat(Kh, s.G, axis=0)) / np.sqrt(s.D)
+        np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-12)
+
+
+def test_decode_zero_query_gives_mean_of_values_and_log_n(oracle):
+    s, x = _small_decode_case(22, B=1, Hq=2, Hkv=1, N=50)
+    x["q"][:] = 0
+    out, lse = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    Vh = _dequant_np(x["v_idx"][0, 0], x["cb_v"][0])
+    np.testing.assert_allclose(out[0, 0], Vh.mean(axis=0), atol=1e-14)
+    np.testing.assert_allclose(out[0, 1], Vh.mean(axis=0), atol=1e-14)
+    np.testing.assert_allclose(lse, np.log(50.0), rtol=1e-14)
+
+
+def test_decode_single_token(oracle):
+    s, x = _small_decode_case(23, B=1, Hq=2, Hkv=2, N=1)
+    out, lse = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    H = scipy.linalg.hadamard(s.D) / np.sqrt(s.D)
+    for h in range(2):
+        np.testing.assert_allclose(out[0, h], _dequant_np(x["v_idx"][0, h], x["cb_v"][h])[0], atol=1e-15)
+        qt = (x["q"][0, h].astype(np.float64) * x["lam"][h].astype(np.float64)) @ H
+        s0 = qt @ _dequant_np(x["k_idx"][0, h], x["cb_k"][h])[0] / np.sqrt(s.D)
+        np.testing.assert_allclose(lse[0, h], s0, rtol=1e-12)
+
+
+def test_decode_output_is_convex_combination(oracle):
+    s, x = _small_decode_case(24)
+    out, _ = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    for b in range(s.B):
+        for h in range(s.Hq):
+            Vh = _dequant_np(x["v_idx"][b, h // s.G], x["cb_v"][h // s.G])
+            assert (out[b, h] <= Vh.max(axis=0) + 1e-12).all() and (out[b, h] >= Vh.min(axis=0) - 1e-12).all()
+
+
+@pytest.mark.parametrize("tile", [1, 7, 64, 1000])
+def test_alg1_lookup_online_softmax_equals_eq10(oracle, tile):
+    """LUT-sum score = explicit dot, and the tiled online softmax = plain softmax (Alg. 1 vs Eq. 10)."""
+    s, x = _small_decode_case(25)
+    seq = np.array([75, 13])
+    a = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"], seq)
+    b = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"], seq,
+                                path="alg1", tile=tile)
+    np.testing.assert_allclose(b[0], a[0], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(b[1], a[1], rtol=1e-12)
+
+
+@pytest.mark.parametrize("cuts", [[0, 75], [0, 1, 75], [0, 20, 21, 50, 75]])
+def test_split_merge_equals_whole(oracle, cuts):
+    s, x = _small_decode_case(26, B=1, Hq=2, Hkv=1)
+    whole, L = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    parts_o, parts_L = [], []
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        o, l = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"],
+                                       x["k_idx"][:, :, lo:hi], x["v_idx"][:, :, lo:hi])
+        parts_o.append(o[0])
+        parts_L.append(l[0])
+    for h in range(2):
+        o, l = oracle.merge_splits(np.stack([p[h] for p in parts_o]), np.array([p[h] for p in parts_L]))
+        np.testing.assert_allclose(o, whole[0, h], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(l, L[0, h], rtol=1e-12)
+    # merge identity on two scalars: L = log(e^{L1} + e^{L2})
+    _, l = oracle.merge_splits(np.zeros((2, 4)), np.array([0.3, -1.2]))
+    assert l == pytest.approx(np.log(np.exp(0.3) + np.exp(-1.2)), rel=1e-14)
+
+
+def test_softmax_shift_invariance(oracle):
+    """Adding one vector u to every centroid of one key sub-space adds q~_m . u / sqrt(D) to every
+    score: the output is unchanged and L moves by exactly that amount."""
+    s, x = _small_decode_case(27, B=1, Hq=2, Hkv=1)
+    base_o, base_L = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    cb2 = x["cb_k"].astype(np.float64).copy()
+    u = np.array([0.5, -1.0, 2.0, 0.25])
+    cb2[0, 5] += u
+    o2, L2 = oracle.decode_attention(x["q"], x["lam"], cb2, x["cb_v"], x["k_idx"], x["v_idx"])
+    np.testing.assert_allclose(o2, base_o, rtol=1e-10, atol=1e-13)
+    for h in range(2):
+        qt = oracle.transform_query(x["q"][0, h], x["lam"][0])
+        np.testing.assert_allclose(L2[0, h] - base_L[0, h], qt[20:24] @ u / np.sqrt(s.D), rtol=1e-9)
+
+
+def test_decode_rejects_empty_sequence(oracle):
+    s, x = _small_decode_case(28, B=2)
+    with pytest.raises(ValueError):
+        oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"], np.array([5, 0]))
+
+
+def test_tiny_config_end_to_end_quantization_is_sane(oracle):
+    """Config 1 (1 head, N 4096, outlier keys): the quantized attention stays close to the
+    full-precision attention of Eq. 1 -- a coarse end-to-end check that encode and decode agree
+    on the side of the transform (a swapped lambda or a missing Hadamard breaks it)."""
+    sh = synth.TINY
+    e = synth.encode_inputs(sh, seed=1, n_outlier=4)
+    K = e["k"][0, 0].astype(np.float64)
+    V = e["v"][0, 0].astype(np.float64)
+    lam = oracle.smoothing_factors(K)[None, :]
+    # codebooks fitted to the data's own scale so that quantization error is small
+    Kt = oracle.transform_keys(K, lam[0])
+    g = synth.rng(99)
+    cb_k = np.stack([Kt[g.choice(sh.N, 256, replace=False), 4 * m:4 * m + 4] for m in range(32)])[None]
+    cb_v = np.stack([V[g.choice(sh.N, 256, replace=False), 4 * m:4 * m + 4] for m in range(32)])[None]
+    k_idx = oracle.encode_keys(e["k"], lam, cb_k)
+    v_idx = oracle.encode_values(e["v"], cb_v)
+    out, _ = oracle.decode_attention(e["q"], lam, cb_k, cb_v, k_idx, v_idx)
+    q = e["q"][0, 0].astype(np.float64)
+    p = scipy.special.softmax(K @ q / np.sqrt(sh.D))
+    full = p @ V
+    # scores of the quantized cache correlate strongly with the exact ones
+    s_q = oracle.vq_dequantize(k_idx[0, 0], cb_k[0]) @ oracle.transform_query(q, lam[0]) / np.sqrt(sh.D)
+    assert np.corrcoef(s_q, K @ q / np.sqrt(sh.D))[0, 1] > 0.9
+    assert np.abs(out[0, 0] - full).max() < 0.5 * np.abs(V).max()
