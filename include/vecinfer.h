@@ -1,0 +1,158 @@
+/*
+ * vecinfer.h -- C ABI of the MI355X (gfx950) fused vector-quantized decode attention.
+ *
+ * The library implements the hot path of VecInfer: a KV cache stored as uint8
+ * codebook indices (Sec. 2.2, Eq. 2) after the key-side smooth + Hadamard
+ * transform (Sec. 3.2, Eq. 3-8), and a decode step that attends to that cache
+ * without ever materialising it in full precision (Sec. 3.2 Eq. 10; Sec. 3.3;
+ * App. A Alg. 1).
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer on the current HIP device, owned by
+ *     the caller, valid until the work enqueued on `stream` has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; they never synchronise, allocate or free device memory.
+ *   - Inputs are read-only.  Outputs are fully overwritten for the rows named.
+ *   - Return value: VECINFER_OK (0) or a negative VECINFER_E* code.  Arguments are
+ *     validated on the host before anything is launched; on error nothing was
+ *     enqueued.  No exception crosses the boundary.
+ *   - Thread-safe; the only state is the caller's workspace (see decode).
+ *
+ * Notation (paper): D head dim, d sub-vector dim, M = D / d sub-spaces, 256
+ * centroids per sub-space (8-bit codes), H_q query heads, H_kv KV heads,
+ * G = H_q / H_kv, query head h reads KV head h / G (consecutive grouping).
+ *
+ * Layouts (row-major, innermost last)
+ *   keys / values      fp16  [B, H_kv, T, D]
+ *   lambda             fp32  [H_kv, D]          smoothing factors, all > 0
+ *   codebooks          fp16  [H_kv, M, 256, d]  one codebook per (KV head, sub-space)
+ *   code cache         uint8 [B, H_kv, n_cap, M] one byte per (token, sub-space): the
+ *                                               paper's N x M code matrix per head
+ *   queries / output   fp16  [B, H_q, D]
+ *   lse                fp32  [B, H_q]           natural-log sum of exp of the scores
+ */
+#ifndef VECINFER_H
+#define VECINFER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VECINFER_VERSION 100          /* major*10000 + minor*100 + patch */
+#define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
+
+enum {
+    VECINFER_OK = 0,
+    VECINFER_EINVAL = -1,       /* null pointer, non-positive size, inconsistent shapes      */
+    VECINFER_EUNSUPPORTED = -2, /* a shape the kernels do not cover (see vecinfer_cfg)       */
+    VECINFER_EWORKSPACE = -3,   /* workspace NULL, misaligned or smaller than required       */
+    VECINFER_ELAUNCH = -4       /* the HIP runtime rejected a launch or a device query       */
+};
+
+/* Decode kernel families (argument `variant` of vecinfer_decode_attention). */
+enum {
+    VECINFER_VARIANT_AUTO = 0,   /* fastest kernel that covers the configuration             */
+    VECINFER_VARIANT_LUT = 1,    /* query-centroid lookup table in LDS, vector ALU (Alg. 1
+                                    steps 4 and 11 taken literally); covers every supported
+                                    configuration                                            */
+    VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
+                                    cores for both q.K and P.V; D = 128, G = 4, d in {2,4}    */
+};
+
+typedef struct vecinfer_cfg {
+    int32_t head_dim;      /* D: 64 or 128 (Walsh-Hadamard needs a power of two, Eq. 5)      */
+    int32_t num_q_heads;   /* H_q                                                            */
+    int32_t num_kv_heads;  /* H_kv, divides H_q; G = H_q / H_kv in {1, 2, 4, 8}              */
+    int32_t k_sub_dim;     /* d for keys: 2, 4 or 8                                          */
+    int32_t v_sub_dim;     /* d for values: 2, 4 or 8 (keys and values may differ, Sec. 3.2)  */
+    int32_t k_bits;        /* code width for keys: 8 (uint8 index, 256 centroids)            */
+    int32_t v_bits;        /* code width for values: 8                                       */
+} vecinfer_cfg;
+
+/*
+ * Cache fill for keys: Alg. 1 "Preprocessing" + "Quantization" (Eq. 3, 6, 8):
+ * for each of the T new tokens, k~ = (k / lambda) H_D, then for every sub-space m
+ *   k_idx[b, g, pos0 + t, m] = argmin_c || k~[m*d .. m*d+d) - cb_k[g, m, c, :] ||^2   (Eq. 2)
+ * with the squared distance summed directly in fp32 in channel order and the lowest
+ * index winning ties.  k~ is not rounded to fp16 before the search.
+ * T = 1 with pos0 = current length is the decode-time append of Eq. 9.
+ *   k_f16   [B, H_kv, T, D] fp16      lambda [H_kv, D] fp32
+ *   cb_k    [H_kv, M_k, 256, d_k]     k_idx  [B, H_kv, n_cap, M_k], rows pos0 .. pos0+T-1 written
+ * Errors: EINVAL for null pointers, B < 1, T < 1, pos0 < 0, pos0 + T > n_cap;
+ * EUNSUPPORTED for a cfg outside the ranges above.
+ */
+int vecinfer_encode_keys(const vecinfer_cfg *cfg, const void *k_f16, const float *lambda,
+                         const void *cb_k_f16, uint8_t *k_idx, int32_t B, int64_t T,
+                         int64_t pos0, int64_t n_cap, void *stream);
+
+/*
+ * Cache fill for values: Eq. 8 on the untransformed values (no smoothing, no Hadamard).
+ * Same argmin rule, layouts and errors as vecinfer_encode_keys, with d_v / M_v.
+ */
+int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const void *cb_v_f16,
+                           uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0,
+                           int64_t n_cap, void *stream);
+
+/*
+ * Number of sequence splits the library would pick for (B, N) when num_splits = 0
+ * (grid axis "num_splits" of Sec. 3.3).  Host-only; returns >= 1, or a negative code.
+ */
+int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t N);
+
+/*
+ * Bytes of workspace vecinfer_decode_attention needs for batch B, up to N tokens and
+ * `num_splits` splits (0 = whatever vecinfer_decode_auto_splits returns for (B, N)).
+ * Host-only.  Returns 0 for an invalid cfg.
+ */
+size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64_t N,
+                                       int32_t num_splits);
+
+/*
+ * Prepare a freshly allocated workspace (256-byte aligned): zeroes the arrival counters
+ * the split merge uses.  Enqueued on `stream`.  Needed once per allocation; every decode
+ * call leaves the counters zero again.  After a failed or aborted launch call it again.
+ */
+int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step of VQ attention (Eq. 10 via Alg. 1 steps 4-23) for a batch:
+ *   q~ = (q * lambda[g]) H_D                                   (Eq. 3, 6, 7)
+ *   s_n = q~ . concat_m cb_k[g, m, k_idx[b, g, n, m], :] / sqrt(D)
+ *   p = softmax(s) over n < len_b;  o = sum_n p_n concat_m cb_v[g, m, v_idx[b, g, n, m], :]
+ *   L = log sum_n exp(s_n)                                      (Alg. 1 step 22)
+ * computed per (b, q head h), g = h / G, fp32 accumulation, fp16 output.  The sequence
+ * is cut into `num_splits` chunks handled by different workgroups; their (o, m, l)
+ * partials go through `workspace` and are merged by log-sum-exp in the same launch.
+ * The result does not depend on num_splits beyond fp32 rounding.
+ *   seq_lens  int32 [B] on the device, or NULL: every sequence has N tokens.  Values are
+ *             clamped to [0, N]; a sequence of length 0 yields o = 0 and L = -inf.
+ *   N         tokens attended (upper bound when seq_lens is given), 1 <= N <= n_cap
+ *   num_splits 0 = auto, else 1 .. VECINFER_MAX_SPLITS
+ *   variant   VECINFER_VARIANT_*
+ *   workspace at least vecinfer_decode_workspace_bytes(cfg, B, N, num_splits) bytes,
+ *             256-byte aligned, prepared by vecinfer_decode_workspace_init; calls that
+ *             share a workspace must be ordered on one stream
+ *   out_f16   [B, H_q, D] fp16          lse  [B, H_q] fp32 or NULL
+ * Errors: EINVAL (null pointers, B < 1, N < 1, N > n_cap, num_splits out of range),
+ * EUNSUPPORTED (cfg, or variant that does not cover cfg), EWORKSPACE, ELAUNCH.
+ */
+int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                              const void *cb_k_f16, const void *cb_v_f16,
+                              const uint8_t *k_idx, const uint8_t *v_idx,
+                              const int32_t *seq_lens, int32_t B, int64_t N, int64_t n_cap,
+                              int32_t num_splits, int32_t variant, void *workspace,
+                              size_t workspace_bytes, void *out_f16, float *lse, void *stream);
+
+/* Human-readable text for a return code (static storage). */
+const char *vecinfer_strerror(int code);
+
+/* VECINFER_VERSION of the built library. */
+int vecinfer_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VECINFER_H */

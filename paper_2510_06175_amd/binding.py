@@ -1,0 +1,186 @@
+"""ctypes binding of ``libvecinfer.so``: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (HIP) tensors used purely as device buffers; shapes, dtypes,
+contiguity and device are checked here and the raw pointers handed to the library,
+which enqueues on torch's current stream unless ``stream`` is given.  If the library
+has not been built the import of it fails loudly: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvecinfer.so")
+
+VARIANT_AUTO, VARIANT_LUT, VARIANT_MFMA = 0, 1, 2
+MAX_SPLITS = 256
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_decode_auto_splits",
+    "vecinfer_decode_workspace_bytes", "vecinfer_decode_workspace_init",
+    "vecinfer_decode_attention", "vecinfer_strerror", "vecinfer_version",
+]
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("head_dim", "num_q_heads", "num_kv_heads", "k_sub_dim",
+                                         "v_sub_dim", "k_bits", "v_bits")]
+
+
+@dataclass(frozen=True)
+class Config:
+    """Mirror of ``vecinfer_cfg``."""
+    head_dim: int
+    num_q_heads: int
+    num_kv_heads: int
+    k_sub_dim: int
+    v_sub_dim: int
+    k_bits: int = 8
+    v_bits: int = 8
+
+    def c(self) -> _Cfg:
+        return _Cfg(self.head_dim, self.num_q_heads, self.num_kv_heads, self.k_sub_dim,
+                    self.v_sub_dim, self.k_bits, self.v_bits)
+
+
+class VecInferError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"vecinfer error {code}: {strerror(code)}")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the built library (raises if it is missing: build it first)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2510_06175_amd.build` "
+                "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        cfgp = C.POINTER(_Cfg)
+        L.vecinfer_encode_keys.argtypes = [cfgp, vp, vp, vp, vp, i32, i64, i64, i64, vp]
+        L.vecinfer_encode_keys.restype = C.c_int
+        L.vecinfer_encode_values.argtypes = [cfgp, vp, vp, vp, i32, i64, i64, i64, vp]
+        L.vecinfer_encode_values.restype = C.c_int
+        L.vecinfer_decode_auto_splits.argtypes = [cfgp, i32, i64]
+        L.vecinfer_decode_auto_splits.restype = i32
+        L.vecinfer_decode_workspace_bytes.argtypes = [cfgp, i32, i64, i32]
+        L.vecinfer_decode_workspace_bytes.restype = sz
+        L.vecinfer_decode_workspace_init.argtypes = [vp, sz, vp]
+        L.vecinfer_decode_workspace_init.restype = C.c_int
+        L.vecinfer_decode_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32,
+                                                i32, vp, sz, vp, vp, vp]
+        L.vecinfer_decode_attention.restype = C.c_int
+        L.vecinfer_strerror.argtypes = [C.c_int]
+        L.vecinfer_strerror.restype = C.c_char_p
+        L.vecinfer_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().vecinfer_strerror(int(code)).decode()
+
+
+def vecinfer_version() -> int:
+    return int(lib().vecinfer_version())
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise VecInferError(rc)
+
+
+def _dev(t: torch.Tensor, dtype, shape, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: expected a tensor on the GPU")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise ValueError(f"{name}: expected contiguous {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def vecinfer_encode_keys(cfg: Config, k_f16, lam, cb_k, k_idx, pos0: int = 0, stream=None) -> None:
+    """Smooth + Hadamard + VQ of T new keys into rows pos0.. of the code cache."""
+    B, Hkv, T, D = k_f16.shape
+    n_cap = k_idx.shape[2]
+    M = cfg.head_dim // cfg.k_sub_dim
+    _check(lib().vecinfer_encode_keys(
+        C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_k, torch.float16, (cfg.num_kv_heads, M, 256, cfg.k_sub_dim), "cb_k"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, M), "k_idx"),
+        B, T, pos0, n_cap, _stream(stream)))
+
+
+def vecinfer_encode_values(cfg: Config, v_f16, cb_v, v_idx, pos0: int = 0, stream=None) -> None:
+    """VQ of T new (untransformed) values into rows pos0.. of the code cache."""
+    B, Hkv, T, D = v_f16.shape
+    n_cap = v_idx.shape[2]
+    M = cfg.head_dim // cfg.v_sub_dim
+    _check(lib().vecinfer_encode_values(
+        C.byref(cfg.c()), _dev(v_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "v_f16"),
+        _dev(cb_v, torch.float16, (cfg.num_kv_heads, M, 256, cfg.v_sub_dim), "cb_v"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, M), "v_idx"),
+        B, T, pos0, n_cap, _stream(stream)))
+
+
+def vecinfer_decode_auto_splits(cfg: Config, B: int, N: int) -> int:
+    return int(lib().vecinfer_decode_auto_splits(C.byref(cfg.c()), B, N))
+
+
+def vecinfer_decode_workspace_bytes(cfg: Config, B: int, N: int, num_splits: int = 0) -> int:
+    return int(lib().vecinfer_decode_workspace_bytes(C.byref(cfg.c()), B, N, num_splits))
+
+
+def vecinfer_decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().vecinfer_decode_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                _stream(stream)))
+
+
+def new_workspace(cfg: Config, B: int, N: int, num_splits: int = 0, device="cuda") -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for vecinfer_decode_attention."""
+    nbytes = vecinfer_decode_workspace_bytes(cfg, B, N, num_splits)
+    if nbytes == 0:
+        raise VecInferError(EUNSUPPORTED)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    vecinfer_decode_workspace_init(ws)
+    return ws
+
+
+def vecinfer_decode_attention(cfg: Config, q_f16, lam, cb_k, cb_v, k_idx, v_idx, workspace, out_f16,
+                              lse=None, seq_lens=None, N: int | None = None, num_splits: int = 0,
+                              variant: int = VARIANT_AUTO, stream=None) -> None:
+    """One fused VQ decode-attention step; writes out_f16 [B, Hq, D] (and lse [B, Hq])."""
+    B = q_f16.shape[0]
+    n_cap = k_idx.shape[2]
+    N = n_cap if N is None else N
+    Mk = cfg.head_dim // cfg.k_sub_dim
+    Mv = cfg.head_dim // cfg.v_sub_dim
+    _check(lib().vecinfer_decode_attention(
+        C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
+        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
+        B, N, n_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
+        None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
+        _stream(stream)))

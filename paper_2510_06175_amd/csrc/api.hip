@@ -1,0 +1,223 @@
+// C ABI of the library: argument validation and kernel dispatch.  See include/vecinfer.h.
+#include "../../include/vecinfer.h"
+
+#include "common.h"
+
+using namespace vecinfer;
+
+namespace {
+
+bool cfg_ok(const vecinfer_cfg *c)
+{
+    if (!c) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads) return false;
+    const int G = c->num_q_heads / c->num_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+    auto sub_ok = [](int d) { return d == 2 || d == 4 || d == 8; };
+    if (!sub_ok(c->k_sub_dim) || !sub_ok(c->v_sub_dim)) return false;
+    if (c->k_bits != 8 || c->v_bits != 8) return false;
+    return true;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int num_cus()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;                     // MI355X; used only to size the grid
+        cached = n;
+    }
+    return cached;
+}
+
+// Splits so that B * H_kv * S fills the compute units once, each split keeping enough
+// tokens to amortise staging the codebooks in LDS.
+int32_t auto_splits(const vecinfer_cfg *c, int32_t B, int64_t N)
+{
+    const int64_t groups = (int64_t)B * c->num_kv_heads;
+    int64_t s = (num_cus() + groups - 1) / groups;
+    const int64_t min_tokens = 1024;
+    const int64_t cap = (N + min_tokens - 1) / min_tokens;
+    if (s > cap) s = cap;
+    if (s > VECINFER_MAX_SPLITS) s = VECINFER_MAX_SPLITS;
+    if (s < 1) s = 1;
+    return (int32_t)s;
+}
+
+struct WorkspaceLayout {
+    size_t off_o, off_m, off_l, off_cnt, total;
+};
+
+WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
+{
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t rows = (size_t)B * c->num_q_heads * S;     // = B * Hkv * S * G
+    WorkspaceLayout w;
+    w.off_cnt = 0;                                           // counters first: init touches only them
+    size_t off = up(sizeof(unsigned) * (size_t)B * c->num_kv_heads);
+    w.off_o = off;
+    off += up(sizeof(float) * rows * c->head_dim);
+    w.off_m = off;
+    off += up(sizeof(float) * rows);
+    w.off_l = off;
+    off += up(sizeof(float) * rows);
+    w.total = off;
+    return w;
+}
+
+int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, bool keys,
+                  const void *cb, uint8_t *idx, int32_t B, int64_t T, int64_t pos0, int64_t n_cap,
+                  void *stream)
+{
+    if (!cfg || !x || !cb || !idx || (keys && !lambda)) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    if (B < 1 || T < 1 || pos0 < 0 || n_cap < 1 || pos0 + T > n_cap) return VECINFER_EINVAL;
+    if ((int64_t)B * cfg->num_kv_heads > 65535) return VECINFER_EUNSUPPORTED;
+    if ((T + 63) / 64 > 0x7fffffffLL) return VECINFER_EUNSUPPORTED;
+    if (!aligned(x, 16) || !aligned(cb, 16) || !aligned(idx, 16) || (keys && !aligned(lambda, 16)))
+        return VECINFER_EINVAL;
+    EncodeParams p;
+    p.x = static_cast<const __half *>(x);
+    p.lam = keys ? lambda : nullptr;
+    p.cb = static_cast<const __half *>(cb);
+    p.idx = idx;
+    p.B = B;
+    p.Hkv = cfg->num_kv_heads;
+    p.D = cfg->head_dim;
+    p.d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
+    p.M = p.D / p.d;
+    p.T = T;
+    p.pos0 = pos0;
+    p.n_cap = n_cap;
+    const int rc = launch_encode(p, static_cast<hipStream_t>(stream));
+    return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
+}
+
+__global__ void zero_counters_kernel(unsigned *c, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) c[i] = 0u;
+}
+
+} // namespace
+
+extern "C" {
+
+int vecinfer_encode_keys(const vecinfer_cfg *cfg, const void *k_f16, const float *lambda,
+                         const void *cb_k_f16, uint8_t *k_idx, int32_t B, int64_t T, int64_t pos0,
+                         int64_t n_cap, void *stream)
+{
+    return encode_common(cfg, k_f16, lambda, true, cb_k_f16, k_idx, B, T, pos0, n_cap, stream);
+}
+
+int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const void *cb_v_f16,
+                           uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0, int64_t n_cap,
+                           void *stream)
+{
+    return encode_common(cfg, v_f16, nullptr, false, cb_v_f16, v_idx, B, T, pos0, n_cap, stream);
+}
+
+int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t N)
+{
+    if (!cfg || B < 1 || N < 1) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    return auto_splits(cfg, B, N);
+}
+
+size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64_t N, int32_t num_splits)
+{
+    if (!cfg_ok(cfg) || B < 1 || N < 1 || num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return 0;
+    const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
+    return ws_layout(cfg, B, S).total;
+}
+
+int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < 256) return VECINFER_EWORKSPACE;
+    // The counters sit at the start of the workspace; how many are in use depends on the
+    // later call's (B, H_kv), so clear every word up to the first data region that any
+    // layout of this size could have: the whole buffer is cheap enough to clear once.
+    const size_t words = workspace_bytes / sizeof(unsigned);
+    const unsigned blocks = (unsigned)((words + 255) / 256);
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<unsigned *>(workspace), words);
+    return hipGetLastError() == hipSuccess ? VECINFER_OK : VECINFER_ELAUNCH;
+}
+
+int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                              const void *cb_k_f16, const void *cb_v_f16, const uint8_t *k_idx,
+                              const uint8_t *v_idx, const int32_t *seq_lens, int32_t B, int64_t N,
+                              int64_t n_cap, int32_t num_splits, int32_t variant, void *workspace,
+                              size_t workspace_bytes, void *out_f16, float *lse, void *stream)
+{
+    if (!cfg || !q_f16 || !lambda || !cb_k_f16 || !cb_v_f16 || !k_idx || !v_idx || !out_f16)
+        return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    if (B < 1 || N < 1 || n_cap < N) return VECINFER_EINVAL;
+    if (num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
+    if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA)
+        return VECINFER_EINVAL;
+    if (B > 65535) return VECINFER_EUNSUPPORTED;
+    if (!aligned(q_f16, 16) || !aligned(lambda, 16) || !aligned(cb_k_f16, 16) || !aligned(cb_v_f16, 16) ||
+        !aligned(k_idx, 16) || !aligned(v_idx, 16) || !aligned(out_f16, 16))
+        return VECINFER_EINVAL;
+    const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
+    const WorkspaceLayout w = ws_layout(cfg, B, S);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return VECINFER_EWORKSPACE;
+
+    DecodeParams p;
+    p.q = static_cast<const __half *>(q_f16);
+    p.lam = lambda;
+    p.cb_k = static_cast<const __half *>(cb_k_f16);
+    p.cb_v = static_cast<const __half *>(cb_v_f16);
+    p.k_idx = k_idx;
+    p.v_idx = v_idx;
+    p.seq_lens = seq_lens;
+    p.B = B;
+    p.Hq = cfg->num_q_heads;
+    p.Hkv = cfg->num_kv_heads;
+    p.G = p.Hq / p.Hkv;
+    p.D = cfg->head_dim;
+    p.dk = cfg->k_sub_dim;
+    p.dv = cfg->v_sub_dim;
+    p.Mk = p.D / p.dk;
+    p.Mv = p.D / p.dv;
+    p.N = N;
+    p.n_cap = n_cap;
+    p.S = S;
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    p.counters = reinterpret_cast<unsigned *>(ws + w.off_cnt);
+    p.part_o = reinterpret_cast<float *>(ws + w.off_o);
+    p.part_m = reinterpret_cast<float *>(ws + w.off_m);
+    p.part_l = reinterpret_cast<float *>(ws + w.off_l);
+    p.out = static_cast<__half *>(out_f16);
+    p.lse = lse;
+
+    const bool mfma_ok = decode_mfma_supports(p);
+    if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
+    const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
+    const int rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
+                            : launch_decode_lut(p, static_cast<hipStream_t>(stream));
+    return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
+}
+
+const char *vecinfer_strerror(int code)
+{
+    switch (code) {
+    case VECINFER_OK: return "ok";
+    case VECINFER_EINVAL: return "invalid argument";
+    case VECINFER_EUNSUPPORTED: return "unsupported configuration";
+    case VECINFER_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case VECINFER_ELAUNCH: return "HIP launch or device query failed";
+    default: return "unknown error code";
+    }
+}
+
+int vecinfer_version(void) { return VECINFER_VERSION; }
+
+} // extern "C"

@@ -1,0 +1,162 @@
+// Cache-fill kernels: key-side dual transform (Eq. 3, Eq. 6) and exhaustive nearest-centroid
+// vector quantization (Eq. 2, Eq. 8).
+//
+// One workgroup (4 wavefronts) handles 64 tokens of one (batch, KV head) and one "chunk" of
+// 64 output channels (64/d sub-spaces).
+//   phase 1  transform: a lane owns 4 consecutive channels of one token; the first two
+//            butterfly stages run inside the lane, the others across lanes with wavefront
+//            shuffles.  Only the chunk's 64 transformed channels are kept, as fp32, in LDS.
+//            (Values skip the transform: the lane just widens its fp16 inputs.)
+//   phase 2  search: a lane owns one token, a wavefront owns one sub-space at a time, so the
+//            centroid under test is the same for all 64 lanes and is read from LDS as a
+//            broadcast.  Squared distances are summed directly, in channel order, in fp32;
+//            a strict "<" keeps the lowest index on ties.
+//   phase 3  the 64 x (64/d) code bytes go out through LDS as whole 32-bit words.
+#include "common.h"
+
+namespace vecinfer {
+
+namespace {
+
+constexpr int kEncBlock = 256;
+constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
+constexpr int kChunkCh = 64;       // output channels per workgroup
+
+template <int D, int d, bool kTransform>
+__global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
+{
+    constexpr int M = D / d;
+    constexpr int MS = kChunkCh / d;           // sub-spaces per chunk
+    constexpr int LPT = D / 4;                 // lanes per token in phase 1
+    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass in phase 1
+    constexpr int XS = kChunkCh + 4;           // padded row stride of the LDS tile (floats)
+
+    __shared__ __align__(16) __half cb_s[MS * kCentroids * d];     // 32 KB
+    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 17 KB
+    __shared__ __align__(16) uint8_t idx_s[kEncTokens * MS];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long t0 = (long long)blockIdx.x * kEncTokens;
+    const int chunk = blockIdx.y;
+    const int bg = blockIdx.z;
+    const int g = bg % p.Hkv;
+
+    // ---- codebook chunk -> LDS (fp16, as given)
+    {
+        const uint4 *src = reinterpret_cast<const uint4 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
+        uint4 *dst = reinterpret_cast<uint4 *>(cb_s);
+        for (int e = tid; e < MS * kCentroids * d / 8; e += kEncBlock) dst[e] = src[e];
+    }
+
+    // ---- phase 1
+    {
+        const int sub = lane % LPT;            // which 4 channels of the token
+        const int tw = lane / LPT;             // which token of this pass
+        const int c0 = 4 * sub;
+        float rl[4] = {1.f, 1.f, 1.f, 1.f};
+        if (kTransform) {
+            const float4 l4 = *reinterpret_cast<const float4 *>(p.lam + (size_t)g * D + c0);
+            rl[0] = l4.x; rl[1] = l4.y; rl[2] = l4.z; rl[3] = l4.w;
+        }
+        const float hs = 1.0f / sqrtf((float)D);
+        for (int pass = wave; pass < kEncTokens / TPW; pass += kEncBlock / 64) {
+            const int tl = pass * TPW + tw;                    // token within the tile
+            long long t = t0 + tl;
+            if (t >= p.T) t = p.T - 1;                         // tail: harmless duplicate
+            const uint2 raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
+            const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
+            const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
+            float v0 = __low2float(h01), v1 = __high2float(h01), v2 = __low2float(h23), v3 = __high2float(h23);
+            if (kTransform) {
+                v0 = v0 / rl[0]; v1 = v1 / rl[1]; v2 = v2 / rl[2]; v3 = v3 / rl[3];
+                // butterflies with partner distance 1 and 2 (inside the lane)
+                float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;
+                v0 = a0 + a2; v1 = a1 + a3; v2 = a0 - a2; v3 = a1 - a3;
+                // partner distance 4 .. D/2 (across lanes)
+#pragma unroll
+                for (int x = 1; x < LPT; x <<= 1) {
+                    const float o0 = __shfl_xor(v0, x), o1 = __shfl_xor(v1, x);
+                    const float o2 = __shfl_xor(v2, x), o3 = __shfl_xor(v3, x);
+                    const bool up = (sub & x) != 0;
+                    v0 = up ? (o0 - v0) : (v0 + o0);
+                    v1 = up ? (o1 - v1) : (v1 + o1);
+                    v2 = up ? (o2 - v2) : (v2 + o2);
+                    v3 = up ? (o3 - v3) : (v3 + o3);
+                }
+                v0 *= hs; v1 *= hs; v2 *= hs; v3 *= hs;
+            }
+            if (c0 / kChunkCh == chunk) {
+                float4 w; w.x = v0; w.y = v1; w.z = v2; w.w = v3;
+                *reinterpret_cast<float4 *>(&x_s[tl * XS + (c0 - chunk * kChunkCh)]) = w;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2
+    for (int ms = wave; ms < MS; ms += kEncBlock / 64) {
+        float x[d];
+#pragma unroll
+        for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + ms * d + j];
+        float best = INFINITY;
+        int arg = 0;
+        const __half *cen = cb_s + (size_t)ms * kCentroids * d;
+#pragma unroll 8
+        for (int c = 0; c < kCentroids; ++c) {
+            float dist = 0.f;
+#pragma unroll
+            for (int j = 0; j < d; ++j) {
+                const float t = x[j] - __half2float(cen[c * d + j]);
+                dist = fmaf(t, t, dist);
+            }
+            if (dist < best) {
+                best = dist;
+                arg = c;
+            }
+        }
+        idx_s[lane * MS + ms] = (uint8_t)arg;
+    }
+    __syncthreads();
+
+    // ---- phase 3: MS bytes per token, written as 32-bit words
+    {
+        constexpr int WPT = MS / 4;            // words per token
+        for (int e = tid; e < kEncTokens * WPT; e += kEncBlock) {
+            const int tl = e / WPT, w = e - tl * WPT;
+            const long long t = t0 + tl;
+            if (t < p.T) {
+                uint32_t *dst = reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t) * M + (size_t)chunk * MS);
+                dst[w] = reinterpret_cast<const uint32_t *>(idx_s)[tl * WPT + w];
+            }
+        }
+    }
+}
+
+template <int D, int d>
+int launch_typed(const EncodeParams &p, hipStream_t stream)
+{
+    dim3 grid((unsigned)((p.T + kEncTokens - 1) / kEncTokens), D / kChunkCh, p.B * p.Hkv);
+    if (p.lam)
+        hipLaunchKernelGGL((encode_kernel<D, d, true>), grid, dim3(kEncBlock), 0, stream, p);
+    else
+        hipLaunchKernelGGL((encode_kernel<D, d, false>), grid, dim3(kEncBlock), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+} // namespace
+
+int launch_encode(const EncodeParams &p, hipStream_t stream)
+{
+    if (p.D == 128) {
+        if (p.d == 2) return launch_typed<128, 2>(p, stream);
+        if (p.d == 4) return launch_typed<128, 4>(p, stream);
+        if (p.d == 8) return launch_typed<128, 8>(p, stream);
+    } else if (p.D == 64) {
+        if (p.d == 2) return launch_typed<64, 2>(p, stream);
+        if (p.d == 4) return launch_typed<64, 4>(p, stream);
+        if (p.d == 8) return launch_typed<64, 8>(p, stream);
+    }
+    return -2;
+}
+
+} // namespace vecinfer

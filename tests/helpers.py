@@ -1,0 +1,90 @@
+"""Helpers of the GPU parity tests: run the library on numpy inputs, compare with the oracle."""
+import numpy as np
+import torch
+
+from paper_2510_06175_amd import binding as vb
+
+# Tolerances of the parity bar:
+#   output  max |err| <= 2e-3 * ||out||_inf per (batch, head) row (fp16 output, fp32 accumulation)
+#   L       |err| <= 1e-3 (scores and their log-sum-exp are O(10); fp32 rounding of a sum of
+#           D terms plus the exp2/log2 units stays orders below this)
+OUT_RTOL_INF = 2e-3
+LSE_ATOL = 1e-3
+NEAR_TIE = 1e-6     # relative distance gap under which an index mismatch is a logged near-tie
+
+
+def cfg_of(shape):
+    return vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_decode(shape, x, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT_AUTO, ws=None, want_lse=True):
+    """x: dict of numpy arrays (q, lam, cb_k, cb_v, k_idx, v_idx) -> (out fp16 as f64, lse f64)."""
+    cfg = cfg_of(shape)
+    t = {k: (v if isinstance(v, torch.Tensor) else dev(v)) for k, v in x.items()
+         if k in ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx")}
+    B = t["q"].shape[0]
+    n_cap = t["k_idx"].shape[2]
+    N = n_cap if N is None else N
+    if ws is None:
+        ws = vb.new_workspace(cfg, B, N, num_splits)
+    out = torch.full((B, shape.Hq, shape.D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((B, shape.Hq), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    sl = None if seq_lens is None else torch.as_tensor(np.asarray(seq_lens), dtype=torch.int32).cuda()
+    vb.vecinfer_decode_attention(cfg, t["q"], t["lam"], t["cb_k"], t["cb_v"], t["k_idx"], t["v_idx"], ws, out,
+                                 lse=lse, seq_lens=sl, N=N, num_splits=num_splits, variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64), (lse.cpu().numpy().astype(np.float64) if want_lse else None)
+
+
+def assert_decode_close(got_out, got_lse, ref_out, ref_lse, what=""):
+    B, Hq, _ = ref_out.shape
+    worst = 0.0
+    for b in range(B):
+        for h in range(Hq):
+            scale = np.abs(ref_out[b, h]).max()
+            err = np.abs(got_out[b, h] - ref_out[b, h]).max()
+            assert np.isfinite(got_out[b, h]).all(), f"{what}: non-finite output at b={b} h={h}"
+            assert err <= OUT_RTOL_INF * scale, (
+                f"{what}: b={b} h={h} max|err|={err:.3e} > {OUT_RTOL_INF}*{scale:.3e}")
+            worst = max(worst, err / scale if scale > 0 else 0.0)
+    if got_lse is not None:
+        d = np.abs(got_lse - ref_lse).max()
+        assert d <= LSE_ATOL, f"{what}: |L err|={d:.3e}"
+    return worst
+
+
+def gpu_encode(shape, k=None, lam=None, cb_k=None, v=None, cb_v=None, pos0=0, n_cap=None):
+    """Encode keys and/or values on the GPU; returns uint8 numpy arrays [B, Hkv, n_cap, M]."""
+    cfg = cfg_of(shape)
+    res = []
+    if k is not None:
+        B, Hkv, T, D = k.shape
+        cap = T + pos0 if n_cap is None else n_cap
+        idx = torch.full((B, Hkv, cap, shape.Mk), 0xEE, dtype=torch.uint8, device="cuda")
+        vb.vecinfer_encode_keys(cfg, dev(k), dev(lam), dev(cb_k), idx, pos0=pos0)
+        res.append(idx)
+    if v is not None:
+        B, Hkv, T, D = v.shape
+        cap = T + pos0 if n_cap is None else n_cap
+        idx = torch.full((B, Hkv, cap, shape.Mv), 0xEE, dtype=torch.uint8, device="cuda")
+        vb.vecinfer_encode_values(cfg, dev(v), dev(cb_v), idx, pos0=pos0)
+        res.append(idx)
+    torch.cuda.synchronize()
+    return [r.cpu().numpy() for r in res]
+
+
+def assert_indices_match(got, ref, gap, what=""):
+    """Bit-exact except where the oracle's own best/second-best relative gap is below NEAR_TIE."""
+    diff = got != ref
+    n_diff = int(diff.sum())
+    if n_diff:
+        bad = diff & ~(gap < NEAR_TIE)
+        print(f"[near-tie log] {what}: {n_diff} of {diff.size} indices differ; "
+              f"max oracle gap among them {gap[diff].max():.3e}")
+        assert not bad.any(), (f"{what}: {int(bad.sum())} index mismatches with relative gap >= {NEAR_TIE} "
+                               f"(worst {gap[bad].max():.3e})")
+    return n_diff

@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments with error codes before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_06175_amd import binding as vb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # non-null, 256-byte aligned; never dereferenced on the host
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "vecinfer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vecinfer_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert sorted(names) == sorted(vb.EXPORTS)
+    L = vb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_strerror():
+    assert vb.vecinfer_version() == 100
+    assert vb.strerror(0) == "ok"
+    for code in (vb.EINVAL, vb.EUNSUPPORTED, vb.EWORKSPACE, vb.ELAUNCH):
+        assert vb.strerror(code) not in ("ok", "unknown error code")
+    assert vb.strerror(-99) == "unknown error code"
+
+
+CFG = vb.Config(128, 32, 8, 4, 4)
+
+
+def _enc_keys(cfg=CFG, k=FAKE, lam=FAKE, cb=FAKE, idx=FAKE, B=1, T=4, pos0=0, n_cap=8):
+    return vb.lib().vecinfer_encode_keys(C.byref(cfg.c()), k, lam, cb, idx, B, T, pos0, n_cap, None)
+
+
+def _enc_vals(cfg=CFG, v=FAKE, cb=FAKE, idx=FAKE, B=1, T=4, pos0=0, n_cap=8):
+    return vb.lib().vecinfer_encode_values(C.byref(cfg.c()), v, cb, idx, B, T, pos0, n_cap, None)
+
+
+def test_encode_argument_errors():
+    assert _enc_keys(k=None) == vb.EINVAL
+    assert _enc_keys(lam=None) == vb.EINVAL
+    assert _enc_keys(idx=None) == vb.EINVAL
+    assert _enc_keys(B=0) == vb.EINVAL
+    assert _enc_keys(T=0) == vb.EINVAL
+    assert _enc_keys(pos0=-1) == vb.EINVAL
+    assert _enc_keys(T=6, pos0=3, n_cap=8) == vb.EINVAL          # runs past the cache
+    assert _enc_keys(k=FAKE + 2) == vb.EINVAL                     # misaligned
+    assert _enc_vals(v=None) == vb.EINVAL
+    assert _enc_vals(T=9) == vb.EINVAL
+    for bad in (vb.Config(96, 32, 8, 4, 4), vb.Config(128, 32, 5, 4, 4), vb.Config(128, 32, 8, 3, 4),
+                vb.Config(128, 32, 8, 4, 4, k_bits=12), vb.Config(128, 48, 8, 4, 4),
+                vb.Config(128, 32, 8, 4, 16)):
+        assert _enc_keys(cfg=bad) == vb.EUNSUPPORTED
+        assert _enc_vals(cfg=bad) == vb.EUNSUPPORTED
+
+
+def _decode(cfg=CFG, q=FAKE, lam=FAKE, cbk=FAKE, cbv=FAKE, ki=FAKE, vi=FAKE, sl=None, B=1, N=1024,
+            n_cap=1024, S=4, variant=0, ws=None, ws_bytes=0, out=FAKE, lse=None):
+    return vb.lib().vecinfer_decode_attention(C.byref(cfg.c()), q, lam, cbk, cbv, ki, vi, sl, B, N, n_cap, S,
+                                              variant, ws, ws_bytes, out, lse, None)
+
+
+def test_decode_argument_errors():
+    assert _decode(q=None) == vb.EINVAL
+    assert _decode(out=None) == vb.EINVAL
+    assert _decode(B=0) == vb.EINVAL
+    assert _decode(N=0) == vb.EINVAL
+    assert _decode(N=2048, n_cap=1024) == vb.EINVAL
+    assert _decode(S=-1) == vb.EINVAL
+    assert _decode(S=vb.MAX_SPLITS + 1) == vb.EINVAL
+    assert _decode(variant=7) == vb.EINVAL
+    assert _decode(ki=FAKE + 1) == vb.EINVAL
+    assert _decode(cfg=vb.Config(128, 32, 8, 4, 4, v_bits=4)) == vb.EUNSUPPORTED
+    # valid arguments but no / too small / misaligned workspace: refused before any launch
+    need = vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, 4)
+    assert need > 0
+    assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
+    assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
+    assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
+    # the matrix-core variant only covers D = 128, G = 4
+    assert _decode(cfg=vb.Config(64, 8, 8, 4, 4), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+
+
+def test_workspace_size_and_auto_splits():
+    assert vb.vecinfer_decode_workspace_bytes(vb.Config(96, 32, 8, 4, 4), 1, 1024, 4) == 0
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, vb.MAX_SPLITS + 1) == 0
+    a = vb.vecinfer_decode_workspace_bytes(CFG, 1, 196608, 32)
+    # partial outputs dominate: B * Hq * S * D floats, plus (m, l) and the counters
+    assert a >= 1 * 32 * 32 * 128 * 4 and a % 256 == 0
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 2, 196608, 32) > a
+    s = vb.vecinfer_decode_auto_splits(CFG, 1, 196608)
+    assert 1 <= s <= vb.MAX_SPLITS
+    assert vb.vecinfer_decode_auto_splits(CFG, 32, 8192) >= 1
+    assert vb.vecinfer_decode_auto_splits(CFG, 1, 100) == 1        # short sequences are not split
+    assert vb.vecinfer_decode_auto_splits(CFG, 0, 100) == vb.EINVAL
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 196608, 0) == vb.vecinfer_decode_workspace_bytes(CFG, 1, 196608, s)
+
+
+def test_workspace_init_rejects_bad_buffers():
+    L = vb.lib()
+    assert L.vecinfer_decode_workspace_init(None, 4096, None) == vb.EWORKSPACE
+    assert L.vecinfer_decode_workspace_init(FAKE + 8, 4096, None) == vb.EWORKSPACE
+    assert L.vecinfer_decode_workspace_init(FAKE, 0, None) == vb.EWORKSPACE
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        vb.vecinfer_encode_values(CFG, torch.zeros(1, 8, 4, 128, dtype=torch.float16),
+                                  torch.zeros(8, 32, 256, 4, dtype=torch.float16),
+                                  torch.zeros(1, 8, 8, 32, dtype=torch.uint8))
