@@ -70,48 +70,81 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Split merge (log-sum-exp over the S partials of one (b, g)), executed by the workgroup
-// that arrives last.  Every workgroup calls this after its partials are written.
-// Returns after the output rows of (b, g) are written by the last arrival; other
-// workgroups return immediately.  `flag` is one int of LDS.
+// Log-sum-exp merge of the S partials of one (b, g) into the final output rows (the paper
+// returns L from each tile loop, Alg. 1 step 22, but leaves the merge to the reader):
+//   M = max_s m_s,  w_s = 2^(m_s - M),  o = sum_s w_s o_s / sum_s w_s l_s,  L = (M + log2 sum) ln 2.
+// Called by all BLOCK threads of one workgroup.  Partials are read in batches of independent
+// loads so that the S-long reduction costs a few memory latencies, not S of them.
 template <int BLOCK>
-__device__ __forceinline__ void merge_if_last(const DecodeParams &p, int b, int g, int *flag)
+__device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g)
 {
-    const int tid = threadIdx.x;
-    __threadfence();                       // release: partials visible device-wide
-    __syncthreads();
-    if (tid == 0) {
-        unsigned old = __hip_atomic_fetch_add(&p.counters[b * p.Hkv + g], 1u, __ATOMIC_ACQ_REL,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-        *flag = (old == (unsigned)(p.S - 1));
-    }
-    __syncthreads();
-    if (!*flag) return;
-    __threadfence();                       // acquire: see the other workgroups' partials
-
+    constexpr int kBatch = 16;
     const int GD = p.G * p.D;
     const size_t bg = (size_t)b * p.Hkv + g;
     const float *po = p.part_o + bg * p.S * GD;
     const float *pm = p.part_m + bg * p.S * p.G;
     const float *pl = p.part_l + bg * p.S * p.G;
-    for (int e = tid; e < GD; e += BLOCK) {
+    for (int e = threadIdx.x; e < GD; e += BLOCK) {
         const int hh = e / p.D, c = e - hh * p.D;
-        float mx = -INFINITY;
-        for (int s = 0; s < p.S; ++s) mx = fmaxf(mx, pm[s * p.G + hh]);
-        float den = 0.f, acc = 0.f;
-        if (mx > -INFINITY) {
-            for (int s = 0; s < p.S; ++s) {
-                const float w = exp2f(pm[s * p.G + hh] - mx);
-                den += w * pl[s * p.G + hh];
-                acc += w * po[(size_t)s * GD + e];
+        float mx = -INFINITY, den = 0.f, acc = 0.f;
+        for (int s0 = 0; s0 < p.S; s0 += kBatch) {
+            float vm[kBatch], vl[kBatch], vo[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int s = s0 + i < p.S ? s0 + i : p.S - 1;
+                vm[i] = pm[s * p.G + hh];
+                vl[i] = pl[s * p.G + hh];
+                vo[i] = po[(size_t)s * GD + e];
+            }
+            float bmx = mx;
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i)
+                if (s0 + i < p.S) bmx = fmaxf(bmx, vm[i]);
+            if (bmx > -INFINITY) {
+                const float rescale = exp2f(mx - bmx);        // 0 when nothing was accumulated yet
+                den *= rescale;
+                acc *= rescale;
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i)
+                    if (s0 + i < p.S) {
+                        const float w = exp2f(vm[i] - bmx);
+                        den += w * vl[i];
+                        acc += w * vo[i];
+                    }
+                mx = bmx;
             }
         }
-        const int h = g * p.G + hh;
-        const size_t row = (size_t)b * p.Hq + h;
+        const size_t row = (size_t)b * p.Hq + g * p.G + hh;
         p.out[row * p.D + c] = __float2half(den > 0.f ? acc / den : 0.f);
         if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (mx + log2f(den)) * kLn2 : -INFINITY;
     }
-    if (tid == 0)
+}
+
+// In-launch merge: every workgroup calls this after its partials are written; the one that
+// arrives last at the (b, g) counter merges.  `flag` is one int of LDS.
+template <int BLOCK>
+__device__ __forceinline__ void merge_if_last(const DecodeParams &p, int b, int g, int *flag)
+{
+    const int tid = threadIdx.x;
+    if (p.S > 1) {
+        // The barrier orders every thread's partial stores before thread 0's device-scope
+        // release fence, which is cumulative: one L2 write-back per workgroup instead of one
+        // per wavefront (on this chip a device-scope release writes the XCD's L2 back).
+        __syncthreads();
+        if (tid == 0) {
+            __threadfence();
+            unsigned old = __hip_atomic_fetch_add(&p.counters[b * p.Hkv + g], 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+            *flag = (old == (unsigned)(p.S - 1));
+        }
+        __syncthreads();
+        if (!*flag) return;
+        __threadfence();                   // acquire: see the other workgroups' partials
+    } else {
+        __syncthreads();                   // single split: only this workgroup's own partials
+    }
+    merge_splits<BLOCK>(p, b, g);
+    if (tid == 0 && p.S > 1)
         __hip_atomic_store(&p.counters[b * p.Hkv + g], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -119,7 +152,6 @@ __device__ __forceinline__ void merge_if_last(const DecodeParams &p, int b, int 
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
 bool decode_mfma_supports(const DecodeParams &p);
-int decode_align(const DecodeParams &p, int variant);
 
 struct EncodeParams {
     const __half *x;      // [B, Hkv, T, D]

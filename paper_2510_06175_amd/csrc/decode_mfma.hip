@@ -27,6 +27,13 @@
 
 namespace vecinfer {
 
+#ifdef VECINFER_PHASE_TIMING
+__device__ unsigned long long *g_phase_buf = nullptr;
+#define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define STAMP(i)
+#endif
+
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -88,6 +95,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         return;
     }
 
+    STAMP(0);
     // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise)
     {
         const uint4 *srck = reinterpret_cast<const uint4 *>(p.cb_k + (size_t)g * kCentroids * kD);
@@ -99,6 +107,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             dv[e] = srcv[e];
         }
     }
+    __syncthreads(); STAMP(1);
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies)
     for (int e = tid; e < kG * kD; e += BLOCK) {
         const int hh = e >> 7, c = e & 127;
@@ -135,6 +144,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             }
     }
 
+    STAMP(2);
     // ---- per-lane constants
     const int t0 = col & 3;                              // channel-in-sub-vector this A row serves
     unsigned mask_a, mask_b;                             // select the fp16 slot(s) of (p, p)
@@ -164,84 +174,171 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #pragma unroll
     for (int r = 0; r < NROUND_V; ++r) acc_o[r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (long long tb = n0 + (long long)wave * kTile; tb < n1; tb += (long long)NW * kTile) {
-        // ---- codes of this tile
+    // Codes of one 64-token tile as this lane needs them: kc = the key-code bytes of the lane's
+    // A row in each sub-tile, vc = the value-code bytes of the 4 tokens of its k-group.
+    struct Codes {
         unsigned kc[4][KW];
         unsigned vc[4][4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            long long tk = tb + 16 * st + krow_tok;
-            tk = tk > last ? last : tk;
-            const unsigned char *src = krow + (size_t)tk * M + kg * (M / 4);
-            if (DSUB == 4) {
-                const uint2 w = *reinterpret_cast<const uint2 *>(src);
-                kc[st][0] = w.x;
-                kc[st][1] = w.y;
-            } else {
-                const uint4 w = *reinterpret_cast<const uint4 *>(src);
-                kc[st][0] = w.x; kc[st][1] = w.y; kc[st][KW - 2] = w.z; kc[st][KW - 1] = w.w;
-            }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                long long tv = tb + 16 * st + 4 * v + kg;
-                tv = tv > last ? last : tv;
-                const unsigned char *vs = vrow + (size_t)tv * M + col * NROUND_V;
-                if (DSUB == 4)
-                    vc[st][v] = *reinterpret_cast<const unsigned short *>(vs);
-                else
-                    vc[st][v] = *reinterpret_cast<const unsigned *>(vs);
-            }
-        }
+    };
+    // 32-bit byte offsets into the (b, g) code rows (the host checks n_cap * M < 2^31)
+    const unsigned koff_lane = (unsigned)(krow_tok * M + kg * (M / 4));
+    const unsigned voff_lane = (unsigned)(kg * M + col * NROUND_V);
+    const unsigned last_off = (unsigned)last * M;
 
-        // ---- scores: 4 sub-tiles x 4 rounds x (hi, lo)
-        floatx4 sacc[4];
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
+    auto load_codes = [&](Codes &cd, long long tb) {
+        if (tb + kTile <= n1) {                 // whole tile in range (uniform over the wavefront)
+            const unsigned base = (unsigned)tb * M;
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                half8 a;
+                const unsigned char *src = krow + (base + koff_lane + 16 * st * M);
                 if (DSUB == 4) {
-                    // sub-spaces 8kg + 2r, 8kg + 2r + 1: code bytes 2r, 2r+1 of the lane's 8
-                    const unsigned w = kc[st][r >> 1];
-                    const unsigned c0 = (w >> (16 * (r & 1))) & 255u;
-                    const unsigned c1 = (w >> (16 * (r & 1) + 8)) & 255u;
-                    const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r) * SUBSPACE_BYTES + c0 * ENTRY);
-                    const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r + 1) * SUBSPACE_BYTES + c1 * ENTRY);
-                    a = as_half8(x0.x, x0.y, x1.x, x1.y);
+                    const uint2 w = *reinterpret_cast<const uint2 *>(src);
+                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y;
                 } else {
-                    // sub-spaces 16kg + 4r .. +3: the 4 code bytes of dword r
-                    const unsigned w = kc[st][r];
-                    unsigned x[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const unsigned c = (w >> (8 * q)) & 255u;
-                        x[q] = *reinterpret_cast<const unsigned *>(smem + lds_k + (4 * r + q) * SUBSPACE_BYTES + c * ENTRY);
-                    }
-                    a = as_half8(x[0], x[1], x[2], x[3]);
+                    const uint4 w = *reinterpret_cast<const uint4 *>(src);
+                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y; cd.kc[st][KW - 2] = w.z; cd.kc[st][KW - 1] = w.w;
                 }
-                sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq_hi[r], sacc[st], 0, 0, 0);
-                sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq_lo[r], sacc[st], 0, 0, 0);
-            }
-
-        // ---- online softmax of this wavefront (Alg. 1 steps 12-13)
-        float tmax = -INFINITY;
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
+                for (int v = 0; v < 4; ++v) {
+                    const unsigned char *vs = vrow + (base + voff_lane + (16 * st + 4 * v) * M);
+                    if (DSUB == 4)
+                        cd.vc[st][v] = *reinterpret_cast<const unsigned short *>(vs);
+                    else
+                        cd.vc[st][v] = *reinterpret_cast<const unsigned *>(vs);
+                }
+            }
+        } else {                                // tail (or past the end): clamp to the last token
+            const long long tbc = tb > last ? last : tb;
+            const unsigned base = (unsigned)tbc * M;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                unsigned ko = base + (16 * st + krow_tok) * M;
+                ko = (ko > last_off ? last_off : ko) + kg * (M / 4);
+                const unsigned char *src = krow + ko;
+                if (DSUB == 4) {
+                    const uint2 w = *reinterpret_cast<const uint2 *>(src);
+                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y;
+                } else {
+                    const uint4 w = *reinterpret_cast<const uint4 *>(src);
+                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y; cd.kc[st][KW - 2] = w.z; cd.kc[st][KW - 1] = w.w;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    unsigned vo = base + (16 * st + 4 * v + kg) * M;
+                    vo = (vo > last_off ? last_off : vo) + col * NROUND_V;
+                    const unsigned char *vs = vrow + vo;
+                    if (DSUB == 4)
+                        cd.vc[st][v] = *reinterpret_cast<const unsigned short *>(vs);
+                    else
+                        cd.vc[st][v] = *reinterpret_cast<const unsigned *>(vs);
+                }
+            }
+        }
+    };
+
+    // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
+    // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic).
+    auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
+        if (DSUB == 4) {
+            // sub-spaces 8kg + 2r, 8kg + 2r + 1: code bytes 2r, 2r+1 of the lane's 8
+            const unsigned w = cd.kc[st][r >> 1];
+            const unsigned c0 = (w >> (16 * (r & 1))) & 255u;
+            const unsigned c1 = (w >> (16 * (r & 1) + 8)) & 255u;
+            const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r) * SUBSPACE_BYTES + c0 * ENTRY);
+            const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r + 1) * SUBSPACE_BYTES + c1 * ENTRY);
+            return as_half8(x0.x, x0.y, x1.x, x1.y);
+        } else {
+            // sub-spaces 16kg + 4r .. +3: the 4 code bytes of dword r
+            const unsigned w = cd.kc[st][r];
+            unsigned x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned c = (w >> (8 * q)) & 255u;
+                x[q] = *reinterpret_cast<const unsigned *>(smem + lds_k + (4 * r + q) * SUBSPACE_BYTES + c * ENTRY);
+            }
+            return as_half8(x[0], x[1], x[2], x[3]);
+        }
+    };
+    // B operand q (0..3) of the P.V MFMAs of sub-tile st.  d = 4: q = 2u + r (step u, round r):
+    // centroids of sub-space 2 col + r for tokens 2u, 2u+1 of the k-group.  d = 2: q = r:
+    // centroids of sub-space 4 col + r for the 4 tokens of the k-group.
+    auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
+        if (DSUB == 4) {
+            const int u = q >> 1, r = q & 1;
+            const unsigned c0 = (cd.vc[st][2 * u] >> (8 * r)) & 255u;
+            const unsigned c1 = (cd.vc[st][2 * u + 1] >> (8 * r)) & 255u;
+            const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c0 * ENTRY);
+            const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c1 * ENTRY);
+            return as_half8(x0.x, x0.y, x1.x, x1.y);
+        } else {
+            unsigned x[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const long long tok = tb + 16 * st + 4 * v + kg;
-                if (tok > last) sacc[st][v] = -INFINITY;
-                tmax = fmaxf(tmax, sacc[st][v]);
+                const unsigned c = (cd.vc[st][v] >> (8 * q)) & 255u;
+                x[v] = *reinterpret_cast<const unsigned *>(smem + lds_v + q * SUBSPACE_BYTES + c * ENTRY);
             }
+            return as_half8(x[0], x[1], x[2], x[3]);
+        }
+    };
+
+    half8 ka[8];                     // score operands of rounds 0-1 of the tile about to be processed
+    // One tile.  LDS gathers are issued one stage ahead of the MFMAs that consume them, in the
+    // order: [rounds 2-3 of K] MFMA(K 0-1) [V of sub-tiles 0-1] MFMA(K 2-3) softmax
+    // [V of sub-tiles 2-3] MFMA(V 0-1) [rounds 0-1 of K of the NEXT tile] MFMA(V 2-3).
+    auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
+        half8 kb[8], va[8], vb[8];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            kb[2 * st] = gather_k(cd, st, 2);
+            kb[2 * st + 1] = gather_k(cd, st, 3);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        floatx4 sacc[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st], bq_hi[0], floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        }
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st], bq_lo[0], sacc[st], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st + 1], bq_hi[1], sacc[st], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st + 1], bq_lo[1], sacc[st], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            va[q] = gather_v(cd, 0, q);
+            va[4 + q] = gather_v(cd, 1, q);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st], bq_hi[2], sacc[st], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st], bq_lo[2], sacc[st], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st + 1], bq_hi[3], sacc[st], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st + 1], bq_lo[3], sacc[st], 0, 0, 0);
+
+        // ---- online softmax of this wavefront (Alg. 1 steps 12-13)
+        if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (tb + 16 * st + 4 * v + kg > last) sacc[st][v] = -INFINITY;
+        }
+        float tmax = fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3]));
+#pragma unroll
+        for (int st = 1; st < 4; ++st)
+            tmax = fmaxf(tmax, fmaxf(fmaxf(sacc[st][0], sacc[st][1]), fmaxf(sacc[st][2], sacc[st][3])));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float m_new = fmaxf(m_run, tmax);
         if (__any(m_new > m_run)) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
             l_part *= alpha;
-            const float alpha_o = __shfl(alpha, 4 * kg);                 // head kg's factor (lane 4kg serves head kg)
+            const float alpha_o = __shfl(alpha, 4 * kg);                 // lane 4kg serves head kg
 #pragma unroll
             for (int r = 0; r < NROUND_V; ++r) acc_o[r] *= alpha_o;
             m_run = m_new;
@@ -255,40 +352,68 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 l_part += pr;
                 pp[st][v] = pack_dup_f16(pr);
             }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            vb[q] = gather_v(cd, 2, q);
+            vb[4 + q] = gather_v(cd, 3, q);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- o += P . VQ^-1(V_q)  (step 16)
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
+        auto pv = [&](int st, const half8 *vops) {
             if (DSUB == 4) {
 #pragma unroll
-                for (int u = 0; u < PV_STEPS; ++u) {
+                for (int u = 0; u < 2; ++u) {
                     const half8 a = as_half8(pp[st][2 * u] & mask_a, pp[st][2 * u] & mask_b,
                                              pp[st][2 * u + 1] & mask_a, pp[st][2 * u + 1] & mask_b);
 #pragma unroll
-                    for (int r = 0; r < NROUND_V; ++r) {
-                        const unsigned c0 = (vc[st][2 * u] >> (8 * r)) & 255u;
-                        const unsigned c1 = (vc[st][2 * u + 1] >> (8 * r)) & 255u;
-                        const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c0 * ENTRY);
-                        const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c1 * ENTRY);
-                        acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, as_half8(x0.x, x0.y, x1.x, x1.y), acc_o[r], 0, 0, 0);
-                    }
+                    for (int r = 0; r < 2; ++r)
+                        acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, vops[2 * u + r], acc_o[r], 0, 0, 0);
                 }
             } else {
                 const half8 a = as_half8(pp[st][0] & mask_a, pp[st][1] & mask_a, pp[st][2] & mask_a, pp[st][3] & mask_a);
 #pragma unroll
-                for (int r = 0; r < NROUND_V; ++r) {
-                    unsigned x[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const unsigned c = (vc[st][v] >> (8 * r)) & 255u;
-                        x[v] = *reinterpret_cast<const unsigned *>(smem + lds_v + r * SUBSPACE_BYTES + c * ENTRY);
-                    }
-                    acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, as_half8(x[0], x[1], x[2], x[3]), acc_o[r], 0, 0, 0);
-                }
+                for (int r = 0; r < NROUND_V; ++r)
+                    acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, vops[r], acc_o[r], 0, 0, 0);
             }
+        };
+        pv(0, va);
+        pv(1, va + 4);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {          // first half of the next tile's score operands
+            ka[2 * st] = gather_k(next, st, 0);
+            ka[2 * st + 1] = gather_k(next, st, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        pv(2, vb);
+        pv(3, vb + 4);
+    };
+
+    // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
+    // its last gather has been issued.  Loads past the end of the split are clamped to its last
+    // token, so the refill and the look-ahead gathers need no bounds branch.
+    {
+        const long long stride = (long long)NW * kTile;
+        long long tb = n0 + (long long)wave * kTile;
+        Codes ca, cb;
+        load_codes(ca, tb);
+        load_codes(cb, tb + stride);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            ka[2 * st] = gather_k(ca, st, 0);
+            ka[2 * st + 1] = gather_k(ca, st, 1);
+        }
+        for (; tb < n1; tb += 2 * stride) {
+            process_tile(ca, cb, tb, tb + 2 * stride);
+            if (tb + stride < n1) process_tile(cb, ca, tb + stride, tb + 3 * stride);
         }
     }
 
+    STAMP(3);
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
     float l_head = l_part + __shfl_xor(l_part, 16);
     l_head += __shfl_xor(l_head, 32);
@@ -329,7 +454,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             p.part_l[pi + hh] = l;
         }
     }
+    STAMP(4);
     merge_if_last<BLOCK>(p, b, g, sm_flag);
+    STAMP(5);
 }
 
 constexpr int kWaves = 8;
@@ -352,9 +479,15 @@ int launch_typed(const DecodeParams &p, hipStream_t stream)
 
 } // namespace
 
+#ifdef VECINFER_PHASE_TIMING
+extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol(HIP_SYMBOL(g_phase_buf), &buf, sizeof(buf)) == hipSuccess ? 0 : -4; }
+#endif
+
 bool decode_mfma_supports(const DecodeParams &p)
 {
-    return p.D == kD && p.G == kG && p.dk == p.dv && (p.dk == 4 || p.dk == 2);
+    // code rows are addressed with 32-bit byte offsets
+    return p.D == kD && p.G == kG && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
+           p.N * (long long)(kD / p.dk) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
