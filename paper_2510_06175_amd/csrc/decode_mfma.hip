@@ -33,21 +33,82 @@ __device__ unsigned long long *g_phase_buf = nullptr;
 #else
 #define STAMP(i)
 #endif
+#ifdef VECINFER_SECTION_TIMING
+#define SECT(i) do { long long _t = clock64(); sect[i] += _t - sect_t; sect_t = _t; } while (0)
+#else
+#define SECT(i)
+#endif
 
 namespace {
 
+#ifdef EXP_NO_MFMA
+#define MFMA16(a, b, c, x, y, z) exp_keep(a, b, c)
+#else
+#define MFMA16(a, b, c, x, y, z) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z)
+#endif
+
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;
 constexpr int kG = 4;
 constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
 
+#ifdef EXP_NO_MFMA
+__device__ __forceinline__ floatx4 exp_keep(half8 a, half8 b, floatx4 c)
+{
+    asm volatile("" ::"v"(a), "v"(b));
+    return c;
+}
+#endif
+
+// loads from an absolute LDS byte address
+__device__ __forceinline__ uint2 lds_load_b64(unsigned addr)
+{
+    typedef uintx2 __attribute__((address_space(3))) *lds_ptr;
+    const uintx2 v = *(lds_ptr)(addr);
+    return make_uint2(v[0], v[1]);
+}
+__device__ __forceinline__ unsigned lds_load_b32(unsigned addr)
+{
+    typedef unsigned __attribute__((address_space(3))) *lds_ptr;
+    return *(lds_ptr)(addr);
+}
+
 __device__ __forceinline__ half8 as_half8(unsigned a, unsigned b, unsigned c, unsigned d)
 {
     uintx4 u = {a, b, c, d};
     return __builtin_bit_cast(half8, u);
+}
+
+// value of quad lane L (0..3) broadcast to the whole quad (DPP quad_perm:[L,L,L,L])
+template <int L>
+__device__ __forceinline__ unsigned quad_bcast(unsigned x)
+{
+    return (unsigned)__builtin_amdgcn_mov_dpp((int)x, L * 0x55, 0xf, 0xf, true);
+}
+
+// value of the lane whose index within the quad differs by XOR (1 or 2)
+template <int XOR>
+__device__ __forceinline__ float quad_xor(float x)
+{
+    constexpr int ctrl = XOR == 1 ? 0xB1 : 0x4E;     // quad_perm:[1,0,3,2] / [2,3,0,1]
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), ctrl, 0xf, 0xf, true));
+}
+
+// max over the four 16-lane rows of the wavefront, on the vector ALU (v_permlane16_swap /
+// v_permlane32_swap exchange rows between two copies of the value; no LDS round trip)
+__device__ __forceinline__ float rows_max(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    float m = fmaxf(__builtin_bit_cast(float, (unsigned)s16[0]), __builtin_bit_cast(float, (unsigned)s16[1]));
+    const unsigned w = __builtin_bit_cast(unsigned, m);
+    auto s32 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)s32[0]), __builtin_bit_cast(float, (unsigned)s32[1]));
 }
 
 __device__ __forceinline__ unsigned pack_dup_f16(float p)
@@ -58,7 +119,7 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
     return (unsigned)b | ((unsigned)b << 16);
 }
 
-template <int DSUB, int NW>
+template <int DSUB, int NW, bool SPLITQ>
 __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int BLOCK = NW * 64;
@@ -68,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     constexpr int SUBSPACE_BYTES = kCentroids * ENTRY; // 2048 or 1024
     constexpr int KW = M / 16;                         // key-code dwords per lane per sub-tile: 2 or 4
     constexpr int NROUND_V = M / 16;                   // value MFMA rounds per P.V step: 2 or 4
-    constexpr int PV_STEPS = DSUB / 2;                 // P.V steps per sub-tile: 2 (d=4) or 1 (d=2)
+    constexpr int VW = DSUB == 4 ? 2 : 4;              // value-code registers per lane per sub-tile
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *const sm_k = smem;
@@ -140,7 +201,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 const float x = sm_qt[hh * kD + 32 * kg + 8 * r + e] * fold;
                 const _Float16 hi = (_Float16)x;
                 bq_hi[r][e] = hi;
-                bq_lo[r][e] = (_Float16)(x - (float)hi);
+                bq_lo[r][e] = SPLITQ ? (_Float16)(x - (float)hi) : (_Float16)0.f;
             }
     }
 
@@ -157,8 +218,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     }
     // LDS byte offsets: keys  sub-space (8/d)*(8kg.. ) i.e. M/4 sub-spaces per kg
     //                   values sub-space NROUND_V*col + r
-    const unsigned lds_k = (unsigned)(kg * (M / 4) * SUBSPACE_BYTES);
-    const unsigned lds_v = (unsigned)(CB_BYTES + col * NROUND_V * SUBSPACE_BYTES);
+    const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
+    const unsigned lds_k = lds_base + (unsigned)(kg * (M / 4) * SUBSPACE_BYTES);
+    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * NROUND_V * SUBSPACE_BYTES);
 
     const uint8_t *krow = p.k_idx + bg * p.n_cap * M;
     const uint8_t *vrow = p.v_idx + bg * p.n_cap * M;
@@ -178,84 +240,82 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // A row in each sub-tile, vc = the value-code bytes of the 4 tokens of its k-group.
     struct Codes {
         unsigned kc[4][KW];
-        unsigned vc[4][4];
+        unsigned vc[4][VW];
     };
-    // 32-bit byte offsets into the (b, g) code rows (the host checks n_cap * M < 2^31)
+    // The code rows of (b, g) are read through buffer descriptors whose extent ends at the
+    // split's last token: a lane's address is one loop-invariant VGPR offset plus the tile's
+    // base plus an instruction immediate, and loads past the end of the split return 0 (a
+    // valid code) instead of needing a clamp.  The host checks N * M < 2^31.
+    const __amdgpu_buffer_rsrc_t rsrc_k =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(krow), 0, (int)((unsigned)n1 * M), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_v =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(vrow), 0, (int)((unsigned)n1 * M), 0x00020000);
     const unsigned koff_lane = (unsigned)(krow_tok * M + kg * (M / 4));
     const unsigned voff_lane = (unsigned)(kg * M + col * NROUND_V);
-    const unsigned last_off = (unsigned)last * M;
 
     auto load_codes = [&](Codes &cd, long long tb) {
-        if (tb + kTile <= n1) {                 // whole tile in range (uniform over the wavefront)
-            const unsigned base = (unsigned)tb * M;
+#ifdef EXP_SAME_TILE
+        tb = n0 + (long long)wave * kTile;
+#endif
+        const unsigned base = (unsigned)tb * M;
+        const unsigned ko = base + koff_lane, vo = base + voff_lane;
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const unsigned char *src = krow + (base + koff_lane + 16 * st * M);
-                if (DSUB == 4) {
-                    const uint2 w = *reinterpret_cast<const uint2 *>(src);
-                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y;
-                } else {
-                    const uint4 w = *reinterpret_cast<const uint4 *>(src);
-                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y; cd.kc[st][KW - 2] = w.z; cd.kc[st][KW - 1] = w.w;
-                }
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const unsigned char *vs = vrow + (base + voff_lane + (16 * st + 4 * v) * M);
-                    if (DSUB == 4)
-                        cd.vc[st][v] = *reinterpret_cast<const unsigned short *>(vs);
-                    else
-                        cd.vc[st][v] = *reinterpret_cast<const unsigned *>(vs);
-                }
+        for (int st = 0; st < 4; ++st) {
+            if (DSUB == 4) {
+                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * M, 0, 0);
+                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1];
+            } else {
+                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * M, 0, 0);
+                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][KW - 2] = w[2]; cd.kc[st][KW - 1] = w[3];
             }
-        } else {                                // tail (or past the end): clamp to the last token
-            const long long tbc = tb > last ? last : tb;
-            const unsigned base = (unsigned)tbc * M;
+#ifdef EXP_V_WIDE
+            if (DSUB == 4) {
+                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_v, ko + 16 * st * M, 0, 0);
+                cd.vc[st][0] = w[0]; cd.vc[st][1] = w[1];
+            } else
+#endif
+            if (DSUB == 4) {
+                // two bytes (sub-spaces 2 col, 2 col + 1) per token; tokens 2u, 2u+1 share a register
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                unsigned ko = base + (16 * st + krow_tok) * M;
-                ko = (ko > last_off ? last_off : ko) + kg * (M / 4);
-                const unsigned char *src = krow + ko;
-                if (DSUB == 4) {
-                    const uint2 w = *reinterpret_cast<const uint2 *>(src);
-                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y;
-                } else {
-                    const uint4 w = *reinterpret_cast<const uint4 *>(src);
-                    cd.kc[st][0] = w.x; cd.kc[st][1] = w.y; cd.kc[st][KW - 2] = w.z; cd.kc[st][KW - 1] = w.w;
+                for (int u = 0; u < 2; ++u) {
+                    ushortx2 t;
+                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * M, 0, 0);
+                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * M, 0, 0);
+                    cd.vc[st][u] = __builtin_bit_cast(unsigned, t);
                 }
+            } else {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    unsigned vo = base + (16 * st + 4 * v + kg) * M;
-                    vo = (vo > last_off ? last_off : vo) + col * NROUND_V;
-                    const unsigned char *vs = vrow + vo;
-                    if (DSUB == 4)
-                        cd.vc[st][v] = *reinterpret_cast<const unsigned short *>(vs);
-                    else
-                        cd.vc[st][v] = *reinterpret_cast<const unsigned *>(vs);
-                }
+                for (int v = 0; v < 4; ++v)
+                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * M, 0, 0);
             }
         }
     };
 
+    // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
+    // one v_dot4_u32_u8 (w . (ENTRY << 8k) + base) instead of a bit-field extract and a shift-add.
+    auto lds_addr = [&](unsigned w, int k, unsigned base) -> unsigned {
+        return __builtin_amdgcn_udot4(w, (unsigned)ENTRY << (8 * k), base, false);
+    };
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
-    // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic).
+    // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
+#ifdef EXP_NO_KGATHER
+        return as_half8(cd.kc[st][0], cd.kc[st][1], cd.kc[st][0] + r, cd.kc[st][1]);
+#endif
         if (DSUB == 4) {
             // sub-spaces 8kg + 2r, 8kg + 2r + 1: code bytes 2r, 2r+1 of the lane's 8
             const unsigned w = cd.kc[st][r >> 1];
-            const unsigned c0 = (w >> (16 * (r & 1))) & 255u;
-            const unsigned c1 = (w >> (16 * (r & 1) + 8)) & 255u;
-            const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r) * SUBSPACE_BYTES + c0 * ENTRY);
-            const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_k + (2 * r + 1) * SUBSPACE_BYTES + c1 * ENTRY);
+            const int k0 = 2 * (r & 1);
+            const uint2 x0 = lds_load_b64(lds_addr(w, k0, lds_k) + (2 * r) * SUBSPACE_BYTES);
+            const uint2 x1 = lds_load_b64(lds_addr(w, k0 + 1, lds_k) + (2 * r + 1) * SUBSPACE_BYTES);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
             // sub-spaces 16kg + 4r .. +3: the 4 code bytes of dword r
             const unsigned w = cd.kc[st][r];
             unsigned x[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned c = (w >> (8 * q)) & 255u;
-                x[q] = *reinterpret_cast<const unsigned *>(smem + lds_k + (4 * r + q) * SUBSPACE_BYTES + c * ENTRY);
-            }
+            for (int q = 0; q < 4; ++q)
+                x[q] = lds_load_b32(lds_addr(w, q, lds_k) + (4 * r + q) * SUBSPACE_BYTES);
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
@@ -263,77 +323,103 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // centroids of sub-space 2 col + r for tokens 2u, 2u+1 of the k-group.  d = 2: q = r:
     // centroids of sub-space 4 col + r for the 4 tokens of the k-group.
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
+#ifdef EXP_NO_VGATHER
+        return as_half8(cd.vc[st][0], cd.vc[st][1], cd.vc[st][0] + q, cd.vc[st][1]);
+#endif
         if (DSUB == 4) {
             const int u = q >> 1, r = q & 1;
-            const unsigned c0 = (cd.vc[st][2 * u] >> (8 * r)) & 255u;
-            const unsigned c1 = (cd.vc[st][2 * u + 1] >> (8 * r)) & 255u;
-            const uint2 x0 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c0 * ENTRY);
-            const uint2 x1 = *reinterpret_cast<const uint2 *>(smem + lds_v + r * SUBSPACE_BYTES + c1 * ENTRY);
+            const unsigned w = cd.vc[st][u];          // bytes: (token 2u: r = 0, 1), (token 2u+1: r = 0, 1)
+            const uint2 x0 = lds_load_b64(lds_addr(w, r, lds_v) + r * SUBSPACE_BYTES);
+            const uint2 x1 = lds_load_b64(lds_addr(w, 2 + r, lds_v) + r * SUBSPACE_BYTES);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
             unsigned x[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const unsigned c = (cd.vc[st][v] >> (8 * q)) & 255u;
-                x[v] = *reinterpret_cast<const unsigned *>(smem + lds_v + q * SUBSPACE_BYTES + c * ENTRY);
-            }
+            for (int v = 0; v < 4; ++v)
+                x[v] = lds_load_b32(lds_addr(cd.vc[st][v], q, lds_v) + q * SUBSPACE_BYTES);
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
 
     half8 ka[8];                     // score operands of rounds 0-1 of the tile about to be processed
-    // One tile.  LDS gathers are issued one stage ahead of the MFMAs that consume them, in the
-    // order: [rounds 2-3 of K] MFMA(K 0-1) [V of sub-tiles 0-1] MFMA(K 2-3) softmax
-    // [V of sub-tiles 2-3] MFMA(V 0-1) [rounds 0-1 of K of the NEXT tile] MFMA(V 2-3).
+    // One tile, as five stages.  In every stage but the softmax the matrix cores work on
+    // operands gathered in the previous stage while the vector ALU forms the addresses of, and
+    // LDS serves, the gathers of the next one; the scheduling hints interleave the three
+    // instruction kinds so that each MFMA's 16 busy cycles are filled:
+    //   1  MFMA K rounds 0-1      | gather K rounds 2-3
+    //   2  MFMA K rounds 2-3      | gather V sub-tiles 0-1
+    //   3  online softmax
+    //   4  MFMA P.V sub-tiles 0-1 | gather V sub-tiles 2-3, refill this tile's code registers
+    //   5  MFMA P.V sub-tiles 2-3 | gather K rounds 0-1 of the NEXT tile
+    constexpr int kReadsPerOperand = DSUB == 4 ? 2 : 4;        // ds_reads (and address ops) per half8
+#define VI_GROUPS8(MF, OPS, XV, VM)                                                        \
+    _Pragma("unroll") for (int gi = 0; gi < 8; ++gi) {                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);                                 \
+        __builtin_amdgcn_sched_group_barrier(0x002, (OPS) * kReadsPerOperand + (XV), 0);    \
+        __builtin_amdgcn_sched_group_barrier(0x100, (OPS) * kReadsPerOperand, 0);           \
+        if ((VM) > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);                   \
+    }
+#ifdef VECINFER_SECTION_TIMING
+    long long sect[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sect_t = clock64();
+#endif
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
+        SECT(0);
         half8 kb[8], va[8], vb[8];
+        const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
+        floatx4 sacc[4];
+
+        // ---- stage 1
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
+            sacc[st] = MFMA16(ka[2 * st], bq_hi[0], kZero4, 0, 0, 0);
+            if (SPLITQ) sacc[st] = MFMA16(ka[2 * st], bq_lo[0], sacc[st], 0, 0, 0);
             kb[2 * st] = gather_k(cd, st, 2);
+        }
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            sacc[st] = MFMA16(ka[2 * st + 1], bq_hi[1], sacc[st], 0, 0, 0);
+            if (SPLITQ) sacc[st] = MFMA16(ka[2 * st + 1], bq_lo[1], sacc[st], 0, 0, 0);
             kb[2 * st + 1] = gather_k(cd, st, 3);
         }
+        VI_GROUPS8(SPLITQ ? 2 : 1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
-        floatx4 sacc[4];
+
+        SECT(1);
+        // ---- stage 2
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st], bq_hi[0], floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            sacc[st] = MFMA16(kb[2 * st], bq_hi[2], sacc[st], 0, 0, 0);
+            if (SPLITQ) sacc[st] = MFMA16(kb[2 * st], bq_lo[2], sacc[st], 0, 0, 0);
+            va[st] = gather_v(cd, 0, st);
         }
 #pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st], bq_lo[0], sacc[st], 0, 0, 0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st + 1], bq_hi[1], sacc[st], 0, 0, 0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[2 * st + 1], bq_lo[1], sacc[st], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            va[q] = gather_v(cd, 0, q);
-            va[4 + q] = gather_v(cd, 1, q);
+        for (int st = 0; st < 4; ++st) {
+            sacc[st] = MFMA16(kb[2 * st + 1], bq_hi[3], sacc[st], 0, 0, 0);
+            if (SPLITQ) sacc[st] = MFMA16(kb[2 * st + 1], bq_lo[3], sacc[st], 0, 0, 0);
+            va[4 + st] = gather_v(cd, 1, st);
         }
+        VI_GROUPS8(SPLITQ ? 2 : 1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st], bq_hi[2], sacc[st], 0, 0, 0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st], bq_lo[2], sacc[st], 0, 0, 0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st + 1], bq_hi[3], sacc[st], 0, 0, 0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) sacc[st] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[2 * st + 1], bq_lo[3], sacc[st], 0, 0, 0);
 
-        // ---- online softmax of this wavefront (Alg. 1 steps 12-13)
+        SECT(2);
+        // ---- stage 3: online softmax of this wavefront (Alg. 1 steps 12-13).
+        // The four lanes of a quad (same head, t0 = 0..3) hold identical copies of all 16 scores
+        // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
+        // exp once; the P.V operand build below fetches them back across the quad with DPP.
+        float sc[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            sc[v] = t0 == 0 ? sacc[0][v] : (t0 == 1 ? sacc[1][v] : (t0 == 2 ? sacc[2][v] : sacc[3][v]));
         if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (tb + 16 * st + 4 * v + kg > last) sacc[st][v] = -INFINITY;
+            for (int v = 0; v < 4; ++v)
+                if (tb + 16 * t0 + 4 * v + kg > last) sc[v] = -INFINITY;
         }
-        float tmax = fmaxf(fmaxf(sacc[0][0], sacc[0][1]), fmaxf(sacc[0][2], sacc[0][3]));
-#pragma unroll
-        for (int st = 1; st < 4; ++st)
-            tmax = fmaxf(tmax, fmaxf(fmaxf(sacc[st][0], sacc[st][1]), fmaxf(sacc[st][2], sacc[st][3])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        tmax = fmaxf(tmax, quad_xor<1>(tmax));
+        tmax = fmaxf(tmax, quad_xor<2>(tmax));
+        tmax = rows_max(tmax);
         const float m_new = fmaxf(m_run, tmax);
         if (__any(m_new > m_run)) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
@@ -343,55 +429,68 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             for (int r = 0; r < NROUND_V; ++r) acc_o[r] *= alpha_o;
             m_run = m_new;
         }
-        unsigned pp[4][4];
+        unsigned pp[4];                          // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float pr = __builtin_amdgcn_exp2f(sacc[st][v] - m_run);
-                l_part += pr;
-                pp[st][v] = pack_dup_f16(pr);
-            }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            vb[q] = gather_v(cd, 2, q);
-            vb[4 + q] = gather_v(cd, 3, q);
+        for (int v = 0; v < 4; ++v) {
+            const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run);
+            l_part += pr;
+            pp[v] = pack_dup_f16(pr);
         }
+
+        // ---- o += P . VQ^-1(V_q)  (step 16)
+        auto pv = [&](auto st_c, const half8 *vops) {
+            constexpr int st = decltype(st_c)::value;
+            // p of sub-tile st lives in quad lane st
+            const unsigned p0 = quad_bcast<st>(pp[0]), p1 = quad_bcast<st>(pp[1]);
+            const unsigned p2 = quad_bcast<st>(pp[2]), p3 = quad_bcast<st>(pp[3]);
+            if (DSUB == 4) {
+                const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
+                const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
+#pragma unroll
+                for (int r = 0; r < 2; ++r) acc_o[r] = MFMA16(a0, vops[r], acc_o[r], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 2; ++r) acc_o[r] = MFMA16(a1, vops[2 + r], acc_o[r], 0, 0, 0);
+            } else {
+                const half8 a = as_half8(p0 & mask_a, p1 & mask_a, p2 & mask_a, p3 & mask_a);
+#pragma unroll
+                for (int r = 0; r < NROUND_V; ++r)
+                    acc_o[r] = MFMA16(a, vops[r], acc_o[r], 0, 0, 0);
+            }
+        };
+        SECT(3);
+        // ---- stage 4
         __builtin_amdgcn_sched_barrier(0);
+        pv(std::integral_constant<int, 0>{}, va);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) vb[q] = gather_v(cd, 2, q);
+        pv(std::integral_constant<int, 1>{}, va + 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) vb[4 + q] = gather_v(cd, 3, q);
+        VI_GROUPS8(1, 1, 3, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        SECT(4);
         load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- o += P . VQ^-1(V_q)  (step 16)
-        auto pv = [&](int st, const half8 *vops) {
-            if (DSUB == 4) {
+        SECT(5);
+        // ---- stage 5
+        pv(std::integral_constant<int, 2>{}, vb);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const half8 a = as_half8(pp[st][2 * u] & mask_a, pp[st][2 * u] & mask_b,
-                                             pp[st][2 * u + 1] & mask_a, pp[st][2 * u + 1] & mask_b);
-#pragma unroll
-                    for (int r = 0; r < 2; ++r)
-                        acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, vops[2 * u + r], acc_o[r], 0, 0, 0);
-                }
-            } else {
-                const half8 a = as_half8(pp[st][0] & mask_a, pp[st][1] & mask_a, pp[st][2] & mask_a, pp[st][3] & mask_a);
-#pragma unroll
-                for (int r = 0; r < NROUND_V; ++r)
-                    acc_o[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, vops[r], acc_o[r], 0, 0, 0);
-            }
-        };
-        pv(0, va);
-        pv(1, va + 4);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {          // first half of the next tile's score operands
+        for (int st = 0; st < 2; ++st) {
             ka[2 * st] = gather_k(next, st, 0);
             ka[2 * st + 1] = gather_k(next, st, 1);
         }
+        pv(std::integral_constant<int, 3>{}, vb + 4);
+#pragma unroll
+        for (int st = 2; st < 4; ++st) {
+            ka[2 * st] = gather_k(next, st, 0);
+            ka[2 * st + 1] = gather_k(next, st, 1);
+        }
+        VI_GROUPS8(1, 1, 3, 0)
         __builtin_amdgcn_sched_barrier(0);
-        pv(2, vb);
-        pv(3, vb + 4);
+        SECT(6);
     };
+#undef VI_GROUPS8
 
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
     // its last gather has been issued.  Loads past the end of the split are clamped to its last
@@ -413,9 +512,15 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     }
 
+#ifdef VECINFER_SECTION_TIMING
+    if (g_phase_buf && lane == 0 && wave == 0)
+        for (int i = 0; i < 8; ++i) g_phase_buf[4096 * 8 + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + i] = sect[i];
+#endif
     STAMP(3);
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
-    float l_head = l_part + __shfl_xor(l_part, 16);
+    float l_head = l_part + quad_xor<1>(l_part);
+    l_head += quad_xor<2>(l_head);
+    l_head += __shfl_xor(l_head, 16);
     l_head += __shfl_xor(l_head, 32);
     __syncthreads();
     float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][128]
@@ -459,21 +564,19 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMP(5);
 }
 
-constexpr int kWaves = 8;
-
-template <int DSUB>
+template <int DSUB, int NW, bool SPLITQ>
 int launch_typed(const DecodeParams &p, hipStream_t stream)
 {
     constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * kG * kD + 16;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<DSUB, kWaves>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<DSUB, NW, SPLITQ>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return -4;
         configured = true;
     }
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<DSUB, kWaves>), grid, dim3(kWaves * 64), smem, stream, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<DSUB, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -493,7 +596,15 @@ bool decode_mfma_supports(const DecodeParams &p)
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
-    return p.dk == 4 ? launch_typed<4>(p, stream) : launch_typed<2>(p, stream);
+    // tuning knobs for experiments (read once): waves per workgroup and the fp16 hi/lo query split
+    static const int nw = [] { const char *e = getenv("VECINFER_MFMA_WAVES"); return e ? atoi(e) : 8; }();
+    static const int sq = [] { const char *e = getenv("VECINFER_MFMA_SPLITQ"); return e ? atoi(e) : 1; }();
+    if (p.dk == 4) {
+        if (nw == 12) return sq ? launch_typed<4, 12, true>(p, stream) : launch_typed<4, 12, false>(p, stream);
+        return sq ? launch_typed<4, 8, true>(p, stream) : launch_typed<4, 8, false>(p, stream);
+    }
+    if (nw == 12) return sq ? launch_typed<2, 12, true>(p, stream) : launch_typed<2, 12, false>(p, stream);
+    return sq ? launch_typed<2, 8, true>(p, stream) : launch_typed<2, 8, false>(p, stream);
 }
 
 } // namespace vecinfer

@@ -132,9 +132,103 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
     }
 }
 
+// Decode-time append (Eq. 9) and other short inputs: one workgroup per (token, batch, KV head).
+// The token is transformed in LDS with the same butterfly order as the tiled kernel (so both
+// produce bit-identical k~).  Then, 32 sub-spaces at a time: thread c writes the distance of
+// every sub-vector to centroid c into LDS; eight threads per sub-space each scan 32 of its 256
+// distances in increasing centroid order (strict "<": lowest index wins) and combine through
+// 64-bit (distance bits, index) keys -- a non-negative fp32 orders like its bit pattern.
+template <int D, int d, bool kTransform>
+__global__ __launch_bounds__(kCentroids) void encode_token_kernel(EncodeParams p)
+{
+    constexpr int M = D / d;
+    constexpr int MC = M < 32 ? M : 32;        // sub-spaces per pass
+    constexpr int RS = kCentroids + 1;         // padded row stride: scanning threads hit distinct banks
+    __shared__ float x_s[D];
+    __shared__ float dist_s[MC * RS];
+
+    const int tid = threadIdx.x;
+    const long long t = blockIdx.x;
+    const int bg = blockIdx.z;
+    const int g = bg % p.Hkv;
+
+    if (tid < D) {
+        float v = __half2float(p.x[((size_t)bg * p.T + t) * D + tid]);
+        if (kTransform) v = v / p.lam[(size_t)g * D + tid];
+        x_s[tid] = v;
+    }
+    __syncthreads();
+    if (kTransform) {
+        for (int st = 1; st < D; st <<= 1) {
+            float mine = 0.f, other = 0.f;
+            if (tid < D) {
+                mine = x_s[tid];
+                other = x_s[tid ^ st];
+            }
+            __syncthreads();
+            if (tid < D) x_s[tid] = (tid & st) ? (other - mine) : (mine + other);
+            __syncthreads();
+        }
+        const float hs = 1.0f / sqrtf((float)D);
+        if (tid < D) x_s[tid] *= hs;
+        __syncthreads();
+    }
+
+    const __half *cb = p.cb + (size_t)g * M * kCentroids * d + (size_t)tid * d;
+    for (int m0 = 0; m0 < M; m0 += MC) {
+#pragma unroll 8
+        for (int mm = 0; mm < MC; ++mm) {
+            const int m = m0 + mm;
+            float dist = 0.f;
+#pragma unroll
+            for (int j = 0; j < d; ++j) {
+                const float tdiff = x_s[m * d + j] - __half2float(cb[(size_t)m * kCentroids * d + j]);
+                dist = fmaf(tdiff, tdiff, dist);
+            }
+            dist_s[mm * RS + tid] = dist;
+        }
+        __syncthreads();
+        {
+            const int mm = tid >> 3, part = tid & 7;
+            float best = INFINITY;
+            unsigned arg = 0;
+            if (mm < MC) {
+#pragma unroll 8
+                for (int i = 0; i < kCentroids / 8; ++i) {
+                    const unsigned c = part + 8 * i;
+                    const float v = dist_s[mm * RS + c];
+                    if (v < best) {
+                        best = v;
+                        arg = c;
+                    }
+                }
+            }
+            unsigned long long key = ((unsigned long long)__float_as_uint(best) << 32) | arg;
+#pragma unroll
+            for (int o = 4; o > 0; o >>= 1) {
+                const unsigned long long other = __shfl_xor(key, o);
+                key = other < key ? other : key;
+            }
+            if (part == 0 && mm < MC)
+                p.idx[((size_t)bg * p.n_cap + p.pos0 + t) * M + m0 + mm] = (uint8_t)(key & 255u);
+        }
+        __syncthreads();
+    }
+}
+
+constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b, g) the per-token kernel wins
+
 template <int D, int d>
 int launch_typed(const EncodeParams &p, hipStream_t stream)
 {
+    if (p.T <= kTokenKernelMaxT) {
+        dim3 tgrid((unsigned)p.T, 1, p.B * p.Hkv);
+        if (p.lam)
+            hipLaunchKernelGGL((encode_token_kernel<D, d, true>), tgrid, dim3(kCentroids), 0, stream, p);
+        else
+            hipLaunchKernelGGL((encode_token_kernel<D, d, false>), tgrid, dim3(kCentroids), 0, stream, p);
+        return hipGetLastError() == hipSuccess ? 0 : -4;
+    }
     dim3 grid((unsigned)((p.T + kEncTokens - 1) / kEncTokens), D / kChunkCh, p.B * p.Hkv);
     if (p.lam)
         hipLaunchKernelGGL((encode_kernel<D, d, true>), grid, dim3(kEncBlock), 0, stream, p);

@@ -144,6 +144,21 @@ def test_encode_append_at_offset_leaves_other_rows_untouched():
     assert (got_k[:, :, mask] == 0xEE).all() and (got_v[:, :, mask] == 0xEE).all()
 
 
+def test_encode_short_and_tiled_kernels_agree():
+    """Short inputs (decode-time append) take a per-token kernel, long ones a tiled kernel:
+    same butterfly order and distance arithmetic, so identical codes on identical tokens."""
+    shape = synth.Shape(2, 8, 2, 128, 40, 4, 2)
+    e = synth.encode_inputs(shape, seed=41, n_outlier=3)
+    lam = synth.lognormal_lambda(synth.rng(4), 2, 128)
+    long_k, long_v = gpu_encode(shape, k=e["k"], lam=lam, cb_k=e["cb_k"], v=e["v"], cb_v=e["cb_v"])
+    short_k, short_v = gpu_encode(shape, k=e["k"][:, :, :9], lam=lam, cb_k=e["cb_k"], v=e["v"][:, :, :9],
+                                  cb_v=e["cb_v"])
+    np.testing.assert_array_equal(short_k, long_k[:, :, :9])
+    np.testing.assert_array_equal(short_v, long_v[:, :, :9])
+    ref_k, gap = oracle.encode_keys(e["k"][:, :, :9], lam, e["cb_k"], want_gap=True)
+    assert_indices_match(short_k, ref_k, gap, "short keys")
+
+
 def test_encode_planted_codes_and_ties():
     """Rows built from centroids come back as exactly those codes; duplicate centroids resolve
     to the lower index."""
