@@ -16,7 +16,7 @@
  *   - Return value: VECINFER_OK (0) or a negative VECINFER_E* code.  Arguments are
  *     validated on the host before anything is launched; on error nothing was
  *     enqueued.  No exception crosses the boundary.
- *   - Thread-safe; the only state is the caller's workspace (see decode).
+ *   - Thread-safe and stateless; decode needs a caller-provided scratch workspace.
  *
  * Notation (paper): D head dim, d sub-vector dim, M = D / d sub-spaces, 256
  * centroids per sub-space (8-bit codes), H_q query heads, H_kv KV heads,
@@ -111,13 +111,6 @@ size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64
                                        int32_t num_splits);
 
 /*
- * Prepare a freshly allocated workspace (256-byte aligned): zeroes the arrival counters
- * the split merge uses.  Enqueued on `stream`.  Needed once per allocation; every decode
- * call leaves the counters zero again.  After a failed or aborted launch call it again.
- */
-int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
-
-/*
  * One decode step of VQ attention (Eq. 10 via Alg. 1 steps 4-23) for a batch:
  *   q~ = (q * lambda[g]) H_D                                   (Eq. 3, 6, 7)
  *   s_n = q~ . concat_m cb_k[g, m, k_idx[b, g, n, m], :] / sqrt(D)
@@ -125,7 +118,8 @@ int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void
  *   L = log sum_n exp(s_n)                                      (Alg. 1 step 22)
  * computed per (b, q head h), g = h / G, fp32 accumulation, fp16 output.  The sequence
  * is cut into `num_splits` chunks handled by different workgroups; their (o, m, l)
- * partials go through `workspace` and are merged by log-sum-exp in the same launch.
+ * partials go through `workspace` and are merged by log-sum-exp by a second small kernel
+ * enqueued right behind (with one split the attention kernel finalises by itself).
  * The result does not depend on num_splits beyond fp32 rounding.
  *   seq_lens  int32 [B] on the device, or NULL: every sequence has N tokens.  Values are
  *             clamped to [0, N]; a sequence of length 0 yields o = 0 and L = -inf.
@@ -133,8 +127,8 @@ int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void
  *   num_splits 0 = auto, else 1 .. VECINFER_MAX_SPLITS
  *   variant   VECINFER_VARIANT_*
  *   workspace at least vecinfer_decode_workspace_bytes(cfg, B, N, num_splits) bytes,
- *             256-byte aligned, prepared by vecinfer_decode_workspace_init; calls that
- *             share a workspace must be ordered on one stream
+ *             256-byte aligned; contents need no initialisation and are overwritten;
+ *             calls that share a workspace must be ordered on one stream
  *   out_f16   [B, H_q, D] fp16          lse  [B, H_q] fp32 or NULL
  * Errors: EINVAL (null pointers, B < 1, N < 1, N > n_cap, num_splits out of range),
  * EUNSUPPORTED (cfg, or variant that does not cover cfg), EWORKSPACE, ELAUNCH.

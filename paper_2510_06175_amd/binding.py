@@ -22,7 +22,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_decode_auto_splits",
-    "vecinfer_decode_workspace_bytes", "vecinfer_decode_workspace_init",
+    "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_strerror", "vecinfer_version",
 ]
 
@@ -76,8 +76,6 @@ def lib() -> C.CDLL:
         L.vecinfer_decode_auto_splits.restype = i32
         L.vecinfer_decode_workspace_bytes.argtypes = [cfgp, i32, i64, i32]
         L.vecinfer_decode_workspace_bytes.restype = sz
-        L.vecinfer_decode_workspace_init.argtypes = [vp, sz, vp]
-        L.vecinfer_decode_workspace_init.restype = C.c_int
         L.vecinfer_decode_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32,
                                                 i32, vp, sz, vp, vp, vp]
         L.vecinfer_decode_attention.restype = C.c_int
@@ -148,19 +146,12 @@ def vecinfer_decode_workspace_bytes(cfg: Config, B: int, N: int, num_splits: int
     return int(lib().vecinfer_decode_workspace_bytes(C.byref(cfg.c()), B, N, num_splits))
 
 
-def vecinfer_decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
-    _check(lib().vecinfer_decode_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                                _stream(stream)))
-
-
 def new_workspace(cfg: Config, B: int, N: int, num_splits: int = 0, device="cuda") -> torch.Tensor:
-    """Allocate (with torch) and prepare a workspace for vecinfer_decode_attention."""
+    """Allocate (with torch) a workspace for vecinfer_decode_attention."""
     nbytes = vecinfer_decode_workspace_bytes(cfg, B, N, num_splits)
     if nbytes == 0:
         raise VecInferError(EUNSUPPORTED)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-    vecinfer_decode_workspace_init(ws)
-    return ws
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
 def vecinfer_decode_attention(cfg: Config, q_f16, lam, cb_k, cb_v, k_idx, v_idx, workspace, out_f16,

@@ -50,7 +50,7 @@ int32_t auto_splits(const vecinfer_cfg *c, int32_t B, int64_t N)
 }
 
 struct WorkspaceLayout {
-    size_t off_o, off_m, off_l, off_cnt, total;
+    size_t off_o, off_m, off_l, total;
 };
 
 WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
@@ -58,8 +58,7 @@ WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     const size_t rows = (size_t)B * c->num_q_heads * S;     // = B * Hkv * S * G
     WorkspaceLayout w;
-    w.off_cnt = 0;                                           // counters first: init touches only them
-    size_t off = up(sizeof(unsigned) * (size_t)B * c->num_kv_heads);
+    size_t off = 0;
     w.off_o = off;
     off += up(sizeof(float) * rows * c->head_dim);
     w.off_m = off;
@@ -98,10 +97,9 @@ int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, b
     return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
 }
 
-__global__ void zero_counters_kernel(unsigned *c, size_t n)
+__global__ __launch_bounds__(512) void merge_kernel(DecodeParams p)
 {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) c[i] = 0u;
+    merge_splits<512>(p, blockIdx.y, blockIdx.x);
 }
 
 } // namespace
@@ -134,19 +132,6 @@ size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64
     if (!cfg_ok(cfg) || B < 1 || N < 1 || num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return 0;
     const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
     return ws_layout(cfg, B, S).total;
-}
-
-int vecinfer_decode_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
-{
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < 256) return VECINFER_EWORKSPACE;
-    // The counters sit at the start of the workspace; how many are in use depends on the
-    // later call's (B, H_kv), so clear every word up to the first data region that any
-    // layout of this size could have: the whole buffer is cheap enough to clear once.
-    const size_t words = workspace_bytes / sizeof(unsigned);
-    const unsigned blocks = (unsigned)((words + 255) / 256);
-    hipLaunchKernelGGL(zero_counters_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<unsigned *>(workspace), words);
-    return hipGetLastError() == hipSuccess ? VECINFER_OK : VECINFER_ELAUNCH;
 }
 
 int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
@@ -191,7 +176,6 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
     p.n_cap = n_cap;
     p.S = S;
     unsigned char *ws = static_cast<unsigned char *>(workspace);
-    p.counters = reinterpret_cast<unsigned *>(ws + w.off_cnt);
     p.part_o = reinterpret_cast<float *>(ws + w.off_o);
     p.part_m = reinterpret_cast<float *>(ws + w.off_m);
     p.part_l = reinterpret_cast<float *>(ws + w.off_l);
@@ -201,8 +185,12 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
     const bool mfma_ok = decode_mfma_supports(p);
     if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
     const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
-    const int rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
-                            : launch_decode_lut(p, static_cast<hipStream_t>(stream));
+    int rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
+                      : launch_decode_lut(p, static_cast<hipStream_t>(stream));
+    if (rc == 0 && p.S > 1) {          // log-sum-exp merge of the splits (single split: done in-kernel)
+        hipLaunchKernelGGL(merge_kernel, dim3(p.Hkv, p.B), dim3(512), 0, static_cast<hipStream_t>(stream), p);
+        rc = hipGetLastError() == hipSuccess ? 0 : -4;
+    }
     return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
 }
 

@@ -28,7 +28,6 @@ struct DecodeParams {
     float *part_o;           // [B, Hkv, S, G, D]  unnormalised partial outputs
     float *part_m;           // [B, Hkv, S, G]     partial running max (log2 units)
     float *part_l;           // [B, Hkv, S, G]     partial sum of exp2(s2 - m)
-    unsigned *counters;      // [B * Hkv]          arrivals per (b, g); zero between launches
     __half *out;             // [B, Hq, D]
     float *lse;              // [B, Hq] or nullptr
 };
@@ -78,7 +77,7 @@ __device__ __forceinline__ float wave_sum(float v)
 template <int BLOCK>
 __device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g)
 {
-    constexpr int kBatch = 16;
+    constexpr int kBatch = 32;
     const int GD = p.G * p.D;
     const size_t bg = (size_t)b * p.Hkv + g;
     const float *po = p.part_o + bg * p.S * GD;
@@ -120,35 +119,20 @@ __device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g
     }
 }
 
-// In-launch merge: every workgroup calls this after its partials are written; the one that
-// arrives last at the (b, g) counter merges.  `flag` is one int of LDS.
+// End of a decode workgroup.  With a single split the workgroup's own partial is the whole
+// answer and it finalises the output rows itself; with several splits a merge kernel follows
+// in the same stream (a device-scope release inside the kernel would write the whole L2 of the
+// XCD back per workgroup, which costs more than the kernel boundary does).
 template <int BLOCK>
-__device__ __forceinline__ void merge_if_last(const DecodeParams &p, int b, int g, int *flag)
+__device__ __forceinline__ void finish_split(const DecodeParams &p, int b, int g)
 {
-    const int tid = threadIdx.x;
-    if (p.S > 1) {
-        // The barrier orders every thread's partial stores before thread 0's device-scope
-        // release fence, which is cumulative: one L2 write-back per workgroup instead of one
-        // per wavefront (on this chip a device-scope release writes the XCD's L2 back).
-        __syncthreads();
-        if (tid == 0) {
-            __threadfence();
-            unsigned old = __hip_atomic_fetch_add(&p.counters[b * p.Hkv + g], 1u, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-            *flag = (old == (unsigned)(p.S - 1));
-        }
-        __syncthreads();
-        if (!*flag) return;
-        __threadfence();                   // acquire: see the other workgroups' partials
-    } else {
-        __syncthreads();                   // single split: only this workgroup's own partials
-    }
+    if (p.S > 1) return;
+    __syncthreads();                       // this workgroup's partial stores, visible to itself
     merge_splits<BLOCK>(p, b, g);
-    if (tid == 0 && p.S > 1)
-        __hip_atomic_store(&p.counters[b * p.Hkv + g], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // launchers (one translation unit each)
+int launch_merge(const DecodeParams &p, hipStream_t stream);
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
 bool decode_mfma_supports(const DecodeParams &p);

@@ -24,7 +24,6 @@ struct LutSmem {
     float *ptile;   // [kBlock]
     float *red;     // [2 * kBlock / 64]
     float *osum;    // [kBlock]  cross-slice reduction of the output
-    int *flag;
 };
 
 __device__ __forceinline__ LutSmem carve(unsigned char *base, int Mk, int D)
@@ -42,7 +41,6 @@ __device__ __forceinline__ LutSmem carve(unsigned char *base, int Mk, int D)
     base += sizeof(float) * 2 * (kBlock / 64);
     s.osum = reinterpret_cast<float *>(base);
     base += sizeof(float) * kBlock;
-    s.flag = reinterpret_cast<int *>(base);
     return s;
 }
 
@@ -166,7 +164,7 @@ __global__ __launch_bounds__(kBlock) void decode_lut_kernel(DecodeParams p)
             }
         }
     }
-    merge_if_last<kBlock>(p, b, g, sm.flag);
+    finish_split<kBlock>(p, b, g);
 }
 
 } // namespace

@@ -135,7 +135,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     unsigned char *const sm_k = smem;
     unsigned char *const sm_v = smem + CB_BYTES;
     float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][128]
-    int *const sm_flag = reinterpret_cast<int *>(smem + 2 * CB_BYTES + sizeof(float) * kG * kD);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int s = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -152,7 +151,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             p.part_m[(bg * p.S + s) * kG + tid] = -INFINITY;
             p.part_l[(bg * p.S + s) * kG + tid] = 0.f;
         }
-        merge_if_last<BLOCK>(p, b, g, sm_flag);
+        finish_split<BLOCK>(p, b, g);
         return;
     }
 
@@ -560,7 +559,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     }
     STAMP(4);
-    merge_if_last<BLOCK>(p, b, g, sm_flag);
+    finish_split<BLOCK>(p, b, g);
     STAMP(5);
 }
 

@@ -80,7 +80,7 @@ def test_decode_split_count_invariance_and_determinism(vname):
 
 @pytest.mark.parametrize("vname", list(VARIANTS))
 def test_decode_workspace_reuse_across_calls(vname):
-    """The arrival counters return to zero: one workspace serves calls with different splits."""
+    """One workspace (never initialised) serves successive calls with different split counts."""
     shape = synth.Shape(2, 8, 2, 128, 3000, 4, 4)
     variant = VARIANTS[vname]
     x = synth.decode_inputs(shape, seed=10)
