@@ -11,8 +11,9 @@
 //   consecutive sub-spaces of that token.  The B operand holds the transformed query:
 //   column j = 4h + t0 carries q~_h (the same vector for the four t0), so the product's
 //   column j is the score of head h and every lane ends up with the scores it will need as
-//   a P.V operand.  q~ is split into an fp16 high and low part (two MFMAs) so that the
-//   scores are fp32-accurate; 1/sqrt(D) and log2(e) are folded into q~.
+//   a P.V operand.  q~ is split into an fp16 high and low part so that the scores are
+//   fp32-accurate: columns t0 < 2 carry the high part, columns t0 >= 2 the low part, and one
+//   DPP add across the quad recombines them.  1/sqrt(D) and log2(e) are folded into q~.
 //
 //   P.V (Alg. 1 step 16).  Row 4h + t0 of the A operand holds p_h of 8/d tokens, placed
 //   only in the k-slots whose channel-in-sub-vector equals t0; the B operand's column n
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 
     // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8), hi and lo fp16 parts.
     // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq_hi[4], bq_lo[4];
+    half8 bq[4];
     {
         const float fold = kLog2e / (float)kD;
         const int hh = col >> 2;
@@ -199,8 +200,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             for (int e = 0; e < 8; ++e) {
                 const float x = sm_qt[hh * kD + 32 * kg + 8 * r + e] * fold;
                 const _Float16 hi = (_Float16)x;
-                bq_hi[r][e] = hi;
-                bq_lo[r][e] = SPLITQ ? (_Float16)(x - (float)hi) : (_Float16)0.f;
+                const _Float16 lo = (_Float16)(x - (float)hi);
+                bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
             }
     }
 
@@ -215,6 +216,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         mask_a = t0 == 0 ? 0x0000ffffu : (t0 == 1 ? 0xffff0000u : 0u);
         mask_b = 0u;
     }
+    unsigned sel[4];                                     // sel[i] = all ones iff t0 == i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sel[i] = t0 == i ? 0xffffffffu : 0u;
     // LDS byte offsets: keys  sub-space (8/d)*(8kg.. ) i.e. M/4 sub-spaces per kg
     //                   values sub-space NROUND_V*col + r
     const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
@@ -371,34 +375,30 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(ka[2 * st], bq_hi[0], kZero4, 0, 0, 0);
-            if (SPLITQ) sacc[st] = MFMA16(ka[2 * st], bq_lo[0], sacc[st], 0, 0, 0);
+            sacc[st] = MFMA16(ka[2 * st], bq[0], kZero4, 0, 0, 0);
             kb[2 * st] = gather_k(cd, st, 2);
         }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(ka[2 * st + 1], bq_hi[1], sacc[st], 0, 0, 0);
-            if (SPLITQ) sacc[st] = MFMA16(ka[2 * st + 1], bq_lo[1], sacc[st], 0, 0, 0);
+            sacc[st] = MFMA16(ka[2 * st + 1], bq[1], sacc[st], 0, 0, 0);
             kb[2 * st + 1] = gather_k(cd, st, 3);
         }
-        VI_GROUPS8(SPLITQ ? 2 : 1, 1, 0, 0)
+        VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         SECT(1);
         // ---- stage 2
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(kb[2 * st], bq_hi[2], sacc[st], 0, 0, 0);
-            if (SPLITQ) sacc[st] = MFMA16(kb[2 * st], bq_lo[2], sacc[st], 0, 0, 0);
+            sacc[st] = MFMA16(kb[2 * st], bq[2], sacc[st], 0, 0, 0);
             va[st] = gather_v(cd, 0, st);
         }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(kb[2 * st + 1], bq_hi[3], sacc[st], 0, 0, 0);
-            if (SPLITQ) sacc[st] = MFMA16(kb[2 * st + 1], bq_lo[3], sacc[st], 0, 0, 0);
+            sacc[st] = MFMA16(kb[2 * st + 1], bq[3], sacc[st], 0, 0, 0);
             va[4 + st] = gather_v(cd, 1, st);
         }
-        VI_GROUPS8(SPLITQ ? 2 : 1, 1, 0, 0)
+        VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         SECT(2);
@@ -406,10 +406,23 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         // The four lanes of a quad (same head, t0 = 0..3) hold identical copies of all 16 scores
         // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
         // exp once; the P.V operand build below fetches them back across the quad with DPP.
+        if (SPLITQ) {
+            // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
+            // of the quad so that all four lanes hold the full-precision score again
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sacc[st][v] += quad_xor<2>(sacc[st][v]);
+        }
         float sc[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            sc[v] = t0 == 0 ? sacc[0][v] : (t0 == 1 ? sacc[1][v] : (t0 == 2 ? sacc[2][v] : sacc[3][v]));
+        for (int v = 0; v < 4; ++v) {
+            // branch-free per-lane pick of sacc[t0][v] (bit masks: exactly one of sel[] is all ones)
+            const float s0 = sacc[0][v], s1 = sacc[1][v], s2 = sacc[2][v], s3 = sacc[3][v];
+            const unsigned u = (__float_as_uint(s0) & sel[0]) | (__float_as_uint(s1) & sel[1]) |
+                               (__float_as_uint(s2) & sel[2]) | (__float_as_uint(s3) & sel[3]);
+            sc[v] = __uint_as_float(u);
+        }
         if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
 #pragma unroll
             for (int v = 0; v < 4; ++v)
@@ -497,6 +510,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     {
         const long long stride = (long long)NW * kTile;
         long long tb = n0 + (long long)wave * kTile;
+#ifdef EXP_STAGGER
+        for (int i = 0; i < wave; ++i) __builtin_amdgcn_s_sleep(EXP_STAGGER);
+#endif
         Codes ca, cb;
         load_codes(ca, tb);
         load_codes(cb, tb + stride);
@@ -600,6 +616,7 @@ int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
     static const int sq = [] { const char *e = getenv("VECINFER_MFMA_SPLITQ"); return e ? atoi(e) : 1; }();
     if (p.dk == 4) {
         if (nw == 12) return sq ? launch_typed<4, 12, true>(p, stream) : launch_typed<4, 12, false>(p, stream);
+        if (nw == 4) return sq ? launch_typed<4, 4, true>(p, stream) : launch_typed<4, 4, false>(p, stream);
         return sq ? launch_typed<4, 8, true>(p, stream) : launch_typed<4, 8, false>(p, stream);
     }
     if (nw == 12) return sq ? launch_typed<2, 12, true>(p, stream) : launch_typed<2, 12, false>(p, stream);
