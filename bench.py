@@ -4,7 +4,7 @@
 Workload (BASELINE configs[3], the one the metric is quoted on): Llama-3.1-8B layer shape,
 batch 1, 32 query / 8 KV heads, head dim 128, 196608 cached tokens, b2d4 codes for K and V.
 One step = one decode step of one layer: append the new token's key and value codes
-(smooth + FWHT + nearest centroid, T = 1) and run the fused VQ attention over the cache.
+(smooth + FWHT + nearest centroid, T = 1, one launch) and run the fused VQ attention over the cache.
 Steps rotate over several distinct layer caches so that the index stream comes from HBM, not
 from the 256 MB Infinity Cache.  Inputs are seeded and synthetic and are resident in HBM
 before the timed region.
@@ -85,8 +85,8 @@ def main() -> int:
     def step(i):
         if not args.decode_only:
             k_idx, v_idx = caches[i % layers]
-            vb.vecinfer_encode_keys(cfg, new_k, base["lam"], base["cb_k"], k_idx, pos0=shape.N - 1)
-            vb.vecinfer_encode_values(cfg, new_v, base["cb_v"], v_idx, pos0=shape.N - 1)
+            vb.vecinfer_append_kv(cfg, new_k, new_v, base["lam"], base["cb_k"], base["cb_v"], k_idx, v_idx,
+                                  pos0=shape.N - 1)
         attend(i)
 
     # ---- timed region: W warm-up steps, then exactly K steps between events on the launch stream
@@ -120,7 +120,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"llama-3.1-8b layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
                                f"D={shape.D}, N={shape.N}, K d{shape.d_k}b8 / V d{shape.d_v}b8",
-                   "step": "attention only" if args.decode_only else "append 1 token (encode K,V) + fused VQ attention",
+                   "step": "attention only" if args.decode_only else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention",
                    "index_bytes_per_step": idx_bytes, "layer_caches_rotated": layers,
                    "num_splits": splits, "variant": args.variant,
                    "us_per_step": round(ms_per_step * 1e3, 3),

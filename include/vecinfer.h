@@ -43,6 +43,7 @@ extern "C" {
 
 #define VECINFER_VERSION 100          /* major*10000 + minor*100 + patch */
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
+#define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
 
 enum {
     VECINFER_OK = 0,
@@ -95,6 +96,16 @@ int vecinfer_encode_keys(const vecinfer_cfg *cfg, const void *k_f16, const float
 int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const void *cb_v_f16,
                            uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0,
                            int64_t n_cap, void *stream);
+
+/*
+ * Decode-time append of Eq. 9 in one launch: the same result as vecinfer_encode_keys followed
+ * by vecinfer_encode_values on the T new tokens (identical codes), for 1 <= T <= VECINFER_MAX_APPEND.
+ * Arguments and errors as for those two calls; EINVAL if T > VECINFER_MAX_APPEND.
+ */
+int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v_f16,
+                       const float *lambda, const void *cb_k_f16, const void *cb_v_f16,
+                       uint8_t *k_idx, uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0,
+                       int64_t n_cap, void *stream);
 
 /*
  * Number of sequence splits the library would pick for (B, N) when num_splits = 0

@@ -21,7 +21,7 @@ MAX_SPLITS = 256
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = [
-    "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_decode_auto_splits",
+    "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_append_kv", "vecinfer_decode_auto_splits",
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_strerror", "vecinfer_version",
 ]
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         L.vecinfer_encode_keys.restype = C.c_int
         L.vecinfer_encode_values.argtypes = [cfgp, vp, vp, vp, i32, i64, i64, i64, vp]
         L.vecinfer_encode_values.restype = C.c_int
+        L.vecinfer_append_kv.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i64, vp]
+        L.vecinfer_append_kv.restype = C.c_int
         L.vecinfer_decode_auto_splits.argtypes = [cfgp, i32, i64]
         L.vecinfer_decode_auto_splits.restype = i32
         L.vecinfer_decode_workspace_bytes.argtypes = [cfgp, i32, i64, i32]
@@ -135,6 +137,23 @@ def vecinfer_encode_values(cfg: Config, v_f16, cb_v, v_idx, pos0: int = 0, strea
         C.byref(cfg.c()), _dev(v_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "v_f16"),
         _dev(cb_v, torch.float16, (cfg.num_kv_heads, M, 256, cfg.v_sub_dim), "cb_v"),
         _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, M), "v_idx"),
+        B, T, pos0, n_cap, _stream(stream)))
+
+
+def vecinfer_append_kv(cfg: Config, k_f16, v_f16, lam, cb_k, cb_v, k_idx, v_idx, pos0: int, stream=None) -> None:
+    """Decode-time append (Eq. 9): encode T <= 16 new keys and values in one launch."""
+    B, Hkv, T, D = k_f16.shape
+    n_cap = k_idx.shape[2]
+    Mk = cfg.head_dim // cfg.k_sub_dim
+    Mv = cfg.head_dim // cfg.v_sub_dim
+    _check(lib().vecinfer_append_kv(
+        C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
+        _dev(v_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "v_f16"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
+        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
         B, T, pos0, n_cap, _stream(stream)))
 
 

@@ -69,9 +69,9 @@ WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
     return w;
 }
 
-int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, bool keys,
-                  const void *cb, uint8_t *idx, int32_t B, int64_t T, int64_t pos0, int64_t n_cap,
-                  void *stream)
+// Validates one encode request and fills the kernel arguments; VECINFER_OK or an error code.
+int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, bool keys, const void *cb,
+                uint8_t *idx, int32_t B, int64_t T, int64_t pos0, int64_t n_cap, EncodeParams &p)
 {
     if (!cfg || !x || !cb || !idx || (keys && !lambda)) return VECINFER_EINVAL;
     if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
@@ -80,7 +80,6 @@ int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, b
     if ((T + 63) / 64 > 0x7fffffffLL) return VECINFER_EUNSUPPORTED;
     if (!aligned(x, 16) || !aligned(cb, 16) || !aligned(idx, 16) || (keys && !aligned(lambda, 16)))
         return VECINFER_EINVAL;
-    EncodeParams p;
     p.x = static_cast<const __half *>(x);
     p.lam = keys ? lambda : nullptr;
     p.cb = static_cast<const __half *>(cb);
@@ -93,8 +92,19 @@ int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, b
     p.T = T;
     p.pos0 = pos0;
     p.n_cap = n_cap;
-    const int rc = launch_encode(p, static_cast<hipStream_t>(stream));
-    return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
+    return VECINFER_OK;
+}
+
+int launch_status(int rc) { return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH); }
+
+int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, bool keys,
+                  const void *cb, uint8_t *idx, int32_t B, int64_t T, int64_t pos0, int64_t n_cap,
+                  void *stream)
+{
+    EncodeParams p;
+    const int rc = encode_args(cfg, x, lambda, keys, cb, idx, B, T, pos0, n_cap, p);
+    if (rc != VECINFER_OK) return rc;
+    return launch_status(launch_encode(p, static_cast<hipStream_t>(stream)));
 }
 
 __global__ __launch_bounds__(512) void merge_kernel(DecodeParams p)
@@ -118,6 +128,19 @@ int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const voi
                            void *stream)
 {
     return encode_common(cfg, v_f16, nullptr, false, cb_v_f16, v_idx, B, T, pos0, n_cap, stream);
+}
+
+int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v_f16, const float *lambda,
+                       const void *cb_k_f16, const void *cb_v_f16, uint8_t *k_idx, uint8_t *v_idx, int32_t B,
+                       int64_t T, int64_t pos0, int64_t n_cap, void *stream)
+{
+    EncodeParams pk, pv;
+    int rc = encode_args(cfg, k_f16, lambda, true, cb_k_f16, k_idx, B, T, pos0, n_cap, pk);
+    if (rc != VECINFER_OK) return rc;
+    rc = encode_args(cfg, v_f16, nullptr, false, cb_v_f16, v_idx, B, T, pos0, n_cap, pv);
+    if (rc != VECINFER_OK) return rc;
+    if (T > append_max_tokens()) return VECINFER_EINVAL;
+    return launch_status(launch_append(pk, pv, static_cast<hipStream_t>(stream)));
 }
 
 int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t N)

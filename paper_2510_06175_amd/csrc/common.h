@@ -146,5 +146,7 @@ struct EncodeParams {
     long long T, pos0, n_cap;
 };
 int launch_encode(const EncodeParams &p, hipStream_t stream);
+int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream);
+int append_max_tokens();
 
 } // namespace vecinfer

@@ -34,19 +34,10 @@ __device__ unsigned long long *g_phase_buf = nullptr;
 #else
 #define STAMP(i)
 #endif
-#ifdef VECINFER_SECTION_TIMING
-#define SECT(i) do { long long _t = clock64(); sect[i] += _t - sect_t; sect_t = _t; } while (0)
-#else
-#define SECT(i)
-#endif
 
 namespace {
 
-#ifdef EXP_NO_MFMA
-#define MFMA16(a, b, c, x, y, z) exp_keep(a, b, c)
-#else
 #define MFMA16(a, b, c, x, y, z) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z)
-#endif
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
@@ -57,14 +48,6 @@ typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 constexpr int kD = 128;
 constexpr int kG = 4;
 constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
-
-#ifdef EXP_NO_MFMA
-__device__ __forceinline__ floatx4 exp_keep(half8 a, half8 b, floatx4 c)
-{
-    asm volatile("" ::"v"(a), "v"(b));
-    return c;
-}
-#endif
 
 // loads from an absolute LDS byte address
 __device__ __forceinline__ uint2 lds_load_b64(unsigned addr)
@@ -156,56 +139,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         return;
     }
 
-    STAMP(0);
-    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise)
-    {
-        const uint4 *srck = reinterpret_cast<const uint4 *>(p.cb_k + (size_t)g * kCentroids * kD);
-        const uint4 *srcv = reinterpret_cast<const uint4 *>(p.cb_v + (size_t)g * kCentroids * kD);
-        uint4 *dk = reinterpret_cast<uint4 *>(sm_k);
-        uint4 *dv = reinterpret_cast<uint4 *>(sm_v);
-        for (int e = tid; e < CB_BYTES / 16; e += BLOCK) {
-            dk[e] = srck[e];
-            dv[e] = srcv[e];
-        }
-    }
-    __syncthreads(); STAMP(1);
-    // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies)
-    for (int e = tid; e < kG * kD; e += BLOCK) {
-        const int hh = e >> 7, c = e & 127;
-        sm_qt[e] = __half2float(p.q[((size_t)b * p.Hq + g * kG + hh) * kD + c]) * p.lam[(size_t)g * kD + c];
-    }
-    __syncthreads();
-    for (int st = 1; st < kD; st <<= 1) {
-        float nv[(kG * kD + BLOCK - 1) / BLOCK];
-        int it = 0;
-        for (int e = tid; e < kG * kD; e += BLOCK, ++it) {
-            const float mine = sm_qt[e], other = sm_qt[e ^ st];
-            nv[it] = (e & st) ? (other - mine) : (mine + other);
-        }
-        __syncthreads();
-        it = 0;
-        for (int e = tid; e < kG * kD; e += BLOCK, ++it) sm_qt[e] = nv[it];
-        __syncthreads();
-    }
-
-    // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8), hi and lo fp16 parts.
-    // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq[4];
-    {
-        const float fold = kLog2e / (float)kD;
-        const int hh = col >> 2;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float x = sm_qt[hh * kD + 32 * kg + 8 * r + e] * fold;
-                const _Float16 hi = (_Float16)x;
-                const _Float16 lo = (_Float16)(x - (float)hi);
-                bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
-            }
-    }
-
-    STAMP(2);
     // ---- per-lane constants
     const int t0 = col & 3;                              // channel-in-sub-vector this A row serves
     unsigned mask_a, mask_b;                             // select the fp16 slot(s) of (p, p)
@@ -233,12 +166,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // of row group rg is token base + 16 st + 4 v + rg
     const int krow_tok = 4 * (col & 3) + (col >> 2);
 
-    float m_run = -INFINITY;          // running max of head col/4 (log2 units), same in all its lanes
-    float l_part = 0.f;               // this lane's share of the running sum
-    floatx4 acc_o[NROUND_V];
-#pragma unroll
-    for (int r = 0; r < NROUND_V; ++r) acc_o[r] = floatx4{0.f, 0.f, 0.f, 0.f};
-
     // Codes of one 64-token tile as this lane needs them: kc = the key-code bytes of the lane's
     // A row in each sub-tile, vc = the value-code bytes of the 4 tokens of its k-group.
     struct Codes {
@@ -257,9 +184,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     const unsigned voff_lane = (unsigned)(kg * M + col * NROUND_V);
 
     auto load_codes = [&](Codes &cd, long long tb) {
-#ifdef EXP_SAME_TILE
-        tb = n0 + (long long)wave * kTile;
-#endif
         const unsigned base = (unsigned)tb * M;
         const unsigned ko = base + koff_lane, vo = base + voff_lane;
 #pragma unroll
@@ -271,12 +195,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * M, 0, 0);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][KW - 2] = w[2]; cd.kc[st][KW - 1] = w[3];
             }
-#ifdef EXP_V_WIDE
-            if (DSUB == 4) {
-                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_v, ko + 16 * st * M, 0, 0);
-                cd.vc[st][0] = w[0]; cd.vc[st][1] = w[1];
-            } else
-#endif
             if (DSUB == 4) {
                 // two bytes (sub-spaces 2 col, 2 col + 1) per token; tokens 2u, 2u+1 share a register
 #pragma unroll
@@ -294,6 +212,80 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     };
 
+    // The first two tiles' codes start their trip from HBM now, under the prologue.
+    const long long tile_stride = (long long)NW * kTile;
+    const long long tb0 = n0 + (long long)wave * kTile;
+    Codes ca, cb;
+    load_codes(ca, tb0);
+    load_codes(cb, tb0 + tile_stride);
+
+    STAMP(0);
+    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise) with
+    // direct global->LDS loads: 1 KB per wavefront instruction (64 lanes x 16 B), no VGPR round
+    // trip, so all of a wavefront's 16 KB is in flight at once.
+    {
+        typedef __attribute__((address_space(1))) const void *gptr_t;
+        typedef __attribute__((address_space(3))) void *lptr_t;
+        const unsigned char *srck = reinterpret_cast<const unsigned char *>(p.cb_k + (size_t)g * kCentroids * kD);
+        const unsigned char *srcv = reinterpret_cast<const unsigned char *>(p.cb_v + (size_t)g * kCentroids * kD);
+        constexpr int kChunks = CB_BYTES / 1024;           // per codebook
+#pragma unroll
+        for (int c = wave; c < kChunks; c += NW) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(srck + c * 1024 + lane * 16),
+                                             (lptr_t)(sm_k + c * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(srcv + c * 1024 + lane * 16),
+                                             (lptr_t)(sm_v + c * 1024), 16, 0, 0);
+        }
+    }
+    // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
+    // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
+    // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
+    if (wave < kG) {
+        const size_t qrow = ((size_t)b * p.Hq + g * kG + wave) * kD;
+        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
+        float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
+        {
+            const float a = x0 + x1, d = x0 - x1;
+            x0 = a;
+            x1 = d;
+        }
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) {
+            const float o0 = __shfl_xor(x0, st), o1 = __shfl_xor(x1, st);
+            const bool up = (lane & st) != 0;
+            x0 = up ? (o0 - x0) : (x0 + o0);
+            x1 = up ? (o1 - x1) : (x1 + o1);
+        }
+        sm_qt[wave * kD + lane] = x0;
+        sm_qt[wave * kD + 64 + lane] = x1;
+    }
+    __syncthreads();
+    STAMP(1);
+
+    // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8), hi and lo fp16 parts.
+    // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
+    half8 bq[4];
+    {
+        const float fold = kLog2e / (float)kD;
+        const int hh = col >> 2;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x = sm_qt[hh * kD + 32 * kg + 8 * r + e] * fold;
+                const _Float16 hi = (_Float16)x;
+                const _Float16 lo = (_Float16)(x - (float)hi);
+                bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
+            }
+    }
+
+    STAMP(2);
+    float m_run = -INFINITY;          // running max of head col/4 (log2 units), same in all its lanes
+    float l_part = 0.f;               // this lane's share of the running sum
+    floatx4 acc_o[NROUND_V];
+#pragma unroll
+    for (int r = 0; r < NROUND_V; ++r) acc_o[r] = floatx4{0.f, 0.f, 0.f, 0.f};
+
     // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
     // one v_dot4_u32_u8 (w . (ENTRY << 8k) + base) instead of a bit-field extract and a shift-add.
     auto lds_addr = [&](unsigned w, int k, unsigned base) -> unsigned {
@@ -302,9 +294,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
-#ifdef EXP_NO_KGATHER
-        return as_half8(cd.kc[st][0], cd.kc[st][1], cd.kc[st][0] + r, cd.kc[st][1]);
-#endif
         if (DSUB == 4) {
             // sub-spaces 8kg + 2r, 8kg + 2r + 1: code bytes 2r, 2r+1 of the lane's 8
             const unsigned w = cd.kc[st][r >> 1];
@@ -326,9 +315,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // centroids of sub-space 2 col + r for tokens 2u, 2u+1 of the k-group.  d = 2: q = r:
     // centroids of sub-space 4 col + r for the 4 tokens of the k-group.
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
-#ifdef EXP_NO_VGATHER
-        return as_half8(cd.vc[st][0], cd.vc[st][1], cd.vc[st][0] + q, cd.vc[st][1]);
-#endif
         if (DSUB == 4) {
             const int u = q >> 1, r = q & 1;
             const unsigned w = cd.vc[st][u];          // bytes: (token 2u: r = 0, 1), (token 2u+1: r = 0, 1)
@@ -362,11 +348,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         __builtin_amdgcn_sched_group_barrier(0x100, (OPS) * kReadsPerOperand, 0);           \
         if ((VM) > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);                   \
     }
-#ifdef VECINFER_SECTION_TIMING
-    long long sect[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sect_t = clock64();
-#endif
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
-        SECT(0);
         half8 kb[8], va[8], vb[8];
         const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
         floatx4 sacc[4];
@@ -386,7 +368,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
-        SECT(1);
         // ---- stage 2
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
@@ -401,7 +382,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
-        SECT(2);
         // ---- stage 3: online softmax of this wavefront (Alg. 1 steps 12-13).
         // The four lanes of a quad (same head, t0 = 0..3) hold identical copies of all 16 scores
         // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
@@ -469,7 +449,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                     acc_o[r] = MFMA16(a, vops[r], acc_o[r], 0, 0, 0);
             }
         };
-        SECT(3);
         // ---- stage 4
         __builtin_amdgcn_sched_barrier(0);
         pv(std::integral_constant<int, 0>{}, va);
@@ -480,11 +459,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int q = 0; q < 4; ++q) vb[4 + q] = gather_v(cd, 3, q);
         VI_GROUPS8(1, 1, 3, 0)
         __builtin_amdgcn_sched_barrier(0);
-        SECT(4);
         load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
         __builtin_amdgcn_sched_barrier(0);
 
-        SECT(5);
         // ---- stage 5
         pv(std::integral_constant<int, 2>{}, vb);
 #pragma unroll
@@ -500,7 +477,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         VI_GROUPS8(1, 1, 3, 0)
         __builtin_amdgcn_sched_barrier(0);
-        SECT(6);
     };
 #undef VI_GROUPS8
 
@@ -508,14 +484,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // its last gather has been issued.  Loads past the end of the split are clamped to its last
     // token, so the refill and the look-ahead gathers need no bounds branch.
     {
-        const long long stride = (long long)NW * kTile;
-        long long tb = n0 + (long long)wave * kTile;
-#ifdef EXP_STAGGER
-        for (int i = 0; i < wave; ++i) __builtin_amdgcn_s_sleep(EXP_STAGGER);
-#endif
-        Codes ca, cb;
-        load_codes(ca, tb);
-        load_codes(cb, tb + stride);
+        const long long stride = tile_stride;
+        long long tb = tb0;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             ka[2 * st] = gather_k(ca, st, 0);
@@ -527,10 +497,6 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     }
 
-#ifdef VECINFER_SECTION_TIMING
-    if (g_phase_buf && lane == 0 && wave == 0)
-        for (int i = 0; i < 8; ++i) g_phase_buf[4096 * 8 + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + i] = sect[i];
-#endif
     STAMP(3);
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
     float l_head = l_part + quad_xor<1>(l_part);

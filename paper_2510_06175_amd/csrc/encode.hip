@@ -138,14 +138,16 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
 // every sub-vector to centroid c into LDS; eight threads per sub-space each scan 32 of its 256
 // distances in increasing centroid order (strict "<": lowest index wins) and combine through
 // 64-bit (distance bits, index) keys -- a non-negative fp32 orders like its bit pattern.
+constexpr int kTokRowStride = kCentroids + 1;    // padded LDS row: scanning threads hit distinct banks
+constexpr int kTokMaxPass = 32;                  // sub-spaces per pass
+constexpr int kTokDistFloats = kTokMaxPass * kTokRowStride;
+
 template <int D, int d, bool kTransform>
-__global__ __launch_bounds__(kCentroids) void encode_token_kernel(EncodeParams p)
+__device__ __forceinline__ void encode_token(const EncodeParams &p, float *x_s, float *dist_s)
 {
     constexpr int M = D / d;
-    constexpr int MC = M < 32 ? M : 32;        // sub-spaces per pass
-    constexpr int RS = kCentroids + 1;         // padded row stride: scanning threads hit distinct banks
-    __shared__ float x_s[D];
-    __shared__ float dist_s[MC * RS];
+    constexpr int MC = M < kTokMaxPass ? M : kTokMaxPass;   // sub-spaces per pass
+    constexpr int RS = kTokRowStride;
 
     const int tid = threadIdx.x;
     const long long t = blockIdx.x;
@@ -216,6 +218,26 @@ __global__ __launch_bounds__(kCentroids) void encode_token_kernel(EncodeParams p
     }
 }
 
+template <int D, int d, bool kTransform>
+__global__ __launch_bounds__(kCentroids) void encode_token_kernel(EncodeParams p)
+{
+    __shared__ float x_s[D];
+    __shared__ float dist_s[kTokDistFloats];
+    encode_token<D, d, kTransform>(p, x_s, dist_s);
+}
+
+// Eq. 9 in one launch: blockIdx.y = 0 appends the key codes (transform + VQ), 1 the value codes.
+template <int D, int dk, int dv>
+__global__ __launch_bounds__(kCentroids) void append_kv_kernel(EncodeParams pk, EncodeParams pv)
+{
+    __shared__ float x_s[D];
+    __shared__ float dist_s[kTokDistFloats];
+    if (blockIdx.y == 0)
+        encode_token<D, dk, true>(pk, x_s, dist_s);
+    else
+        encode_token<D, dv, false>(pv, x_s, dist_s);
+}
+
 constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b, g) the per-token kernel wins
 
 template <int D, int d>
@@ -237,7 +259,41 @@ int launch_typed(const EncodeParams &p, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
+template <int D, int dk>
+int launch_append_dv(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    dim3 grid((unsigned)pk.T, 2, pk.B * pk.Hkv);
+    if (pv.d == 2)
+        hipLaunchKernelGGL((append_kv_kernel<D, dk, 2>), grid, dim3(kCentroids), 0, stream, pk, pv);
+    else if (pv.d == 4)
+        hipLaunchKernelGGL((append_kv_kernel<D, dk, 4>), grid, dim3(kCentroids), 0, stream, pk, pv);
+    else if (pv.d == 8)
+        hipLaunchKernelGGL((append_kv_kernel<D, dk, 8>), grid, dim3(kCentroids), 0, stream, pk, pv);
+    else
+        return -2;
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+template <int D>
+int launch_append_dk(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    if (pk.d == 2) return launch_append_dv<D, 2>(pk, pv, stream);
+    if (pk.d == 4) return launch_append_dv<D, 4>(pk, pv, stream);
+    if (pk.d == 8) return launch_append_dv<D, 8>(pk, pv, stream);
+    return -2;
+}
+
 } // namespace
+
+int append_max_tokens() { return (int)kTokenKernelMaxT; }
+
+int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    if (pk.T > kTokenKernelMaxT) return -2;
+    if (pk.D == 128) return launch_append_dk<128>(pk, pv, stream);
+    if (pk.D == 64) return launch_append_dk<64>(pk, pv, stream);
+    return -2;
+}
 
 int launch_encode(const EncodeParams &p, hipStream_t stream)
 {

@@ -63,6 +63,19 @@ def test_encode_argument_errors():
         assert _enc_vals(cfg=bad) == vb.EUNSUPPORTED
 
 
+def test_append_argument_errors():
+    def app(cfg=CFG, k=FAKE, v=FAKE, lam=FAKE, cbk=FAKE, cbv=FAKE, ki=FAKE, vi=FAKE, B=1, T=1, pos0=7, n_cap=8):
+        return vb.lib().vecinfer_append_kv(C.byref(cfg.c()), k, v, lam, cbk, cbv, ki, vi, B, T, pos0, n_cap, None)
+    assert app(k=None) == vb.EINVAL
+    assert app(v=None) == vb.EINVAL
+    assert app(lam=None) == vb.EINVAL
+    assert app(vi=None) == vb.EINVAL
+    assert app(T=0) == vb.EINVAL
+    assert app(T=2) == vb.EINVAL                          # pos0 + T > n_cap
+    assert app(T=17, pos0=0, n_cap=64) == vb.EINVAL       # more than VECINFER_MAX_APPEND tokens
+    assert app(cfg=vb.Config(128, 32, 8, 4, 3)) == vb.EUNSUPPORTED
+
+
 def _decode(cfg=CFG, q=FAKE, lam=FAKE, cbk=FAKE, cbv=FAKE, ki=FAKE, vi=FAKE, sl=None, B=1, N=1024,
             n_cap=1024, S=4, variant=0, ws=None, ws_bytes=0, out=FAKE, lse=None):
     return vb.lib().vecinfer_decode_attention(C.byref(cfg.c()), q, lam, cbk, cbv, ki, vi, sl, B, N, n_cap, S,

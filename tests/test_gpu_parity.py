@@ -159,6 +159,24 @@ def test_encode_short_and_tiled_kernels_agree():
     assert_indices_match(short_k, ref_k, gap, "short keys")
 
 
+def test_append_kv_equals_separate_encodes():
+    """vecinfer_append_kv (one launch) writes exactly the codes of encode_keys + encode_values,
+    for mixed sub-vector dims, at an offset, leaving the other rows alone."""
+    shape = synth.Shape(2, 8, 2, 128, 3, 4, 2)
+    e = synth.encode_inputs(shape, seed=43, n_outlier=3)
+    lam = synth.lognormal_lambda(synth.rng(6), 2, 128)
+    sep_k, sep_v = gpu_encode(shape, k=e["k"], lam=lam, cb_k=e["cb_k"], v=e["v"], cb_v=e["cb_v"], pos0=5, n_cap=16)
+    cfg = cfg_of(shape)
+    k_idx = torch.full((2, 2, 16, shape.Mk), 0xEE, dtype=torch.uint8, device="cuda")
+    v_idx = torch.full((2, 2, 16, shape.Mv), 0xEE, dtype=torch.uint8, device="cuda")
+    vb.vecinfer_append_kv(cfg, dev(e["k"]), dev(e["v"]), dev(lam), dev(e["cb_k"]), dev(e["cb_v"]), k_idx, v_idx, pos0=5)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(k_idx.cpu().numpy(), sep_k)
+    np.testing.assert_array_equal(v_idx.cpu().numpy(), sep_v)
+    ref_k, gap = oracle.encode_keys(e["k"], lam, e["cb_k"], want_gap=True)
+    assert_indices_match(sep_k[:, :, 5:8], ref_k, gap, "append keys")
+
+
 def test_encode_planted_codes_and_ties():
     """Rows built from centroids come back as exactly those codes; duplicate centroids resolve
     to the lower index."""
