@@ -25,6 +25,9 @@ if ROOT not in sys.path:
 
 METRIC = "fused VQ decode-attn: compressed-KV GB/s (% HBM peak) + µs/step, 8B @196k"
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per attention launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a copy
+# kernel of known size); see profiles/decode_attention_b2d4_196k_hbm_traffic.txt.  Not measured live.
+MEASURED_TRAFFIC_BYTES = {"196k-b2d4": 109.37e6 + 0.54e6}
 
 
 def main() -> int:
@@ -38,6 +41,9 @@ def main() -> int:
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run 8 plain 256 MiB device copies first: a kernel of known HBM traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     ap.add_argument("--decode-only", action="store_true",
                     help="time the attention call alone (no append) - for profiling, not the metric")
     args = ap.parse_args()
@@ -89,6 +95,14 @@ def main() -> int:
                                   pos0=shape.N - 1)
         attend(i)
 
+    if args.traffic_probe:
+        src = torch.empty(256 * 2**20, dtype=torch.uint8, device="cuda").random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- timed region: W warm-up steps, then exactly K steps between events on the launch stream
     for i in range(args.warmup):
         step(i)
@@ -127,7 +141,8 @@ def main() -> int:
                    "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},
         "roofline": {"bound": "hbm", "kernel": "vecinfer_decode_attention", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "kernel_us_avg": round(kern_avg_ms * 1e3, 3),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant != vb.VARIANT_LUT else None,
+                     "algorithmic_bytes": idx_bytes, "kernel_us_avg": round(kern_avg_ms * 1e3, 3),
                      "kernel_us_median": round(kern_ms[len(kern_ms) // 2] * 1e3, 3),
                      "kernel_us_min": round(kern_ms[0] * 1e3, 3)},
     }
