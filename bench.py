@@ -147,16 +147,22 @@ def main() -> int:
                      "kernel_us_min": round(kern_ms[0] * 1e3, 3)},
     }
 
-    # ---- the oracle on the host cores, same inputs (layer 0), one step
+    # ---- the oracle (as it stands) on the host cores: the same attention step on layer cache 0,
+    # repeated until about 10 s of wall time have passed (bounded sample of the same workload)
     if not args.no_cpu_baseline:
         import oracle
-        t0 = time.perf_counter()
-        oracle.decode_attention(x0["q"], x0["lam"], x0["cb_k"], x0["cb_v"], x0["k_idx"], x0["v_idx"])
-        dt = time.perf_counter() - t0
-        rec["cpu_baseline"] = {"value": round(idx_bytes / dt / 1e9, 5), "unit": "GB/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "seconds": round(dt, 3),
-                               "sample": "the full workload once: one attention step over layer cache 0 "
-                                         "(float64 explicit dequantize-then-attend, OpenMP over heads)"}
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            oracle.decode_attention(x0["q"], x0["lam"], x0["cb_k"], x0["cb_v"], x0["k_idx"], x0["v_idx"])
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or reps >= 64:
+                break
+        rec["cpu_baseline"] = {"value": round(idx_bytes * reps / dt / 1e9, 5), "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
+                               "sample": f"{reps} full attention steps of this workload over layer cache 0 "
+                                         "(float64 explicit dequantize-then-attend, OpenMP across the 32 heads; "
+                                         "the append is not included)"}
     print(json.dumps(rec))
     return 0
 

@@ -1,17 +1,22 @@
 // Cache-fill kernels: key-side dual transform (Eq. 3, Eq. 6) and exhaustive nearest-centroid
 // vector quantization (Eq. 2, Eq. 8).
 //
-// One workgroup (4 wavefronts) handles 64 tokens of one (batch, KV head) and one "chunk" of
-// 64 output channels (64/d sub-spaces).
+// One workgroup (4 wavefronts) handles 64 tokens of one (batch, KV head).  The sub-spaces are
+// searched four at a time (one per wavefront); the four codebooks are staged in LDS widened
+// to fp32, one group after the other.
 //   phase 1  transform: a lane owns 4 consecutive channels of one token; the first two
 //            butterfly stages run inside the lane, the others across lanes with wavefront
-//            shuffles.  Only the chunk's 64 transformed channels are kept, as fp32, in LDS.
+//            shuffles.  The transformed tile is kept, as fp32, in LDS.
 //            (Values skip the transform: the lane just widens its fp16 inputs.)
 //   phase 2  search: a lane owns one token, a wavefront owns one sub-space at a time, so the
 //            centroid under test is the same for all 64 lanes and is read from LDS as a
-//            broadcast.  Squared distances are summed directly, in channel order, in fp32;
-//            a strict "<" keeps the lowest index on ties.
-//   phase 3  the 64 x (64/d) code bytes go out through LDS as whole 32-bit words.
+//            broadcast.  Squared distances are summed directly, in channel order, in fp32.
+//            Centroids are scanned in groups of 8: only the group minimum is compared with
+//            the running best (strict "<": the earliest group wins ties), and the winning
+//            group is re-evaluated at the end to find the lowest index that attains the
+//            minimum.  A non-negative fp32 orders like its bit pattern, so the minima are
+//            taken on the bits (integer min: no NaN canonicalisation on the way).
+//   phase 3  the 64 x M code bytes go out through LDS as whole 32-bit words.
 #include "common.h"
 
 namespace vecinfer {
@@ -20,35 +25,29 @@ namespace {
 
 constexpr int kEncBlock = 256;
 constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
-constexpr int kChunkCh = 64;       // output channels per workgroup
+constexpr int kChunkSub = 4;       // sub-spaces searched per pass: one per wavefront
 
 template <int D, int d, bool kTransform>
 __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
 {
     constexpr int M = D / d;
-    constexpr int MS = kChunkCh / d;           // sub-spaces per chunk
+    constexpr int MS = kChunkSub;              // sub-spaces per chunk
+    constexpr int kChunkCh = MS * d;           // channels per chunk
+    constexpr int NCHUNK = M / MS;             // chunks per token row
     constexpr int LPT = D / 4;                 // lanes per token in phase 1
     constexpr int TPW = 64 / LPT;              // tokens per wavefront pass in phase 1
-    constexpr int XS = kChunkCh + 4;           // padded row stride of the LDS tile (floats)
+    constexpr int XS = D + 4;                  // padded row stride of the LDS tile (floats)
 
-    __shared__ __align__(16) __half cb_s[MS * kCentroids * d];     // 32 KB
-    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 17 KB
-    __shared__ __align__(16) uint8_t idx_s[kEncTokens * MS];
+    __shared__ __align__(16) float cb_s[MS * kCentroids * d];      // 4096 d bytes: fp32 copies of one chunk's centroids
+    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 33 KB (D = 128): the transformed tile
+    __shared__ __align__(16) uint8_t idx_s[kEncTokens * M];        // codes of the tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long t0 = (long long)blockIdx.x * kEncTokens;
-    const int chunk = blockIdx.y;
     const int bg = blockIdx.z;
     const int g = bg % p.Hkv;
 
-    // ---- codebook chunk -> LDS (fp16, as given)
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
-        uint4 *dst = reinterpret_cast<uint4 *>(cb_s);
-        for (int e = tid; e < MS * kCentroids * d / 8; e += kEncBlock) dst[e] = src[e];
-    }
-
-    // ---- phase 1
+    // ---- phase 1: the whole transformed tile -> LDS (once per workgroup)
     {
         const int sub = lane % LPT;            // which 4 channels of the token
         const int tw = lane / LPT;             // which token of this pass
@@ -59,73 +58,122 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
             rl[0] = l4.x; rl[1] = l4.y; rl[2] = l4.z; rl[3] = l4.w;
         }
         const float hs = 1.0f / sqrtf((float)D);
-        for (int pass = wave; pass < kEncTokens / TPW; pass += kEncBlock / 64) {
-            const int tl = pass * TPW + tw;                    // token within the tile
+        constexpr int NP = kEncTokens / TPW / (kEncBlock / 64);   // passes per wavefront
+        // All passes of the wavefront advance stage by stage, so that a stage's shuffles (NP x 4
+        // independent ones) are in flight together instead of one LDS round trip at a time.
+        float v[NP][4];
+#pragma unroll
+        for (int pi = 0; pi < NP; ++pi) {
+            const int tl = (wave + pi * (kEncBlock / 64)) * TPW + tw;   // token within the tile
             long long t = t0 + tl;
-            if (t >= p.T) t = p.T - 1;                         // tail: harmless duplicate
+            if (t >= p.T) t = p.T - 1;                                  // tail: harmless duplicate
             const uint2 raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
             const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
             const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
-            float v0 = __low2float(h01), v1 = __high2float(h01), v2 = __low2float(h23), v3 = __high2float(h23);
-            if (kTransform) {
-                v0 = v0 / rl[0]; v1 = v1 / rl[1]; v2 = v2 / rl[2]; v3 = v3 / rl[3];
+            v[pi][0] = __low2float(h01); v[pi][1] = __high2float(h01);
+            v[pi][2] = __low2float(h23); v[pi][3] = __high2float(h23);
+        }
+        if (kTransform) {
+#pragma unroll
+            for (int pi = 0; pi < NP; ++pi) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[pi][j] = v[pi][j] / rl[j];
                 // butterflies with partner distance 1 and 2 (inside the lane)
-                float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;
-                v0 = a0 + a2; v1 = a1 + a3; v2 = a0 - a2; v3 = a1 - a3;
-                // partner distance 4 .. D/2 (across lanes)
+                const float a0 = v[pi][0] + v[pi][1], a1 = v[pi][0] - v[pi][1];
+                const float a2 = v[pi][2] + v[pi][3], a3 = v[pi][2] - v[pi][3];
+                v[pi][0] = a0 + a2; v[pi][1] = a1 + a3; v[pi][2] = a0 - a2; v[pi][3] = a1 - a3;
+            }
+            // partner distance 4 .. D/2 (across lanes)
 #pragma unroll
-                for (int x = 1; x < LPT; x <<= 1) {
-                    const float o0 = __shfl_xor(v0, x), o1 = __shfl_xor(v1, x);
-                    const float o2 = __shfl_xor(v2, x), o3 = __shfl_xor(v3, x);
-                    const bool up = (sub & x) != 0;
-                    v0 = up ? (o0 - v0) : (v0 + o0);
-                    v1 = up ? (o1 - v1) : (v1 + o1);
-                    v2 = up ? (o2 - v2) : (v2 + o2);
-                    v3 = up ? (o3 - v3) : (v3 + o3);
+            for (int x = 1; x < LPT; x <<= 1) {
+                float o[NP][4];
+#pragma unroll
+                for (int pi = 0; pi < NP; ++pi)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) o[pi][j] = __shfl_xor(v[pi][j], x);
+                const bool up = (sub & x) != 0;
+#pragma unroll
+                for (int pi = 0; pi < NP; ++pi)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[pi][j] = up ? (o[pi][j] - v[pi][j]) : (v[pi][j] + o[pi][j]);
+            }
+#pragma unroll
+            for (int pi = 0; pi < NP; ++pi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[pi][j] *= hs;
+        }
+#pragma unroll
+        for (int pi = 0; pi < NP; ++pi) {
+            const int tl = (wave + pi * (kEncBlock / 64)) * TPW + tw;
+            float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
+            *reinterpret_cast<float4 *>(&x_s[tl * XS + c0]) = w;
+        }
+    }
+
+    auto dist_bits = [&](const float (&x)[d], const float *cen) -> unsigned {
+        float dist = 0.f;
+#pragma unroll
+        for (int j = 0; j < d; ++j) {
+            const float t = x[j] - cen[j];
+            dist = fmaf(t, t, dist);
+        }
+        return __float_as_uint(dist);
+    };
+
+    for (int chunk = 0; chunk < NCHUNK; ++chunk) {
+        __syncthreads();                       // x_s complete / previous chunk's search done with cb_s
+        // ---- this chunk's centroids -> LDS, widened to fp32 once (exact)
+        {
+            const uint2 *src = reinterpret_cast<const uint2 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
+            float4 *dst = reinterpret_cast<float4 *>(cb_s);
+            for (int e = tid; e < MS * kCentroids * d / 4; e += kEncBlock) {
+                const uint2 raw = src[e];
+                const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
+                const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
+                float4 w; w.x = __low2float(h01); w.y = __high2float(h01); w.z = __low2float(h23); w.w = __high2float(h23);
+                dst[e] = w;
+            }
+        }
+        __syncthreads();
+
+        // ---- phase 2: search
+        for (int ms = wave; ms < MS; ms += kEncBlock / 64) {
+            float x[d];
+#pragma unroll
+            for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + chunk * kChunkCh + ms * d + j];
+            const float *cen = cb_s + (size_t)ms * kCentroids * d;
+            unsigned best = 0x7f800000u;            // +inf
+            int best_group = 0;
+#pragma unroll 2
+            for (int c0 = 0; c0 < kCentroids; c0 += 8) {
+                unsigned gmin = dist_bits(x, cen + c0 * d);
+#pragma unroll
+                for (int k = 1; k < 8; ++k) {
+                    const unsigned v = dist_bits(x, cen + (c0 + k) * d);
+                    gmin = v < gmin ? v : gmin;
                 }
-                v0 *= hs; v1 *= hs; v2 *= hs; v3 *= hs;
+                if (gmin < best) {
+                    best = gmin;
+                    best_group = c0;
+                }
             }
-            if (c0 / kChunkCh == chunk) {
-                float4 w; w.x = v0; w.y = v1; w.z = v2; w.w = v3;
-                *reinterpret_cast<float4 *>(&x_s[tl * XS + (c0 - chunk * kChunkCh)]) = w;
-            }
+            int arg = best_group;
+#pragma unroll
+            for (int k = 7; k >= 0; --k)
+                if (dist_bits(x, cen + (best_group + k) * d) == best) arg = best_group + k;
+            idx_s[lane * M + chunk * MS + ms] = (uint8_t)arg;
         }
     }
     __syncthreads();
 
-    // ---- phase 2
-    for (int ms = wave; ms < MS; ms += kEncBlock / 64) {
-        float x[d];
-#pragma unroll
-        for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + ms * d + j];
-        float best = INFINITY;
-        int arg = 0;
-        const __half *cen = cb_s + (size_t)ms * kCentroids * d;
-#pragma unroll 8
-        for (int c = 0; c < kCentroids; ++c) {
-            float dist = 0.f;
-#pragma unroll
-            for (int j = 0; j < d; ++j) {
-                const float t = x[j] - __half2float(cen[c * d + j]);
-                dist = fmaf(t, t, dist);
-            }
-            if (dist < best) {
-                best = dist;
-                arg = c;
-            }
-        }
-        idx_s[lane * MS + ms] = (uint8_t)arg;
-    }
-    __syncthreads();
-
-    // ---- phase 3: MS bytes per token, written as 32-bit words
+    // ---- phase 3: M bytes per token, written as 32-bit words (whole rows: coalesced)
     {
-        constexpr int WPT = MS / 4;            // words per token
+        constexpr int WPT = M / 4;             // words per token
         for (int e = tid; e < kEncTokens * WPT; e += kEncBlock) {
             const int tl = e / WPT, w = e - tl * WPT;
             const long long t = t0 + tl;
             if (t < p.T) {
-                uint32_t *dst = reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t) * M + (size_t)chunk * MS);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t) * M);
                 dst[w] = reinterpret_cast<const uint32_t *>(idx_s)[tl * WPT + w];
             }
         }
@@ -251,7 +299,7 @@ int launch_typed(const EncodeParams &p, hipStream_t stream)
             hipLaunchKernelGGL((encode_token_kernel<D, d, false>), tgrid, dim3(kCentroids), 0, stream, p);
         return hipGetLastError() == hipSuccess ? 0 : -4;
     }
-    dim3 grid((unsigned)((p.T + kEncTokens - 1) / kEncTokens), D / kChunkCh, p.B * p.Hkv);
+    dim3 grid((unsigned)((p.T + kEncTokens - 1) / kEncTokens), 1, p.B * p.Hkv);
     if (p.lam)
         hipLaunchKernelGGL((encode_kernel<D, d, true>), grid, dim3(kEncBlock), 0, stream, p);
     else
