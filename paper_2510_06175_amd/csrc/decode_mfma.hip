@@ -262,7 +262,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     __syncthreads();
     STAMP(1);
 
-    // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8), hi and lo fp16 parts.
+    // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8); columns with t0 < 2 take the
+    // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
     // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
     half8 bq[4];
     {
@@ -481,8 +482,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #undef VI_GROUPS8
 
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
-    // its last gather has been issued.  Loads past the end of the split are clamped to its last
-    // token, so the refill and the look-ahead gathers need no bounds branch.
+    // its last gather has been issued.  Loads past the end of the split return code 0 (buffer
+    // range check), so the refill and the look-ahead gathers need no bounds branch.
     {
         const long long stride = tile_stride;
         long long tb = tb0;
@@ -577,16 +578,8 @@ bool decode_mfma_supports(const DecodeParams &p)
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
-    // tuning knobs for experiments (read once): waves per workgroup and the fp16 hi/lo query split
-    static const int nw = [] { const char *e = getenv("VECINFER_MFMA_WAVES"); return e ? atoi(e) : 8; }();
-    static const int sq = [] { const char *e = getenv("VECINFER_MFMA_SPLITQ"); return e ? atoi(e) : 1; }();
-    if (p.dk == 4) {
-        if (nw == 12) return sq ? launch_typed<4, 12, true>(p, stream) : launch_typed<4, 12, false>(p, stream);
-        if (nw == 4) return sq ? launch_typed<4, 4, true>(p, stream) : launch_typed<4, 4, false>(p, stream);
-        return sq ? launch_typed<4, 8, true>(p, stream) : launch_typed<4, 8, false>(p, stream);
-    }
-    if (nw == 12) return sq ? launch_typed<2, 12, true>(p, stream) : launch_typed<2, 12, false>(p, stream);
-    return sq ? launch_typed<2, 8, true>(p, stream) : launch_typed<2, 8, false>(p, stream);
+    // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster, 4 is latency-bound
+    return p.dk == 4 ? launch_typed<4, 8, true>(p, stream) : launch_typed<2, 8, true>(p, stream);
 }
 
 } // namespace vecinfer
