@@ -338,9 +338,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // instruction kinds so that each MFMA's 16 busy cycles are filled:
     //   1  MFMA K rounds 0-1      | gather K rounds 2-3
     //   2  MFMA K rounds 2-3      | gather V sub-tiles 0-1
-    //   3  online softmax
-    //   4  MFMA P.V sub-tiles 0-1 | gather V sub-tiles 2-3, refill this tile's code registers
-    //   5  MFMA P.V sub-tiles 2-3 | gather K rounds 0-1 of the NEXT tile
+    //   3  online softmax         | gather V sub-tiles 2-3 (issued first, lands under the softmax)
+    //   4  MFMA P.V sub-tiles 0-1 | gather K rounds 0-1 of the NEXT tile
+    //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
     constexpr int kReadsPerOperand = DSUB == 4 ? 2 : 4;        // ds_reads (and address ops) per half8
 #define VI_GROUPS8(MF, OPS, XV, VM)                                                        \
     _Pragma("unroll") for (int gi = 0; gi < 8; ++gi) {                                      \
@@ -387,6 +387,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         // The four lanes of a quad (same head, t0 = 0..3) hold identical copies of all 16 scores
         // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
         // exp once; the P.V operand build below fetches them back across the quad with DPP.
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            vb[q] = gather_v(cd, 2, q);
+            vb[4 + q] = gather_v(cd, 3, q);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         if (SPLITQ) {
             // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
             // of the quad so that all four lanes hold the full-precision score again
@@ -454,29 +460,23 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         __builtin_amdgcn_sched_barrier(0);
         pv(std::integral_constant<int, 0>{}, va);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) vb[q] = gather_v(cd, 2, q);
-        pv(std::integral_constant<int, 1>{}, va + 4);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) vb[4 + q] = gather_v(cd, 3, q);
-        VI_GROUPS8(1, 1, 3, 0)
-        __builtin_amdgcn_sched_barrier(0);
-        load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- stage 5
-        pv(std::integral_constant<int, 2>{}, vb);
-#pragma unroll
         for (int st = 0; st < 2; ++st) {
             ka[2 * st] = gather_k(next, st, 0);
             ka[2 * st + 1] = gather_k(next, st, 1);
         }
-        pv(std::integral_constant<int, 3>{}, vb + 4);
+        pv(std::integral_constant<int, 1>{}, va + 4);
 #pragma unroll
         for (int st = 2; st < 4; ++st) {
             ka[2 * st] = gather_k(next, st, 0);
             ka[2 * st + 1] = gather_k(next, st, 1);
         }
         VI_GROUPS8(1, 1, 3, 0)
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- stage 5
+        pv(std::integral_constant<int, 2>{}, vb);
+        load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
+        pv(std::integral_constant<int, 3>{}, vb + 4);
         __builtin_amdgcn_sched_barrier(0);
     };
 #undef VI_GROUPS8
