@@ -55,6 +55,10 @@ def _load():
                                         C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_int64, dp, dp]
         lib.vo_decode_batch.restype = C.c_int
+        lib.vo_decode_residual_batch.argtypes = [dp, dp, dp, dp, u8p, u8p, i64p, dp, dp, i64p, C.c_int, C.c_int,
+                                                 C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                                 C.c_int, dp, dp]
+        lib.vo_decode_residual_batch.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -219,4 +223,38 @@ def decode_attention(q_f16, lam, cb_k, cb_v, k_idx, v_idx, seq_lens=None, *,
                                  _dp(out), _dp(lse))
     if rc != 0:
         raise ValueError("vo_decode_batch rejected the inputs (empty sequence or bad shapes)")
+    return out, lse
+
+
+def decode_attention_residual(q_f16, lam, cb_k, cb_v, k_idx, v_idx, k_res, v_res, seq_lens=None, res_lens=None):
+    """Decode step with a full-precision residual window (Sec. 4.1, residual length):
+    Eq. 10 over the quantized tokens plus raw-query x raw-key scores for the window, one
+    softmax over both.  k_res, v_res [B, Hkv, r_cap, D] (fp16 in the GPU path); res_lens [B]
+    or None (= r_cap).  seq_lens[b] may be 0 if the window of b is not empty.
+    Returns (out [B, Hq, D] f64, lse [B, Hq] f64)."""
+    q = _f64(q_f16)
+    lam = _f64(lam)
+    cb_k = _f64(cb_k)
+    cb_v = _f64(cb_v)
+    k_res = _f64(k_res)
+    v_res = _f64(v_res)
+    k_idx = np.ascontiguousarray(k_idx, dtype=np.uint8)
+    v_idx = np.ascontiguousarray(v_idx, dtype=np.uint8)
+    B, Hq, D = q.shape
+    Hkv, Mk, Cn, d_k = cb_k.shape
+    _, Mv, _, d_v = cb_v.shape
+    n_cap = k_idx.shape[2]
+    r_cap = k_res.shape[2]
+    assert k_res.shape == (B, Hkv, r_cap, D) and v_res.shape == (B, Hkv, r_cap, D)
+    sl = np.full(B, n_cap, dtype=np.int64) if seq_lens is None else np.ascontiguousarray(seq_lens, dtype=np.int64)
+    rl = np.full(B, r_cap, dtype=np.int64) if res_lens is None else np.ascontiguousarray(res_lens, dtype=np.int64)
+    assert int(sl.max()) <= n_cap and int(rl.max()) <= r_cap
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    i64p = C.POINTER(C.c_int64)
+    rc = _load().vo_decode_residual_batch(_dp(q), _dp(lam), _dp(cb_k), _dp(cb_v), _u8p(k_idx), _u8p(v_idx),
+                                          sl.ctypes.data_as(i64p), _dp(k_res), _dp(v_res), rl.ctypes.data_as(i64p),
+                                          B, Hq, Hkv, n_cap, r_cap, D, d_k, d_v, Cn, _dp(out), _dp(lse))
+    if rc != 0:
+        raise ValueError("vo_decode_residual_batch rejected the inputs (a sequence with no token at all, or bad shapes)")
     return out, lse

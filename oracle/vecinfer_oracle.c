@@ -19,6 +19,8 @@
  *   vo_vq_dequantize       Sec. 2.2 (last paragraph): VQ^{-1} = centroid lookup
  *   vo_vq_attention        Sec. 3.2, Eq. 10 (explicit dequantize-then-attend)
  *   vo_vq_attention_alg1   App. A, Alg. 1 steps 4-23 (lookup table, tiles, online softmax, LSE)
+ *   vo_vq_attention_residual  Eq. 10 plus the full-precision residual window of Sec. 4.1
+ *                          ("residual length ... 128"): recent tokens kept unquantized
  *   vo_merge_splits        log-sum-exp merge of per-split (o, L) pairs; the paper
  *                          returns L (Alg. 1 step 22) but does not print the merge
  *
@@ -205,6 +207,56 @@ int vo_vq_attention(const double *qt, const uint8_t *kidx, const uint8_t *vidx,
     return 0;
 }
 
+/* Eq. 10 with a residual window (Sec. 4.1 keeps the most recent tokens, 128 of them in the
+ * paper's runs, in full precision).  The N quantized tokens are scored as in vo_vq_attention
+ * (transformed query against dequantized transformed keys); the R window tokens are scored
+ * with the raw query against their raw keys, which is the same quantity by Eq. 7; one softmax
+ * runs over all N + R scores and the window contributes its raw values.
+ * Returns 0, or -1 if N + R < 1. */
+int vo_vq_attention_residual(const double *qt, const double *q_raw, const uint8_t *kidx,
+                             const uint8_t *vidx, const double *cb_k, const double *cb_v,
+                             int64_t N, const double *kres, const double *vres, int64_t R, int D,
+                             int d_k, int d_v, int C, double *out, double *lse)
+{
+    if (N < 0 || R < 0 || N + R < 1) return -1;
+    const int64_t T = N + R;
+    double *Kall = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * D);
+    double *Vall = (double *)malloc(sizeof(double) * (size_t)T * D);
+    double *s = (double *)malloc(sizeof(double) * (size_t)T);
+    if (N > 0) {
+        vo_vq_dequantize(kidx, N, D, d_k, C, cb_k, Kall);
+        vo_vq_dequantize(vidx, N, D, d_v, C, cb_v, Vall);
+    }
+    for (int64_t r = 0; r < R; ++r)
+        for (int i = 0; i < D; ++i) Vall[(N + r) * D + i] = vres[r * D + i];
+    const double scale = 1.0 / sqrt((double)D);
+    double mx = -INFINITY;
+    for (int64_t n = 0; n < T; ++n) {
+        double acc = 0.0;
+        if (n < N)
+            for (int i = 0; i < D; ++i) acc += qt[i] * Kall[n * D + i];
+        else
+            for (int i = 0; i < D; ++i) acc += q_raw[i] * kres[(n - N) * D + i];
+        s[n] = acc * scale;
+        if (s[n] > mx) mx = s[n];
+    }
+    double denom = 0.0;
+    for (int64_t n = 0; n < T; ++n) {
+        s[n] = exp(s[n] - mx);
+        denom += s[n];
+    }
+    for (int i = 0; i < D; ++i) out[i] = 0.0;
+    for (int64_t n = 0; n < T; ++n) {
+        const double p = s[n] / denom;
+        for (int i = 0; i < D; ++i) out[i] += p * Vall[n * D + i];
+    }
+    if (lse) *lse = mx + log(denom);
+    free(Kall);
+    free(Vall);
+    free(s);
+    return 0;
+}
+
 /* Alg. 1 steps 4-23 for one query row against one KV head, in the order and
  * notation of the listing: lut = qt' C_k^T; tiles of `Bt` tokens; per tile
  * s = lookup(K_q, lut)/sqrt(D), m_new, p, l_new, o update; then o / l and
@@ -355,6 +407,46 @@ int vo_decode_batch(const double *q, const double *lam, const double *cb_k,
                 rc = vo_vq_attention(qt, ki, vi, ck, cv, seq_lens[b], D, d_k, d_v, C, o, L);
             else
                 rc = vo_vq_attention_alg1(qt, ki, vi, ck, cv, seq_lens[b], D, d_k, d_v, C, Bt, o, L);
+            if (rc != 0) {
+#pragma omp atomic write
+                err = -1;
+            }
+            free(qt);
+        }
+    free(H);
+    return err;
+}
+
+/* Decode step with a residual window: as vo_decode_batch (path 0) plus
+ *   kres, vres [B, Hkv, r_cap, D]  raw keys / values of the window
+ *   res_lens   [B]                 window tokens in use per sequence (0 .. r_cap)
+ * seq_lens[b] may be 0 when res_lens[b] >= 1. */
+int vo_decode_residual_batch(const double *q, const double *lam, const double *cb_k,
+                             const double *cb_v, const uint8_t *kidx, const uint8_t *vidx,
+                             const int64_t *seq_lens, const double *kres, const double *vres,
+                             const int64_t *res_lens, int B, int Hq, int Hkv, int64_t n_cap,
+                             int64_t r_cap, int D, int d_k, int d_v, int C, double *out, double *lse)
+{
+    if (Hq % Hkv != 0 || D % d_k != 0 || D % d_v != 0) return -1;
+    const int G = Hq / Hkv, Mk = D / d_k, Mv = D / d_v;
+    double *H = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if (vo_hadamard(D, H) != 0) {
+        free(H);
+        return -1;
+    }
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            const double *qr = q + ((int64_t)b * Hq + h) * D;
+            double *qt = (double *)malloc(sizeof(double) * (size_t)D);
+            vo_transform_query(qr, D, lam + (int64_t)g * D, H, qt);
+            const int64_t bg = (int64_t)b * Hkv + g;
+            const int rc = vo_vq_attention_residual(
+                qt, qr, kidx + bg * n_cap * Mk, vidx + bg * n_cap * Mv, cb_k + (int64_t)g * Mk * C * d_k,
+                cb_v + (int64_t)g * Mv * C * d_v, seq_lens[b], kres + bg * r_cap * D, vres + bg * r_cap * D,
+                res_lens[b], D, d_k, d_v, C, out + ((int64_t)b * Hq + h) * D, lse + ((int64_t)b * Hq + h));
             if (rc != 0) {
 #pragma omp atomic write
                 err = -1;

@@ -346,6 +346,72 @@ def test_softmax_shift_invariance(oracle):
         np.testing.assert_allclose(L2[0, h] - base_L[0, h], qt[20:24] @ u / np.sqrt(s.D), rtol=1e-9)
 
 
+# --------------------------------------------------------------------------- residual window (Sec. 4.1)
+
+def _residual_case(seed, B=2, Hq=4, Hkv=2, D=64, N=75, R=9):
+    s, x = _small_decode_case(seed, B=B, Hq=Hq, Hkv=Hkv, D=D, N=N)
+    g = synth.rng(seed + 1000)
+    x["k_res"] = (g.standard_normal((B, Hkv, R, D)) * np.where(g.random(D) < 0.1, 8.0, 1.0)).astype(np.float16)
+    x["v_res"] = g.standard_normal((B, Hkv, R, D)).astype(np.float16)
+    return s, x
+
+
+def test_residual_window_matches_sdpa_on_concatenated_cache(oracle):
+    """The window's raw-query x raw-key scores equal transformed-query x transformed-key scores
+    (Eq. 7), so the result is textbook attention of q~ over [K^ ; k~_res] and [V^ ; v_res]."""
+    s, x = _residual_case(41)
+    seq, res = np.array([75, 40]), np.array([9, 4])
+    out, lse = oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                                x["k_res"], x["v_res"], seq, res)
+    H = scipy.linalg.hadamard(s.D) / np.sqrt(s.D)
+    for b in range(s.B):
+        n, r = seq[b], res[b]
+        K, V = [], []
+        for g in range(s.Hkv):
+            kt_res = (x["k_res"][b, g, :r].astype(np.float64) / x["lam"][g].astype(np.float64)) @ H
+            K.append(np.concatenate([_dequant_np(x["k_idx"][b, g, :n], x["cb_k"][g]), kt_res]))
+            V.append(np.concatenate([_dequant_np(x["v_idx"][b, g, :n], x["cb_v"][g]),
+                                     x["v_res"][b, g, :r].astype(np.float64)]))
+        lam_q = np.repeat(x["lam"].astype(np.float64), s.G, axis=0)
+        qt = (x["q"][b].astype(np.float64) * lam_q) @ H
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qt)[None, :, None, :],
+            torch.from_numpy(np.stack(K)).repeat_interleave(s.G, dim=0)[None],
+            torch.from_numpy(np.stack(V)).repeat_interleave(s.G, dim=0)[None])[0, :, 0].numpy()
+        np.testing.assert_allclose(out[b], ref, rtol=1e-10, atol=1e-12)
+        scores = np.einsum("hd,hnd->hn", qt, np.repeat(np.stack(K), s.G, axis=0)) / np.sqrt(s.D)
+        np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-11)
+
+
+def test_residual_window_special_cases(oracle):
+    s, x = _residual_case(42, B=1, Hq=2, Hkv=1, N=30, R=5)
+    base = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    # an empty window changes nothing
+    o0, l0 = oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                              x["k_res"], x["v_res"], res_lens=np.array([0]))
+    np.testing.assert_array_equal(o0, base[0])
+    np.testing.assert_array_equal(l0, base[1])
+    # no quantized token at all: plain attention (Eq. 1) of the raw query over the window
+    o1, l1 = oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                              x["k_res"], x["v_res"], seq_lens=np.array([0]))
+    q = x["q"][0].astype(np.float64)
+    K = x["k_res"][0, 0].astype(np.float64)
+    V = x["v_res"][0, 0].astype(np.float64)
+    sc = q @ K.T / np.sqrt(s.D)
+    np.testing.assert_allclose(o1[0], scipy.special.softmax(sc, axis=1) @ V, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(l1[0], scipy.special.logsumexp(sc, axis=1), rtol=1e-12)
+    # window and quantized part attended separately, then merged by log-sum-exp = joint result
+    joint, L = oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                                x["k_res"], x["v_res"])
+    for h in range(2):
+        o, l = oracle.merge_splits(np.stack([base[0][0, h], o1[0, h]]), np.array([base[1][0, h], l1[0, h]]))
+        np.testing.assert_allclose(o, joint[0, h], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(l, L[0, h], rtol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                         x["k_res"], x["v_res"], seq_lens=np.array([0]), res_lens=np.array([0]))
+
+
 def test_decode_rejects_empty_sequence(oracle):
     s, x = _small_decode_case(28, B=2)
     with pytest.raises(ValueError):
