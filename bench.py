@@ -44,6 +44,10 @@ def main() -> int:
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run 8 plain 256 MiB device copies first: a kernel of known HBM traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
+    ap.add_argument("--residual", type=int, default=0,
+                    help="keep this many most recent tokens in a full-precision fp16 window (at most 128) and "
+                         "attend to them in the same call; the new token then goes into the window (a copy on "
+                         "the caller's side), so the step has no append - a side measurement, not the metric")
     ap.add_argument("--decode-only", action="store_true",
                     help="time the attention call alone (no append) - for profiling, not the metric")
     args = ap.parse_args()
@@ -83,8 +87,17 @@ def main() -> int:
     lse = torch.empty((shape.B, shape.Hq), dtype=torch.float32, device="cuda")
     splits = args.splits or vb.vecinfer_decode_auto_splits(cfg, shape.B, shape.N)
 
+    if args.residual:
+        args.decode_only = True
+        win = {k: dev(v) for k, v in synth.residual_window(shape, seed=78, r_cap=args.residual).items()}
+
     def attend(i):
         k_idx, v_idx = caches[i % layers]
+        if args.residual:
+            vb.vecinfer_decode_attention_residual(cfg, base["q"], base["lam"], base["cb_k"], base["cb_v"], k_idx,
+                                                  v_idx, win["k_res"], win["v_res"], ws, out, lse=lse,
+                                                  num_splits=args.splits, variant=variant)
+            return
         vb.vecinfer_decode_attention(cfg, base["q"], base["lam"], base["cb_k"], base["cb_v"], k_idx, v_idx,
                                      ws, out, lse=lse, num_splits=args.splits, variant=variant)
 
@@ -134,7 +147,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"llama-3.1-8b layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
                                f"D={shape.D}, N={shape.N}, K d{shape.d_k}b8 / V d{shape.d_v}b8",
-                   "step": "attention only" if args.decode_only else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention",
+                   "step": f"attention over the code cache and a {args.residual}-token fp16 window" if args.residual
+                   else "attention only" if args.decode_only else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention",
                    "index_bytes_per_step": idx_bytes, "layer_caches_rotated": layers,
                    "num_splits": splits, "variant": args.variant,
                    "us_per_step": round(ms_per_step * 1e3, 3),

@@ -44,6 +44,7 @@ extern "C" {
 #define VECINFER_VERSION 100          /* major*10000 + minor*100 + patch */
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
 #define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
+#define VECINFER_MAX_RESIDUAL 128     /* most rows of the full-precision residual window */
 
 enum {
     VECINFER_OK = 0,
@@ -116,7 +117,8 @@ int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t 
 /*
  * Bytes of workspace vecinfer_decode_attention needs for batch B, up to N tokens and
  * `num_splits` splits (0 = whatever vecinfer_decode_auto_splits returns for (B, N)).
- * Host-only.  Returns 0 for an invalid cfg.
+ * N = 0 (only meaningful for vecinfer_decode_attention_residual) gives the one-split size.
+ * Host-only.  Returns 0 for an invalid cfg or negative sizes.
  */
 size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64_t N,
                                        int32_t num_splits);
@@ -150,6 +152,34 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
                               const int32_t *seq_lens, int32_t B, int64_t N, int64_t n_cap,
                               int32_t num_splits, int32_t variant, void *workspace,
                               size_t workspace_bytes, void *out_f16, float *lse, void *stream);
+
+/*
+ * Decode step with a full-precision residual window.  The paper's runs keep the most recent
+ * tokens (residual length 128, Sec. 4.1) unquantized; this call attends to the N quantized
+ * tokens exactly as vecinfer_decode_attention does and, in the same softmax, to the window:
+ *   s_r = q . k_res[b, g, r, :] / sqrt(D)     raw query against raw key, which equals the
+ *                                             transformed product q~ . k~ by Eq. 7
+ *   p = softmax over the len_b + res_len_b scores;   o += sum_r p_r v_res[b, g, r, :]
+ * The window is scored by the merge kernel and joins the log-sum-exp merge as one more partial.
+ * Filling the window and flushing it into the code cache (vecinfer_encode_keys / _values with
+ * T = window length, pos0 = N, reading the window as [B, H_kv, T, D] when r_cap = T) is the caller's.
+ *   k_res_f16, v_res_f16  fp16 [B, H_kv, r_cap, D], rows 0 .. res_len_b - 1 are attended
+ *   res_lens  int32 [B] on the device, or NULL: every window holds R rows; clamped to [0, R]
+ *   R         window rows attended, 0 <= R <= min(r_cap, VECINFER_MAX_RESIDUAL)
+ *   N         may be 0 when R >= 1 (nothing quantized yet); k_idx / v_idx may then be NULL
+ * A sequence with no token in either part yields o = 0 and L = -inf.  Everything else, and the
+ * workspace size, as for vecinfer_decode_attention.
+ * Errors: as vecinfer_decode_attention, plus EINVAL for a NULL window, R < 0, R > r_cap,
+ * N + R < 1, and EUNSUPPORTED for R > VECINFER_MAX_RESIDUAL.
+ */
+int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                                       const void *cb_k_f16, const void *cb_v_f16,
+                                       const uint8_t *k_idx, const uint8_t *v_idx,
+                                       const int32_t *seq_lens, int32_t B, int64_t N, int64_t n_cap,
+                                       const void *k_res_f16, const void *v_res_f16,
+                                       const int32_t *res_lens, int32_t R, int64_t r_cap,
+                                       int32_t num_splits, int32_t variant, void *workspace,
+                                       size_t workspace_bytes, void *out_f16, float *lse, void *stream);
 
 /* Human-readable text for a return code (static storage). */
 const char *vecinfer_strerror(int code);

@@ -107,9 +107,80 @@ int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, b
     return launch_status(launch_encode(p, static_cast<hipStream_t>(stream)));
 }
 
-__global__ __launch_bounds__(512) void merge_kernel(DecodeParams p)
+static_assert(VECINFER_MAX_RESIDUAL == kMaxResidual, "header and kernels agree on the window size");
+
+// Shared body of the two decode entry points; k_res == nullptr means no residual window.
+int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda, const void *cb_k_f16,
+                  const void *cb_v_f16, const uint8_t *k_idx, const uint8_t *v_idx, const int32_t *seq_lens,
+                  int32_t B, int64_t N, int64_t n_cap, const void *k_res, const void *v_res,
+                  const int32_t *res_lens, int32_t R, int64_t r_cap, int32_t num_splits, int32_t variant,
+                  void *workspace, size_t workspace_bytes, void *out_f16, float *lse, void *stream)
 {
-    merge_splits<512>(p, blockIdx.y, blockIdx.x);
+    if (!cfg || !q_f16 || !lambda || !cb_k_f16 || !cb_v_f16 || !out_f16) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    const bool window = k_res != nullptr;
+    if (B < 1 || N < (window ? 0 : 1) || n_cap < N) return VECINFER_EINVAL;
+    if (N > 0 && (!k_idx || !v_idx)) return VECINFER_EINVAL;
+    if (window) {
+        if (!v_res || R < 0 || R > r_cap || N + R < 1) return VECINFER_EINVAL;
+        if (R > VECINFER_MAX_RESIDUAL) return VECINFER_EUNSUPPORTED;
+        if (!aligned(k_res, 16) || !aligned(v_res, 16)) return VECINFER_EINVAL;
+    }
+    if (num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
+    if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA)
+        return VECINFER_EINVAL;
+    if (B > 65535) return VECINFER_EUNSUPPORTED;
+    if (!aligned(q_f16, 16) || !aligned(lambda, 16) || !aligned(cb_k_f16, 16) || !aligned(cb_v_f16, 16) ||
+        !aligned(k_idx, 16) || !aligned(v_idx, 16) || !aligned(out_f16, 16))
+        return VECINFER_EINVAL;
+    const int32_t S = N == 0 ? 1 : (num_splits ? num_splits : auto_splits(cfg, B, N));
+    const WorkspaceLayout w = ws_layout(cfg, B, S);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return VECINFER_EWORKSPACE;
+
+    DecodeParams p;
+    p.q = static_cast<const __half *>(q_f16);
+    p.lam = lambda;
+    p.cb_k = static_cast<const __half *>(cb_k_f16);
+    p.cb_v = static_cast<const __half *>(cb_v_f16);
+    p.k_idx = k_idx;
+    p.v_idx = v_idx;
+    p.seq_lens = seq_lens;
+    p.B = B;
+    p.Hq = cfg->num_q_heads;
+    p.Hkv = cfg->num_kv_heads;
+    p.G = p.Hq / p.Hkv;
+    p.D = cfg->head_dim;
+    p.dk = cfg->k_sub_dim;
+    p.dv = cfg->v_sub_dim;
+    p.Mk = p.D / p.dk;
+    p.Mv = p.D / p.dv;
+    p.N = N;
+    p.n_cap = n_cap;
+    p.S = S;
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    p.part_o = reinterpret_cast<float *>(ws + w.off_o);
+    p.part_m = reinterpret_cast<float *>(ws + w.off_m);
+    p.part_l = reinterpret_cast<float *>(ws + w.off_l);
+    p.out = static_cast<__half *>(out_f16);
+    p.lse = lse;
+    p.k_res = static_cast<const __half *>(k_res);
+    p.v_res = static_cast<const __half *>(v_res);
+    p.res_lens = window ? res_lens : nullptr;
+    p.R = window ? R : 0;
+    p.r_cap = window ? r_cap : 0;
+
+    const bool mfma_ok = decode_mfma_supports(p);
+    if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
+    const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
+    int rc = 0;
+    if (N > 0)
+        rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
+                      : launch_decode_lut(p, static_cast<hipStream_t>(stream));
+    else
+        p.S = 0;                        // nothing but the window: the merge kernel sees no split partial
+    // log-sum-exp merge of the splits and of the window (single split, no window: done in-kernel)
+    if (rc == 0 && (p.S != 1 || window)) rc = launch_merge(p, static_cast<hipStream_t>(stream));
+    return launch_status(rc);
 }
 
 } // namespace
@@ -152,8 +223,8 @@ int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t 
 
 size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64_t N, int32_t num_splits)
 {
-    if (!cfg_ok(cfg) || B < 1 || N < 1 || num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return 0;
-    const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
+    if (!cfg_ok(cfg) || B < 1 || N < 0 || num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return 0;
+    const int32_t S = N == 0 ? 1 : (num_splits ? num_splits : auto_splits(cfg, B, N));
     return ws_layout(cfg, B, S).total;
 }
 
@@ -163,58 +234,23 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
                               int64_t n_cap, int32_t num_splits, int32_t variant, void *workspace,
                               size_t workspace_bytes, void *out_f16, float *lse, void *stream)
 {
-    if (!cfg || !q_f16 || !lambda || !cb_k_f16 || !cb_v_f16 || !k_idx || !v_idx || !out_f16)
-        return VECINFER_EINVAL;
-    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
-    if (B < 1 || N < 1 || n_cap < N) return VECINFER_EINVAL;
-    if (num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
-    if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA)
-        return VECINFER_EINVAL;
-    if (B > 65535) return VECINFER_EUNSUPPORTED;
-    if (!aligned(q_f16, 16) || !aligned(lambda, 16) || !aligned(cb_k_f16, 16) || !aligned(cb_v_f16, 16) ||
-        !aligned(k_idx, 16) || !aligned(v_idx, 16) || !aligned(out_f16, 16))
-        return VECINFER_EINVAL;
-    const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
-    const WorkspaceLayout w = ws_layout(cfg, B, S);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < w.total) return VECINFER_EWORKSPACE;
+    return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, nullptr,
+                         nullptr, nullptr, 0, 0, num_splits, variant, workspace, workspace_bytes, out_f16, lse,
+                         stream);
+}
 
-    DecodeParams p;
-    p.q = static_cast<const __half *>(q_f16);
-    p.lam = lambda;
-    p.cb_k = static_cast<const __half *>(cb_k_f16);
-    p.cb_v = static_cast<const __half *>(cb_v_f16);
-    p.k_idx = k_idx;
-    p.v_idx = v_idx;
-    p.seq_lens = seq_lens;
-    p.B = B;
-    p.Hq = cfg->num_q_heads;
-    p.Hkv = cfg->num_kv_heads;
-    p.G = p.Hq / p.Hkv;
-    p.D = cfg->head_dim;
-    p.dk = cfg->k_sub_dim;
-    p.dv = cfg->v_sub_dim;
-    p.Mk = p.D / p.dk;
-    p.Mv = p.D / p.dv;
-    p.N = N;
-    p.n_cap = n_cap;
-    p.S = S;
-    unsigned char *ws = static_cast<unsigned char *>(workspace);
-    p.part_o = reinterpret_cast<float *>(ws + w.off_o);
-    p.part_m = reinterpret_cast<float *>(ws + w.off_m);
-    p.part_l = reinterpret_cast<float *>(ws + w.off_l);
-    p.out = static_cast<__half *>(out_f16);
-    p.lse = lse;
-
-    const bool mfma_ok = decode_mfma_supports(p);
-    if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
-    const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
-    int rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
-                      : launch_decode_lut(p, static_cast<hipStream_t>(stream));
-    if (rc == 0 && p.S > 1) {          // log-sum-exp merge of the splits (single split: done in-kernel)
-        hipLaunchKernelGGL(merge_kernel, dim3(p.Hkv, p.B), dim3(512), 0, static_cast<hipStream_t>(stream), p);
-        rc = hipGetLastError() == hipSuccess ? 0 : -4;
-    }
-    return rc == 0 ? VECINFER_OK : (rc == -2 ? VECINFER_EUNSUPPORTED : VECINFER_ELAUNCH);
+int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                                       const void *cb_k_f16, const void *cb_v_f16, const uint8_t *k_idx,
+                                       const uint8_t *v_idx, const int32_t *seq_lens, int32_t B, int64_t N,
+                                       int64_t n_cap, const void *k_res_f16, const void *v_res_f16,
+                                       const int32_t *res_lens, int32_t R, int64_t r_cap, int32_t num_splits,
+                                       int32_t variant, void *workspace, size_t workspace_bytes, void *out_f16,
+                                       float *lse, void *stream)
+{
+    if (!k_res_f16 || !v_res_f16) return VECINFER_EINVAL;
+    return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, k_res_f16,
+                         v_res_f16, res_lens, R, r_cap, num_splits, variant, workspace, workspace_bytes, out_f16,
+                         lse, stream);
 }
 
 const char *vecinfer_strerror(int code)

@@ -30,6 +30,12 @@ struct DecodeParams {
     float *part_l;           // [B, Hkv, S, G]     partial sum of exp2(s2 - m)
     __half *out;             // [B, Hq, D]
     float *lse;              // [B, Hq] or nullptr
+    // full-precision residual window (Sec. 4.1, residual length); k_res == nullptr: none
+    const __half *k_res;     // [B, Hkv, r_cap, D] raw keys of the most recent tokens
+    const __half *v_res;     // [B, Hkv, r_cap, D] raw values
+    const int32_t *res_lens; // [B] or nullptr
+    int R;                   // window rows attended (upper bound when res_lens is given)
+    long long r_cap;
 };
 
 // Token range [n0, n1) of split s for a sequence of `len` tokens: equal chunks rounded
@@ -72,10 +78,11 @@ __device__ __forceinline__ float wave_sum(float v)
 // Log-sum-exp merge of the S partials of one (b, g) into the final output rows (the paper
 // returns L from each tile loop, Alg. 1 step 22, but leaves the merge to the reader):
 //   M = max_s m_s,  w_s = 2^(m_s - M),  o = sum_s w_s o_s / sum_s w_s l_s,  L = (M + log2 sum) ln 2.
-// Called by all BLOCK threads of one workgroup.  Partials are read in batches of independent
-// loads so that the S-long reduction costs a few memory latencies, not S of them.
-template <int BLOCK>
-__device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g)
+// reduce_partials folds the S workspace partials of output element e = hh * D + c into the
+// running (mx, den, acc).  Partials are read in batches of independent loads so that the
+// S-long reduction costs a few memory latencies, not S of them.
+__device__ __forceinline__ void reduce_partials(const DecodeParams &p, int b, int g, int e, float &mx,
+                                                float &den, float &acc)
 {
     constexpr int kBatch = 32;
     const int GD = p.G * p.D;
@@ -83,56 +90,73 @@ __device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g
     const float *po = p.part_o + bg * p.S * GD;
     const float *pm = p.part_m + bg * p.S * p.G;
     const float *pl = p.part_l + bg * p.S * p.G;
-    for (int e = threadIdx.x; e < GD; e += BLOCK) {
-        const int hh = e / p.D, c = e - hh * p.D;
-        float mx = -INFINITY, den = 0.f, acc = 0.f;
-        for (int s0 = 0; s0 < p.S; s0 += kBatch) {
-            float vm[kBatch], vl[kBatch], vo[kBatch];
+    const int hh = e / p.D;
+    for (int s0 = 0; s0 < p.S; s0 += kBatch) {
+        float vm[kBatch], vl[kBatch], vo[kBatch];
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                const int s = s0 + i < p.S ? s0 + i : p.S - 1;
-                vm[i] = pm[s * p.G + hh];
-                vl[i] = pl[s * p.G + hh];
-                vo[i] = po[(size_t)s * GD + e];
-            }
-            float bmx = mx;
+        for (int i = 0; i < kBatch; ++i) {
+            const int s = s0 + i < p.S ? s0 + i : p.S - 1;
+            vm[i] = pm[s * p.G + hh];
+            vl[i] = pl[s * p.G + hh];
+            vo[i] = po[(size_t)s * GD + e];
+        }
+        float bmx = mx;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i)
+            if (s0 + i < p.S) bmx = fmaxf(bmx, vm[i]);
+        if (bmx > -INFINITY) {
+            const float rescale = exp2f(mx - bmx);        // 0 when nothing was accumulated yet
+            den *= rescale;
+            acc *= rescale;
 #pragma unroll
             for (int i = 0; i < kBatch; ++i)
-                if (s0 + i < p.S) bmx = fmaxf(bmx, vm[i]);
-            if (bmx > -INFINITY) {
-                const float rescale = exp2f(mx - bmx);        // 0 when nothing was accumulated yet
-                den *= rescale;
-                acc *= rescale;
-#pragma unroll
-                for (int i = 0; i < kBatch; ++i)
-                    if (s0 + i < p.S) {
-                        const float w = exp2f(vm[i] - bmx);
-                        den += w * vl[i];
-                        acc += w * vo[i];
-                    }
-                mx = bmx;
-            }
+                if (s0 + i < p.S) {
+                    const float w = exp2f(vm[i] - bmx);
+                    den += w * vl[i];
+                    acc += w * vo[i];
+                }
+            mx = bmx;
         }
-        const size_t row = (size_t)b * p.Hq + g * p.G + hh;
-        p.out[row * p.D + c] = __float2half(den > 0.f ? acc / den : 0.f);
-        if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (mx + log2f(den)) * kLn2 : -INFINITY;
     }
 }
 
-// End of a decode workgroup.  With a single split the workgroup's own partial is the whole
-// answer and it finalises the output rows itself; with several splits a merge kernel follows
+// Normalises the merged (mx, den, acc) of output element e and writes out (and lse once per row).
+__device__ __forceinline__ void store_merged(const DecodeParams &p, int b, int g, int e, float mx, float den,
+                                             float acc)
+{
+    const int hh = e / p.D, c = e - hh * p.D;
+    const size_t row = (size_t)b * p.Hq + g * p.G + hh;
+    p.out[row * p.D + c] = __float2half(den > 0.f ? acc / den : 0.f);
+    if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (mx + log2f(den)) * kLn2 : -INFINITY;
+}
+
+// Called by all BLOCK threads of one workgroup.
+template <int BLOCK>
+__device__ __forceinline__ void merge_splits(const DecodeParams &p, int b, int g)
+{
+    for (int e = threadIdx.x; e < p.G * p.D; e += BLOCK) {
+        float mx = -INFINITY, den = 0.f, acc = 0.f;
+        reduce_partials(p, b, g, e, mx, den, acc);
+        store_merged(p, b, g, e, mx, den, acc);
+    }
+}
+
+// End of a decode workgroup.  With a single split and no residual window the workgroup's own
+// partial is the whole answer and it finalises the output rows itself; otherwise a merge kernel follows
 // in the same stream (a device-scope release inside the kernel would write the whole L2 of the
 // XCD back per workgroup, which costs more than the kernel boundary does).
 template <int BLOCK>
 __device__ __forceinline__ void finish_split(const DecodeParams &p, int b, int g)
 {
-    if (p.S > 1) return;
+    if (p.S > 1 || p.k_res) return;
     __syncthreads();                       // this workgroup's partial stores, visible to itself
     merge_splits<BLOCK>(p, b, g);
 }
 
+constexpr int kMaxResidual = 128;                  // rows of the residual window (the paper's setting)
+
 // launchers (one translation unit each)
-int launch_merge(const DecodeParams &p, hipStream_t stream);
+int launch_merge(const DecodeParams &p, hipStream_t stream);   // splits (+ residual window) -> out, lse
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
 bool decode_mfma_supports(const DecodeParams &p);

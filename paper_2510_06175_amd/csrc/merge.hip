@@ -1,0 +1,236 @@
+// Second kernel of a decode step: log-sum-exp merge of the split partials, and, when the caller
+// keeps the most recent tokens unquantized (Sec. 4.1, residual length), attention over that
+// fp16 window computed here and merged in with them.
+//
+// The kernel runs right behind the attention kernel on data that sits in other compute units'
+// caches or in memory, so what it costs is dependent memory round trips, not arithmetic: every
+// global load it needs is issued up front, back to back, and consumed after one barrier.
+#include "common.h"
+
+namespace vecinfer {
+namespace {
+
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxSplits = 256;                         // VECINFER_MAX_SPLITS
+constexpr int kBatch = 32;                              // split partials a thread keeps in flight
+constexpr int kRowsPerWave = kMaxResidual / kWaves;     // 16: one MFMA column block of window rows per wave
+static_assert(kRowsPerWave == 16, "a wave scores 16 window rows with 16x16x32 MFMAs");
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// One workgroup per (KV head g, sequence b); D = head dim, HB = bound on G (4 or 8).
+//
+// Merge (the paper returns L from each tile loop, Alg. 1 step 22, and leaves the merge to the reader):
+//   M = max_s m_s,  w_s = 2^(m_s - M),  o = sum_s w_s o_s / sum_s w_s l_s,  L = (M + log2 sum) ln 2.
+// A thread owns output elements e = hh * D + c; it loads its o_s for the first kBatch splits at
+// once (clamped to the last split; the (m, l) table in LDS is padded with m = -inf so that the
+// surplus gets weight 0), the (m, l) pairs go through LDS.
+//
+// Window (WINDOW = true): rows are scored with the raw query against the raw keys,
+// q . k = (q * lambda) H . (k / lambda) H (Eq. 7), so the scores live on the same scale as the
+// quantized tokens' and share their softmax.  Wave w owns rows 16 w .. 16 w + 15 and turns them
+// into one more partial (m, l, o):
+//   scores  S[hh][r] = q[hh] . k[r] on the matrix cores.  v_mfma_f32_16x16x32_f16 wants, per lane
+//           l, eight consecutive k-values of row / column l % 16 starting at 8 (l / 16): for both
+//           the query rows and the row-major window keys that is one 16-byte global load, so the
+//           operands come straight from memory.  The result lands with window row l % 16 in lane l
+//           and head 4 (l / 16) + v in register v.
+//   softmax over the 16 rows: xor-shuffles inside each 16-lane group.
+//   o[hh][c] = sum_r p[hh][r] v[r][c] on the vector ALU: a lane owns two adjacent channels, p comes
+//           from the owning lane by v_readlane.
+// Window loads are clamped to row R - 1 (always inside the allocation) and masked by the
+// sequence's own window length afterwards, so they do not wait for that length to arrive.
+template <int D, int HB, bool WINDOW>
+__global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
+{
+    constexpr int kSteps = D / 32;                                   // MFMA k-steps over the head dimension
+    constexpr int kElems = (HB * D + kThreads - 1) / kThreads;       // output elements per thread
+    constexpr int kML = kMaxSplits * HB / kThreads;                  // (m, l) table entries per thread
+    __shared__ float pm_s[kMaxSplits * HB], pl_s[kMaxSplits * HB];   // [s][hh], padded to a multiple of kBatch splits
+    __shared__ float wo_s[WINDOW ? kWaves * HB * D : 1];             // wave partial outputs, [wave][hh][c]
+    __shared__ float wm_s[kWaves * HB], wl_s[kWaves * HB];
+
+    const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+    const int w = t >> 6, lane = t & 63;
+    const int G = p.G, GD = G * D, S = p.S;
+    const size_t bg = (size_t)b * p.Hkv + g;
+
+    // ---- 1. window operands -> registers
+    half8 qa[kSteps], kb[kSteps];
+    unsigned vv[kRowsPerWave];
+    const int row0 = w * kRowsPerWave;
+    const bool wave_loads = WINDOW && row0 < p.R;            // wave-uniform
+    int r_len = 0;
+    if (WINDOW) {
+        r_len = p.R;
+        if (p.res_lens) {
+            const int v = p.res_lens[b];
+            r_len = v < 0 ? 0 : (v > p.R ? p.R : v);
+        }
+        if (wave_loads) {
+            const __half *kg = p.k_res + bg * p.r_cap * D;
+            const __half *vg = p.v_res + bg * p.r_cap * D;
+            const __half *qg = p.q + ((size_t)b * p.Hq + (size_t)g * G) * D;
+            const int last = p.R - 1;
+            const int qrow = (lane & 15) < G ? (lane & 15) : 0;
+            const int krow = row0 + (lane & 15) < last ? row0 + (lane & 15) : last;
+#pragma unroll
+            for (int ks = 0; ks < kSteps; ++ks) {
+                const int col = ks * 32 + 8 * (lane >> 4);
+                qa[ks] = *reinterpret_cast<const half8 *>(qg + qrow * D + col);
+                kb[ks] = *reinterpret_cast<const half8 *>(kg + (size_t)krow * D + col);
+            }
+            const int c2 = 2 * lane < D ? 2 * lane : 0;
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                const int vrow = row0 + r < last ? row0 + r : last;
+                vv[r] = *reinterpret_cast<const unsigned *>(vg + (size_t)vrow * D + c2);
+            }
+        }
+    }
+
+    // ---- 2. split partials: this thread's o_s of the first kBatch splits, and its share of the (m, l) table
+    float vo[kElems][kBatch], tm[kML], tl[kML];
+    const int SG = S * G;
+    if (S > 0) {
+        const float *po = p.part_o + bg * S * GD;
+        const float *pm = p.part_m + bg * SG;
+        const float *pl = p.part_l + bg * SG;
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+            const int e = t + i * kThreads < GD ? t + i * kThreads : 0;
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) vo[i][j] = po[(size_t)(j < S ? j : S - 1) * GD + e];
+        }
+#pragma unroll
+        for (int i = 0; i < kML; ++i) {
+            const int idx = t + i * kThreads < SG ? t + i * kThreads : SG - 1;
+            tm[i] = pm[idx];
+            tl[i] = pl[idx];
+        }
+    }
+
+    // ---- 3. the wave's window partial -> LDS
+    if (WINDOW && row0 < r_len) {
+        floatx4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < kSteps; ++ks) sc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[ks], kb[ks], sc, 0, 0, 0);
+        const float scale = kLog2e * rsqrtf((float)D);
+        const bool valid = row0 + (lane & 15) < r_len;
+        float pr[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float s2 = valid ? sc[v] * scale : -INFINITY;
+            float m = s2;
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+            pr[v] = __builtin_amdgcn_exp2f(s2 - m);          // row row0 is valid, so m is finite
+            float l = pr[v];
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) l += __shfl_xor(l, o);
+            const int hh = 4 * (lane >> 4) + v;
+            if ((lane & 15) == 0 && hh < HB) {               // heads G .. HB - 1 hold finite filler
+                wm_s[w * HB + hh] = m;
+                wl_s[w * HB + hh] = l;
+            }
+        }
+        float o2[HB][2];
+#pragma unroll
+        for (int hh = 0; hh < HB; ++hh) o2[hh][0] = o2[hh][1] = 0.f;
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) {
+            const float2 vf = __half22float2(*reinterpret_cast<const __half2 *>(&vv[r]));
+#pragma unroll
+            for (int hh = 0; hh < HB; ++hh) {
+                const float ph = __uint_as_float(
+                    __builtin_amdgcn_readlane(__float_as_uint(pr[hh & 3]), 16 * (hh >> 2) + r));
+                o2[hh][0] = fmaf(ph, vf.x, o2[hh][0]);
+                o2[hh][1] = fmaf(ph, vf.y, o2[hh][1]);
+            }
+        }
+        if (2 * lane < D) {
+#pragma unroll
+            for (int hh = 0; hh < HB; ++hh)
+                *reinterpret_cast<float2 *>(&wo_s[(w * HB + hh) * D + 2 * lane]) = make_float2(o2[hh][0], o2[hh][1]);
+        }
+    }
+
+    // ---- 4. (m, l) table -> LDS, padded with empty splits up to a multiple of kBatch
+    const int Spad = (S + kBatch - 1) / kBatch * kBatch;
+#pragma unroll
+    for (int i = 0; i < kML; ++i) {
+        const int idx = t + i * kThreads;
+        if (idx < Spad * G) {
+            pm_s[idx] = idx < SG ? tm[i] : -INFINITY;
+            pl_s[idx] = idx < SG ? tl[i] : 0.f;
+        }
+    }
+    __syncthreads();
+
+    // ---- 5. merge and write the rows
+    const int n_waves = WINDOW ? (r_len + kRowsPerWave - 1) / kRowsPerWave : 0;
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = t + i * kThreads;
+        if (e >= GD) continue;
+        const int hh = e / D, c = e % D;
+        float M = -INFINITY;
+        for (int s = 0; s < S; ++s) M = fmaxf(M, pm_s[s * G + hh]);
+        for (int ww = 0; ww < n_waves; ++ww) M = fmaxf(M, wm_s[ww * HB + hh]);
+        const float Mc = M > -INFINITY ? M : 0.f;            // nothing to attend to: all weights 0
+        float den = 0.f, acc = 0.f;
+        if (S > 0) {
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const float wgt = __builtin_amdgcn_exp2f(pm_s[j * G + hh] - Mc);
+                den = fmaf(wgt, pl_s[j * G + hh], den);
+                acc = fmaf(wgt, vo[i][j], acc);
+            }
+            const float *po = p.part_o + bg * S * GD;
+            for (int s0 = kBatch; s0 < S; s0 += kBatch) {    // more than kBatch splits: further rounds
+                float vx[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) vx[j] = po[(size_t)(s0 + j < S ? s0 + j : S - 1) * GD + e];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const float wgt = __builtin_amdgcn_exp2f(pm_s[(s0 + j) * G + hh] - Mc);
+                    den = fmaf(wgt, pl_s[(s0 + j) * G + hh], den);
+                    acc = fmaf(wgt, vx[j], acc);
+                }
+            }
+        }
+        for (int ww = 0; ww < n_waves; ++ww) {
+            const float wgt = __builtin_amdgcn_exp2f(wm_s[ww * HB + hh] - Mc);
+            den = fmaf(wgt, wl_s[ww * HB + hh], den);
+            acc = fmaf(wgt, wo_s[(ww * HB + hh) * D + c], acc);
+        }
+        const size_t row = (size_t)b * p.Hq + g * G + hh;
+        p.out[row * D + c] = __float2half(den > 0.f ? acc / den : 0.f);
+        if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
+    }
+}
+
+template <int D, int HB>
+int launch_for(const DecodeParams &p, hipStream_t stream)
+{
+    const dim3 grid(p.Hkv, p.B), block(kThreads);
+    if (p.k_res)
+        hipLaunchKernelGGL((merge_kernel<D, HB, true>), grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL((merge_kernel<D, HB, false>), grid, block, 0, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+} // namespace
+
+int launch_merge(const DecodeParams &p, hipStream_t stream)
+{
+    if (p.S > kMaxSplits || p.G > 8 || (p.k_res && p.R > kMaxResidual)) return -2;
+    if (p.D == 128) return p.G <= 4 ? launch_for<128, 4>(p, stream) : launch_for<128, 8>(p, stream);
+    if (p.D == 64) return p.G <= 4 ? launch_for<64, 4>(p, stream) : launch_for<64, 8>(p, stream);
+    return -2;
+}
+
+} // namespace vecinfer

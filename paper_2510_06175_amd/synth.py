@@ -111,6 +111,14 @@ def decode_inputs(shape: Shape, seed: int, n_cap: int | None = None) -> dict:
     }
 
 
+def residual_window(shape: Shape, seed: int, r_cap: int, n_outlier: int = 4) -> dict:
+    """Full-precision window of the r_cap most recent tokens: raw fp16 keys (with outlier
+    channels, as un-smoothed keys have) and raw values, [B, Hkv, r_cap, D] each."""
+    g = rng(seed)
+    k, _ = keys_with_outlier_channels(g, shape.B, shape.Hkv, r_cap, shape.D, n_outlier)
+    return {"k_res": k, "v_res": values(g, shape.B, shape.Hkv, r_cap, shape.D)}
+
+
 def encode_inputs(shape: Shape, seed: int, n_outlier: int) -> dict:
     """Inputs of a cache fill: raw keys (with outlier channels), raw values, codebooks,
     and the decode-step query.  The smoothing factors are NOT drawn here: where a

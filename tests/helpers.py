@@ -40,6 +40,25 @@ def gpu_decode(shape, x, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT
     return out.cpu().numpy().astype(np.float64), (lse.cpu().numpy().astype(np.float64) if want_lse else None)
 
 
+def gpu_decode_residual(shape, x, seq_lens=None, res_lens=None, N=None, R=None, num_splits=0,
+                        variant=vb.VARIANT_AUTO):
+    """As gpu_decode, plus the fp16 window x["k_res"], x["v_res"] [B, Hkv, r_cap, D]."""
+    cfg = cfg_of(shape)
+    t = {k: dev(v) for k, v in x.items() if k in ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx", "k_res", "v_res")}
+    B = t["q"].shape[0]
+    N = t["k_idx"].shape[2] if N is None else N
+    ws = vb.new_workspace(cfg, B, N, num_splits)
+    out = torch.full((B, shape.Hq, shape.D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((B, shape.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    as_i32 = lambda a: None if a is None else torch.as_tensor(np.asarray(a), dtype=torch.int32).cuda()
+    vb.vecinfer_decode_attention_residual(cfg, t["q"], t["lam"], t["cb_k"], t["cb_v"], t["k_idx"], t["v_idx"],
+                                          t["k_res"], t["v_res"], ws, out, lse=lse, seq_lens=as_i32(seq_lens),
+                                          res_lens=as_i32(res_lens), N=N, R=R, num_splits=num_splits,
+                                          variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+
+
 def assert_decode_close(got_out, got_lse, ref_out, ref_lse, what=""):
     B, Hq, _ = ref_out.shape
     worst = 0.0

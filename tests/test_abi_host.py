@@ -103,6 +103,26 @@ def test_decode_argument_errors():
     assert _decode(cfg=vb.Config(64, 8, 8, 4, 4), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
 
 
+def test_decode_residual_argument_errors():
+    def res(cfg=CFG, ki=FAKE, vi=FAKE, N=1024, n_cap=1024, kr=FAKE, vr=FAKE, rl=None, R=128, r_cap=128, S=4,
+            ws=None, ws_bytes=0):
+        return vb.lib().vecinfer_decode_attention_residual(
+            C.byref(cfg.c()), FAKE, FAKE, FAKE, FAKE, ki, vi, None, 1, N, n_cap, kr, vr, rl, R, r_cap, S, 0, ws,
+            ws_bytes, FAKE, None, None)
+    assert res(kr=None) == vb.EINVAL
+    assert res(vr=None) == vb.EINVAL
+    assert res(R=-1) == vb.EINVAL
+    assert res(R=64, r_cap=32) == vb.EINVAL                     # more rows than the window holds
+    assert res(N=0, R=0) == vb.EINVAL                           # nothing to attend to
+    assert res(kr=FAKE + 2) == vb.EINVAL
+    assert res(R=vb.MAX_RESIDUAL + 1, r_cap=256) == vb.EUNSUPPORTED
+    assert res(N=0, ki=None, vi=None, R=8) == vb.EWORKSPACE     # valid without a code cache; no workspace given
+    assert res(N=1024, ki=None) == vb.EINVAL                    # but codes are needed when N > 0
+    need = vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, 4)
+    assert res(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 0, 0) == vb.vecinfer_decode_workspace_bytes(CFG, 1, 1, 1) > 0
+
+
 def test_workspace_size_and_auto_splits():
     assert vb.vecinfer_decode_workspace_bytes(vb.Config(96, 32, 8, 4, 4), 1, 1024, 4) == 0
     assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, vb.MAX_SPLITS + 1) == 0

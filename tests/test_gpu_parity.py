@@ -7,7 +7,8 @@ import oracle
 from paper_2510_06175_amd import binding as vb
 from paper_2510_06175_amd import synth
 
-from helpers import (assert_decode_close, assert_indices_match, cfg_of, dev, gpu_decode, gpu_encode)
+from helpers import (assert_decode_close, assert_indices_match, cfg_of, dev, gpu_decode, gpu_decode_residual,
+                     gpu_encode)
 
 pytestmark = pytest.mark.gpu
 
@@ -242,3 +243,107 @@ def test_config5_cache_fill_then_decode():
     x = {"q": e["q"], "lam": lam, "cb_k": e["cb_k"], "cb_v": e["cb_v"], "k_idx": got_k, "v_idx": got_v}
     ref = oracle.decode_attention(e["q"], lam, e["cb_k"], e["cb_v"], got_k, got_v)
     assert_decode_close(*gpu_decode(shape, x), *ref, what="config5 decode")
+
+
+# ------------------------------------------------------------------ residual window (Sec. 4.1)
+
+RESIDUAL = [
+    # shape, rows in the window
+    (synth.Shape(2, 8, 2, 128, 777, 4, 4), 128),
+    (synth.Shape(1, 8, 2, 128, 1500, 2, 2), 37),
+    (synth.Shape(1, 4, 2, 64, 513, 4, 2), 128),
+    (synth.Shape(1, 8, 1, 64, 300, 8, 8), 5),
+    (synth.Shape(3, 4, 4, 128, 65, 2, 8), 1),
+]
+
+
+def _oracle_residual(x, seq_lens=None, res_lens=None):
+    return oracle.decode_attention_residual(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"],
+                                            x["k_res"], x["v_res"], seq_lens, res_lens)
+
+
+@pytest.mark.parametrize("vname", list(VARIANTS))
+@pytest.mark.parametrize("case", RESIDUAL, ids=lambda c: f"B{c[0].B}h{c[0].Hq}-{c[0].Hkv}D{c[0].D}N{c[0].N}R{c[1]}")
+@pytest.mark.parametrize("splits", [1, 3])
+def test_decode_residual_window(case, splits, vname):
+    shape, R = case
+    variant = VARIANTS[vname]
+    if not _supported(shape, variant):
+        pytest.skip("variant does not cover this configuration")
+    x = synth.decode_inputs(shape, seed=shape.N + R)
+    x.update(synth.residual_window(shape, seed=R, r_cap=R))
+    ref = _oracle_residual(x)
+    base = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    # the window must matter in this input: it holds a visible share of the softmax mass somewhere
+    share = 1.0 - np.exp(base[1] - ref[1])
+    assert share.max() > 1e-3
+    got = gpu_decode_residual(shape, x, num_splits=splits, variant=variant)
+    assert_decode_close(*got, *ref, what=f"{vname} R={R} splits={splits}")
+
+
+def test_decode_residual_ragged_empty_parts_and_capacity():
+    """Ragged code-cache and window lengths: a sequence with only a window, one with only codes,
+    one with neither (o = 0, L = -inf); R below the window capacity."""
+    shape = synth.Shape(4, 8, 2, 128, 640, 4, 4)
+    x = synth.decode_inputs(shape, seed=21, n_cap=700)
+    x.update(synth.residual_window(shape, seed=22, r_cap=128))
+    seq = np.array([640, 0, 0, 333])
+    res = np.array([100, 17, 0, 0])
+    got_o, got_l = gpu_decode_residual(shape, x, seq_lens=seq, res_lens=res, N=640, R=100, num_splits=4)
+    keep = [0, 1, 3]
+    sub = {k: (v[keep] if k in ("q", "k_idx", "v_idx", "k_res", "v_res") else v) for k, v in x.items()}
+    ref_o, ref_l = _oracle_residual(sub, seq[keep], res[keep])
+    assert_decode_close(got_o[keep], got_l[keep], ref_o, ref_l, what="ragged residual")
+    assert (got_o[2] == 0).all() and np.isneginf(got_l[2]).all()
+    # rows at or beyond R are not attended even if res_lens says more
+    got2 = gpu_decode_residual(shape, x, seq_lens=seq, res_lens=np.array([128, 128, 0, 0]), N=640, R=17)
+    ref2 = _oracle_residual(sub, seq[keep], np.array([17, 17, 0]))
+    assert_decode_close(got2[0][keep], got2[1][keep], *ref2, what="R clamps res_lens")
+
+
+def test_decode_residual_without_code_cache_and_empty_window():
+    shape = synth.Shape(2, 8, 2, 128, 256, 4, 4)
+    x = synth.decode_inputs(shape, seed=23)
+    x.update(synth.residual_window(shape, seed=24, r_cap=64))
+    # N = 0: plain attention over the window
+    got = gpu_decode_residual(shape, x, N=0)
+    ref = _oracle_residual(x, seq_lens=np.zeros(2, dtype=np.int64))
+    assert_decode_close(*got, *ref, what="window only")
+    # R = 0: the same numbers as the call without a window
+    got0 = gpu_decode_residual(shape, x, R=0, num_splits=2)
+    base = gpu_decode(shape, x, num_splits=2)
+    np.testing.assert_array_equal(got0[0], base[0])
+    np.testing.assert_array_equal(got0[1], base[1])
+
+
+def test_decode_residual_flush_then_attend():
+    """Life cycle of the window: attend with it, then quantize it into the code cache
+    (encode with pos0 = N) and attend without: the codes written are the oracle's."""
+    shape = synth.Shape(1, 8, 2, 128, 512, 4, 4)
+    R = 128
+    x = synth.decode_inputs(shape, seed=25, n_cap=shape.N + R)
+    x.update(synth.residual_window(shape, seed=26, r_cap=R))
+    cfg = cfg_of(shape)
+    k_idx, v_idx = dev(x["k_idx"]), dev(x["v_idx"])
+    vb.vecinfer_encode_keys(cfg, dev(x["k_res"]), dev(x["lam"]), dev(x["cb_k"]), k_idx, pos0=shape.N)
+    vb.vecinfer_encode_values(cfg, dev(x["v_res"]), dev(x["cb_v"]), v_idx, pos0=shape.N)
+    torch.cuda.synchronize()
+    ref_k, gap_k = oracle.encode_keys(x["k_res"], x["lam"], x["cb_k"], want_gap=True)
+    ref_v, gap_v = oracle.encode_values(x["v_res"], x["cb_v"], want_gap=True)
+    assert_indices_match(k_idx.cpu().numpy()[:, :, shape.N:], ref_k, gap_k, "flushed keys")
+    assert_indices_match(v_idx.cpu().numpy()[:, :, shape.N:], ref_v, gap_v, "flushed values")
+    np.testing.assert_array_equal(k_idx.cpu().numpy()[:, :, :shape.N], x["k_idx"][:, :, :shape.N])
+    y = dict(x, k_idx=k_idx.cpu().numpy(), v_idx=v_idx.cpu().numpy())
+    got = gpu_decode(shape, y)
+    ref = oracle.decode_attention(y["q"], y["lam"], y["cb_k"], y["cb_v"], y["k_idx"], y["v_idx"])
+    assert_decode_close(*got, *ref, what="after flush")
+
+
+def test_decode_residual_full_size_196k():
+    """The benchmark's launch configuration plus a full 128-row window."""
+    shape = synth.LLAMA8B_196K
+    x = synth.decode_inputs(shape, seed=4)
+    x.update(synth.residual_window(shape, seed=27, r_cap=128))
+    ref = _oracle_residual(x)
+    got = gpu_decode_residual(shape, x)
+    assert_decode_close(*got, *ref, what="196k + window")
