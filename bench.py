@@ -3,8 +3,8 @@
 
 Workload (BASELINE configs[3], the one the metric is quoted on): Llama-3.1-8B layer shape,
 batch 1, 32 query / 8 KV heads, head dim 128, 196608 cached tokens, b2d4 codes for K and V.
-One step = one decode step of one layer: append the new token's key and value codes
-(smooth + FWHT + nearest centroid, T = 1, one launch) and run the fused VQ attention over the cache.
+One step = one decode step of one layer (vecinfer_decode_step): append the new token's key and
+value codes (smooth + FWHT + nearest centroid) and run the fused VQ attention over the cache.
 Steps rotate over several distinct layer caches so that the index stream comes from HBM, not
 from the 256 MB Infinity Cache.  Inputs are seeded and synthetic and are resident in HBM
 before the timed region.
@@ -48,6 +48,9 @@ def main() -> int:
                     help="keep this many most recent tokens in a full-precision fp16 window (at most 128) and "
                          "attend to them in the same call; the new token then goes into the window (a copy on "
                          "the caller's side), so the step has no append - a side measurement, not the metric")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="append with vecinfer_append_kv and attend with vecinfer_decode_attention (two calls) "
+                         "instead of the fused vecinfer_decode_step")
     ap.add_argument("--decode-only", action="store_true",
                     help="time the attention call alone (no append) - for profiling, not the metric")
     args = ap.parse_args()
@@ -102,11 +105,17 @@ def main() -> int:
                                      ws, out, lse=lse, num_splits=args.splits, variant=variant)
 
     def step(i):
-        if not args.decode_only:
-            k_idx, v_idx = caches[i % layers]
+        if args.decode_only:
+            attend(i)
+            return
+        k_idx, v_idx = caches[i % layers]
+        if args.separate_append:
             vb.vecinfer_append_kv(cfg, new_k, new_v, base["lam"], base["cb_k"], base["cb_v"], k_idx, v_idx,
                                   pos0=shape.N - 1)
-        attend(i)
+            attend(i)
+        else:
+            vb.vecinfer_decode_step(cfg, base["q"], new_k, new_v, base["lam"], base["cb_k"], base["cb_v"], k_idx,
+                                    v_idx, ws, out, lse=lse, num_splits=args.splits, variant=variant)
 
     if args.traffic_probe:
         src = torch.empty(256 * 2**20, dtype=torch.uint8, device="cuda").random_(0, 256)
@@ -148,7 +157,9 @@ def main() -> int:
         "config": {"workload": f"llama-3.1-8b layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
                                f"D={shape.D}, N={shape.N}, K d{shape.d_k}b8 / V d{shape.d_v}b8",
                    "step": f"attention over the code cache and a {args.residual}-token fp16 window" if args.residual
-                   else "attention only" if args.decode_only else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention",
+                   else "attention only" if args.decode_only
+                   else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention, "
+                        + ("two calls" if args.separate_append else "one call (vecinfer_decode_step)"),
                    "index_bytes_per_step": idx_bytes, "layer_caches_rotated": layers,
                    "num_splits": splits, "variant": args.variant,
                    "us_per_step": round(ms_per_step * 1e3, 3),

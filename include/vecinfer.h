@@ -181,6 +181,29 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
                                        int32_t num_splits, int32_t variant, void *workspace,
                                        size_t workspace_bytes, void *out_f16, float *lse, void *stream);
 
+/*
+ * One whole decode step of a layer: the append of Eq. 9 and the attention of Eq. 10 in one call.
+ * The new token of sequence b (key k_new[b, g, 0, :], value v_new[b, g, 0, :]) becomes its last
+ * token, position len_b - 1 (len_b = seq_lens[b] clamped to [0, N], or N without seq_lens, so
+ * len_b counts the new token); rows len_b - 1 of k_idx and v_idx receive exactly the codes
+ * vecinfer_append_kv would write there, and the output is what vecinfer_decode_attention
+ * returns afterwards for the same N and seq_lens.  A sequence with len_b = 0 appends nothing
+ * and yields o = 0, L = -inf.
+ * With VECINFER_VARIANT_MFMA (or AUTO when it covers cfg) nothing is launched in front of the
+ * attention: its workgroups share out the sub-spaces of the new token while the code cache of
+ * the older tokens streams, and the merge kernel joins the new token as one more partial.
+ * Other configurations run the append kernel first.
+ *   k_new_f16, v_new_f16  fp16 [B, H_kv, 1, D]
+ *   k_idx, v_idx          as in vecinfer_decode_attention, but written at row len_b - 1
+ * Everything else, the workspace size and the errors as for vecinfer_decode_attention
+ * (EINVAL also for NULL k_new_f16 / v_new_f16).
+ */
+int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void *k_new_f16,
+                         const void *v_new_f16, const float *lambda, const void *cb_k_f16,
+                         const void *cb_v_f16, uint8_t *k_idx, uint8_t *v_idx, const int32_t *seq_lens,
+                         int32_t B, int64_t N, int64_t n_cap, int32_t num_splits, int32_t variant,
+                         void *workspace, size_t workspace_bytes, void *out_f16, float *lse, void *stream);
+
 /* Human-readable text for a return code (static storage). */
 const char *vecinfer_strerror(int code);
 

@@ -24,7 +24,8 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
 EXPORTS = [
     "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_append_kv", "vecinfer_decode_auto_splits",
     "vecinfer_decode_workspace_bytes",
-    "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_strerror", "vecinfer_version",
+    "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
+    "vecinfer_strerror", "vecinfer_version",
 ]
 
 
@@ -85,6 +86,9 @@ def lib() -> C.CDLL:
         L.vecinfer_decode_attention_residual.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, vp, vp,
                                                          vp, i32, i64, i32, i32, vp, sz, vp, vp, vp]
         L.vecinfer_decode_attention_residual.restype = C.c_int
+        L.vecinfer_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, vp, sz,
+                                           vp, vp, vp]
+        L.vecinfer_decode_step.restype = C.c_int
         L.vecinfer_strerror.argtypes = [C.c_int]
         L.vecinfer_strerror.restype = C.c_char_p
         L.vecinfer_version.restype = C.c_int
@@ -225,6 +229,31 @@ def vecinfer_decode_attention_residual(cfg: Config, q_f16, lam, cb_k, cb_v, k_id
         _dev(v_res, torch.float16, (B, cfg.num_kv_heads, r_cap, cfg.head_dim), "v_res"),
         None if res_lens is None else _dev(res_lens, torch.int32, (B,), "res_lens"),
         R, r_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
+        None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
+        _stream(stream)))
+
+
+def vecinfer_decode_step(cfg: Config, q_f16, k_new, v_new, lam, cb_k, cb_v, k_idx, v_idx, workspace, out_f16,
+                         lse=None, seq_lens=None, N: int | None = None, num_splits: int = 0,
+                         variant: int = VARIANT_AUTO, stream=None) -> None:
+    """Append the new token (k_new, v_new [B, Hkv, 1, D]) as each sequence's last one and attend."""
+    B = q_f16.shape[0]
+    n_cap = k_idx.shape[2]
+    N = n_cap if N is None else N
+    Mk = cfg.head_dim // cfg.k_sub_dim
+    Mv = cfg.head_dim // cfg.v_sub_dim
+    _check(lib().vecinfer_decode_step(
+        C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
+        _dev(k_new, torch.float16, (B, cfg.num_kv_heads, 1, cfg.head_dim), "k_new"),
+        _dev(v_new, torch.float16, (B, cfg.num_kv_heads, 1, cfg.head_dim), "v_new"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
+        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
+        B, N, n_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
         None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
         _stream(stream)))

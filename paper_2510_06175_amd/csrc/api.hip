@@ -50,7 +50,7 @@ int32_t auto_splits(const vecinfer_cfg *c, int32_t B, int64_t N)
 }
 
 struct WorkspaceLayout {
-    size_t off_o, off_m, off_l, total;
+    size_t off_o, off_m, off_l, off_nsc, off_nv, total;
 };
 
 WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
@@ -65,6 +65,11 @@ WorkspaceLayout ws_layout(const vecinfer_cfg *c, int32_t B, int32_t S)
     off += up(sizeof(float) * rows);
     w.off_l = off;
     off += up(sizeof(float) * rows);
+    // fused append: score shares [B, Hkv, Mk, G] and dequantized value [B, Hkv, D] of the new token
+    w.off_nsc = off;
+    off += up(sizeof(float) * (size_t)B * c->num_q_heads * (c->head_dim / c->k_sub_dim));
+    w.off_nv = off;
+    off += up(sizeof(float) * (size_t)B * c->num_kv_heads * c->head_dim);
     w.total = off;
     return w;
 }
@@ -92,6 +97,8 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     p.T = T;
     p.pos0 = pos0;
     p.n_cap = n_cap;
+    p.seq_lens = nullptr;
+    p.len_max = 0;
     return VECINFER_OK;
 }
 
@@ -109,16 +116,20 @@ int encode_common(const vecinfer_cfg *cfg, const void *x, const float *lambda, b
 
 static_assert(VECINFER_MAX_RESIDUAL == kMaxResidual, "header and kernels agree on the window size");
 
-// Shared body of the two decode entry points; k_res == nullptr means no residual window.
+// Shared body of the decode entry points; k_res == nullptr means no residual window,
+// k_new == nullptr no fused append (the two are never given together).
 int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda, const void *cb_k_f16,
                   const void *cb_v_f16, const uint8_t *k_idx, const uint8_t *v_idx, const int32_t *seq_lens,
                   int32_t B, int64_t N, int64_t n_cap, const void *k_res, const void *v_res,
-                  const int32_t *res_lens, int32_t R, int64_t r_cap, int32_t num_splits, int32_t variant,
-                  void *workspace, size_t workspace_bytes, void *out_f16, float *lse, void *stream)
+                  const int32_t *res_lens, int32_t R, int64_t r_cap, const void *k_new, const void *v_new,
+                  int32_t num_splits, int32_t variant, void *workspace, size_t workspace_bytes, void *out_f16,
+                  float *lse, void *stream)
 {
     if (!cfg || !q_f16 || !lambda || !cb_k_f16 || !cb_v_f16 || !out_f16) return VECINFER_EINVAL;
     if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
     const bool window = k_res != nullptr;
+    const bool append = k_new != nullptr;
+    if (append && (!v_new || !aligned(k_new, 16) || !aligned(v_new, 16))) return VECINFER_EINVAL;
     if (B < 1 || N < (window ? 0 : 1) || n_cap < N) return VECINFER_EINVAL;
     if (N > 0 && (!k_idx || !v_idx)) return VECINFER_EINVAL;
     if (window) {
@@ -168,11 +179,31 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     p.res_lens = window ? res_lens : nullptr;
     p.R = window ? R : 0;
     p.r_cap = window ? r_cap : 0;
+    p.k_new = p.v_new = nullptr;
+    p.k_idx_w = p.v_idx_w = nullptr;
+    p.new_sc = reinterpret_cast<float *>(ws + w.off_nsc);
+    p.new_v = reinterpret_cast<float *>(ws + w.off_nv);
 
     const bool mfma_ok = decode_mfma_supports(p);
     if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
     const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
     int rc = 0;
+    if (append && use_mfma) {           // the attention launch encodes the new token itself
+        p.k_new = static_cast<const __half *>(k_new);
+        p.v_new = static_cast<const __half *>(v_new);
+        p.k_idx_w = const_cast<uint8_t *>(k_idx);
+        p.v_idx_w = const_cast<uint8_t *>(v_idx);
+    } else if (append) {                // separate append launch in front of the plain attention
+        EncodeParams pk, pv;
+        rc = encode_args(cfg, k_new, lambda, true, cb_k_f16, const_cast<uint8_t *>(k_idx), B, 1, N - 1, n_cap, pk);
+        if (rc != VECINFER_OK) return rc;
+        rc = encode_args(cfg, v_new, nullptr, false, cb_v_f16, const_cast<uint8_t *>(v_idx), B, 1, N - 1, n_cap, pv);
+        if (rc != VECINFER_OK) return rc;
+        pk.seq_lens = pv.seq_lens = seq_lens;
+        pk.len_max = pv.len_max = N;
+        rc = launch_append(pk, pv, static_cast<hipStream_t>(stream));
+        if (rc != 0) return launch_status(rc);
+    }
     if (N > 0)
         rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
                       : launch_decode_lut(p, static_cast<hipStream_t>(stream));
@@ -235,8 +266,20 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
                               size_t workspace_bytes, void *out_f16, float *lse, void *stream)
 {
     return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, nullptr,
-                         nullptr, nullptr, 0, 0, num_splits, variant, workspace, workspace_bytes, out_f16, lse,
-                         stream);
+                         nullptr, nullptr, 0, 0, nullptr, nullptr, num_splits, variant, workspace,
+                         workspace_bytes, out_f16, lse, stream);
+}
+
+int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void *k_new_f16,
+                         const void *v_new_f16, const float *lambda, const void *cb_k_f16,
+                         const void *cb_v_f16, uint8_t *k_idx, uint8_t *v_idx, const int32_t *seq_lens,
+                         int32_t B, int64_t N, int64_t n_cap, int32_t num_splits, int32_t variant,
+                         void *workspace, size_t workspace_bytes, void *out_f16, float *lse, void *stream)
+{
+    if (!k_new_f16 || !v_new_f16 || !k_idx || !v_idx) return VECINFER_EINVAL;
+    return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, nullptr,
+                         nullptr, nullptr, 0, 0, k_new_f16, v_new_f16, num_splits, variant, workspace,
+                         workspace_bytes, out_f16, lse, stream);
 }
 
 int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
@@ -249,8 +292,8 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
 {
     if (!k_res_f16 || !v_res_f16) return VECINFER_EINVAL;
     return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, k_res_f16,
-                         v_res_f16, res_lens, R, r_cap, num_splits, variant, workspace, workspace_bytes, out_f16,
-                         lse, stream);
+                         v_res_f16, res_lens, R, r_cap, nullptr, nullptr, num_splits, variant, workspace,
+                         workspace_bytes, out_f16, lse, stream);
 }
 
 const char *vecinfer_strerror(int code)

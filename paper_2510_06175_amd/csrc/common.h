@@ -36,6 +36,17 @@ struct DecodeParams {
     const int32_t *res_lens; // [B] or nullptr
     int R;                   // window rows attended (upper bound when res_lens is given)
     long long r_cap;
+    // fused append of the step's new token (Eq. 9 inside the decode step); k_new == nullptr: none.
+    // The new token is the last one of each sequence (position len_b - 1): the attention kernel
+    // reads codes of the len_b - 1 older tokens only, its workgroups share out the sub-spaces of
+    // the new token (nearest centroid, code byte, score share, dequantized value) and the merge
+    // kernel joins the new token as one more partial.
+    const __half *k_new;     // [B, Hkv, 1, D] raw key of the new token
+    const __half *v_new;     // [B, Hkv, 1, D] raw value
+    uint8_t *k_idx_w;        // = k_idx, writable: row len_b - 1 receives the key codes
+    uint8_t *v_idx_w;        // = v_idx, writable
+    float *new_sc;           // [B, Hkv, Mk, G] score share of each key sub-space (log2 units)
+    float *new_v;            // [B, Hkv, D]     dequantized value of the new token
 };
 
 // Token range [n0, n1) of split s for a sequence of `len` tokens: equal chunks rounded
@@ -168,6 +179,10 @@ struct EncodeParams {
     uint8_t *idx;         // [B, Hkv, n_cap, M]
     int B, Hkv, D, d, M;
     long long T, pos0, n_cap;
+    // per-sequence append position (T = 1 only): when seq_lens != nullptr the token of sequence b
+    // goes to row clamp(seq_lens[b], 0, len_max) - 1, and a sequence of length 0 is skipped
+    const int32_t *seq_lens;
+    long long len_max;
 };
 int launch_encode(const EncodeParams &p, hipStream_t stream);
 int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream);

@@ -30,9 +30,12 @@ namespace vecinfer {
 
 #ifdef VECINFER_PHASE_TIMING
 __device__ unsigned long long *g_phase_buf = nullptr;
-#define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 8 + (i)] = wall_clock64(); } while (0)
+#define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); } while (0)
+// per-wavefront stamp: slot 8 * (j + 1) + wave, j in {0, 1, 2}
+#define STAMPW(j) do { if (g_phase_buf && (threadIdx.x & 63) == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 * ((j) + 1) + (threadIdx.x >> 6)] = wall_clock64(); } while (0)
 #else
 #define STAMP(i)
+#define STAMPW(j)
 #endif
 
 namespace {
@@ -95,6 +98,23 @@ __device__ __forceinline__ float rows_max(float x)
     return fmaxf(__builtin_bit_cast(float, (unsigned)s32[0]), __builtin_bit_cast(float, (unsigned)s32[1]));
 }
 
+// unsigned minimum over the wavefront, in every lane: DPP inside the 16-lane rows
+// (quad_perm xor 1, 2, then row rotations by 4 and 8), row swaps across them
+__device__ __forceinline__ unsigned wave_umin(unsigned x)
+{
+    auto dpp = [](unsigned v, auto ctrl) {
+        return (unsigned)__builtin_amdgcn_mov_dpp((int)v, decltype(ctrl)::value, 0xf, 0xf, true);
+    };
+    x = min(x, dpp(x, std::integral_constant<int, 0xB1>{}));      // quad_perm:[1,0,3,2]
+    x = min(x, dpp(x, std::integral_constant<int, 0x4E>{}));      // quad_perm:[2,3,0,1]
+    x = min(x, dpp(x, std::integral_constant<int, 0x124>{}));     // row_ror:4
+    x = min(x, dpp(x, std::integral_constant<int, 0x128>{}));     // row_ror:8
+    auto s16 = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = min((unsigned)s16[0], (unsigned)s16[1]);
+    auto s32 = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return min((unsigned)s32[0], (unsigned)s32[1]);
+}
+
 __device__ __forceinline__ unsigned pack_dup_f16(float p)
 {
     // (p, p) as two fp16, round-to-nearest-even
@@ -119,17 +139,30 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     unsigned char *const sm_k = smem;
     unsigned char *const sm_v = smem + CB_BYTES;
     float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][128]
+    float *const sm_new = sm_qt + kG * kD;                                 // [2][128]: k~ and v of the new token
+    float *const sm_nsc = sm_new + 2 * kD;                                 // [M][4]: its score shares (log2 units)
+    float *const sm_nv = sm_nsc + M * kG;                                  // [128]:  its dequantized value
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int s = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
+    // fastest: with 8 KV heads every XCD serves one head and its L2 fetches one codebook set
+    // (128 KB) instead of all of them.
+    const int lin = blockIdx.x + gridDim.x * blockIdx.y;
+    const int g = lin % p.Hkv, s = lin / p.Hkv, b = blockIdx.z;
     const int col = lane & 15;       // MFMA row (A) / column (B, D) index of this lane
     const int kg = lane >> 4;        // k-group (A, B) / row group (D) of this lane
     const size_t bg = (size_t)b * p.Hkv + g;
 
+    // With a fused append the new token is the sequence's last one: its codes are produced in
+    // this launch (below), so the tile loop covers the len - 1 older tokens only.  Workgroup s
+    // encodes sub-spaces s, s + S, ... of the new token's key and value.
+    const long long len = seq_len_of(p, b);
+    const bool fused = p.k_new != nullptr && len > 0;
+    const bool has_new = fused && s < M;
     long long n0, n1;
-    split_range(seq_len_of(p, b), p.S, s, kTile, n0, n1);
+    split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
 
-    if (n0 >= n1) {                                    // empty split: neutral partial
+    if (n0 >= n1 && !has_new) {                        // empty split: neutral partial
         for (int e = tid; e < kG * kD; e += BLOCK) p.part_o[(bg * p.S + s) * kG * kD + e] = 0.f;
         if (tid < kG) {
             p.part_m[(bg * p.S + s) * kG + tid] = -INFINITY;
@@ -212,12 +245,30 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     };
 
+    // Which tiles a wavefront owns.  The two wavefronts of a SIMD do not run at the same speed:
+    // the one launched first (wavefronts 0 .. NW/2-1) wins the issue arbitration and gets through
+    // a tile about 13 % sooner, so an even deal leaves it idle at the end of a long split.  Tiles
+    // are therefore dealt in periods of 12 rounds: 11 rounds to every wavefront in turn and one
+    // round shared by the first half only, two tiles each (13 : 11).  Short splits (under 11
+    // rounds) see the plain round-robin.  The deal is static, so results are reproducible.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto tile_base = [&](int k) -> long long {          // first token of this wavefront's k-th tile
+        constexpr int kFull = 11, kPeriod = (kFull + 1) * NW;
+        int per, off;
+        if (wave_u < NW / 2) {
+            per = k / (kFull + 2);
+            const int i = k % (kFull + 2);
+            off = i < kFull ? i * NW + wave_u : kFull * NW + (i - kFull) * (NW / 2) + wave_u;
+        } else {
+            per = k / kFull;
+            off = (k % kFull) * NW + wave_u;
+        }
+        return n0 + ((long long)per * kPeriod + off) * kTile;
+    };
     // The first two tiles' codes start their trip from HBM now, under the prologue.
-    const long long tile_stride = (long long)NW * kTile;
-    const long long tb0 = n0 + (long long)wave * kTile;
     Codes ca, cb;
-    load_codes(ca, tb0);
-    load_codes(cb, tb0 + tile_stride);
+    load_codes(ca, tile_base(0));
+    load_codes(cb, tile_base(1));
 
     STAMP(0);
     // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise) with
@@ -258,6 +309,25 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         sm_qt[wave * kD + lane] = x0;
         sm_qt[wave * kD + 64 + lane] = x1;
+    } else if (has_new && wave == kG) {
+        // k~ = (k / lambda) H_D of the new token (Eq. 9), operation for operation what the
+        // cache-fill kernels compute (true division, butterfly stages at distance 1, 2, .. 64,
+        // then 1/sqrt D), so that the fused step writes the codes a separate append would
+        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
+        float x1 = __half2float(p.k_new[bg * kD + 64 + lane]) / p.lam[(size_t)g * kD + 64 + lane];
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) {
+            const float o0 = __shfl_xor(x0, st), o1 = __shfl_xor(x1, st);
+            const bool up = (lane & st) != 0;
+            x0 = up ? (o0 - x0) : (x0 + o0);
+            x1 = up ? (o1 - x1) : (x1 + o1);
+        }
+        const float hs = 1.0f / sqrtf((float)kD);
+        sm_new[lane] = (x0 + x1) * hs;
+        sm_new[64 + lane] = (x0 - x1) * hs;
+    } else if (has_new && wave == kG + 1) {
+        sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
+        sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
     }
     __syncthreads();
     STAMP(1);
@@ -278,6 +348,71 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 const _Float16 lo = (_Float16)(x - (float)hi);
                 bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
             }
+    }
+
+    // ---- fused append: this workgroup's sub-spaces of the new token, one (sub-space, key | value)
+    // item per wavefront in turn.  Eq. 2 by exhaustive search over the table already in LDS: a lane
+    // scans centroids lane, lane + 64, ..; squared distances summed in channel order in fp32; the
+    // lowest index among the centroids at minimum distance wins.  The key item
+    // also leaves the new token's score share of its sub-space for the 4 heads, the value item
+    // the dequantized channels, for the merge kernel.
+    if (has_new) {
+        const long long pos = len - 1;
+        const float fold = kLog2e / (float)kD;
+        int item = 0;
+        for (int m = s; m < M; m += p.S) {
+#pragma unroll
+            for (int kv = 0; kv < 2; ++kv, ++item) {
+                if (item % NW != wave_u) continue;
+                const unsigned char *tab = (kv == 0 ? sm_k : sm_v) + m * SUBSPACE_BYTES;
+                float x[DSUB];
+#pragma unroll
+                for (int j = 0; j < DSUB; ++j) x[j] = sm_new[kv * kD + m * DSUB + j];
+                float best = INFINITY;
+                unsigned arg = 0;
+#pragma unroll
+                for (int i = 0; i < kCentroids / 64; ++i) {
+                    const unsigned c = lane + 64 * i;
+                    _Float16 cen[DSUB];
+                    __builtin_memcpy(cen, tab + c * ENTRY, ENTRY);
+                    float dist = 0.f;
+#pragma unroll
+                    for (int j = 0; j < DSUB; ++j) {
+                        const float tdiff = x[j] - (float)cen[j];
+                        dist = fmaf(tdiff, tdiff, dist);
+                    }
+                    if (dist < best) {
+                        best = dist;
+                        arg = c;
+                    }
+                }
+                // a non-negative fp32 orders like its bit pattern
+                const unsigned dmin = wave_umin(__float_as_uint(best));
+                const unsigned code = wave_umin(__float_as_uint(best) == dmin ? arg : 0xffffffffu);
+                _Float16 win[DSUB];
+                __builtin_memcpy(win, tab + code * ENTRY, ENTRY);
+                if (kv == 0) {
+                    if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
+                    if (lane < kG) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int j = 0; j < DSUB; ++j)
+                            sc = fmaf(sm_qt[lane * kD + m * DSUB + j] * fold, (float)win[j], sc);
+                        p.new_sc[((size_t)bg * M + m) * kG + lane] = sc;
+                        sm_nsc[m * kG + lane] = sc;
+                    }
+                } else {
+                    if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
+                    float mine = (float)win[0];
+#pragma unroll
+                    for (int j = 1; j < DSUB; ++j) mine = lane == j ? (float)win[j] : mine;
+                    if (lane < DSUB) {
+                        p.new_v[(size_t)bg * kD + m * DSUB + lane] = mine;
+                        sm_nv[m * DSUB + lane] = mine;
+                    }
+                }
+            }
+        }
     }
 
     STAMP(2);
@@ -484,27 +619,33 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
     // its last gather has been issued.  Loads past the end of the split return code 0 (buffer
     // range check), so the refill and the look-ahead gathers need no bounds branch.
+    STAMPW(0);
     {
-        const long long stride = tile_stride;
-        long long tb = tb0;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             ka[2 * st] = gather_k(ca, st, 0);
             ka[2 * st + 1] = gather_k(ca, st, 1);
         }
-        for (; tb < n1; tb += 2 * stride) {
-            process_tile(ca, cb, tb, tb + 2 * stride);
-            if (tb + stride < n1) process_tile(cb, ca, tb + stride, tb + 3 * stride);
+        // a wavefront's tile bases increase with k: once one is past the end, all later ones are
+        long long ta = tile_base(0), tb = tile_base(1);
+        for (int k = 2; ta < n1; k += 2) {
+            const long long tc = tile_base(k), td = tile_base(k + 1);
+            process_tile(ca, cb, ta, tc);
+            if (tb < n1) process_tile(cb, ca, tb, td);
+            ta = tc;
+            tb = td;
         }
     }
 
     STAMP(3);
+    STAMPW(1);
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
     float l_head = l_part + quad_xor<1>(l_part);
     l_head += quad_xor<2>(l_head);
     l_head += __shfl_xor(l_head, 16);
     l_head += __shfl_xor(l_head, 32);
     __syncthreads();
+    STAMPW(2);
     float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][128]
     float *const sm_m = sm_o + NW * kG * kD;                              // [NW][4]
     float *const sm_l = sm_m + NW * kG;                                   // [NW][4]
@@ -534,22 +675,38 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             o += f * sm_o[w * kG * kD + e];
             l += f * sm_l[w * kG + hh];
         }
-        const size_t pi = (bg * p.S + s) * kG;
-        p.part_o[pi * kD + e] = o;
-        if ((e & 127) == 0) {
-            p.part_m[pi + hh] = mx;
-            p.part_l[pi + hh] = l;
+        if (p.S == 1 && !p.k_res) {
+            // the workgroup holds the whole answer (a single split also encoded every sub-space of
+            // a fused new token): fold the new token in and write the output rows
+            if (has_new) {
+                float s_new = 0.f;
+                for (int m = 0; m < M; ++m) s_new += sm_nsc[m * kG + hh];
+                const float mt = fmaxf(mx, s_new);
+                const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
+                o = f * o + wgt * sm_nv[e & 127];
+                l = f * l + wgt;
+                mx = mt;
+            }
+            const size_t row = (size_t)b * p.Hq + g * kG + hh;
+            p.out[row * kD + (e & 127)] = __float2half(l > 0.f ? o / l : 0.f);
+            if ((e & 127) == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
+        } else {
+            const size_t pi = (bg * p.S + s) * kG;
+            p.part_o[pi * kD + e] = o;
+            if ((e & 127) == 0) {
+                p.part_m[pi + hh] = mx;
+                p.part_l[pi + hh] = l;
+            }
         }
     }
     STAMP(4);
-    finish_split<BLOCK>(p, b, g);
     STAMP(5);
 }
 
 template <int DSUB, int NW, bool SPLITQ>
 int launch_typed(const DecodeParams &p, hipStream_t stream)
 {
-    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * kG * kD + 16;
+    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((kG + 3) * kD + (kD / DSUB) * kG) + 16;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<DSUB, NW, SPLITQ>),

@@ -201,6 +201,13 @@ __device__ __forceinline__ void encode_token(const EncodeParams &p, float *x_s, 
     const long long t = blockIdx.x;
     const int bg = blockIdx.z;
     const int g = bg % p.Hkv;
+    long long pos = p.pos0 + t;
+    if (p.seq_lens) {                          // per-sequence position: the last token of the sequence
+        const long long v = p.seq_lens[bg / p.Hkv];
+        const long long len = v < 0 ? 0 : (v > p.len_max ? p.len_max : v);
+        if (len == 0) return;                  // uniform over the workgroup
+        pos = len - 1;
+    }
 
     if (tid < D) {
         float v = __half2float(p.x[((size_t)bg * p.T + t) * D + tid]);
@@ -260,7 +267,7 @@ __device__ __forceinline__ void encode_token(const EncodeParams &p, float *x_s, 
                 key = other < key ? other : key;
             }
             if (part == 0 && mm < MC)
-                p.idx[((size_t)bg * p.n_cap + p.pos0 + t) * M + m0 + mm] = (uint8_t)(key & 255u);
+                p.idx[((size_t)bg * p.n_cap + pos) * M + m0 + mm] = (uint8_t)(key & 255u);
         }
         __syncthreads();
     }

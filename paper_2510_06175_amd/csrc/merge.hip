@@ -20,7 +20,7 @@ static_assert(kRowsPerWave == 16, "a wave scores 16 window rows with 16x16x32 MF
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// One workgroup per (KV head g, sequence b); D = head dim, HB = bound on G (4 or 8).
+// One workgroup per (KV head g, sequence b); D = head dim, HB = bound on G (4 or 8), MODE below.
 //
 // Merge (the paper returns L from each tile loop, Alg. 1 step 22, and leaves the merge to the reader):
 //   M = max_s m_s,  w_s = 2^(m_s - M),  o = sum_s w_s o_s / sum_s w_s l_s,  L = (M + log2 sum) ln 2.
@@ -42,15 +42,25 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 //           from the owning lane by v_readlane.
 // Window loads are clamped to row R - 1 (always inside the allocation) and masked by the
 // sequence's own window length afterwards, so they do not wait for that length to arrive.
-template <int D, int HB, bool WINDOW>
+//
+// New token (MODE = kNewToken, the fused append of Eq. 9): the attention kernel left, per key
+// sub-space, the new token's score share for each head and, per channel, its dequantized
+// value; the token joins as the partial (m = sum of the shares, l = 1, o = value).
+enum { kPlain = 0, kWindow = 1, kNewToken = 2 };
+
+template <int D, int HB, int MODE>
 __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
 {
+    constexpr bool WINDOW = MODE == kWindow;
+    constexpr int kMaxM = D / 2;                                      // key sub-spaces at d = 2
     constexpr int kSteps = D / 32;                                   // MFMA k-steps over the head dimension
     constexpr int kElems = (HB * D + kThreads - 1) / kThreads;       // output elements per thread
     constexpr int kML = kMaxSplits * HB / kThreads;                  // (m, l) table entries per thread
     __shared__ float pm_s[kMaxSplits * HB], pl_s[kMaxSplits * HB];   // [s][hh], padded to a multiple of kBatch splits
     __shared__ float wo_s[WINDOW ? kWaves * HB * D : 1];             // wave partial outputs, [wave][hh][c]
     __shared__ float wm_s[kWaves * HB], wl_s[kWaves * HB];
+    __shared__ float ns_s[MODE == kNewToken ? kMaxM * HB : 1];      // [m][hh] score shares of the new token
+    __shared__ float nv_s[MODE == kNewToken ? D : 1];
 
     const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int w = t >> 6, lane = t & 63;
@@ -89,6 +99,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
                 vv[r] = *reinterpret_cast<const unsigned *>(vg + (size_t)vrow * D + c2);
             }
         }
+    }
+
+    // new token: its shares and value (read unconditionally; ignored for an empty sequence)
+    const long long len_b = MODE == kNewToken ? seq_len_of(p, b) : 0;
+    float nsc = 0.f, nvv = 0.f;
+    if (MODE == kNewToken) {
+        if (t < p.Mk * G) nsc = p.new_sc[bg * p.Mk * G + t];
+        if (t < D) nvv = p.new_v[bg * D + t];
     }
 
     // ---- 2. split partials: this thread's o_s of the first kBatch splits, and its share of the (m, l) table
@@ -157,6 +175,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
         }
     }
 
+    if (MODE == kNewToken) {
+        if (t < p.Mk * G) ns_s[t] = nsc;
+        if (t < D) nv_s[t] = nvv;
+    }
+
     // ---- 4. (m, l) table -> LDS, padded with empty splits up to a multiple of kBatch
     const int Spad = (S + kBatch - 1) / kBatch * kBatch;
 #pragma unroll
@@ -171,6 +194,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
 
     // ---- 5. merge and write the rows
     const int n_waves = WINDOW ? (r_len + kRowsPerWave - 1) / kRowsPerWave : 0;
+    const bool new_tok = MODE == kNewToken && len_b > 0;
 #pragma unroll
     for (int i = 0; i < kElems; ++i) {
         const int e = t + i * kThreads;
@@ -179,6 +203,12 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
         float M = -INFINITY;
         for (int s = 0; s < S; ++s) M = fmaxf(M, pm_s[s * G + hh]);
         for (int ww = 0; ww < n_waves; ++ww) M = fmaxf(M, wm_s[ww * HB + hh]);
+        float s_new = -INFINITY;
+        if (new_tok) {
+            s_new = 0.f;
+            for (int m = 0; m < p.Mk; ++m) s_new += ns_s[m * G + hh];
+            M = fmaxf(M, s_new);
+        }
         const float Mc = M > -INFINITY ? M : 0.f;            // nothing to attend to: all weights 0
         float den = 0.f, acc = 0.f;
         if (S > 0) {
@@ -206,6 +236,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
             den = fmaf(wgt, wl_s[ww * HB + hh], den);
             acc = fmaf(wgt, wo_s[(ww * HB + hh) * D + c], acc);
         }
+        if (new_tok) {
+            const float wgt = __builtin_amdgcn_exp2f(s_new - Mc);
+            den += wgt;
+            acc = fmaf(wgt, nv_s[c], acc);
+        }
         const size_t row = (size_t)b * p.Hq + g * G + hh;
         p.out[row * D + c] = __float2half(den > 0.f ? acc / den : 0.f);
         if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
@@ -217,9 +252,11 @@ int launch_for(const DecodeParams &p, hipStream_t stream)
 {
     const dim3 grid(p.Hkv, p.B), block(kThreads);
     if (p.k_res)
-        hipLaunchKernelGGL((merge_kernel<D, HB, true>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kWindow>), grid, block, 0, stream, p);
+    else if (p.k_new)
+        hipLaunchKernelGGL((merge_kernel<D, HB, kNewToken>), grid, block, 0, stream, p);
     else
-        hipLaunchKernelGGL((merge_kernel<D, HB, false>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kPlain>), grid, block, 0, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

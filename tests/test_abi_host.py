@@ -123,6 +123,22 @@ def test_decode_residual_argument_errors():
     assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 0, 0) == vb.vecinfer_decode_workspace_bytes(CFG, 1, 1, 1) > 0
 
 
+def test_decode_step_argument_errors():
+    def step(cfg=CFG, kn=FAKE, vn=FAKE, ki=FAKE, vi=FAKE, N=1024, n_cap=1024, S=4, variant=0, ws=None, ws_bytes=0):
+        return vb.lib().vecinfer_decode_step(C.byref(cfg.c()), FAKE, kn, vn, FAKE, FAKE, FAKE, ki, vi, None, 1, N,
+                                             n_cap, S, variant, ws, ws_bytes, FAKE, None, None)
+    assert step(kn=None) == vb.EINVAL
+    assert step(vn=None) == vb.EINVAL
+    assert step(ki=None) == vb.EINVAL
+    assert step(kn=FAKE + 4) == vb.EINVAL
+    assert step(N=0) == vb.EINVAL                               # the new token itself makes N >= 1
+    assert step(N=2048) == vb.EINVAL
+    assert step(cfg=vb.Config(128, 32, 8, 4, 4, k_bits=4)) == vb.EUNSUPPORTED
+    assert step(cfg=vb.Config(64, 8, 8, 4, 4), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    need = vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, 4)
+    assert step(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
+
+
 def test_workspace_size_and_auto_splits():
     assert vb.vecinfer_decode_workspace_bytes(vb.Config(96, 32, 8, 4, 4), 1, 1024, 4) == 0
     assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, vb.MAX_SPLITS + 1) == 0

@@ -347,3 +347,112 @@ def test_decode_residual_full_size_196k():
     ref = _oracle_residual(x)
     got = gpu_decode_residual(shape, x)
     assert_decode_close(*got, *ref, what="196k + window")
+
+
+# ------------------------------------------------------------------ fused decode step (Eq. 9 + Eq. 10)
+
+def _new_token(shape, seed):
+    g = synth.rng(seed)
+    k, _ = synth.keys_with_outlier_channels(g, shape.B, shape.Hkv, 1, shape.D, 3)
+    return k, synth.values(g, shape.B, shape.Hkv, 1, shape.D)
+
+
+def _gpu_step(shape, x, k_new, v_new, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT_AUTO):
+    cfg = cfg_of(shape)
+    t = {k: dev(v) for k, v in x.items() if k in ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx")}
+    B, n_cap = shape.B, x["k_idx"].shape[2]
+    N = n_cap if N is None else N
+    ws = vb.new_workspace(cfg, B, N, num_splits)
+    out = torch.full((B, shape.Hq, shape.D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((B, shape.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    sl = None if seq_lens is None else torch.as_tensor(np.asarray(seq_lens), dtype=torch.int32).cuda()
+    vb.vecinfer_decode_step(cfg, t["q"], dev(k_new), dev(v_new), t["lam"], t["cb_k"], t["cb_v"], t["k_idx"],
+                            t["v_idx"], ws, out, lse=lse, seq_lens=sl, N=N, num_splits=num_splits, variant=variant)
+    torch.cuda.synchronize()
+    return (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64),
+            t["k_idx"].cpu().numpy(), t["v_idx"].cpu().numpy())
+
+
+def _check_step(shape, x, k_new, v_new, got, lens, what):
+    """Codes of the new token against the oracle's encode (near-ties logged), every other row
+    untouched, and the attention against the oracle on the cache the step left behind."""
+    out, lse, k_idx, v_idx = got
+    ref_k, gap_k = oracle.encode_keys(k_new, x["lam"], x["cb_k"], want_gap=True)
+    ref_v, gap_v = oracle.encode_values(v_new, x["cb_v"], want_gap=True)
+    exp_k, exp_v = x["k_idx"].copy(), x["v_idx"].copy()
+    for b in range(shape.B):
+        if lens[b] == 0:
+            continue
+        pos = lens[b] - 1
+        assert_indices_match(k_idx[b, :, pos], ref_k[b, :, 0], gap_k[b, :, 0], f"{what}: key codes b={b}")
+        assert_indices_match(v_idx[b, :, pos], ref_v[b, :, 0], gap_v[b, :, 0], f"{what}: value codes b={b}")
+        exp_k[b, :, pos] = k_idx[b, :, pos]
+        exp_v[b, :, pos] = v_idx[b, :, pos]
+    np.testing.assert_array_equal(k_idx, exp_k)          # no other row was written
+    np.testing.assert_array_equal(v_idx, exp_v)
+    keep = [b for b in range(shape.B) if lens[b] > 0]
+    ref = oracle.decode_attention(x["q"][keep], x["lam"], x["cb_k"], x["cb_v"], k_idx[keep], v_idx[keep],
+                                  np.asarray(lens)[keep])
+    assert_decode_close(out[keep], lse[keep], *ref, what=what)
+    for b in range(shape.B):
+        if lens[b] == 0:
+            assert (out[b] == 0).all() and np.isneginf(lse[b]).all()
+
+
+STEP_SHAPES = [
+    synth.Shape(2, 8, 2, 128, 777, 4, 4),
+    synth.Shape(1, 8, 2, 128, 1500, 2, 2),
+    synth.Shape(1, 4, 1, 128, 4099, 4, 4),
+    synth.Shape(1, 4, 2, 64, 513, 4, 2),
+    synth.Shape(1, 8, 1, 64, 300, 8, 8),
+]
+
+
+@pytest.mark.parametrize("vname", list(VARIANTS))
+@pytest.mark.parametrize("shape", STEP_SHAPES, ids=lambda s: f"B{s.B}h{s.Hq}-{s.Hkv}D{s.D}N{s.N}k{s.d_k}v{s.d_v}")
+@pytest.mark.parametrize("splits", [1, 5, 64, 0])
+def test_decode_step(shape, splits, vname):
+    variant = VARIANTS[vname]
+    if not _supported(shape, variant):
+        pytest.skip("variant does not cover this configuration")
+    x = synth.decode_inputs(shape, seed=shape.N + 31)
+    k_new, v_new = _new_token(shape, seed=shape.N + 32)
+    got = _gpu_step(shape, x, k_new, v_new, num_splits=splits, variant=variant)
+    _check_step(shape, x, k_new, v_new, got, [shape.N] * shape.B, f"step {vname} S={splits}")
+
+
+@pytest.mark.parametrize("vname", list(VARIANTS))
+def test_decode_step_ragged_and_degenerate(vname):
+    """Per-sequence append positions; a sequence whose only token is the new one; an empty one."""
+    shape = synth.Shape(4, 8, 2, 128, 900, 4, 4)
+    x = synth.decode_inputs(shape, seed=41, n_cap=1000)
+    k_new, v_new = _new_token(shape, seed=42)
+    lens = [900, 1, 0, 334]
+    got = _gpu_step(shape, x, k_new, v_new, seq_lens=lens, N=900, num_splits=4, variant=VARIANTS[vname])
+    _check_step(shape, x, k_new, v_new, got, lens, f"ragged step {vname}")
+
+
+def test_decode_step_equals_append_then_attend():
+    """The fused step writes exactly the codes of vecinfer_append_kv and returns the numbers of
+    vecinfer_decode_attention on the result, up to the rounding of one more merged partial."""
+    shape = synth.Shape(2, 8, 2, 128, 2049, 4, 4)
+    x = synth.decode_inputs(shape, seed=43)
+    k_new, v_new = _new_token(shape, seed=44)
+    out, lse, k_idx, v_idx = _gpu_step(shape, x, k_new, v_new)
+    cfg = cfg_of(shape)
+    k2, v2 = dev(x["k_idx"]), dev(x["v_idx"])
+    vb.vecinfer_append_kv(cfg, dev(k_new), dev(v_new), dev(x["lam"]), dev(x["cb_k"]), dev(x["cb_v"]), k2, v2,
+                          pos0=shape.N - 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(k_idx, k2.cpu().numpy())
+    np.testing.assert_array_equal(v_idx, v2.cpu().numpy())
+    ref = gpu_decode(shape, dict(x, k_idx=k2, v_idx=v2))
+    assert_decode_close(out, lse, *ref, what="fused vs separate")
+
+
+def test_decode_step_full_size_196k():
+    shape = synth.LLAMA8B_196K
+    x = synth.decode_inputs(shape, seed=4)
+    k_new, v_new = _new_token(shape, seed=45)
+    got = _gpu_step(shape, x, k_new, v_new)
+    _check_step(shape, x, k_new, v_new, got, [shape.N], "step 196k")
