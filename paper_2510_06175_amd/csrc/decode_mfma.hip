@@ -134,6 +134,13 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     constexpr int KW = M / 16;                         // key-code dwords per lane per sub-tile: 2 or 4
     constexpr int NROUND_V = M / 16;                   // value MFMA rounds per P.V step: 2 or 4
     constexpr int VW = DSUB == 4 ? 2 : 4;              // value-code registers per lane per sub-tile
+    // LDS layout of the value codebook: [r][code][col] with sub-space m = NROUND_V * col + r.
+    // LDS serves a gather 16 lanes at a time, and the 16 lanes of such a group read the same r
+    // and 16 different col: with the 16 entries of a code in one ROW_V-byte row they fall on
+    // disjoint banks whatever their codes are (4.4 instead of 6.7 cycles per gather).  The key
+    // codebook keeps the [m][code] order: the 16 lanes of a group all read one sub-space there.
+    constexpr int ROW_V = 16 * ENTRY;                  // 128 or 64 bytes
+    constexpr int PLANE_V = kCentroids * ROW_V;        // one r: 32768 or 16384 bytes
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *const sm_k = smem;
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     //                   values sub-space NROUND_V*col + r
     const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
     const unsigned lds_k = lds_base + (unsigned)(kg * (M / 4) * SUBSPACE_BYTES);
-    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * NROUND_V * SUBSPACE_BYTES);
+    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * ENTRY);
 
     const uint8_t *krow = p.k_idx + bg * p.n_cap * M;
     const uint8_t *vrow = p.v_idx + bg * p.n_cap * M;
@@ -255,7 +262,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     auto tile_base = [&](int k) -> long long {          // first token of this wavefront's k-th tile
         constexpr int kFull = 11, kPeriod = (kFull + 1) * NW;
         int per, off;
-        if (wave_u < NW / 2) {
+        if (NW != 8) {
+            per = 0;
+            off = k * NW + wave_u;                          // plain round-robin
+        } else if (wave_u < NW / 2) {
             per = k / (kFull + 2);
             const int i = k % (kFull + 2);
             off = i < kFull ? i * NW + wave_u : kFull * NW + (i - kFull) * (NW / 2) + wave_u;
@@ -271,23 +281,49 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     load_codes(cb, tile_base(1));
 
     STAMP(0);
-    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise) with
-    // direct global->LDS loads: 1 KB per wavefront instruction (64 lanes x 16 B), no VGPR round
-    // trip, so all of a wavefront's 16 KB is in flight at once.
+#ifdef VECINFER_PROLOGUE_STAMPS
+    STAMPW(0);
+#endif
+    constexpr int CPL = 16 / ENTRY;                    // codes per 16-byte load of the value codebook
+    static_assert(NROUND_V * (32 / (4 * CPL)) == 8, "32 codes of every sub-space take 8 loads");
+    // each codebook is staged as 64 items of 1 KB (one wavefront instruction each), dealt round-robin
+    constexpr int kStageItems = 64, kStagePerWave = (kStageItems + NW - 1) / NW;
+    const int vq = lane >> 4, vcol = lane & 15;
+    uintx4 vreg[kStagePerWave];
+    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise), through
+    // registers: all 16 loads of a wavefront (16 KB) are issued back to back and share one trip
+    // to memory with the first code tiles and the query; the LDS writes come after the q~ section.
+    // (Direct global->LDS loads measured slower here: a wavefront got through its 8 of them at
+    // about one L2 latency each.)
+    uintx4 kreg[kStagePerWave];
     {
-        typedef __attribute__((address_space(1))) const void *gptr_t;
-        typedef __attribute__((address_space(3))) void *lptr_t;
         const unsigned char *srck = reinterpret_cast<const unsigned char *>(p.cb_k + (size_t)g * kCentroids * kD);
         const unsigned char *srcv = reinterpret_cast<const unsigned char *>(p.cb_v + (size_t)g * kCentroids * kD);
-        constexpr int kChunks = CB_BYTES / 1024;           // per codebook
+        // keys keep the [m][code] order: item = 1 KB chunk, 16 bytes per lane
 #pragma unroll
-        for (int c = wave; c < kChunks; c += NW) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(srck + c * 1024 + lane * 16),
-                                             (lptr_t)(sm_k + c * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(srcv + c * 1024 + lane * 16),
-                                             (lptr_t)(sm_v + c * 1024), 16, 0, 0);
+        for (int j = 0; j < kStagePerWave; ++j) {
+            const int it = wave + NW * j;
+            if (kStageItems % NW == 0 || it < kStageItems)
+                kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
+        }
+        // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
+        // (CPL = 16 / ENTRY consecutive codes of one sub-space) and writes them entry by entry.
+        // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
+        // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
+        // bytes of 16 tables.  A wavefront covers 32 codes of every sub-space in 8 loads:
+        // instruction i serves r = i / (8 / NROUND_V), code group i % (8 / NROUND_V), so that
+        // instructions next to each other read the two halves of the same cache lines.
+#pragma unroll
+        for (int j = 0; j < kStagePerWave; ++j) {
+            const int it = wave + NW * j, i = it & 7;        // item = (32-code block it / 8, instruction i)
+            const int r = i / (8 / NROUND_V), code = 32 * (it >> 3) + (i % (8 / NROUND_V)) * 4 * CPL + vq * CPL;
+            if (kStageItems % NW == 0 || it < kStageItems)
+                vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUBSPACE_BYTES + code * ENTRY);
         }
     }
+#ifdef VECINFER_PROLOGUE_STAMPS
+    STAMPW(2);
+#endif
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
@@ -329,6 +365,28 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
         sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
     }
+    // second half of the codebook staging: registers -> LDS
+#pragma unroll
+    for (int j = 0; j < kStagePerWave; ++j) {
+        const int it = wave + NW * j;
+        if (kStageItems % NW == 0 || it < kStageItems)
+            *reinterpret_cast<uintx4 *>(sm_k + it * 1024 + lane * 16) = kreg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < kStagePerWave; ++j) {
+        const int it = wave + NW * j, i = it & 7;
+        const int r = i / (8 / NROUND_V), code = 32 * (it >> 3) + (i % (8 / NROUND_V)) * 4 * CPL + vq * CPL;
+        if (kStageItems % NW == 0 || it < kStageItems) {
+#pragma unroll
+            for (int e = 0; e < CPL; ++e) {
+                unsigned char *const d = sm_v + r * PLANE_V + (code + e) * ROW_V + vcol * ENTRY;
+                if (DSUB == 4)
+                    *reinterpret_cast<uintx2 *>(d) = uintx2{vreg[j][2 * e], vreg[j][2 * e + 1]};
+                else
+                    *reinterpret_cast<unsigned *>(d) = vreg[j][e];
+            }
+        }
+    }
     __syncthreads();
     STAMP(1);
 
@@ -364,7 +422,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #pragma unroll
             for (int kv = 0; kv < 2; ++kv, ++item) {
                 if (item % NW != wave_u) continue;
-                const unsigned char *tab = (kv == 0 ? sm_k : sm_v) + m * SUBSPACE_BYTES;
+                // entry c of the sub-space sits at tab + c * stride (value tables are transposed)
+                const unsigned char *tab = kv == 0 ? sm_k + m * SUBSPACE_BYTES
+                                                   : sm_v + (m % NROUND_V) * PLANE_V + (m / NROUND_V) * ENTRY;
+                const int stride = kv == 0 ? ENTRY : ROW_V;
                 float x[DSUB];
 #pragma unroll
                 for (int j = 0; j < DSUB; ++j) x[j] = sm_new[kv * kD + m * DSUB + j];
@@ -374,7 +435,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 for (int i = 0; i < kCentroids / 64; ++i) {
                     const unsigned c = lane + 64 * i;
                     _Float16 cen[DSUB];
-                    __builtin_memcpy(cen, tab + c * ENTRY, ENTRY);
+                    __builtin_memcpy(cen, tab + c * stride, ENTRY);
                     float dist = 0.f;
 #pragma unroll
                     for (int j = 0; j < DSUB; ++j) {
@@ -390,7 +451,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 const unsigned dmin = wave_umin(__float_as_uint(best));
                 const unsigned code = wave_umin(__float_as_uint(best) == dmin ? arg : 0xffffffffu);
                 _Float16 win[DSUB];
-                __builtin_memcpy(win, tab + code * ENTRY, ENTRY);
+                __builtin_memcpy(win, tab + code * stride, ENTRY);
                 if (kv == 0) {
                     if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
                     if (lane < kG) {
@@ -427,6 +488,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     auto lds_addr = [&](unsigned w, int k, unsigned base) -> unsigned {
         return __builtin_amdgcn_udot4(w, (unsigned)ENTRY << (8 * k), base, false);
     };
+    auto lds_addr_v = [&](unsigned w, int k, unsigned base) -> unsigned {   // code * ROW_V + base
+        return __builtin_amdgcn_udot4(w, (unsigned)ROW_V << (8 * k), base, false);
+    };
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
@@ -454,14 +518,14 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         if (DSUB == 4) {
             const int u = q >> 1, r = q & 1;
             const unsigned w = cd.vc[st][u];          // bytes: (token 2u: r = 0, 1), (token 2u+1: r = 0, 1)
-            const uint2 x0 = lds_load_b64(lds_addr(w, r, lds_v) + r * SUBSPACE_BYTES);
-            const uint2 x1 = lds_load_b64(lds_addr(w, 2 + r, lds_v) + r * SUBSPACE_BYTES);
+            const uint2 x0 = lds_load_b64(lds_addr_v(w, r, lds_v) + r * PLANE_V);
+            const uint2 x1 = lds_load_b64(lds_addr_v(w, 2 + r, lds_v) + r * PLANE_V);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
             unsigned x[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                x[v] = lds_load_b32(lds_addr(cd.vc[st][v], q, lds_v) + q * SUBSPACE_BYTES);
+                x[v] = lds_load_b32(lds_addr_v(cd.vc[st][v], q, lds_v) + q * PLANE_V);
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
@@ -619,7 +683,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
     // its last gather has been issued.  Loads past the end of the split return code 0 (buffer
     // range check), so the refill and the look-ahead gathers need no bounds branch.
+#ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(0);
+#endif
     {
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
@@ -638,14 +704,18 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     }
 
     STAMP(3);
+#ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(1);
+#endif
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
     float l_head = l_part + quad_xor<1>(l_part);
     l_head += quad_xor<2>(l_head);
     l_head += __shfl_xor(l_head, 16);
     l_head += __shfl_xor(l_head, 32);
     __syncthreads();
+#ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(2);
+#endif
     float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][128]
     float *const sm_m = sm_o + NW * kG * kD;                              // [NW][4]
     float *const sm_l = sm_m + NW * kG;                                   // [NW][4]
@@ -735,7 +805,7 @@ bool decode_mfma_supports(const DecodeParams &p)
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
-    // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster, 4 is latency-bound
+    // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster (LDS-bound), 4 is latency-bound
     return p.dk == 4 ? launch_typed<4, 8, true>(p, stream) : launch_typed<2, 8, true>(p, stream);
 }
 
