@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="196k-b2d4",
-                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32"])
+                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
@@ -66,7 +66,8 @@ def main() -> int:
     from paper_2510_06175_amd import synth
 
     shape = {"196k-b2d4": synth.LLAMA8B_196K, "196k-b4d2": synth.LLAMA8B_196K_B4D2,
-             "32k": synth.LLAMA8B_32K, "batch32": synth.LLAMA8B_BATCH32}[args.workload]
+             "32k": synth.LLAMA8B_32K, "batch32": synth.LLAMA8B_BATCH32,
+             "196k-d64": synth.HEADDIM64_196K}[args.workload]
     cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v)
     variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
     idx_bytes = shape.index_bytes()
@@ -154,7 +155,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8 codes, f16 tables, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"llama-3.1-8b layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
+        "config": {"workload": f"{'llama-3.1-8b' if shape.D == 128 else 'head-dim-64'} layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
                                f"D={shape.D}, N={shape.N}, K d{shape.d_k}b8 / V d{shape.d_v}b8",
                    "step": f"attention over the code cache and a {args.residual}-token fp16 window" if args.residual
                    else "attention only" if args.decode_only

@@ -1,5 +1,5 @@
-// Matrix-core decode attention for gfx950: D = 128, G = 4 query heads per KV head,
-// sub-vector dim d = 4 (32 sub-spaces) or d = 2 (64 sub-spaces), 8-bit codes.
+// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 4 query heads per KV
+// head, sub-vector dim d = 4 or 2 (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
 //
 // Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
 // row is never assembled: each lane gathers a few centroids with ds_read and hands them
@@ -48,7 +48,6 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
-constexpr int kD = 128;
 constexpr int kG = 4;
 constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
 
@@ -123,17 +122,21 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
     return (unsigned)b | ((unsigned)b << 16);
 }
 
-template <int DSUB, int NW, bool SPLITQ>
+template <int kD, int DSUB, int NW, bool SPLITQ>
 __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 {
+    static_assert((kD == 128 || kD == 64) && (DSUB == 4 || DSUB == 2), "shapes this kernel is laid out for");
     constexpr int BLOCK = NW * 64;
-    constexpr int M = kD / DSUB;                       // sub-spaces: 32 or 64
-    constexpr int CB_BYTES = kCentroids * kD * 2;      // one codebook set of a KV head: 64 KB
+    constexpr int M = kD / DSUB;                       // sub-spaces: 16, 32 or 64
+    constexpr int CB_BYTES = kCentroids * kD * 2;      // one codebook set of a KV head: 64 or 32 KB
     constexpr int ENTRY = DSUB * 2;                    // bytes per centroid: 8 or 4
     constexpr int SUBSPACE_BYTES = kCentroids * ENTRY; // 2048 or 1024
-    constexpr int KW = M / 16;                         // key-code dwords per lane per sub-tile: 2 or 4
-    constexpr int NROUND_V = M / 16;                   // value MFMA rounds per P.V step: 2 or 4
-    constexpr int VW = DSUB == 4 ? 2 : 4;              // value-code registers per lane per sub-tile
+    constexpr int NR = kD / 32;                        // score MFMA rounds (32 channels each): 4 or 2;
+                                                       // also the P.V operands (and MFMAs) per sub-tile
+    constexpr int H = NR / 2;                          // rounds per pipeline stage
+    constexpr int KW = (M / 4 + 3) / 4;                // key-code dwords per lane per sub-tile (M / 4 bytes)
+    constexpr int NROUND_V = M / 16;                   // value sub-spaces per MFMA column: 1, 2 or 4
+    constexpr int VW = NROUND_V;                       // value-code dwords per lane per sub-tile (4 tokens x NROUND_V bytes)
     // LDS layout of the value codebook: [r][code][col] with sub-space m = NROUND_V * col + r.
     // LDS serves a gather 16 lanes at a time, and the 16 lanes of such a group read the same r
     // and 16 different col: with the 16 entries of a code in one ROW_V-byte row they fall on
@@ -145,10 +148,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *const sm_k = smem;
     unsigned char *const sm_v = smem + CB_BYTES;
-    float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][128]
-    float *const sm_new = sm_qt + kG * kD;                                 // [2][128]: k~ and v of the new token
+    float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][D]
+    float *const sm_new = sm_qt + kG * kD;                                 // [2][D]: k~ and v of the new token
     float *const sm_nsc = sm_new + 2 * kD;                                 // [M][4]: its score shares (log2 units)
-    float *const sm_nv = sm_nsc + M * kG;                                  // [128]:  its dequantized value
+    float *const sm_nv = sm_nsc + M * kG;                                  // [D]:    its dequantized value
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
@@ -228,15 +231,25 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         const unsigned ko = base + koff_lane, vo = base + voff_lane;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            if (DSUB == 4) {
+            // keys: the M / 4 code bytes of the lane's k-slot range of its token
+            if constexpr (M / 4 == 4) {
+                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * M, 0, 0);
+            } else if constexpr (M / 4 == 8) {
                 const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * M, 0, 0);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1];
             } else {
                 const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * M, 0, 0);
-                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][KW - 2] = w[2]; cd.kc[st][KW - 1] = w[3];
+                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][2] = w[2]; cd.kc[st][3] = w[3];
             }
-            if (DSUB == 4) {
-                // two bytes (sub-spaces 2 col, 2 col + 1) per token; tokens 2u, 2u+1 share a register
+            // values: NROUND_V bytes (sub-spaces NROUND_V col ..) of each of the tokens 4 v + kg,
+            // packed token after token: byte v * NROUND_V + r
+            if constexpr (NROUND_V == 1) {
+                unsigned w = 0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * M, 0, 0) << (8 * v);
+                cd.vc[st][0] = w;
+            } else if constexpr (NROUND_V == 2) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     ushortx2 t;
@@ -285,9 +298,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMPW(0);
 #endif
     constexpr int CPL = 16 / ENTRY;                    // codes per 16-byte load of the value codebook
-    static_assert(NROUND_V * (32 / (4 * CPL)) == 8, "32 codes of every sub-space take 8 loads");
-    // each codebook is staged as 64 items of 1 KB (one wavefront instruction each), dealt round-robin
-    constexpr int kStageItems = 64, kStagePerWave = (kStageItems + NW - 1) / NW;
+    // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
+    constexpr int kStageItems = CB_BYTES / 1024, kStagePerWave = (kStageItems + NW - 1) / NW;
+    static_assert(NROUND_V * (kCentroids / (4 * CPL)) == kStageItems, "value items: (code group, r)");
     const int vq = lane >> 4, vcol = lane & 15;
     uintx4 vreg[kStagePerWave];
     // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise), through
@@ -310,13 +323,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         // (CPL = 16 / ENTRY consecutive codes of one sub-space) and writes them entry by entry.
         // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
         // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
-        // bytes of 16 tables.  A wavefront covers 32 codes of every sub-space in 8 loads:
-        // instruction i serves r = i / (8 / NROUND_V), code group i % (8 / NROUND_V), so that
-        // instructions next to each other read the two halves of the same cache lines.
+        // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
+        // group it / NROUND_V.
 #pragma unroll
         for (int j = 0; j < kStagePerWave; ++j) {
-            const int it = wave + NW * j, i = it & 7;        // item = (32-code block it / 8, instruction i)
-            const int r = i / (8 / NROUND_V), code = 32 * (it >> 3) + (i % (8 / NROUND_V)) * 4 * CPL + vq * CPL;
+            const int it = wave + NW * j;
+            const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
             if (kStageItems % NW == 0 || it < kStageItems)
                 vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUBSPACE_BYTES + code * ENTRY);
         }
@@ -327,7 +339,17 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
-    if (wave < kG) {
+    if (wave < kG && kD == 64) {
+        // D = 64: one channel per lane, six butterfly stages across lanes
+        const size_t qrow = ((size_t)b * p.Hq + g * kG + wave) * kD;
+        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) {
+            const float o0 = __shfl_xor(x0, st);
+            x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
+        }
+        sm_qt[wave * kD + lane] = x0;
+    } else if (wave < kG) {
         const size_t qrow = ((size_t)b * p.Hq + g * kG + wave) * kD;
         float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
         float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
@@ -345,6 +367,14 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         sm_qt[wave * kD + lane] = x0;
         sm_qt[wave * kD + 64 + lane] = x1;
+    } else if (has_new && wave == kG && kD == 64) {
+        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
+#pragma unroll
+        for (int st = 1; st < 64; st <<= 1) {
+            const float o0 = __shfl_xor(x0, st);
+            x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
+        }
+        sm_new[lane] = x0 * (1.0f / sqrtf((float)kD));
     } else if (has_new && wave == kG) {
         // k~ = (k / lambda) H_D of the new token (Eq. 9), operation for operation what the
         // cache-fill kernels compute (true division, butterfly stages at distance 1, 2, .. 64,
@@ -363,7 +393,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         sm_new[64 + lane] = (x0 - x1) * hs;
     } else if (has_new && wave == kG + 1) {
         sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
-        sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
+        if (kD == 128) sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
     }
     // second half of the codebook staging: registers -> LDS
 #pragma unroll
@@ -374,8 +404,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     }
 #pragma unroll
     for (int j = 0; j < kStagePerWave; ++j) {
-        const int it = wave + NW * j, i = it & 7;
-        const int r = i / (8 / NROUND_V), code = 32 * (it >> 3) + (i % (8 / NROUND_V)) * 4 * CPL + vq * CPL;
+        const int it = wave + NW * j;
+        const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
         if (kStageItems % NW == 0 || it < kStageItems) {
 #pragma unroll
             for (int e = 0; e < CPL; ++e) {
@@ -390,18 +420,18 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     __syncthreads();
     STAMP(1);
 
-    // ---- B operands of the score MFMAs: q~_h[32kg + 8r .. +8); columns with t0 < 2 take the
+    // ---- B operands of the score MFMAs: q~_h[(D/4) kg + 8r .. +8); columns with t0 < 2 take the
     // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
     // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq[4];
+    half8 bq[NR];
     {
         const float fold = kLog2e / (float)kD;
         const int hh = col >> 2;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < NR; ++r)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float x = sm_qt[hh * kD + 32 * kg + 8 * r + e] * fold;
+                const float x = sm_qt[hh * kD + (kD / 4) * kg + 8 * r + e] * fold;
                 const _Float16 hi = (_Float16)x;
                 const _Float16 lo = (_Float16)(x - (float)hi);
                 bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
@@ -495,14 +525,14 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
         if (DSUB == 4) {
-            // sub-spaces 8kg + 2r, 8kg + 2r + 1: code bytes 2r, 2r+1 of the lane's 8
+            // sub-spaces (M/4) kg + 2r, + 2r + 1: code bytes 2r, 2r+1 of the lane's M / 4
             const unsigned w = cd.kc[st][r >> 1];
             const int k0 = 2 * (r & 1);
             const uint2 x0 = lds_load_b64(lds_addr(w, k0, lds_k) + (2 * r) * SUBSPACE_BYTES);
             const uint2 x1 = lds_load_b64(lds_addr(w, k0 + 1, lds_k) + (2 * r + 1) * SUBSPACE_BYTES);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
-            // sub-spaces 16kg + 4r .. +3: the 4 code bytes of dword r
+            // sub-spaces (M/4) kg + 4r .. +3: the 4 code bytes of dword r
             const unsigned w = cd.kc[st][r];
             unsigned x[4];
 #pragma unroll
@@ -511,74 +541,72 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
-    // B operand q (0..3) of the P.V MFMAs of sub-tile st.  d = 4: q = 2u + r (step u, round r):
-    // centroids of sub-space 2 col + r for tokens 2u, 2u+1 of the k-group.  d = 2: q = r:
-    // centroids of sub-space 4 col + r for the 4 tokens of the k-group.
+    // B operand q (0 .. NR-1) of the P.V MFMAs of sub-tile st; the code of (token v of the
+    // k-group, round r) is byte v * NROUND_V + r of the packed value codes.  d = 4:
+    // q = u * NROUND_V + r (step u, round r): centroids of sub-space NROUND_V col + r for tokens
+    // 2u, 2u+1.  d = 2: q = r: centroids of sub-space NROUND_V col + r for the 4 tokens.
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
         if (DSUB == 4) {
-            const int u = q >> 1, r = q & 1;
-            const unsigned w = cd.vc[st][u];          // bytes: (token 2u: r = 0, 1), (token 2u+1: r = 0, 1)
-            const uint2 x0 = lds_load_b64(lds_addr_v(w, r, lds_v) + r * PLANE_V);
-            const uint2 x1 = lds_load_b64(lds_addr_v(w, 2 + r, lds_v) + r * PLANE_V);
+            const int u = q / NROUND_V, r = q % NROUND_V;
+            const int b0 = 2 * u * NROUND_V + r, b1 = (2 * u + 1) * NROUND_V + r;
+            const uint2 x0 = lds_load_b64(lds_addr_v(cd.vc[st][b0 >> 2], b0 & 3, lds_v) + r * PLANE_V);
+            const uint2 x1 = lds_load_b64(lds_addr_v(cd.vc[st][b1 >> 2], b1 & 3, lds_v) + r * PLANE_V);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
             unsigned x[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                x[v] = lds_load_b32(lds_addr_v(cd.vc[st][v], q, lds_v) + q * PLANE_V);
+            for (int v = 0; v < 4; ++v) {
+                const int bi = v * NROUND_V + q;
+                x[v] = lds_load_b32(lds_addr_v(cd.vc[st][bi >> 2], bi & 3, lds_v) + q * PLANE_V);
+            }
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
 
-    half8 ka[8];                     // score operands of rounds 0-1 of the tile about to be processed
+    half8 ka[4 * H];                 // score operands of the first H rounds of the tile about to be processed
     // One tile, as five stages.  In every stage but the softmax the matrix cores work on
     // operands gathered in the previous stage while the vector ALU forms the addresses of, and
     // LDS serves, the gathers of the next one; the scheduling hints interleave the three
     // instruction kinds so that each MFMA's 16 busy cycles are filled:
-    //   1  MFMA K rounds 0-1      | gather K rounds 2-3
-    //   2  MFMA K rounds 2-3      | gather V sub-tiles 0-1
+    //   1  MFMA K first H rounds  | gather K last H rounds          (H = 2 at D = 128, 1 at D = 64)
+    //   2  MFMA K last H rounds   | gather V sub-tiles 0-1
     //   3  online softmax         | gather V sub-tiles 2-3 (issued first, lands under the softmax)
-    //   4  MFMA P.V sub-tiles 0-1 | gather K rounds 0-1 of the NEXT tile
+    //   4  MFMA P.V sub-tiles 0-1 | gather K first H rounds of the NEXT tile
     //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
+    // Every stage pairs 4 H MFMAs with 4 H operand gathers.
     constexpr int kReadsPerOperand = DSUB == 4 ? 2 : 4;        // ds_reads (and address ops) per half8
 #define VI_GROUPS8(MF, OPS, XV, VM)                                                        \
-    _Pragma("unroll") for (int gi = 0; gi < 8; ++gi) {                                      \
+    _Pragma("unroll") for (int gi = 0; gi < 4 * H; ++gi) {                                    \
         __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);                                 \
         __builtin_amdgcn_sched_group_barrier(0x002, (OPS) * kReadsPerOperand + (XV), 0);    \
         __builtin_amdgcn_sched_group_barrier(0x100, (OPS) * kReadsPerOperand, 0);           \
         if ((VM) > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);                   \
     }
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
-        half8 kb[8], va[8], vb[8];
+        half8 kb[4 * H], va[2 * NR], vb[2 * NR];
         const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
         floatx4 sacc[4];
 
         // ---- stage 1
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(ka[2 * st], bq[0], kZero4, 0, 0, 0);
-            kb[2 * st] = gather_k(cd, st, 2);
-        }
+        for (int hr = 0; hr < H; ++hr)
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(ka[2 * st + 1], bq[1], sacc[st], 0, 0, 0);
-            kb[2 * st + 1] = gather_k(cd, st, 3);
-        }
+            for (int st = 0; st < 4; ++st) {
+                sacc[st] = MFMA16(ka[H * st + hr], bq[hr], hr == 0 ? kZero4 : sacc[st], 0, 0, 0);
+                kb[H * st + hr] = gather_k(cd, st, H + hr);
+            }
         VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 2
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(kb[2 * st], bq[2], sacc[st], 0, 0, 0);
-            va[st] = gather_v(cd, 0, st);
-        }
+        for (int hr = 0; hr < H; ++hr)
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            sacc[st] = MFMA16(kb[2 * st + 1], bq[3], sacc[st], 0, 0, 0);
-            va[4 + st] = gather_v(cd, 1, st);
-        }
+            for (int st = 0; st < 4; ++st) {
+                sacc[st] = MFMA16(kb[H * st + hr], bq[H + hr], sacc[st], 0, 0, 0);
+                va[4 * hr + st] = gather_v(cd, (4 * hr + st) / NR, (4 * hr + st) % NR);   // sub-tiles 0, 1
+            }
         VI_GROUPS8(1, 1, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
 
@@ -587,9 +615,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
         // exp once; the P.V operand build below fetches them back across the quad with DPP.
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NR; ++q) {
             vb[q] = gather_v(cd, 2, q);
-            vb[4 + q] = gather_v(cd, 3, q);
+            vb[NR + q] = gather_v(cd, 3, q);
         }
         __builtin_amdgcn_sched_barrier(0);
         if (SPLITQ) {
@@ -645,9 +673,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
                 const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
 #pragma unroll
-                for (int r = 0; r < 2; ++r) acc_o[r] = MFMA16(a0, vops[r], acc_o[r], 0, 0, 0);
+                for (int r = 0; r < NROUND_V; ++r) acc_o[r] = MFMA16(a0, vops[r], acc_o[r], 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < 2; ++r) acc_o[r] = MFMA16(a1, vops[2 + r], acc_o[r], 0, 0, 0);
+                for (int r = 0; r < NROUND_V; ++r) acc_o[r] = MFMA16(a1, vops[NROUND_V + r], acc_o[r], 0, 0, 0);
             } else {
                 const half8 a = as_half8(p0 & mask_a, p1 & mask_a, p2 & mask_a, p3 & mask_a);
 #pragma unroll
@@ -659,23 +687,21 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         __builtin_amdgcn_sched_barrier(0);
         pv(std::integral_constant<int, 0>{}, va);
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            ka[2 * st] = gather_k(next, st, 0);
-            ka[2 * st + 1] = gather_k(next, st, 1);
-        }
-        pv(std::integral_constant<int, 1>{}, va + 4);
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int st = 2; st < 4; ++st) {
-            ka[2 * st] = gather_k(next, st, 0);
-            ka[2 * st + 1] = gather_k(next, st, 1);
-        }
+            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
+        pv(std::integral_constant<int, 1>{}, va + NR);
+#pragma unroll
+        for (int st = 2; st < 4; ++st)
+#pragma unroll
+            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
         VI_GROUPS8(1, 1, 3, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 5
         pv(std::integral_constant<int, 2>{}, vb);
         load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
-        pv(std::integral_constant<int, 3>{}, vb + 4);
+        pv(std::integral_constant<int, 3>{}, vb + NR);
         __builtin_amdgcn_sched_barrier(0);
     };
 #undef VI_GROUPS8
@@ -688,10 +714,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #endif
     {
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            ka[2 * st] = gather_k(ca, st, 0);
-            ka[2 * st + 1] = gather_k(ca, st, 1);
-        }
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(ca, st, hr);
         // a wavefront's tile bases increase with k: once one is past the end, all later ones are
         long long ta = tile_base(0), tb = tile_base(1);
         for (int k = 2; ta < n1; k += 2) {
@@ -716,7 +741,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(2);
 #endif
-    float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][128]
+    float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][D]
     float *const sm_m = sm_o + NW * kG * kD;                              // [NW][4]
     float *const sm_l = sm_m + NW * kG;                                   // [NW][4]
     {
@@ -733,7 +758,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     }
     __syncthreads();
     for (int e = tid; e < kG * kD; e += BLOCK) {
-        const int hh = e >> 7;
+        const int hh = e / kD, c = e % kD;
         float mx = -INFINITY;
 #pragma unroll
         for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w * kG + hh]);
@@ -753,17 +778,17 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 for (int m = 0; m < M; ++m) s_new += sm_nsc[m * kG + hh];
                 const float mt = fmaxf(mx, s_new);
                 const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
-                o = f * o + wgt * sm_nv[e & 127];
+                o = f * o + wgt * sm_nv[c];
                 l = f * l + wgt;
                 mx = mt;
             }
             const size_t row = (size_t)b * p.Hq + g * kG + hh;
-            p.out[row * kD + (e & 127)] = __float2half(l > 0.f ? o / l : 0.f);
-            if ((e & 127) == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
+            p.out[row * kD + c] = __float2half(l > 0.f ? o / l : 0.f);
+            if (c == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
         } else {
             const size_t pi = (bg * p.S + s) * kG;
             p.part_o[pi * kD + e] = o;
-            if ((e & 127) == 0) {
+            if (c == 0) {
                 p.part_m[pi + hh] = mx;
                 p.part_l[pi + hh] = l;
             }
@@ -773,19 +798,19 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMP(5);
 }
 
-template <int DSUB, int NW, bool SPLITQ>
+template <int kD, int DSUB, int NW, bool SPLITQ>
 int launch_typed(const DecodeParams &p, hipStream_t stream)
 {
     constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((kG + 3) * kD + (kD / DSUB) * kG) + 16;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<DSUB, NW, SPLITQ>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DSUB, NW, SPLITQ>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return -4;
         configured = true;
     }
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<DSUB, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<kD, DSUB, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -798,15 +823,16 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 bool decode_mfma_supports(const DecodeParams &p)
 {
     // code rows are addressed with 32-bit byte offsets
-    return p.D == kD && p.G == kG && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
-           p.N * (long long)(kD / p.dk) < (1LL << 31);
+    return (p.D == 128 || p.D == 64) && p.G == kG && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
+           p.N * (long long)(p.D / p.dk) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
     // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster (LDS-bound), 4 is latency-bound
-    return p.dk == 4 ? launch_typed<4, 8, true>(p, stream) : launch_typed<2, 8, true>(p, stream);
+    if (p.D == 128) return p.dk == 4 ? launch_typed<128, 4, 8, true>(p, stream) : launch_typed<128, 2, 8, true>(p, stream);
+    return p.dk == 4 ? launch_typed<64, 4, 8, true>(p, stream) : launch_typed<64, 2, 8, true>(p, stream);
 }
 
 } // namespace vecinfer

@@ -52,6 +52,8 @@ LLAMA8B_32K = Shape(B=1, Hq=32, Hkv=8, D=128, N=32768, d_k=4, d_v=4)
 LLAMA8B_BATCH32 = Shape(B=32, Hq=32, Hkv=8, D=128, N=8192, d_k=4, d_v=4)
 LLAMA8B_196K = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=4, d_v=4)
 LLAMA8B_196K_B4D2 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=2)
+# head dim 64 (the paper's kernel sweep also covers it; Mistral / Qwen-class shapes), d = 4
+HEADDIM64_196K = Shape(1, 32, 8, 64, 196608, 4, 4)
 ENCODE_64K = Shape(B=1, Hq=32, Hkv=8, D=128, N=65536, d_k=4, d_v=4)
 
 

@@ -99,7 +99,7 @@ def test_decode_argument_errors():
     assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
     assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
-    # the matrix-core variant only covers D = 128, G = 4
+    # the matrix-core variant only covers G = 4
     assert _decode(cfg=vb.Config(64, 8, 8, 4, 4), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
 
 

@@ -16,7 +16,7 @@ VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
 
 
 def _supported(shape, variant):
-    return variant == vb.VARIANT_LUT or (shape.D == 128 and shape.G == 4 and shape.d_k in (2, 4)
+    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G == 4 and shape.d_k in (2, 4)
                                          and shape.d_v == shape.d_k)
 
 
@@ -31,6 +31,9 @@ SMALL = [
     synth.Shape(1, 8, 1, 64, 300, 8, 8),
     synth.Shape(3, 4, 4, 128, 65, 2, 8),
     synth.Shape(1, 4, 1, 128, 4099, 4, 4),
+    synth.Shape(2, 8, 2, 64, 777, 4, 4),          # head dim 64 on the matrix-core path
+    synth.Shape(1, 8, 2, 64, 1500, 2, 2),
+    synth.Shape(1, 4, 1, 64, 4099, 4, 4),
 ]
 
 
@@ -254,6 +257,8 @@ RESIDUAL = [
     (synth.Shape(1, 4, 2, 64, 513, 4, 2), 128),
     (synth.Shape(1, 8, 1, 64, 300, 8, 8), 5),
     (synth.Shape(3, 4, 4, 128, 65, 2, 8), 1),
+    (synth.Shape(2, 8, 2, 64, 777, 4, 4), 100),
+    (synth.Shape(1, 8, 2, 64, 1500, 2, 2), 128),
 ]
 
 
@@ -405,6 +410,8 @@ STEP_SHAPES = [
     synth.Shape(1, 4, 1, 128, 4099, 4, 4),
     synth.Shape(1, 4, 2, 64, 513, 4, 2),
     synth.Shape(1, 8, 1, 64, 300, 8, 8),
+    synth.Shape(2, 8, 2, 64, 777, 4, 4),
+    synth.Shape(1, 8, 2, 64, 1500, 2, 2),
 ]
 
 
@@ -456,3 +463,16 @@ def test_decode_step_full_size_196k():
     k_new, v_new = _new_token(shape, seed=45)
     got = _gpu_step(shape, x, k_new, v_new)
     _check_step(shape, x, k_new, v_new, got, [shape.N], "step 196k")
+
+
+def test_decode_head_dim_64_long():
+    """Head dim 64 (the paper's second kernel-sweep shape) at a length that gives every
+    wavefront several tiles and uses the uneven tile deal: 32 / 8 heads, 65536 tokens."""
+    shape = synth.Shape(1, 32, 8, 64, 65536, 4, 4)
+    x = synth.decode_inputs(shape, seed=64)
+    ref = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    got = gpu_decode(shape, x, variant=vb.VARIANT_MFMA)
+    assert_decode_close(*got, *ref, what="D=64, 64k tokens")
+    k_new, v_new = _new_token(shape, seed=65)
+    step = _gpu_step(shape, x, k_new, v_new, variant=vb.VARIANT_MFMA)
+    _check_step(shape, x, k_new, v_new, step, [shape.N], "step D=64, 64k tokens")
