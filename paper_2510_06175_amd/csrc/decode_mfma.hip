@@ -1,5 +1,5 @@
-// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 4 query heads per KV
-// head, sub-vector dim d = 4 or 2 (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
+// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 4 (or 2, 1) query heads
+// per KV head, sub-vector dim d = 4 or 2 (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
 //
 // Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
 // row is never assembled: each lane gathers a few centroids with ds_read and hands them
@@ -48,7 +48,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
-constexpr int kG = 4;
+constexpr int kG = 4;              // head slots of the MFMA layout; G = 1, 2 run with the spare slots on a zero query
 constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
 
 // loads from an absolute LDS byte address
@@ -173,10 +173,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
 
     if (n0 >= n1 && !has_new) {                        // empty split: neutral partial
-        for (int e = tid; e < kG * kD; e += BLOCK) p.part_o[(bg * p.S + s) * kG * kD + e] = 0.f;
-        if (tid < kG) {
-            p.part_m[(bg * p.S + s) * kG + tid] = -INFINITY;
-            p.part_l[(bg * p.S + s) * kG + tid] = 0.f;
+        for (int e = tid; e < p.G * kD; e += BLOCK) p.part_o[(bg * p.S + s) * p.G * kD + e] = 0.f;
+        if (tid < p.G) {
+            p.part_m[(bg * p.S + s) * p.G + tid] = -INFINITY;
+            p.part_l[(bg * p.S + s) * p.G + tid] = 0.f;
         }
         finish_split<BLOCK>(p, b, g);
         return;
@@ -339,9 +339,13 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
-    if (wave < kG && kD == 64) {
+    if (wave < kG && wave >= p.G) {
+        // spare head slot (G < 4): a zero query; its scores and outputs are never written out
+        sm_qt[wave * kD + lane] = 0.f;
+        if (kD == 128) sm_qt[wave * kD + 64 + lane] = 0.f;
+    } else if (wave < kG && kD == 64) {
         // D = 64: one channel per lane, six butterfly stages across lanes
-        const size_t qrow = ((size_t)b * p.Hq + g * kG + wave) * kD;
+        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
         float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) {
@@ -350,7 +354,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         sm_qt[wave * kD + lane] = x0;
     } else if (wave < kG) {
-        const size_t qrow = ((size_t)b * p.Hq + g * kG + wave) * kD;
+        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
         float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
         float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
         {
@@ -484,12 +488,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 __builtin_memcpy(win, tab + code * stride, ENTRY);
                 if (kv == 0) {
                     if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
-                    if (lane < kG) {
+                    if (lane < p.G) {
                         float sc = 0.f;
 #pragma unroll
                         for (int j = 0; j < DSUB; ++j)
                             sc = fmaf(sm_qt[lane * kD + m * DSUB + j] * fold, (float)win[j], sc);
-                        p.new_sc[((size_t)bg * M + m) * kG + lane] = sc;
+                        p.new_sc[((size_t)bg * M + m) * p.G + lane] = sc;
                         sm_nsc[m * kG + lane] = sc;
                     }
                 } else {
@@ -757,7 +761,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     }
     __syncthreads();
-    for (int e = tid; e < kG * kD; e += BLOCK) {
+    for (int e = tid; e < p.G * kD; e += BLOCK) {
         const int hh = e / kD, c = e % kD;
         float mx = -INFINITY;
 #pragma unroll
@@ -782,11 +786,11 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 l = f * l + wgt;
                 mx = mt;
             }
-            const size_t row = (size_t)b * p.Hq + g * kG + hh;
+            const size_t row = (size_t)b * p.Hq + g * p.G + hh;
             p.out[row * kD + c] = __float2half(l > 0.f ? o / l : 0.f);
             if (c == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
         } else {
-            const size_t pi = (bg * p.S + s) * kG;
+            const size_t pi = (bg * p.S + s) * p.G;
             p.part_o[pi * kD + e] = o;
             if (c == 0) {
                 p.part_m[pi + hh] = mx;
@@ -823,7 +827,7 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 bool decode_mfma_supports(const DecodeParams &p)
 {
     // code rows are addressed with 32-bit byte offsets
-    return (p.D == 128 || p.D == 64) && p.G == kG && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
+    return (p.D == 128 || p.D == 64) && (p.G == 4 || p.G == 2 || p.G == 1) && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
            p.N * (long long)(p.D / p.dk) < (1LL << 31);
 }
 

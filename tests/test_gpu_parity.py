@@ -16,7 +16,7 @@ VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
 
 
 def _supported(shape, variant):
-    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G == 4 and shape.d_k in (2, 4)
+    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G in (1, 2, 4) and shape.d_k in (2, 4)
                                          and shape.d_v == shape.d_k)
 
 
@@ -34,6 +34,9 @@ SMALL = [
     synth.Shape(2, 8, 2, 64, 777, 4, 4),          # head dim 64 on the matrix-core path
     synth.Shape(1, 8, 2, 64, 1500, 2, 2),
     synth.Shape(1, 4, 1, 64, 4099, 4, 4),
+    synth.Shape(2, 4, 2, 128, 777, 4, 4),         # G = 2 and G = 1 on the matrix-core path (spare head slots)
+    synth.Shape(1, 3, 3, 128, 1000, 2, 2),
+    synth.Shape(2, 2, 2, 64, 900, 4, 4),
 ]
 
 
@@ -259,6 +262,7 @@ RESIDUAL = [
     (synth.Shape(3, 4, 4, 128, 65, 2, 8), 1),
     (synth.Shape(2, 8, 2, 64, 777, 4, 4), 100),
     (synth.Shape(1, 8, 2, 64, 1500, 2, 2), 128),
+    (synth.Shape(1, 3, 3, 128, 1000, 2, 2), 20),
 ]
 
 
@@ -412,6 +416,8 @@ STEP_SHAPES = [
     synth.Shape(1, 8, 1, 64, 300, 8, 8),
     synth.Shape(2, 8, 2, 64, 777, 4, 4),
     synth.Shape(1, 8, 2, 64, 1500, 2, 2),
+    synth.Shape(2, 4, 2, 128, 777, 4, 4),
+    synth.Shape(2, 2, 2, 64, 900, 4, 4),
 ]
 
 
