@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="196k-b2d4",
-                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64"])
+                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-kd2vd4"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
@@ -67,7 +67,7 @@ def main() -> int:
 
     shape = {"196k-b2d4": synth.LLAMA8B_196K, "196k-b4d2": synth.LLAMA8B_196K_B4D2,
              "32k": synth.LLAMA8B_32K, "batch32": synth.LLAMA8B_BATCH32,
-             "196k-d64": synth.HEADDIM64_196K}[args.workload]
+             "196k-d64": synth.HEADDIM64_196K, "196k-kd2vd4": synth.LLAMA8B_196K_KD2_VD4}[args.workload]
     cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v)
     variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
     idx_bytes = shape.index_bytes()

@@ -62,7 +62,7 @@ enum {
                                     configuration                                            */
     VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
                                     cores for both q.K and P.V; D in {64,128}, G in {1,2,4},
-                                    d_k = d_v in {2,4}                                        */
+                                    d_k and d_v in {2,4}                                      */
 };
 
 typedef struct vecinfer_cfg {

@@ -1,5 +1,6 @@
 // Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 4 (or 2, 1) query heads
-// per KV head, sub-vector dim d = 4 or 2 (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
+// per KV head, sub-vector dims d_k, d_v = 4 or 2, chosen separately for keys and values
+// (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
 //
 // Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
 // row is never assembled: each lane gathers a few centroids with ds_read and hands them
@@ -122,27 +123,31 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
     return (unsigned)b | ((unsigned)b << 16);
 }
 
-template <int kD, int DSUB, int NW, bool SPLITQ>
+// DK, DV: sub-vector dims of the key and the value codebooks (keys and values may be quantized
+// differently, Sec. 3.2).
+template <int kD, int DK, int DV, int NW, bool SPLITQ>
 __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 {
-    static_assert((kD == 128 || kD == 64) && (DSUB == 4 || DSUB == 2), "shapes this kernel is laid out for");
+    static_assert((kD == 128 || kD == 64) && (DK == 4 || DK == 2) && (DV == 4 || DV == 2),
+                  "shapes this kernel is laid out for");
     constexpr int BLOCK = NW * 64;
-    constexpr int M = kD / DSUB;                       // sub-spaces: 16, 32 or 64
+    constexpr int MK = kD / DK, MV = kD / DV;          // sub-spaces: 16, 32 or 64
     constexpr int CB_BYTES = kCentroids * kD * 2;      // one codebook set of a KV head: 64 or 32 KB
-    constexpr int ENTRY = DSUB * 2;                    // bytes per centroid: 8 or 4
-    constexpr int SUBSPACE_BYTES = kCentroids * ENTRY; // 2048 or 1024
+    constexpr int ENTRY_K = DK * 2, ENTRY_V = DV * 2;  // bytes per centroid: 8 or 4
+    constexpr int SUB_K = kCentroids * ENTRY_K;        // one sub-space table: 2048 or 1024 bytes
+    constexpr int SUB_V = kCentroids * ENTRY_V;
     constexpr int NR = kD / 32;                        // score MFMA rounds (32 channels each): 4 or 2;
                                                        // also the P.V operands (and MFMAs) per sub-tile
     constexpr int H = NR / 2;                          // rounds per pipeline stage
-    constexpr int KW = (M / 4 + 3) / 4;                // key-code dwords per lane per sub-tile (M / 4 bytes)
-    constexpr int NROUND_V = M / 16;                   // value sub-spaces per MFMA column: 1, 2 or 4
+    constexpr int KW = (MK / 4 + 3) / 4;               // key-code dwords per lane per sub-tile (MK / 4 bytes)
+    constexpr int NROUND_V = MV / 16;                  // value sub-spaces per MFMA column: 1, 2 or 4
     constexpr int VW = NROUND_V;                       // value-code dwords per lane per sub-tile (4 tokens x NROUND_V bytes)
     // LDS layout of the value codebook: [r][code][col] with sub-space m = NROUND_V * col + r.
     // LDS serves a gather 16 lanes at a time, and the 16 lanes of such a group read the same r
     // and 16 different col: with the 16 entries of a code in one ROW_V-byte row they fall on
     // disjoint banks whatever their codes are (4.4 instead of 6.7 cycles per gather).  The key
     // codebook keeps the [m][code] order: the 16 lanes of a group all read one sub-space there.
-    constexpr int ROW_V = 16 * ENTRY;                  // 128 or 64 bytes
+    constexpr int ROW_V = 16 * ENTRY_V;                // 128 or 64 bytes
     constexpr int PLANE_V = kCentroids * ROW_V;        // one r: 32768 or 16384 bytes
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -150,8 +155,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     unsigned char *const sm_v = smem + CB_BYTES;
     float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][D]
     float *const sm_new = sm_qt + kG * kD;                                 // [2][D]: k~ and v of the new token
-    float *const sm_nsc = sm_new + 2 * kD;                                 // [M][4]: its score shares (log2 units)
-    float *const sm_nv = sm_nsc + M * kG;                                  // [D]:    its dequantized value
+    float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][4]: its score shares (log2 units)
+    float *const sm_nv = sm_nsc + MK * kG;                                 // [D]:    its dequantized value
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
@@ -168,7 +173,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // encodes sub-spaces s, s + S, ... of the new token's key and value.
     const long long len = seq_len_of(p, b);
     const bool fused = p.k_new != nullptr && len > 0;
-    const bool has_new = fused && s < M;
+    const bool has_new = fused && s < (MK > MV ? MK : MV);
     long long n0, n1;
     split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
 
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- per-lane constants
     const int t0 = col & 3;                              // channel-in-sub-vector this A row serves
     unsigned mask_a, mask_b;                             // select the fp16 slot(s) of (p, p)
-    if (DSUB == 4) {
+    if (DV == 4) {
         mask_a = t0 == 0 ? 0x0000ffffu : (t0 == 1 ? 0xffff0000u : 0u);
         mask_b = t0 == 2 ? 0x0000ffffu : (t0 == 3 ? 0xffff0000u : 0u);
     } else {
@@ -195,14 +200,14 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     unsigned sel[4];                                     // sel[i] = all ones iff t0 == i
 #pragma unroll
     for (int i = 0; i < 4; ++i) sel[i] = t0 == i ? 0xffffffffu : 0u;
-    // LDS byte offsets: keys  sub-space (8/d)*(8kg.. ) i.e. M/4 sub-spaces per kg
+    // LDS byte offsets: keys  MK/4 sub-spaces per kg
     //                   values sub-space NROUND_V*col + r
     const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
-    const unsigned lds_k = lds_base + (unsigned)(kg * (M / 4) * SUBSPACE_BYTES);
-    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * ENTRY);
+    const unsigned lds_k = lds_base + (unsigned)(kg * (MK / 4) * SUB_K);
+    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * ENTRY_V);
 
-    const uint8_t *krow = p.k_idx + bg * p.n_cap * M;
-    const uint8_t *vrow = p.v_idx + bg * p.n_cap * M;
+    const uint8_t *krow = p.k_idx + bg * p.n_cap * MK;
+    const uint8_t *vrow = p.v_idx + bg * p.n_cap * MV;
     const long long last = n1 - 1;
 
     // token owned by A-row i of sub-tile st: base + 16 st + 4 (i % 4) + i / 4, so that D-register v
@@ -220,25 +225,24 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // base plus an instruction immediate, and loads past the end of the split return 0 (a
     // valid code) instead of needing a clamp.  The host checks N * M < 2^31.
     const __amdgpu_buffer_rsrc_t rsrc_k =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(krow), 0, (int)((unsigned)n1 * M), 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(krow), 0, (int)((unsigned)n1 * MK), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_v =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(vrow), 0, (int)((unsigned)n1 * M), 0x00020000);
-    const unsigned koff_lane = (unsigned)(krow_tok * M + kg * (M / 4));
-    const unsigned voff_lane = (unsigned)(kg * M + col * NROUND_V);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(vrow), 0, (int)((unsigned)n1 * MV), 0x00020000);
+    const unsigned koff_lane = (unsigned)(krow_tok * MK + kg * (MK / 4));
+    const unsigned voff_lane = (unsigned)(kg * MV + col * NROUND_V);
 
     auto load_codes = [&](Codes &cd, long long tb) {
-        const unsigned base = (unsigned)tb * M;
-        const unsigned ko = base + koff_lane, vo = base + voff_lane;
+        const unsigned ko = (unsigned)tb * MK + koff_lane, vo = (unsigned)tb * MV + voff_lane;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            // keys: the M / 4 code bytes of the lane's k-slot range of its token
-            if constexpr (M / 4 == 4) {
-                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * M, 0, 0);
-            } else if constexpr (M / 4 == 8) {
-                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * M, 0, 0);
+            // keys: the MK / 4 code bytes of the lane's k-slot range of its token
+            if constexpr (MK / 4 == 4) {
+                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * MK, 0, 0);
+            } else if constexpr (MK / 4 == 8) {
+                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, 0);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1];
             } else {
-                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * M, 0, 0);
+                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, 0);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][2] = w[2]; cd.kc[st][3] = w[3];
             }
             // values: NROUND_V bytes (sub-spaces NROUND_V col ..) of each of the tokens 4 v + kg,
@@ -247,20 +251,20 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 unsigned w = 0;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * M, 0, 0) << (8 * v);
+                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0) << (8 * v);
                 cd.vc[st][0] = w;
             } else if constexpr (NROUND_V == 2) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     ushortx2 t;
-                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * M, 0, 0);
-                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * M, 0, 0);
+                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, 0);
+                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, 0);
                     cd.vc[st][u] = __builtin_bit_cast(unsigned, t);
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * M, 0, 0);
+                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0);
             }
         }
     };
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #ifdef VECINFER_PROLOGUE_STAMPS
     STAMPW(0);
 #endif
-    constexpr int CPL = 16 / ENTRY;                    // codes per 16-byte load of the value codebook
+    constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
     // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
     constexpr int kStageItems = CB_BYTES / 1024, kStagePerWave = (kStageItems + NW - 1) / NW;
     static_assert(NROUND_V * (kCentroids / (4 * CPL)) == kStageItems, "value items: (code group, r)");
@@ -320,7 +324,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
         }
         // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
-        // (CPL = 16 / ENTRY consecutive codes of one sub-space) and writes them entry by entry.
+        // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
         // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
         // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
         // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
@@ -330,7 +334,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             const int it = wave + NW * j;
             const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
             if (kStageItems % NW == 0 || it < kStageItems)
-                vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUBSPACE_BYTES + code * ENTRY);
+                vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
         }
     }
 #ifdef VECINFER_PROLOGUE_STAMPS
@@ -413,8 +417,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         if (kStageItems % NW == 0 || it < kStageItems) {
 #pragma unroll
             for (int e = 0; e < CPL; ++e) {
-                unsigned char *const d = sm_v + r * PLANE_V + (code + e) * ROW_V + vcol * ENTRY;
-                if (DSUB == 4)
+                unsigned char *const d = sm_v + r * PLANE_V + (code + e) * ROW_V + vcol * ENTRY_V;
+                if (DV == 4)
                     *reinterpret_cast<uintx2 *>(d) = uintx2{vreg[j][2 * e], vreg[j][2 * e + 1]};
                 else
                     *reinterpret_cast<unsigned *>(d) = vreg[j][e];
@@ -451,63 +455,65 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     if (has_new) {
         const long long pos = len - 1;
         const float fold = kLog2e / (float)kD;
-        int item = 0;
-        for (int m = s; m < M; m += p.S) {
+        auto new_item = [&](auto kv_c, int m) {
+            constexpr int kv = decltype(kv_c)::value;          // 0: key sub-space m, 1: value sub-space m
+            constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS;
+            // entry c of the sub-space sits at tab + c * stride (value tables are transposed)
+            const unsigned char *tab = kv == 0 ? sm_k + m * SUB_K
+                                               : sm_v + (m % NROUND_V) * PLANE_V + (m / NROUND_V) * ENTRY_V;
+            constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
+            float x[DS];
 #pragma unroll
-            for (int kv = 0; kv < 2; ++kv, ++item) {
-                if (item % NW != wave_u) continue;
-                // entry c of the sub-space sits at tab + c * stride (value tables are transposed)
-                const unsigned char *tab = kv == 0 ? sm_k + m * SUBSPACE_BYTES
-                                                   : sm_v + (m % NROUND_V) * PLANE_V + (m / NROUND_V) * ENTRY;
-                const int stride = kv == 0 ? ENTRY : ROW_V;
-                float x[DSUB];
+            for (int j = 0; j < DS; ++j) x[j] = sm_new[kv * kD + m * DS + j];
+            float best = INFINITY;
+            unsigned arg = 0;
 #pragma unroll
-                for (int j = 0; j < DSUB; ++j) x[j] = sm_new[kv * kD + m * DSUB + j];
-                float best = INFINITY;
-                unsigned arg = 0;
+            for (int i = 0; i < kCentroids / 64; ++i) {
+                const unsigned c = lane + 64 * i;
+                _Float16 cen[DS];
+                __builtin_memcpy(cen, tab + c * stride, EN);
+                float dist = 0.f;
 #pragma unroll
-                for (int i = 0; i < kCentroids / 64; ++i) {
-                    const unsigned c = lane + 64 * i;
-                    _Float16 cen[DSUB];
-                    __builtin_memcpy(cen, tab + c * stride, ENTRY);
-                    float dist = 0.f;
-#pragma unroll
-                    for (int j = 0; j < DSUB; ++j) {
-                        const float tdiff = x[j] - (float)cen[j];
-                        dist = fmaf(tdiff, tdiff, dist);
-                    }
-                    if (dist < best) {
-                        best = dist;
-                        arg = c;
-                    }
+                for (int j = 0; j < DS; ++j) {
+                    const float tdiff = x[j] - (float)cen[j];
+                    dist = fmaf(tdiff, tdiff, dist);
                 }
-                // a non-negative fp32 orders like its bit pattern
-                const unsigned dmin = wave_umin(__float_as_uint(best));
-                const unsigned code = wave_umin(__float_as_uint(best) == dmin ? arg : 0xffffffffu);
-                _Float16 win[DSUB];
-                __builtin_memcpy(win, tab + code * stride, ENTRY);
-                if (kv == 0) {
-                    if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
-                    if (lane < p.G) {
-                        float sc = 0.f;
-#pragma unroll
-                        for (int j = 0; j < DSUB; ++j)
-                            sc = fmaf(sm_qt[lane * kD + m * DSUB + j] * fold, (float)win[j], sc);
-                        p.new_sc[((size_t)bg * M + m) * p.G + lane] = sc;
-                        sm_nsc[m * kG + lane] = sc;
-                    }
-                } else {
-                    if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * M + m] = (uint8_t)code;
-                    float mine = (float)win[0];
-#pragma unroll
-                    for (int j = 1; j < DSUB; ++j) mine = lane == j ? (float)win[j] : mine;
-                    if (lane < DSUB) {
-                        p.new_v[(size_t)bg * kD + m * DSUB + lane] = mine;
-                        sm_nv[m * DSUB + lane] = mine;
-                    }
+                if (dist < best) {
+                    best = dist;
+                    arg = c;
                 }
             }
-        }
+            // a non-negative fp32 orders like its bit pattern
+            const unsigned dmin = wave_umin(__float_as_uint(best));
+            const unsigned code = wave_umin(__float_as_uint(best) == dmin ? arg : 0xffffffffu);
+            _Float16 win[DS];
+            __builtin_memcpy(win, tab + code * stride, EN);
+            if (kv == 0) {
+                if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m] = (uint8_t)code;
+                if (lane < p.G) {
+                    float sc = 0.f;
+#pragma unroll
+                    for (int j = 0; j < DS; ++j)
+                        sc = fmaf(sm_qt[lane * kD + m * DS + j] * fold, (float)win[j], sc);
+                    p.new_sc[((size_t)bg * MK + m) * p.G + lane] = sc;
+                    sm_nsc[m * kG + lane] = sc;
+                }
+            } else {
+                if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m] = (uint8_t)code;
+                float mine = (float)win[0];
+#pragma unroll
+                for (int j = 1; j < DS; ++j) mine = lane == j ? (float)win[j] : mine;
+                if (lane < DS) {
+                    p.new_v[(size_t)bg * kD + m * DS + lane] = mine;
+                    sm_nv[m * DS + lane] = mine;
+                }
+            }
+        };
+        int item = 0;
+        for (int m = s; m < MK; m += p.S, ++item)
+            if (item % NW == wave_u) new_item(std::integral_constant<int, 0>{}, m);
+        for (int m = s; m < MV; m += p.S, ++item)
+            if (item % NW == wave_u) new_item(std::integral_constant<int, 1>{}, m);
     }
 
     STAMP(2);
@@ -518,9 +524,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     for (int r = 0; r < NROUND_V; ++r) acc_o[r] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
-    // one v_dot4_u32_u8 (w . (ENTRY << 8k) + base) instead of a bit-field extract and a shift-add.
+    // one v_dot4_u32_u8 (w . (ENTRY_K << 8k) + base) instead of a bit-field extract and a shift-add.
     auto lds_addr = [&](unsigned w, int k, unsigned base) -> unsigned {
-        return __builtin_amdgcn_udot4(w, (unsigned)ENTRY << (8 * k), base, false);
+        return __builtin_amdgcn_udot4(w, (unsigned)ENTRY_K << (8 * k), base, false);
     };
     auto lds_addr_v = [&](unsigned w, int k, unsigned base) -> unsigned {   // code * ROW_V + base
         return __builtin_amdgcn_udot4(w, (unsigned)ROW_V << (8 * k), base, false);
@@ -528,20 +534,20 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
-        if (DSUB == 4) {
-            // sub-spaces (M/4) kg + 2r, + 2r + 1: code bytes 2r, 2r+1 of the lane's M / 4
+        if (DK == 4) {
+            // sub-spaces (MK/4) kg + 2r, + 2r + 1: code bytes 2r, 2r+1 of the lane's MK / 4
             const unsigned w = cd.kc[st][r >> 1];
             const int k0 = 2 * (r & 1);
-            const uint2 x0 = lds_load_b64(lds_addr(w, k0, lds_k) + (2 * r) * SUBSPACE_BYTES);
-            const uint2 x1 = lds_load_b64(lds_addr(w, k0 + 1, lds_k) + (2 * r + 1) * SUBSPACE_BYTES);
+            const uint2 x0 = lds_load_b64(lds_addr(w, k0, lds_k) + (2 * r) * SUB_K);
+            const uint2 x1 = lds_load_b64(lds_addr(w, k0 + 1, lds_k) + (2 * r + 1) * SUB_K);
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else {
-            // sub-spaces (M/4) kg + 4r .. +3: the 4 code bytes of dword r
+            // sub-spaces (MK/4) kg + 4r .. +3: the 4 code bytes of dword r
             const unsigned w = cd.kc[st][r];
             unsigned x[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                x[q] = lds_load_b32(lds_addr(w, q, lds_k) + (4 * r + q) * SUBSPACE_BYTES);
+                x[q] = lds_load_b32(lds_addr(w, q, lds_k) + (4 * r + q) * SUB_K);
             return as_half8(x[0], x[1], x[2], x[3]);
         }
     };
@@ -550,7 +556,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // q = u * NROUND_V + r (step u, round r): centroids of sub-space NROUND_V col + r for tokens
     // 2u, 2u+1.  d = 2: q = r: centroids of sub-space NROUND_V col + r for the 4 tokens.
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
-        if (DSUB == 4) {
+        if (DV == 4) {
             const int u = q / NROUND_V, r = q % NROUND_V;
             const int b0 = 2 * u * NROUND_V + r, b1 = (2 * u + 1) * NROUND_V + r;
             const uint2 x0 = lds_load_b64(lds_addr_v(cd.vc[st][b0 >> 2], b0 & 3, lds_v) + r * PLANE_V);
@@ -578,13 +584,14 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     //   4  MFMA P.V sub-tiles 0-1 | gather K first H rounds of the NEXT tile
     //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
     // Every stage pairs 4 H MFMAs with 4 H operand gathers.
-    constexpr int kReadsPerOperand = DSUB == 4 ? 2 : 4;        // ds_reads (and address ops) per half8
-#define VI_GROUPS8(MF, OPS, XV, VM)                                                        \
+    constexpr int kReadsK = DK == 4 ? 2 : 4;          // ds_reads (and address ops) per gathered half8
+    constexpr int kReadsV = DV == 4 ? 2 : 4;
+    // 4 H groups of: MF MFMAs, RD + XV vector-ALU ops, RD LDS reads
+#define VI_GROUPS8(MF, RD, XV)                                                             \
     _Pragma("unroll") for (int gi = 0; gi < 4 * H; ++gi) {                                    \
         __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);                                 \
-        __builtin_amdgcn_sched_group_barrier(0x002, (OPS) * kReadsPerOperand + (XV), 0);    \
-        __builtin_amdgcn_sched_group_barrier(0x100, (OPS) * kReadsPerOperand, 0);           \
-        if ((VM) > 0) __builtin_amdgcn_sched_group_barrier(0x020, VM, 0);                   \
+        __builtin_amdgcn_sched_group_barrier(0x002, (RD) + (XV), 0);                        \
+        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);                                 \
     }
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
         half8 kb[4 * H], va[2 * NR], vb[2 * NR];
@@ -600,7 +607,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 sacc[st] = MFMA16(ka[H * st + hr], bq[hr], hr == 0 ? kZero4 : sacc[st], 0, 0, 0);
                 kb[H * st + hr] = gather_k(cd, st, H + hr);
             }
-        VI_GROUPS8(1, 1, 0, 0)
+        VI_GROUPS8(1, kReadsK, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 2
@@ -611,7 +618,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 sacc[st] = MFMA16(kb[H * st + hr], bq[H + hr], sacc[st], 0, 0, 0);
                 va[4 * hr + st] = gather_v(cd, (4 * hr + st) / NR, (4 * hr + st) % NR);   // sub-tiles 0, 1
             }
-        VI_GROUPS8(1, 1, 0, 0)
+        VI_GROUPS8(1, kReadsV, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 3: online softmax of this wavefront (Alg. 1 steps 12-13).
@@ -673,7 +680,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             // p of sub-tile st lives in quad lane st
             const unsigned p0 = quad_bcast<st>(pp[0]), p1 = quad_bcast<st>(pp[1]);
             const unsigned p2 = quad_bcast<st>(pp[2]), p3 = quad_bcast<st>(pp[3]);
-            if (DSUB == 4) {
+            if (DV == 4) {
                 const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
                 const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
 #pragma unroll
@@ -699,7 +706,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int st = 2; st < 4; ++st)
 #pragma unroll
             for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
-        VI_GROUPS8(1, 1, 3, 0)
+        VI_GROUPS8(1, kReadsK, 3)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 5
@@ -753,8 +760,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #pragma unroll
         for (int r = 0; r < NROUND_V; ++r)
 #pragma unroll
-            for (int v = 0; v < DSUB; ++v)
-                sm_o[(wave * kG + kg) * kD + DSUB * (NROUND_V * col + r) + v] = acc_o[r][v];
+            for (int v = 0; v < DV; ++v)
+                sm_o[(wave * kG + kg) * kD + DV * (NROUND_V * col + r) + v] = acc_o[r][v];
         if (kg == 0 && (col & 3) == 0) {
             sm_m[wave * kG + (col >> 2)] = m_run;
             sm_l[wave * kG + (col >> 2)] = l_head;
@@ -779,7 +786,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             // a fused new token): fold the new token in and write the output rows
             if (has_new) {
                 float s_new = 0.f;
-                for (int m = 0; m < M; ++m) s_new += sm_nsc[m * kG + hh];
+                for (int m = 0; m < MK; ++m) s_new += sm_nsc[m * kG + hh];
                 const float mt = fmaxf(mx, s_new);
                 const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
                 o = f * o + wgt * sm_nv[c];
@@ -802,19 +809,19 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMP(5);
 }
 
-template <int kD, int DSUB, int NW, bool SPLITQ>
+template <int kD, int DK, int DV, int NW, bool SPLITQ>
 int launch_typed(const DecodeParams &p, hipStream_t stream)
 {
-    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((kG + 3) * kD + (kD / DSUB) * kG) + 16;
+    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((kG + 3) * kD + (kD / DK) * kG) + 16;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DSUB, NW, SPLITQ>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, NW, SPLITQ>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return -4;
         configured = true;
     }
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<kD, DSUB, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -827,16 +834,26 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 bool decode_mfma_supports(const DecodeParams &p)
 {
     // code rows are addressed with 32-bit byte offsets
-    return (p.D == 128 || p.D == 64) && (p.G == 4 || p.G == 2 || p.G == 1) && p.dk == p.dv && (p.dk == 4 || p.dk == 2) &&
-           p.N * (long long)(p.D / p.dk) < (1LL << 31);
+    return (p.D == 128 || p.D == 64) && (p.G == 4 || p.G == 2 || p.G == 1) && (p.dk == 4 || p.dk == 2) &&
+           (p.dv == 4 || p.dv == 2) && p.N * (long long)(p.D / 2) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
     // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster (LDS-bound), 4 is latency-bound
-    if (p.D == 128) return p.dk == 4 ? launch_typed<128, 4, 8, true>(p, stream) : launch_typed<128, 2, 8, true>(p, stream);
-    return p.dk == 4 ? launch_typed<64, 4, 8, true>(p, stream) : launch_typed<64, 2, 8, true>(p, stream);
+    const int key = p.D * 100 + p.dk * 10 + p.dv;
+    switch (key) {
+    case 12844: return launch_typed<128, 4, 4, 8, true>(p, stream);
+    case 12822: return launch_typed<128, 2, 2, 8, true>(p, stream);
+    case 12824: return launch_typed<128, 2, 4, 8, true>(p, stream);
+    case 12842: return launch_typed<128, 4, 2, 8, true>(p, stream);
+    case 6444: return launch_typed<64, 4, 4, 8, true>(p, stream);
+    case 6422: return launch_typed<64, 2, 2, 8, true>(p, stream);
+    case 6424: return launch_typed<64, 2, 4, 8, true>(p, stream);
+    case 6442: return launch_typed<64, 4, 2, 8, true>(p, stream);
+    default: return -2;
+    }
 }
 
 } // namespace vecinfer

@@ -54,6 +54,8 @@ LLAMA8B_196K = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=4, d_v=4)
 LLAMA8B_196K_B4D2 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=2)
 # head dim 64 (the paper's kernel sweep also covers it; Mistral / Qwen-class shapes), d = 4
 HEADDIM64_196K = Shape(1, 32, 8, 64, 196608, 4, 4)
+# keys at 4 bits per element (d = 2), values at 2 (d = 4): "more bits for the keys", Sec. 3.2
+LLAMA8B_196K_KD2_VD4 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=4)
 ENCODE_64K = Shape(B=1, Hq=32, Hkv=8, D=128, N=65536, d_k=4, d_v=4)
 
 

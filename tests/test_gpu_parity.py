@@ -17,7 +17,7 @@ VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
 
 def _supported(shape, variant):
     return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G in (1, 2, 4) and shape.d_k in (2, 4)
-                                         and shape.d_v == shape.d_k)
+                                         and shape.d_v in (2, 4))
 
 
 # ------------------------------------------------------------------ decode, small shapes
@@ -37,6 +37,9 @@ SMALL = [
     synth.Shape(2, 4, 2, 128, 777, 4, 4),         # G = 2 and G = 1 on the matrix-core path (spare head slots)
     synth.Shape(1, 3, 3, 128, 1000, 2, 2),
     synth.Shape(2, 2, 2, 64, 900, 4, 4),
+    synth.Shape(2, 8, 2, 128, 777, 2, 4),         # keys and values quantized differently (Sec. 3.2)
+    synth.Shape(1, 8, 2, 128, 900, 4, 2),
+    synth.Shape(1, 8, 2, 64, 1100, 2, 4),
 ]
 
 
@@ -418,6 +421,8 @@ STEP_SHAPES = [
     synth.Shape(1, 8, 2, 64, 1500, 2, 2),
     synth.Shape(2, 4, 2, 128, 777, 4, 4),
     synth.Shape(2, 2, 2, 64, 900, 4, 4),
+    synth.Shape(2, 8, 2, 128, 777, 2, 4),
+    synth.Shape(1, 8, 2, 128, 900, 4, 2),
 ]
 
 
