@@ -61,14 +61,14 @@ enum {
                                     steps 4 and 11 taken literally); covers every supported
                                     configuration                                            */
     VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
-                                    cores for both q.K and P.V; D in {64,128}, G in {1,2,4},
-                                    d_k and d_v in {2,4}                                      */
+                                    cores for both q.K and P.V; D in {64,128}, d_k and d_v
+                                    in {2,4}, any G the cfg allows                           */
 };
 
 typedef struct vecinfer_cfg {
     int32_t head_dim;      /* D: 64 or 128 (Walsh-Hadamard needs a power of two, Eq. 5)      */
     int32_t num_q_heads;   /* H_q                                                            */
-    int32_t num_kv_heads;  /* H_kv, divides H_q; G = H_q / H_kv in {1, 2, 4, 8}              */
+    int32_t num_kv_heads;  /* H_kv, divides H_q; G = H_q / H_kv in 1 .. 8                    */
     int32_t k_sub_dim;     /* d for keys: 2, 4 or 8                                          */
     int32_t v_sub_dim;     /* d for values: 2, 4 or 8 (keys and values may differ, Sec. 3.2)  */
     int32_t k_bits;        /* code width for keys: 8 (uint8 index, 256 centroids)            */

@@ -13,7 +13,7 @@ bool cfg_ok(const vecinfer_cfg *c)
     if (c->head_dim != 64 && c->head_dim != 128) return false;
     if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads) return false;
     const int G = c->num_q_heads / c->num_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+    if (G > 8) return false;
     auto sub_ok = [](int d) { return d == 2 || d == 4 || d == 8; };
     if (!sub_ok(c->k_sub_dim) || !sub_ok(c->v_sub_dim)) return false;
     if (c->k_bits != 8 || c->v_bits != 8) return false;

@@ -1,5 +1,5 @@
-// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 4 (or 2, 1) query heads
-// per KV head, sub-vector dims d_k, d_v = 4 or 2, chosen separately for keys and values
+// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1, 2, 4 or 8 query heads
+// per KV head (8: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 4 or 2, chosen separately for keys and values
 // (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
 //
 // Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
@@ -49,7 +49,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
-constexpr int kG = 4;              // head slots of the MFMA layout; G = 1, 2 run with the spare slots on a zero query
+constexpr int kG = 4;              // head slots of one MFMA pass; spare slots (G not a multiple of 4) run on a zero query
 constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
 
 // loads from an absolute LDS byte address
@@ -125,9 +125,11 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
 
 // DK, DV: sub-vector dims of the key and the value codebooks (keys and values may be quantized
 // differently, Sec. 3.2).
-template <int kD, int DK, int DV, int NW, bool SPLITQ>
+// HG: head groups of 4 query heads that share the gathered key / value operands (G <= 4 HG).
+template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ>
 __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 {
+    constexpr int KG = kG * HG;                        // head slots of the workgroup
     static_assert((kD == 128 || kD == 64) && (DK == 4 || DK == 2) && (DV == 4 || DV == 2),
                   "shapes this kernel is laid out for");
     constexpr int BLOCK = NW * 64;
@@ -153,10 +155,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *const sm_k = smem;
     unsigned char *const sm_v = smem + CB_BYTES;
-    float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [4][D]
-    float *const sm_new = sm_qt + kG * kD;                                 // [2][D]: k~ and v of the new token
-    float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][4]: its score shares (log2 units)
-    float *const sm_nv = sm_nsc + MK * kG;                                 // [D]:    its dequantized value
+    float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [KG][D]
+    float *const sm_new = sm_qt + KG * kD;                                 // [2][D]: k~ and v of the new token
+    float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][KG]: its score shares (log2 units)
+    float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
@@ -343,11 +345,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
-    if (wave < kG && wave >= p.G) {
+    static_assert(KG <= NW && NW >= 2, "one wavefront per head slot for the query transform");
+    if (wave < KG && wave >= p.G) {
         // spare head slot (G < 4): a zero query; its scores and outputs are never written out
         sm_qt[wave * kD + lane] = 0.f;
         if (kD == 128) sm_qt[wave * kD + 64 + lane] = 0.f;
-    } else if (wave < kG && kD == 64) {
+    } else if (wave < KG && kD == 64) {
         // D = 64: one channel per lane, six butterfly stages across lanes
         const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
         float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
         }
         sm_qt[wave * kD + lane] = x0;
-    } else if (wave < kG) {
+    } else if (wave < KG) {
         const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
         float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
         float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
@@ -375,7 +378,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         sm_qt[wave * kD + lane] = x0;
         sm_qt[wave * kD + 64 + lane] = x1;
-    } else if (has_new && wave == kG && kD == 64) {
+    }
+    // the new token's key and value (fused append): the last two wavefronts
+    if (has_new && wave == NW - 2 && kD == 64) {
         float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) {
@@ -383,7 +388,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
         }
         sm_new[lane] = x0 * (1.0f / sqrtf((float)kD));
-    } else if (has_new && wave == kG) {
+    } else if (has_new && wave == NW - 2) {
         // k~ = (k / lambda) H_D of the new token (Eq. 9), operation for operation what the
         // cache-fill kernels compute (true division, butterfly stages at distance 1, 2, .. 64,
         // then 1/sqrt D), so that the fused step writes the codes a separate append would
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         const float hs = 1.0f / sqrtf((float)kD);
         sm_new[lane] = (x0 + x1) * hs;
         sm_new[64 + lane] = (x0 - x1) * hs;
-    } else if (has_new && wave == kG + 1) {
+    } else if (has_new && wave == NW - 1) {
         sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
         if (kD == 128) sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
     }
@@ -431,19 +436,22 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- B operands of the score MFMAs: q~_h[(D/4) kg + 8r .. +8); columns with t0 < 2 take the
     // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
     // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq[NR];
+    half8 bq[HG][NR];
     {
         const float fold = kLog2e / (float)kD;
-        const int hh = col >> 2;
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+        for (int hg = 0; hg < HG; ++hg) {
+            const int hh = kG * hg + (col >> 2);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float x = sm_qt[hh * kD + (kD / 4) * kg + 8 * r + e] * fold;
-                const _Float16 hi = (_Float16)x;
-                const _Float16 lo = (_Float16)(x - (float)hi);
-                bq[r][e] = (SPLITQ && (col & 2)) ? lo : hi;
-            }
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = sm_qt[hh * kD + (kD / 4) * kg + 8 * r + e] * fold;
+                    const _Float16 hi = (_Float16)x;
+                    const _Float16 lo = (_Float16)(x - (float)hi);
+                    bq[hg][r][e] = (SPLITQ && (col & 2)) ? lo : hi;
+                }
+        }
     }
 
     // ---- fused append: this workgroup's sub-spaces of the new token, one (sub-space, key | value)
@@ -496,7 +504,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                     for (int j = 0; j < DS; ++j)
                         sc = fmaf(sm_qt[lane * kD + m * DS + j] * fold, (float)win[j], sc);
                     p.new_sc[((size_t)bg * MK + m) * p.G + lane] = sc;
-                    sm_nsc[m * kG + lane] = sc;
+                    sm_nsc[m * KG + lane] = sc;
                 }
             } else {
                 if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m] = (uint8_t)code;
@@ -517,11 +525,16 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     }
 
     STAMP(2);
-    float m_run = -INFINITY;          // running max of head col/4 (log2 units), same in all its lanes
-    float l_part = 0.f;               // this lane's share of the running sum
-    floatx4 acc_o[NROUND_V];
+    float m_run[HG];                  // running max of head 4 hg + col/4 (log2 units), same in all its lanes
+    float l_part[HG];                 // this lane's share of the running sum
+    floatx4 acc_o[HG][NROUND_V];
 #pragma unroll
-    for (int r = 0; r < NROUND_V; ++r) acc_o[r] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int hg = 0; hg < HG; ++hg) {
+        m_run[hg] = -INFINITY;
+        l_part[hg] = 0.f;
+#pragma unroll
+        for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
 
     // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
     // one v_dot4_u32_u8 (w . (ENTRY_K << 8k) + base) instead of a bit-field extract and a shift-add.
@@ -596,7 +609,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
         half8 kb[4 * H], va[2 * NR], vb[2 * NR];
         const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
-        floatx4 sacc[4];
+        floatx4 sacc[HG][4];
 
         // ---- stage 1
         __builtin_amdgcn_sched_barrier(0);
@@ -604,10 +617,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int hr = 0; hr < H; ++hr)
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                sacc[st] = MFMA16(ka[H * st + hr], bq[hr], hr == 0 ? kZero4 : sacc[st], 0, 0, 0);
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg)
+                    sacc[hg][st] = MFMA16(ka[H * st + hr], bq[hg][hr], hr == 0 ? kZero4 : sacc[hg][st], 0, 0, 0);
                 kb[H * st + hr] = gather_k(cd, st, H + hr);
             }
-        VI_GROUPS8(1, kReadsK, 0)
+        VI_GROUPS8(HG, kReadsK, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 2
@@ -615,10 +630,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int hr = 0; hr < H; ++hr)
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                sacc[st] = MFMA16(kb[H * st + hr], bq[H + hr], sacc[st], 0, 0, 0);
+#pragma unroll
+                for (int hg = 0; hg < HG; ++hg)
+                    sacc[hg][st] = MFMA16(kb[H * st + hr], bq[hg][H + hr], sacc[hg][st], 0, 0, 0);
                 va[4 * hr + st] = gather_v(cd, (4 * hr + st) / NR, (4 * hr + st) % NR);   // sub-tiles 0, 1
             }
-        VI_GROUPS8(1, kReadsV, 0)
+        VI_GROUPS8(HG, kReadsV, 0)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 3: online softmax of this wavefront (Alg. 1 steps 12-13).
@@ -631,67 +648,74 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
             vb[NR + q] = gather_v(cd, 3, q);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (SPLITQ) {
-            // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
-            // of the quad so that all four lanes hold the full-precision score again
+        unsigned pp[HG][4];                      // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
+        for (int hg = 0; hg < HG; ++hg) {
+            if (SPLITQ) {
+                // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
+                // of the quad so that all four lanes hold the full-precision score again
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sacc[st][v] += quad_xor<2>(sacc[st][v]);
-        }
-        float sc[4];
+                for (int st = 0; st < 4; ++st)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            // branch-free per-lane pick of sacc[t0][v] (bit masks: exactly one of sel[] is all ones)
-            const float s0 = sacc[0][v], s1 = sacc[1][v], s2 = sacc[2][v], s3 = sacc[3][v];
-            const unsigned u = (__float_as_uint(s0) & sel[0]) | (__float_as_uint(s1) & sel[1]) |
-                               (__float_as_uint(s2) & sel[2]) | (__float_as_uint(s3) & sel[3]);
-            sc[v] = __uint_as_float(u);
-        }
-        if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
+                    for (int v = 0; v < 4; ++v) sacc[hg][st][v] += quad_xor<2>(sacc[hg][st][v]);
+            }
+            float sc[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (tb + 16 * t0 + 4 * v + kg > last) sc[v] = -INFINITY;
-        }
-        float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        tmax = fmaxf(tmax, quad_xor<1>(tmax));
-        tmax = fmaxf(tmax, quad_xor<2>(tmax));
-        tmax = rows_max(tmax);
-        const float m_new = fmaxf(m_run, tmax);
-        if (__any(m_new > m_run)) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first tile
-            l_part *= alpha;
-            const float alpha_o = __shfl(alpha, 4 * kg);                 // lane 4kg serves head kg
+            for (int v = 0; v < 4; ++v) {
+                // branch-free per-lane pick of sacc[t0][v] (bit masks: exactly one of sel[] is all ones)
+                const float s0 = sacc[hg][0][v], s1 = sacc[hg][1][v], s2 = sacc[hg][2][v], s3 = sacc[hg][3][v];
+                const unsigned u = (__float_as_uint(s0) & sel[0]) | (__float_as_uint(s1) & sel[1]) |
+                                   (__float_as_uint(s2) & sel[2]) | (__float_as_uint(s3) & sel[3]);
+                sc[v] = __uint_as_float(u);
+            }
+            if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
 #pragma unroll
-            for (int r = 0; r < NROUND_V; ++r) acc_o[r] *= alpha_o;
-            m_run = m_new;
-        }
-        unsigned pp[4];                          // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
+                for (int v = 0; v < 4; ++v)
+                    if (tb + 16 * t0 + 4 * v + kg > last) sc[v] = -INFINITY;
+            }
+            float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+            tmax = fmaxf(tmax, quad_xor<1>(tmax));
+            tmax = fmaxf(tmax, quad_xor<2>(tmax));
+            tmax = rows_max(tmax);
+            const float m_new = fmaxf(m_run[hg], tmax);
+            if (__any(m_new > m_run[hg])) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run[hg] - m_new);   // 0 on the first tile
+                l_part[hg] *= alpha;
+                const float alpha_o = __shfl(alpha, 4 * kg);                     // lane 4kg serves head kg
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run);
-            l_part += pr;
-            pp[v] = pack_dup_f16(pr);
+                for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] *= alpha_o;
+                m_run[hg] = m_new;
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run[hg]);
+                l_part[hg] += pr;
+                pp[hg][v] = pack_dup_f16(pr);
+            }
         }
 
         // ---- o += P . VQ^-1(V_q)  (step 16)
         auto pv = [&](auto st_c, const half8 *vops) {
             constexpr int st = decltype(st_c)::value;
-            // p of sub-tile st lives in quad lane st
-            const unsigned p0 = quad_bcast<st>(pp[0]), p1 = quad_bcast<st>(pp[1]);
-            const unsigned p2 = quad_bcast<st>(pp[2]), p3 = quad_bcast<st>(pp[3]);
-            if (DV == 4) {
-                const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
-                const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
 #pragma unroll
-                for (int r = 0; r < NROUND_V; ++r) acc_o[r] = MFMA16(a0, vops[r], acc_o[r], 0, 0, 0);
+            for (int hg = 0; hg < HG; ++hg) {
+                // p of sub-tile st lives in quad lane st
+                const unsigned p0 = quad_bcast<st>(pp[hg][0]), p1 = quad_bcast<st>(pp[hg][1]);
+                const unsigned p2 = quad_bcast<st>(pp[hg][2]), p3 = quad_bcast<st>(pp[hg][3]);
+                if (DV == 4) {
+                    const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
+                    const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
 #pragma unroll
-                for (int r = 0; r < NROUND_V; ++r) acc_o[r] = MFMA16(a1, vops[NROUND_V + r], acc_o[r], 0, 0, 0);
-            } else {
-                const half8 a = as_half8(p0 & mask_a, p1 & mask_a, p2 & mask_a, p3 & mask_a);
+                    for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] = MFMA16(a0, vops[r], acc_o[hg][r], 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < NROUND_V; ++r)
-                    acc_o[r] = MFMA16(a, vops[r], acc_o[r], 0, 0, 0);
+                    for (int r = 0; r < NROUND_V; ++r)
+                        acc_o[hg][r] = MFMA16(a1, vops[NROUND_V + r], acc_o[hg][r], 0, 0, 0);
+                } else {
+                    const half8 a = as_half8(p0 & mask_a, p1 & mask_a, p2 & mask_a, p3 & mask_a);
+#pragma unroll
+                    for (int r = 0; r < NROUND_V; ++r)
+                        acc_o[hg][r] = MFMA16(a, vops[r], acc_o[hg][r], 0, 0, 0);
+                }
             }
         };
         // ---- stage 4
@@ -706,7 +730,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int st = 2; st < 4; ++st)
 #pragma unroll
             for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
-        VI_GROUPS8(1, kReadsK, 3)
+        VI_GROUPS8(HG, kReadsK, 3 * HG)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 5
@@ -744,27 +768,32 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMPW(1);
 #endif
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
-    float l_head = l_part + quad_xor<1>(l_part);
-    l_head += quad_xor<2>(l_head);
-    l_head += __shfl_xor(l_head, 16);
-    l_head += __shfl_xor(l_head, 32);
+    float l_head[HG];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        l_head[hg] = l_part[hg] + quad_xor<1>(l_part[hg]);
+        l_head[hg] += quad_xor<2>(l_head[hg]);
+        l_head[hg] += __shfl_xor(l_head[hg], 16);
+        l_head[hg] += __shfl_xor(l_head[hg], 32);
+    }
     __syncthreads();
 #ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(2);
 #endif
-    float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][4][D]
-    float *const sm_m = sm_o + NW * kG * kD;                              // [NW][4]
-    float *const sm_l = sm_m + NW * kG;                                   // [NW][4]
-    {
-        // acc_o[r] register v of lane (col, kg): head kg, channel d * (NROUND_V * col + r) + v
+    float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][KG][D]
+    float *const sm_m = sm_o + NW * KG * kD;                              // [NW][KG]
+    float *const sm_l = sm_m + NW * KG;                                   // [NW][KG]
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+        // acc_o[hg][r] register v of lane (col, kg): head 4 hg + kg, channel d * (NROUND_V * col + r) + v
 #pragma unroll
         for (int r = 0; r < NROUND_V; ++r)
 #pragma unroll
             for (int v = 0; v < DV; ++v)
-                sm_o[(wave * kG + kg) * kD + DV * (NROUND_V * col + r) + v] = acc_o[r][v];
+                sm_o[(wave * KG + kG * hg + kg) * kD + DV * (NROUND_V * col + r) + v] = acc_o[hg][r][v];
         if (kg == 0 && (col & 3) == 0) {
-            sm_m[wave * kG + (col >> 2)] = m_run;
-            sm_l[wave * kG + (col >> 2)] = l_head;
+            sm_m[wave * KG + kG * hg + (col >> 2)] = m_run[hg];
+            sm_l[wave * KG + kG * hg + (col >> 2)] = l_head[hg];
         }
     }
     __syncthreads();
@@ -772,21 +801,21 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         const int hh = e / kD, c = e % kD;
         float mx = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w * kG + hh]);
+        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w * KG + hh]);
         float o = 0.f, l = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const float mw = sm_m[w * kG + hh];
+            const float mw = sm_m[w * KG + hh];
             const float f = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - mx) : 0.f;
-            o += f * sm_o[w * kG * kD + e];
-            l += f * sm_l[w * kG + hh];
+            o += f * sm_o[w * KG * kD + e];
+            l += f * sm_l[w * KG + hh];
         }
         if (p.S == 1 && !p.k_res) {
             // the workgroup holds the whole answer (a single split also encoded every sub-space of
             // a fused new token): fold the new token in and write the output rows
             if (has_new) {
                 float s_new = 0.f;
-                for (int m = 0; m < MK; ++m) s_new += sm_nsc[m * kG + hh];
+                for (int m = 0; m < MK; ++m) s_new += sm_nsc[m * KG + hh];
                 const float mt = fmaxf(mx, s_new);
                 const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
                 o = f * o + wgt * sm_nv[c];
@@ -809,20 +838,27 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMP(5);
 }
 
-template <int kD, int DK, int DV, int NW, bool SPLITQ>
-int launch_typed(const DecodeParams &p, hipStream_t stream)
+template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ>
+int launch_hg(const DecodeParams &p, hipStream_t stream)
 {
-    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((kG + 3) * kD + (kD / DK) * kG) + 16;
+    constexpr int KG = kG * HG;
+    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((KG + 3) * kD + (kD / DK) * KG) + 16;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, NW, SPLITQ>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return -4;
         configured = true;
     }
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+template <int kD, int DK, int DV, int NW, bool SPLITQ>
+int launch_typed(const DecodeParams &p, hipStream_t stream)
+{
+    return p.G <= kG ? launch_hg<kD, DK, DV, 1, NW, SPLITQ>(p, stream) : launch_hg<kD, DK, DV, 2, NW, SPLITQ>(p, stream);
 }
 
 } // namespace
@@ -834,7 +870,7 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 bool decode_mfma_supports(const DecodeParams &p)
 {
     // code rows are addressed with 32-bit byte offsets
-    return (p.D == 128 || p.D == 64) && (p.G == 4 || p.G == 2 || p.G == 1) && (p.dk == 4 || p.dk == 2) &&
+    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && (p.dk == 4 || p.dk == 2) &&
            (p.dv == 4 || p.dv == 2) && p.N * (long long)(p.D / 2) < (1LL << 31);
 }
 

@@ -57,7 +57,7 @@ def test_encode_argument_errors():
     assert _enc_vals(v=None) == vb.EINVAL
     assert _enc_vals(T=9) == vb.EINVAL
     for bad in (vb.Config(96, 32, 8, 4, 4), vb.Config(128, 32, 5, 4, 4), vb.Config(128, 32, 8, 3, 4),
-                vb.Config(128, 32, 8, 4, 4, k_bits=12), vb.Config(128, 48, 8, 4, 4),
+                vb.Config(128, 32, 8, 4, 4, k_bits=12), vb.Config(128, 128, 8, 4, 4),
                 vb.Config(128, 32, 8, 4, 16)):
         assert _enc_keys(cfg=bad) == vb.EUNSUPPORTED
         assert _enc_vals(cfg=bad) == vb.EUNSUPPORTED
@@ -99,8 +99,8 @@ def test_decode_argument_errors():
     assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
     assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
-    # the matrix-core variant does not cover G = 8 or d = 8
-    assert _decode(cfg=vb.Config(64, 8, 1, 4, 4), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # the matrix-core variant does not cover d = 8
+    assert _decode(cfg=vb.Config(64, 8, 1, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
 
 
 def test_decode_residual_argument_errors():

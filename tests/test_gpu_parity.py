@@ -16,7 +16,7 @@ VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
 
 
 def _supported(shape, variant):
-    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G in (1, 2, 4) and shape.d_k in (2, 4)
+    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G <= 8 and shape.d_k in (2, 4)
                                          and shape.d_v in (2, 4))
 
 
@@ -40,6 +40,10 @@ SMALL = [
     synth.Shape(2, 8, 2, 128, 777, 2, 4),         # keys and values quantized differently (Sec. 3.2)
     synth.Shape(1, 8, 2, 128, 900, 4, 2),
     synth.Shape(1, 8, 2, 64, 1100, 2, 4),
+    synth.Shape(1, 16, 2, 128, 777, 4, 4),        # G = 8: two passes of four heads over the same operands
+    synth.Shape(2, 8, 1, 64, 513, 2, 2),
+    synth.Shape(1, 7, 1, 128, 900, 4, 4),         # G = 7, G = 3: spare head slots
+    synth.Shape(1, 6, 2, 128, 600, 4, 2),
 ]
 
 
@@ -266,6 +270,8 @@ RESIDUAL = [
     (synth.Shape(2, 8, 2, 64, 777, 4, 4), 100),
     (synth.Shape(1, 8, 2, 64, 1500, 2, 2), 128),
     (synth.Shape(1, 3, 3, 128, 1000, 2, 2), 20),
+    (synth.Shape(1, 16, 2, 128, 777, 4, 4), 128),
+    (synth.Shape(1, 7, 1, 128, 900, 4, 4), 64),
 ]
 
 
@@ -423,6 +429,8 @@ STEP_SHAPES = [
     synth.Shape(2, 2, 2, 64, 900, 4, 4),
     synth.Shape(2, 8, 2, 128, 777, 2, 4),
     synth.Shape(1, 8, 2, 128, 900, 4, 2),
+    synth.Shape(1, 16, 2, 128, 777, 4, 4),
+    synth.Shape(1, 7, 1, 64, 900, 4, 4),
 ]
 
 
