@@ -843,13 +843,11 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
 {
     constexpr int KG = kG * HG;
     constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((KG + 3) * kD + (kD / DK) * KG) + 16;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return -4;
-        configured = true;
-    }
+    // once per process and instantiation (function-local static: initialised thread-safely)
+    static const bool configured =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!configured) return -4;
     dim3 grid(p.S, p.Hkv, p.B);
     hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
