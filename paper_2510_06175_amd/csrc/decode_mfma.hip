@@ -294,10 +294,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
         return n0 + ((long long)per * kPeriod + off) * kTile;
     };
-    // The first two tiles' codes start their trip from HBM now, under the prologue.
     Codes ca, cb;
-    load_codes(ca, tile_base(0));
-    load_codes(cb, tile_base(1));
 
     STAMP(0);
 #ifdef VECINFER_PROLOGUE_STAMPS
@@ -339,6 +336,11 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
         }
     }
+    // The first two tiles' codes start their trip from HBM now, under the prologue.  They are
+    // requested after the codebooks: loads return in order, and the first touch of the code stream
+    // is the slowest load of the kernel, so the other way round the staging would wait behind it.
+    load_codes(ca, tile_base(0));
+    load_codes(cb, tile_base(1));
 #ifdef VECINFER_PROLOGUE_STAMPS
     STAMPW(2);
 #endif
