@@ -456,8 +456,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         }
     }
 
-    // ---- fused append: this workgroup's sub-spaces of the new token, one (sub-space, key | value)
-    // item per wavefront in turn.  Eq. 2 by exhaustive search over the table already in LDS: a lane
+    // ---- fused append: this workgroup's sub-spaces of the new token, dealt to the wavefronts as
+    // (sub-space, key | value) items.  Eq. 2 by exhaustive search over the table already in LDS: a lane
     // scans centroids lane, lane + 64, ..; squared distances summed in channel order in fp32; the
     // lowest index among the centroids at minimum distance wins.  The key item
     // also leaves the new token's score share of its sub-space for the 4 heads, the value item
@@ -465,65 +465,89 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     if (has_new) {
         const long long pos = len - 1;
         const float fold = kLog2e / (float)kD;
-        auto new_item = [&](auto kv_c, int m) {
-            constexpr int kv = decltype(kv_c)::value;          // 0: key sub-space m, 1: value sub-space m
-            constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS;
-            // entry c of the sub-space sits at tab + c * stride (value tables are transposed)
-            const unsigned char *tab = kv == 0 ? sm_k + m * SUB_K
-                                               : sm_v + (m % NROUND_V) * PLANE_V + (m / NROUND_V) * ENTRY_V;
+        // A wavefront takes up to four items of one kind at a time (items i0, i0 + NW, ..): their
+        // chains of LDS reads, distance arithmetic and cross-lane reductions are independent, so
+        // they overlap instead of paying their latencies one after the other.
+        auto new_items = [&](auto kv_c, int i0) {
+            constexpr int kv = decltype(kv_c)::value;          // 0: key sub-spaces, 1: value sub-spaces
+            constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS, MX = kv == 0 ? MK : MV, NB = 4;
+            // entry c of a sub-space sits at tab + c * stride (value tables are transposed)
             constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
-            float x[DS];
+            int m[NB];
+            bool ok[NB];
+            const unsigned char *tab[NB];
+            float best[NB];
+            unsigned arg[NB];
 #pragma unroll
-            for (int j = 0; j < DS; ++j) x[j] = sm_new[kv * kD + m * DS + j];
-            float best = INFINITY;
-            unsigned arg = 0;
+            for (int b4 = 0; b4 < NB; ++b4) {
+                const int mm = s + (i0 + NW * b4) * p.S;
+                ok[b4] = mm < MX;
+                m[b4] = ok[b4] ? mm : 0;                        // a surplus slot redoes sub-space 0 and writes nothing
+                tab[b4] = kv == 0 ? sm_k + m[b4] * SUB_K
+                                  : sm_v + (m[b4] % NROUND_V) * PLANE_V + (m[b4] / NROUND_V) * ENTRY_V;
+                best[b4] = INFINITY;
+                arg[b4] = 0;
+            }
 #pragma unroll
-            for (int i = 0; i < kCentroids / 64; ++i) {
-                const unsigned c = lane + 64 * i;
-                _Float16 cen[DS];
-                __builtin_memcpy(cen, tab + c * stride, EN);
-                float dist = 0.f;
+            for (int b4 = 0; b4 < NB; ++b4) {
+                float x[DS];
 #pragma unroll
-                for (int j = 0; j < DS; ++j) {
-                    const float tdiff = x[j] - (float)cen[j];
-                    dist = fmaf(tdiff, tdiff, dist);
-                }
-                if (dist < best) {
-                    best = dist;
-                    arg = c;
+                for (int jj = 0; jj < DS; ++jj) x[jj] = sm_new[kv * kD + m[b4] * DS + jj];
+#pragma unroll
+                for (int i = 0; i < kCentroids / 64; ++i) {
+                    const unsigned c = lane + 64 * i;
+                    _Float16 cen[DS];
+                    __builtin_memcpy(cen, tab[b4] + c * stride, EN);
+                    float dist = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < DS; ++jj) {
+                        const float tdiff = x[jj] - (float)cen[jj];
+                        dist = fmaf(tdiff, tdiff, dist);
+                    }
+                    if (dist < best[b4]) {
+                        best[b4] = dist;
+                        arg[b4] = c;
+                    }
                 }
             }
-            // a non-negative fp32 orders like its bit pattern
-            const unsigned dmin = wave_umin(__float_as_uint(best));
-            const unsigned code = wave_umin(__float_as_uint(best) == dmin ? arg : 0xffffffffu);
-            _Float16 win[DS];
-            __builtin_memcpy(win, tab + code * stride, EN);
-            if (kv == 0) {
-                if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m] = (uint8_t)code;
-                if (lane < p.G) {
-                    float sc = 0.f;
+            unsigned code[NB];
 #pragma unroll
-                    for (int j = 0; j < DS; ++j)
-                        sc = fmaf(sm_qt[lane * kD + m * DS + j] * fold, (float)win[j], sc);
-                    p.new_sc[((size_t)bg * MK + m) * p.G + lane] = sc;
-                    sm_nsc[m * KG + lane] = sc;
-                }
-            } else {
-                if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m] = (uint8_t)code;
-                float mine = (float)win[0];
+            for (int b4 = 0; b4 < NB; ++b4) {
+                // a non-negative fp32 orders like its bit pattern
+                const unsigned dmin = wave_umin(__float_as_uint(best[b4]));
+                code[b4] = wave_umin(__float_as_uint(best[b4]) == dmin ? arg[b4] : 0xffffffffu);
+            }
 #pragma unroll
-                for (int j = 1; j < DS; ++j) mine = lane == j ? (float)win[j] : mine;
-                if (lane < DS) {
-                    p.new_v[(size_t)bg * kD + m * DS + lane] = mine;
-                    sm_nv[m * DS + lane] = mine;
+            for (int b4 = 0; b4 < NB; ++b4) {
+                if (!ok[b4]) continue;                          // wave-uniform
+                _Float16 win[DS];
+                __builtin_memcpy(win, tab[b4] + code[b4] * stride, EN);
+                if (kv == 0) {
+                    if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m[b4]] = (uint8_t)code[b4];
+                    if (lane < p.G) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int jj = 0; jj < DS; ++jj)
+                            sc = fmaf(sm_qt[lane * kD + m[b4] * DS + jj] * fold, (float)win[jj], sc);
+                        p.new_sc[((size_t)bg * MK + m[b4]) * p.G + lane] = sc;
+                        sm_nsc[m[b4] * KG + lane] = sc;
+                    }
+                } else {
+                    if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m[b4]] = (uint8_t)code[b4];
+                    float mine = (float)win[0];
+#pragma unroll
+                    for (int jj = 1; jj < DS; ++jj) mine = lane == jj ? (float)win[jj] : mine;
+                    if (lane < DS) {
+                        p.new_v[(size_t)bg * kD + m[b4] * DS + lane] = mine;
+                        sm_nv[m[b4] * DS + lane] = mine;
+                    }
                 }
             }
         };
-        int item = 0;
-        for (int m = s; m < MK; m += p.S, ++item)
-            if (item % NW == wave_u) new_item(std::integral_constant<int, 0>{}, m);
-        for (int m = s; m < MV; m += p.S, ++item)
-            if (item % NW == wave_u) new_item(std::integral_constant<int, 1>{}, m);
+        // key item i (sub-space s + i S) goes to wavefront i % NW, value item i to wavefront (i + 1) % NW
+        for (int i0 = wave_u; s + i0 * p.S < MK; i0 += 4 * NW) new_items(std::integral_constant<int, 0>{}, i0);
+        for (int i0 = (wave_u + NW - 1) % NW; s + i0 * p.S < MV; i0 += 4 * NW)
+            new_items(std::integral_constant<int, 1>{}, i0);
     }
 
     STAMP(2);
