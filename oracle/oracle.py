@@ -59,6 +59,7 @@ def _load():
                                                  C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                                  C.c_int, dp, dp]
         lib.vo_decode_residual_batch.restype = C.c_int
+        lib.vo_kmeans_update.argtypes = [dp, u8p, C.c_int64, C.c_int, C.c_int, C.c_int, dp, dp, i64p]
         _lib = lib
     return _lib
 
@@ -258,3 +259,39 @@ def decode_attention_residual(q_f16, lam, cb_k, cb_v, k_idx, v_idx, k_res, v_res
     if rc != 0:
         raise ValueError("vo_decode_residual_batch rejected the inputs (a sequence with no token at all, or bad shapes)")
     return out, lse
+
+
+def kmeans_update(X, idx, cb_in):
+    """Centroid update of one Lloyd iteration of the K-Means codebook training (Sec. 2.2, 4.1):
+    X [N, D] rows (keys already transformed), idx [N, M] their codes, cb_in [M, C, d].
+    Returns (cb_out [M, C, d] f64, counts [M, C] int64); an empty cluster keeps its centroid."""
+    X = _f64(X)
+    cb_in = _f64(cb_in)
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    N, D = X.shape
+    M, Cn, d = cb_in.shape
+    assert M * d == D and idx.shape == (N, M)
+    cb_out = np.empty_like(cb_in)
+    counts = np.empty((M, Cn), dtype=np.int64)
+    _load().vo_kmeans_update(_dp(X), _u8p(idx), N, D, d, Cn, _dp(cb_in), _dp(cb_out),
+                             counts.ctypes.data_as(C.POINTER(C.c_int64)))
+    return cb_out, counts
+
+
+def kmeans_step(x_f16, lam, cb):
+    """One Lloyd iteration per (KV head, sub-space) over all tokens of all sequences:
+    x_f16 [B, Hkv, T, D]; lam [Hkv, D] (keys: trained on the transformed keys, Sec. 3.2) or None
+    (values: raw); cb [Hkv, M, C, d].  Returns (cb_new [Hkv, M, C, d] f64, counts [Hkv, M, C],
+    idx [B, Hkv, T, M])."""
+    x = _f64(x_f16)
+    cb = _f64(cb)
+    B, Hkv, T, D = x.shape
+    idx = encode_keys(x_f16, lam, cb) if lam is not None else encode_values(x_f16, cb)
+    cb_new = np.empty_like(cb)
+    counts = np.empty(cb.shape[:3], dtype=np.int64)
+    for g in range(Hkv):
+        rows = x[:, g].reshape(B * T, D)
+        if lam is not None:
+            rows = transform_keys(rows, _f64(lam)[g])
+        cb_new[g], counts[g] = kmeans_update(rows, idx[:, g].reshape(B * T, -1), cb[g])
+    return cb_new, counts, idx

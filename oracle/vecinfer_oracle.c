@@ -21,6 +21,8 @@
  *   vo_vq_attention_alg1   App. A, Alg. 1 steps 4-23 (lookup table, tiles, online softmax, LSE)
  *   vo_vq_attention_residual  Eq. 10 plus the full-precision residual window of Sec. 4.1
  *                          ("residual length ... 128"): recent tokens kept unquantized
+ *   vo_kmeans_update       centroid update of one Lloyd iteration of the K-Means codebook training
+ *                          (Sec. 2.2: the codebook is built by K-Means; Sec. 4.1: at most 30 iterations)
  *   vo_merge_splits        log-sum-exp merge of per-split (o, L) pairs; the paper
  *                          returns L (Alg. 1 step 22) but does not print the merge
  *
@@ -455,4 +457,31 @@ int vo_decode_residual_batch(const double *q, const double *lam, const double *c
         }
     free(H);
     return err;
+}
+
+/* Centroid update of one Lloyd iteration (K-Means builds the codebook, Sec. 2.2; it is trained on
+ * the transformed keys and on the raw values, Sec. 3.2, for at most 30 iterations, Sec. 4.1).
+ * X [N, D] rows already assigned: idx [N, M] holds the code of every sub-vector (Eq. 2, from
+ * vo_vq_encode).  New centroid of (m, c) = mean of the sub-vectors assigned to it; a centroid
+ * nobody was assigned to keeps its old value.  cb_in, cb_out [M, C, d]; counts [M, C]. */
+void vo_kmeans_update(const double *X, const uint8_t *idx, int64_t N, int D, int d, int C,
+                      const double *cb_in, double *cb_out, int64_t *counts)
+{
+    const int M = D / d;
+    for (int m = 0; m < M; ++m) {
+        double *sum = (double *)calloc((size_t)C * d, sizeof(double));
+        int64_t *cnt = counts + (int64_t)m * C;
+        for (int c = 0; c < C; ++c) cnt[c] = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            const int c = idx[n * M + m];
+            cnt[c] += 1;
+            for (int j = 0; j < d; ++j) sum[c * d + j] += X[n * D + m * d + j];
+        }
+        for (int c = 0; c < C; ++c)
+            for (int j = 0; j < d; ++j) {
+                const int64_t e = ((int64_t)m * C + c) * d + j;
+                cb_out[e] = cnt[c] > 0 ? sum[c * d + j] / (double)cnt[c] : cb_in[e];
+            }
+        free(sum);
+    }
 }

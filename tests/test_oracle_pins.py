@@ -412,6 +412,76 @@ def test_residual_window_special_cases(oracle):
                                          x["k_res"], x["v_res"], seq_lens=np.array([0]), res_lens=np.array([0]))
 
 
+# --------------------------------------------------------------------------- K-Means step (Sec. 2.2, 4.1)
+
+def test_kmeans_update_matches_scipy_lloyd_iteration(oracle):
+    """One sub-space, 256 centroids: scipy's kmeans2 with a given start and one iteration does
+    exactly assignment (Eq. 2) + mean update; an empty cluster keeps its centroid there too."""
+    import warnings
+    from scipy.cluster.vq import kmeans2
+    g = synth.rng(51)
+    for d in (2, 4, 8):
+        X = g.standard_normal((3000, d))
+        init = g.standard_normal((256, d)) * 1.5
+        init[7] = 50.0                                   # far away: stays empty
+        idx = oracle.vq_encode(X, init[None])
+        new, counts = oracle.kmeans_update(X, idx, init[None])
+        with warnings.catch_warnings():
+            warnings.simplefilter("ignore")
+            ref, label = kmeans2(X, init.copy(), iter=1, minit="matrix")
+        np.testing.assert_array_equal(idx[:, 0], label)
+        np.testing.assert_allclose(new[0], ref, rtol=1e-12, atol=1e-14)
+        np.testing.assert_array_equal(counts[0], np.bincount(label, minlength=256))
+        assert counts[0, 7] == 0 and (new[0, 7] == 50.0).all()
+
+
+def test_kmeans_update_is_the_mean_per_sub_space_and_code(oracle):
+    g = synth.rng(52)
+    D, d, N = 16, 4, 500
+    X = g.standard_normal((N, D))
+    cb = g.standard_normal((D // d, 256, d))
+    idx = g.integers(0, 5, size=(N, D // d)).astype(np.uint8)          # any assignment, not only the nearest
+    new, counts = oracle.kmeans_update(X, idx, cb)
+    for m in range(D // d):
+        for c in range(256):
+            sel = idx[:, m] == c
+            assert counts[m, c] == sel.sum()
+            want = X[sel, m * d:(m + 1) * d].mean(axis=0) if sel.any() else cb[m, c]
+            np.testing.assert_allclose(new[m, c], want, rtol=1e-12, atol=1e-14)
+
+
+def test_kmeans_step_never_increases_the_quantization_error(oracle):
+    """Lloyd's monotonicity over the batched entry (keys: on the transformed keys), and a fixed
+    point: centroids that already are the means of their clusters do not move."""
+    g = synth.rng(53)
+    B, Hkv, T, D, d = 2, 2, 700, 64, 4
+    k, _ = synth.keys_with_outlier_channels(g, B, Hkv, T, D, 2)
+    lam = np.stack([oracle.smoothing_factors(k[:, h]) for h in range(Hkv)])
+    cb = synth.codebooks(g, Hkv, D // d, d).astype(np.float64)
+
+    def error(cbx):
+        tot = 0.0
+        idx = oracle.encode_keys(k, lam, cbx)
+        for h in range(Hkv):
+            rows = oracle.transform_keys(k[:, h].reshape(B * T, D).astype(np.float64), lam[h])
+            tot += ((rows - oracle.vq_dequantize(idx[:, h].reshape(B * T, -1), cbx[h])) ** 2).sum()
+        return tot
+
+    errs = [error(cb)]
+    for _ in range(4):
+        cb, counts, _ = oracle.kmeans_step(k, lam, cb)
+        assert counts.sum() == Hkv * (D // d) * B * T
+        errs.append(error(cb))
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(errs, errs[1:])) and errs[-1] < 0.8 * errs[0]
+    for _ in range(60):                                   # run to the fixed point
+        nxt, _, _ = oracle.kmeans_step(k, lam, cb)
+        if np.array_equal(nxt, cb):
+            break
+        cb = nxt
+    again, _, _ = oracle.kmeans_step(k, lam, cb)
+    np.testing.assert_allclose(again, cb, rtol=1e-13, atol=1e-15)
+
+
 def test_decode_rejects_empty_sequence(oracle):
     s, x = _small_decode_case(28, B=2)
     with pytest.raises(ValueError):
