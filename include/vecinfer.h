@@ -110,6 +110,29 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
                        int64_t n_cap, void *stream);
 
 /*
+ * One Lloyd iteration of the K-Means codebook training.  The paper builds the codebooks by
+ * K-Means (Sec. 2.2), on the transformed keys and on the original values (Sec. 3.2), with at most
+ * 30 iterations (Sec. 4.1); initialisation, the number of iterations and the stopping rule are the
+ * caller's.  Per (KV head, sub-space), over the T tokens of all B sequences:
+ *   assignment  codes[b, g, t, m] = the code vecinfer_encode_keys (lambda != NULL: the vectors
+ *               are smoothed and Hadamard-transformed first) or vecinfer_encode_values
+ *               (lambda == NULL) would write with cb_in
+ *   update      cb_out[g, m, c, :] = fp16(mean of the sub-vectors assigned to c), summed in fp32;
+ *               a centroid nobody was assigned to keeps its cb_in value
+ * The sums are formed with hardware fp32 atomics, so their last bits (and rarely the fp16
+ * rounding of a centroid) may differ between runs.
+ *   x_f16  [B, H_kv, T, D] fp16       cb_in_f16, cb_out_f16 [H_kv, M, 256, d] (may not alias)
+ *   codes  [B, H_kv, T, M] uint8 (written)    counts int32 [H_kv, M, 256] or NULL: cluster sizes
+ *   workspace  vecinfer_kmeans_workspace_bytes(cfg, lambda != NULL) bytes, 256-byte aligned
+ * d and M are the key values of cfg when lambda is given, else the value ones.
+ * Errors: as vecinfer_encode_keys / _values, plus EWORKSPACE.
+ */
+size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys);
+int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda,
+                         const void *cb_in_f16, void *cb_out_f16, uint8_t *codes, int32_t *counts,
+                         int32_t B, int64_t T, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Number of sequence splits the library would pick for (B, N) when num_splits = 0
  * (grid axis "num_splits" of Sec. 3.3).  Host-only; returns >= 1, or a negative code.
  */

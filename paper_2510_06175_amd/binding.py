@@ -25,6 +25,7 @@ EXPORTS = [
     "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_append_kv", "vecinfer_decode_auto_splits",
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
+    "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
     "vecinfer_strerror", "vecinfer_version",
 ]
 
@@ -89,6 +90,10 @@ def lib() -> C.CDLL:
         L.vecinfer_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32, i32, vp, sz,
                                            vp, vp, vp]
         L.vecinfer_decode_step.restype = C.c_int
+        L.vecinfer_kmeans_workspace_bytes.argtypes = [cfgp, i32]
+        L.vecinfer_kmeans_workspace_bytes.restype = sz
+        L.vecinfer_kmeans_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i32, i64, vp, sz, vp]
+        L.vecinfer_kmeans_step.restype = C.c_int
         L.vecinfer_strerror.argtypes = [C.c_int]
         L.vecinfer_strerror.restype = C.c_char_p
         L.vecinfer_version.restype = C.c_int
@@ -257,3 +262,29 @@ def vecinfer_decode_step(cfg: Config, q_f16, k_new, v_new, lam, cb_k, cb_v, k_id
         _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
         None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
         _stream(stream)))
+
+
+def vecinfer_kmeans_workspace_bytes(cfg: Config, keys: bool) -> int:
+    return int(lib().vecinfer_kmeans_workspace_bytes(C.byref(cfg.c()), 1 if keys else 0))
+
+
+def new_kmeans_workspace(cfg: Config, keys: bool, device="cuda") -> torch.Tensor:
+    return torch.empty(vecinfer_kmeans_workspace_bytes(cfg, keys), dtype=torch.uint8, device=device)
+
+
+def vecinfer_kmeans_step(cfg: Config, x_f16, lam, cb_in, cb_out, codes, workspace, counts=None, stream=None) -> None:
+    """One Lloyd iteration of the codebook training on x_f16 [B, Hkv, T, D]; lam = None trains a
+    value codebook (no transform).  Writes cb_out, codes [B, Hkv, T, M] and, if given, counts."""
+    B, Hkv, T, D = x_f16.shape
+    keys = lam is not None
+    d = cfg.k_sub_dim if keys else cfg.v_sub_dim
+    M = cfg.head_dim // d
+    ws = workspace
+    _check(lib().vecinfer_kmeans_step(
+        C.byref(cfg.c()), _dev(x_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "x_f16"),
+        None if lam is None else _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_in, torch.float16, (cfg.num_kv_heads, M, 256, d), "cb_in"),
+        _dev(cb_out, torch.float16, (cfg.num_kv_heads, M, 256, d), "cb_out"),
+        _dev(codes, torch.uint8, (B, cfg.num_kv_heads, T, M), "codes"),
+        None if counts is None else _dev(counts, torch.int32, (cfg.num_kv_heads, M, 256), "counts"),
+        B, T, ws.data_ptr(), ws.numel(), _stream(stream)))

@@ -99,6 +99,8 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     p.n_cap = n_cap;
     p.seq_lens = nullptr;
     p.len_max = 0;
+    p.km_sums = nullptr;
+    p.km_counts = nullptr;
     return VECINFER_OK;
 }
 
@@ -243,6 +245,37 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
     if (rc != VECINFER_OK) return rc;
     if (T > append_max_tokens()) return VECINFER_EINVAL;
     return launch_status(launch_append(pk, pv, static_cast<hipStream_t>(stream)));
+}
+
+size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys)
+{
+    if (!cfg_ok(cfg)) return 0;
+    const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
+    const size_t cen = (size_t)cfg->num_kv_heads * (cfg->head_dim / d) * kCentroids;
+    return (cen * d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
+}
+
+int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, const void *cb_in_f16,
+                         void *cb_out_f16, uint8_t *codes, int32_t *counts, int32_t B, int64_t T, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    if (!cb_out_f16 || !aligned(cb_out_f16, 16)) return VECINFER_EINVAL;
+    EncodeParams p;
+    const bool keys = lambda != nullptr;
+    const int rc = encode_args(cfg, x_f16, lambda, keys, cb_in_f16, codes, B, T, 0, T, p);
+    if (rc != VECINFER_OK) return rc;
+    const size_t need = vecinfer_kmeans_workspace_bytes(cfg, keys ? 1 : 0);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return VECINFER_EWORKSPACE;
+    const size_t cen = (size_t)p.Hkv * p.M * kCentroids;
+    p.km_sums = static_cast<float *>(workspace);
+    p.km_counts = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(workspace) +
+                                              (cen * p.d * sizeof(float) + 255) / 256 * 256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int lr = launch_kmeans_zero(p.km_sums, p.km_counts, cen * p.d, cen, st);
+    if (lr == 0) lr = launch_encode(p, st);
+    if (lr == 0)
+        lr = launch_kmeans_finalize(p.km_sums, p.km_counts, p.cb, static_cast<__half *>(cb_out_f16), counts, cen, p.d, st);
+    return launch_status(lr);
 }
 
 int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t N)

@@ -183,7 +183,14 @@ struct EncodeParams {
     // goes to row clamp(seq_lens[b], 0, len_max) - 1, and a sequence of length 0 is skipped
     const int32_t *seq_lens;
     long long len_max;
+    // K-Means training (one Lloyd iteration): when km_sums != nullptr the tiled kernel also adds
+    // every (transformed) sub-vector into the sum of the centroid it was assigned to
+    float *km_sums;       // [Hkv, M, 256, d] fp32, zeroed beforehand
+    int32_t *km_counts;   // [Hkv, M, 256]
 };
+int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, hipStream_t stream);
+int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
+                           int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream);
 int launch_encode(const EncodeParams &p, hipStream_t stream);
 int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream);
 int append_max_tokens();

@@ -178,6 +178,41 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
             }
         }
     }
+
+    // ---- K-Means training only: every sub-vector of the tile joins the sum of its centroid
+    // (fp32 hardware atomics; the order of the additions, and with it the last bits of the sums,
+    // varies from run to run)
+    if (p.km_sums) {
+        for (int e = tid; e < kEncTokens * M; e += kEncBlock) {
+            const int tl = e / M, m = e - tl * M;
+            if (t0 + tl < p.T) {
+                const size_t cen = ((size_t)g * M + m) * kCentroids + idx_s[tl * M + m];
+#pragma unroll
+                for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
+                atomicAdd(p.km_counts + cen, 1);
+            }
+        }
+    }
+}
+
+__global__ void kmeans_zero_kernel(float *sums, int32_t *counts, size_t n_sums, size_t n_counts)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_sums) sums[i] = 0.f;
+    if (i < n_counts) counts[i] = 0;
+}
+
+// New centroid = sum / count (fp32), rounded to fp16; a centroid nobody was assigned to keeps its
+// old value.
+__global__ void kmeans_finalize_kernel(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
+                                       int32_t *counts_out, size_t n_centroids, int d)
+{
+    const size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n_centroids) return;
+    const int n = counts[c];
+    if (counts_out) counts_out[c] = n;
+    for (int j = 0; j < d; ++j)
+        cb_out[c * d + j] = n > 0 ? __float2half(sums[c * d + j] / (float)n) : cb_in[c * d + j];
 }
 
 // Decode-time append (Eq. 9) and other short inputs: one workgroup per (token, batch, KV head).
@@ -298,7 +333,7 @@ constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b,
 template <int D, int d>
 int launch_typed(const EncodeParams &p, hipStream_t stream)
 {
-    if (p.T <= kTokenKernelMaxT) {
+    if (p.T <= kTokenKernelMaxT && !p.km_sums) {
         dim3 tgrid((unsigned)p.T, 1, p.B * p.Hkv);
         if (p.lam)
             hipLaunchKernelGGL((encode_token_kernel<D, d, true>), tgrid, dim3(kCentroids), 0, stream, p);
@@ -341,6 +376,22 @@ int launch_append_dk(const EncodeParams &pk, const EncodeParams &pv, hipStream_t
 } // namespace
 
 int append_max_tokens() { return (int)kTokenKernelMaxT; }
+
+int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, hipStream_t stream)
+{
+    const size_t n = n_sums > n_counts ? n_sums : n_counts;
+    hipLaunchKernelGGL(kmeans_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, sums, counts,
+                       n_sums, n_counts);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
+                           int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream)
+{
+    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)((n_centroids + 255) / 256)), dim3(256), 0, stream,
+                       sums, counts, cb_in, cb_out, counts_out, n_centroids, d);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
 
 int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
 {

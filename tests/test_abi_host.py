@@ -139,6 +139,24 @@ def test_decode_step_argument_errors():
     assert step(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
 
 
+def test_kmeans_argument_errors():
+    def km(cfg=CFG, x=FAKE, lam=FAKE, cbi=FAKE, cbo=FAKE, codes=FAKE, B=1, T=64, ws=FAKE, ws_bytes=1 << 30):
+        return vb.lib().vecinfer_kmeans_step(C.byref(cfg.c()), x, lam, cbi, cbo, codes, None, B, T, ws, ws_bytes, None)
+    assert km(x=None) == vb.EINVAL
+    assert km(cbo=None) == vb.EINVAL
+    assert km(codes=None) == vb.EINVAL
+    assert km(T=0) == vb.EINVAL
+    assert km(cfg=vb.Config(128, 32, 8, 3, 4)) == vb.EUNSUPPORTED
+    need = vb.vecinfer_kmeans_workspace_bytes(CFG, True)
+    assert need >= 8 * 32 * 256 * (4 * 4 + 4)
+    assert km(ws=None) == vb.EWORKSPACE
+    assert km(ws_bytes=need - 1) == vb.EWORKSPACE
+    # the sums take the same room for every d (H_kv x D x 256 floats); the counts scale with M
+    mixed = vb.Config(128, 32, 8, 2, 8)
+    assert vb.vecinfer_kmeans_workspace_bytes(mixed, True) > vb.vecinfer_kmeans_workspace_bytes(mixed, False)
+    assert vb.vecinfer_kmeans_workspace_bytes(vb.Config(96, 32, 8, 4, 4), True) == 0
+
+
 def test_workspace_size_and_auto_splits():
     assert vb.vecinfer_decode_workspace_bytes(vb.Config(96, 32, 8, 4, 4), 1, 1024, 4) == 0
     assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, vb.MAX_SPLITS + 1) == 0

@@ -495,3 +495,84 @@ def test_decode_head_dim_64_long():
     k_new, v_new = _new_token(shape, seed=65)
     step = _gpu_step(shape, x, k_new, v_new, variant=vb.VARIANT_MFMA)
     _check_step(shape, x, k_new, v_new, step, [shape.N], "step D=64, 64k tokens")
+
+
+# ------------------------------------------------------------------ K-Means codebook training step
+
+def _gpu_kmeans(shape, x, lam, cb):
+    cfg = cfg_of(shape)
+    keys = lam is not None
+    d = shape.d_k if keys else shape.d_v
+    M = shape.D // d
+    B, Hkv, T, _ = x.shape
+    cb_out = torch.full((Hkv, M, 256, d), float("nan"), dtype=torch.float16, device="cuda")
+    codes = torch.full((B, Hkv, T, M), 0xEE, dtype=torch.uint8, device="cuda")
+    counts = torch.full((Hkv, M, 256), -1, dtype=torch.int32, device="cuda")
+    ws = vb.new_kmeans_workspace(cfg, keys)
+    vb.vecinfer_kmeans_step(cfg, dev(x), None if lam is None else dev(lam), dev(cb), cb_out, codes, ws, counts=counts)
+    torch.cuda.synchronize()
+    return cb_out.cpu().numpy(), codes.cpu().numpy(), counts.cpu().numpy()
+
+
+def _check_kmeans(shape, x, lam, cb, got, what):
+    """Assignment against the oracle's Eq. 2 (near-ties logged); update against the oracle's means
+    for the assignment the GPU made (fp32 sums, fp16 result: one fp16 ulp)."""
+    cb_out, codes, counts = got
+    B, Hkv, T, D = x.shape
+    if lam is not None:
+        ref_idx, gap = oracle.encode_keys(x, lam, cb, want_gap=True)
+    else:
+        ref_idx, gap = oracle.encode_values(x, cb, want_gap=True)
+    assert_indices_match(codes, ref_idx, gap, f"{what}: assignment")
+    for g in range(Hkv):
+        rows = x[:, g].reshape(B * T, D).astype(np.float64)
+        if lam is not None:
+            rows = oracle.transform_keys(rows, lam[g])
+        ref_cb, ref_counts = oracle.kmeans_update(rows, codes[:, g].reshape(B * T, -1), cb[g])
+        np.testing.assert_array_equal(counts[g], ref_counts)
+        np.testing.assert_allclose(cb_out[g].astype(np.float64), ref_cb, rtol=1.5e-3, atol=1e-6,
+                                   err_msg=f"{what}: centroids of head {g}")
+        empty = ref_counts == 0
+        np.testing.assert_array_equal(cb_out[g][empty], cb[g][empty])     # untouched, bit for bit
+
+
+@pytest.mark.parametrize("kind", ["keys", "values"])
+@pytest.mark.parametrize("shape", [synth.Shape(2, 4, 2, 128, 1000, 4, 4), synth.Shape(1, 2, 2, 64, 777, 2, 8),
+                                   synth.Shape(3, 1, 1, 128, 70, 8, 2)],
+                         ids=lambda s: f"B{s.B}g{s.Hkv}D{s.D}T{s.N}k{s.d_k}v{s.d_v}")
+def test_kmeans_step(shape, kind):
+    e = synth.encode_inputs(shape, seed=shape.N + 7, n_outlier=3)
+    if kind == "keys":
+        lam = np.stack([oracle.smoothing_factors(e["k"][:, h]) for h in range(shape.Hkv)]).astype(np.float32)
+        x, cb = e["k"], e["cb_k"]
+    else:
+        lam, x, cb = None, e["v"], e["cb_v"]
+    cb = cb.copy()
+    cb[:, :, 9] = 300.0                                   # a centroid nobody is assigned to
+    got = _gpu_kmeans(shape, x, lam, cb)
+    _check_kmeans(shape, x, lam, cb, got, f"kmeans {kind}")
+
+
+def test_kmeans_iterations_reduce_the_quantization_error():
+    """A few Lloyd iterations on the GPU: the error of the codebook (measured by the oracle) goes
+    down monotonically (up to the fp16 rounding of the centroids)."""
+    shape = synth.Shape(2, 2, 2, 128, 2048, 4, 4)
+    e = synth.encode_inputs(shape, seed=71, n_outlier=3)
+    x = e["v"]
+    cb = e["cb_v"]
+
+    def error(cbx):
+        idx = oracle.encode_values(x, cbx)
+        tot = 0.0
+        for g in range(shape.Hkv):
+            rows = x[:, g].reshape(-1, shape.D).astype(np.float64)
+            tot += ((rows - oracle.vq_dequantize(idx[:, g].reshape(rows.shape[0], -1), cbx[g])) ** 2).sum()
+        return tot
+
+    errs = [error(cb)]
+    for _ in range(4):
+        cb, _, counts = _gpu_kmeans(shape, x, None, cb)
+        assert counts.sum() == shape.Hkv * shape.Mv * shape.B * shape.N
+        errs.append(error(cb))
+    assert all(b <= a * (1 + 1e-3) for a, b in zip(errs, errs[1:])), errs
+    assert errs[-1] < 0.8 * errs[0]
