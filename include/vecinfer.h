@@ -62,7 +62,8 @@ enum {
                                     configuration                                            */
     VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
                                     cores for both q.K and P.V; D in {64,128}, d_k and d_v
-                                    in {2,4}, any G the cfg allows                           */
+                                    in {2,4,8} (d_v = 8 only with D = 128), any G the cfg
+                                    allows                                                   */
 };
 
 typedef struct vecinfer_cfg {

@@ -1,6 +1,6 @@
 // Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1, 2, 4 or 8 query heads
-// per KV head (8: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 4 or 2, chosen separately for keys and values
-// (M = D / d = 16 .. 64 sub-spaces), 8-bit codes.
+// per KV head (8: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 8,
+// 4 or 2, chosen separately for keys and values (M = D / d = 8 .. 64 sub-spaces), 8-bit codes.
 //
 // Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
 // row is never assembled: each lane gathers a few centroids with ds_read and hands them
@@ -65,6 +65,12 @@ __device__ __forceinline__ unsigned lds_load_b32(unsigned addr)
     return *(lds_ptr)(addr);
 }
 
+__device__ __forceinline__ uintx4 lds_load_b128(unsigned addr)
+{
+    typedef uintx4 __attribute__((address_space(3))) *lds_ptr;
+    return *(lds_ptr)(addr);
+}
+
 __device__ __forceinline__ half8 as_half8(unsigned a, unsigned b, unsigned c, unsigned d)
 {
     uintx4 u = {a, b, c, d};
@@ -126,12 +132,17 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
 // DK, DV: sub-vector dims of the key and the value codebooks (keys and values may be quantized
 // differently, Sec. 3.2).
 // HG: head groups of 4 query heads that share the gathered key / value operands (G <= 4 HG).
+// At D = 128 the codebooks fill LDS, so a CU holds one workgroup = NW / 4 wavefronts per SIMD: say
+// so, or the compiler squeezes some instantiations under 168 registers for a third wavefront
+// that can never come, and serialises gathers to do it (58 -> 43 us for d_k = 4, d_v = 8).
 template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ>
-__global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
+void decode_mfma_kernel(DecodeParams p)
 {
     constexpr int KG = kG * HG;                        // head slots of the workgroup
-    static_assert((kD == 128 || kD == 64) && (DK == 4 || DK == 2) && (DV == 4 || DV == 2),
-                  "shapes this kernel is laid out for");
+    static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DV == 8 || DV == 4 || DV == 2) &&
+                      (DV != 8 || kD == 128),
+                  "shapes this kernel is laid out for (d_v = 8 needs 16 value sub-spaces: D = 128)");
     constexpr int BLOCK = NW * 64;
     constexpr int MK = kD / DK, MV = kD / DV;          // sub-spaces: 16, 32 or 64
     constexpr int CB_BYTES = kCentroids * kD * 2;      // one codebook set of a KV head: 64 or 32 KB
@@ -144,6 +155,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     constexpr int KW = (MK / 4 + 3) / 4;               // key-code dwords per lane per sub-tile (MK / 4 bytes)
     constexpr int NROUND_V = MV / 16;                  // value sub-spaces per MFMA column: 1, 2 or 4
     constexpr int VW = NROUND_V;                       // value-code dwords per lane per sub-tile (4 tokens x NROUND_V bytes)
+    // P.V accumulators per head group: one per value sub-space of the lane's column, except at
+    // d_v = 8, where the one sub-space is covered in two halves of 4 channels (the four t0 rows of
+    // a head serve channels t0 and t0 + 4 in turn).  Register v of accumulator a is channel
+    // kChanBlock * (NACC * col + a) + v.
+    constexpr int NACC = DV == 8 ? 2 : NROUND_V;
+    constexpr int kChanBlock = DV == 8 ? 4 : DV;
     // LDS layout of the value codebook: [r][code][col] with sub-space m = NROUND_V * col + r.
     // LDS serves a gather 16 lanes at a time, and the 16 lanes of such a group read the same r
     // and 16 different col: with the 16 entries of a code in one ROW_V-byte row they fall on
@@ -192,7 +209,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // ---- per-lane constants
     const int t0 = col & 3;                              // channel-in-sub-vector this A row serves
     unsigned mask_a, mask_b;                             // select the fp16 slot(s) of (p, p)
-    if (DV == 4) {
+    if (DV == 4 || DV == 8) {
+        // d_v = 8: the same two masks pick channel t0 in the first dword pair of the operand
+        // (channels 0-3) or channel t0 + 4 in the second pair (channels 4-7)
         mask_a = t0 == 0 ? 0x0000ffffu : (t0 == 1 ? 0xffff0000u : 0u);
         mask_b = t0 == 2 ? 0x0000ffffu : (t0 == 3 ? 0xffff0000u : 0u);
     } else {
@@ -238,7 +257,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             // keys: the MK / 4 code bytes of the lane's k-slot range of its token
-            if constexpr (MK / 4 == 4) {
+            if constexpr (MK / 4 == 2) {
+                cd.kc[st][0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_k, ko + 16 * st * MK, 0, 0);
+            } else if constexpr (MK / 4 == 4) {
                 cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * MK, 0, 0);
             } else if constexpr (MK / 4 == 8) {
                 const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, 0);
@@ -425,7 +446,9 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
 #pragma unroll
             for (int e = 0; e < CPL; ++e) {
                 unsigned char *const d = sm_v + r * PLANE_V + (code + e) * ROW_V + vcol * ENTRY_V;
-                if (DV == 4)
+                if constexpr (DV == 8)
+                    *reinterpret_cast<uintx4 *>(d) = vreg[j];
+                else if constexpr (DV == 4)
                     *reinterpret_cast<uintx2 *>(d) = uintx2{vreg[j][2 * e], vreg[j][2 * e + 1]};
                 else
                     *reinterpret_cast<unsigned *>(d) = vreg[j][e];
@@ -553,13 +576,13 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     STAMP(2);
     float m_run[HG];                  // running max of head 4 hg + col/4 (log2 units), same in all its lanes
     float l_part[HG];                 // this lane's share of the running sum
-    floatx4 acc_o[HG][NROUND_V];
+    floatx4 acc_o[HG][NACC];
 #pragma unroll
     for (int hg = 0; hg < HG; ++hg) {
         m_run[hg] = -INFINITY;
         l_part[hg] = 0.f;
 #pragma unroll
-        for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < NACC; ++r) acc_o[hg][r] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
     // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
@@ -568,12 +591,18 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         return __builtin_amdgcn_udot4(w, (unsigned)ENTRY_K << (8 * k), base, false);
     };
     auto lds_addr_v = [&](unsigned w, int k, unsigned base) -> unsigned {   // code * ROW_V + base
-        return __builtin_amdgcn_udot4(w, (unsigned)ROW_V << (8 * k), base, false);
+        if constexpr (ROW_V > 255)                  // the multiplier of v_dot4 is one byte: halve, then double
+            return __builtin_amdgcn_udot4(w, (unsigned)(ROW_V / 2) << (8 * k), base >> 1, false) << 1;
+        else
+            return __builtin_amdgcn_udot4(w, (unsigned)ROW_V << (8 * k), base, false);
     };
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
-        if (DK == 4) {
+        if constexpr (DK == 8) {
+            // sub-space (MK/4) kg + r: one 16-byte entry is the whole operand
+            return __builtin_bit_cast(half8, lds_load_b128(lds_addr(cd.kc[st][0], r, lds_k) + r * SUB_K));
+        } else if (DK == 4) {
             // sub-spaces (MK/4) kg + 2r, + 2r + 1: code bytes 2r, 2r+1 of the lane's MK / 4
             const unsigned w = cd.kc[st][r >> 1];
             const int k0 = 2 * (r & 1);
@@ -595,7 +624,10 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     // q = u * NROUND_V + r (step u, round r): centroids of sub-space NROUND_V col + r for tokens
     // 2u, 2u+1.  d = 2: q = r: centroids of sub-space NROUND_V col + r for the 4 tokens.
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
-        if (DV == 4) {
+        if constexpr (DV == 8) {
+            // q = token v of the k-group: the 8 channels of sub-space col of that token
+            return __builtin_bit_cast(half8, lds_load_b128(lds_addr_v(cd.vc[st][0], q, lds_v)));
+        } else if (DV == 4) {
             const int u = q / NROUND_V, r = q % NROUND_V;
             const int b0 = 2 * u * NROUND_V + r, b1 = (2 * u + 1) * NROUND_V + r;
             const uint2 x0 = lds_load_b64(lds_addr_v(cd.vc[st][b0 >> 2], b0 & 3, lds_v) + r * PLANE_V);
@@ -623,8 +655,8 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     //   4  MFMA P.V sub-tiles 0-1 | gather K first H rounds of the NEXT tile
     //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
     // Every stage pairs 4 H MFMAs with 4 H operand gathers.
-    constexpr int kReadsK = DK == 4 ? 2 : 4;          // ds_reads (and address ops) per gathered half8
-    constexpr int kReadsV = DV == 4 ? 2 : 4;
+    constexpr int kReadsK = 8 / DK;                   // ds_reads (and address ops) per gathered half8
+    constexpr int kReadsV = 8 / DV;
     // 4 H groups of: MF MFMAs, RD + XV vector-ALU ops, RD LDS reads
 #define VI_GROUPS8(MF, RD, XV)                                                             \
     _Pragma("unroll") for (int gi = 0; gi < 4 * H; ++gi) {                                    \
@@ -709,7 +741,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 l_part[hg] *= alpha;
                 const float alpha_o = __shfl(alpha, 4 * kg);                     // lane 4kg serves head kg
 #pragma unroll
-                for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] *= alpha_o;
+                for (int r = 0; r < NACC; ++r) acc_o[hg][r] *= alpha_o;
                 m_run[hg] = m_new;
             }
 #pragma unroll
@@ -728,7 +760,17 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
                 // p of sub-tile st lives in quad lane st
                 const unsigned p0 = quad_bcast<st>(pp[hg][0]), p1 = quad_bcast<st>(pp[hg][1]);
                 const unsigned p2 = quad_bcast<st>(pp[hg][2]), p3 = quad_bcast<st>(pp[hg][3]);
-                if (DV == 4) {
+                if constexpr (DV == 8) {
+                    // one token per step; channels t0 (first accumulator) and t0 + 4 (second)
+                    const unsigned pt[4] = {p0, p1, p2, p3};
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const half8 alo = as_half8(pt[v] & mask_a, pt[v] & mask_b, 0u, 0u);
+                        const half8 ahi = as_half8(0u, 0u, pt[v] & mask_a, pt[v] & mask_b);
+                        acc_o[hg][0] = MFMA16(alo, vops[v], acc_o[hg][0], 0, 0, 0);
+                        acc_o[hg][1] = MFMA16(ahi, vops[v], acc_o[hg][1], 0, 0, 0);
+                    }
+                } else if (DV == 4) {
                     const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
                     const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
 #pragma unroll
@@ -756,7 +798,7 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
         for (int st = 2; st < 4; ++st)
 #pragma unroll
             for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
-        VI_GROUPS8(HG, kReadsK, 3 * HG)
+        VI_GROUPS8(HG * (DV == 8 ? 2 : 1), kReadsK, 3 * HG)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 5
@@ -811,12 +853,12 @@ __global__ __launch_bounds__(NW * 64) void decode_mfma_kernel(DecodeParams p)
     float *const sm_l = sm_m + NW * KG;                                   // [NW][KG]
 #pragma unroll
     for (int hg = 0; hg < HG; ++hg) {
-        // acc_o[hg][r] register v of lane (col, kg): head 4 hg + kg, channel d * (NROUND_V * col + r) + v
+        // acc_o[hg][r] register v of lane (col, kg): head 4 hg + kg, channel kChanBlock * (NACC * col + r) + v
 #pragma unroll
-        for (int r = 0; r < NROUND_V; ++r)
+        for (int r = 0; r < NACC; ++r)
 #pragma unroll
-            for (int v = 0; v < DV; ++v)
-                sm_o[(wave * KG + kG * hg + kg) * kD + DV * (NROUND_V * col + r) + v] = acc_o[hg][r][v];
+            for (int v = 0; v < kChanBlock; ++v)
+                sm_o[(wave * KG + kG * hg + kg) * kD + kChanBlock * (NACC * col + r) + v] = acc_o[hg][r][v];
         if (kg == 0 && (col & 3) == 0) {
             sm_m[wave * KG + kG * hg + (col >> 2)] = m_run[hg];
             sm_l[wave * KG + kG * hg + (col >> 2)] = l_head[hg];
@@ -894,8 +936,10 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 bool decode_mfma_supports(const DecodeParams &p)
 {
     // code rows are addressed with 32-bit byte offsets
-    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && (p.dk == 4 || p.dk == 2) &&
-           (p.dv == 4 || p.dv == 2) && p.N * (long long)(p.D / 2) < (1LL << 31);
+    const bool dk_ok = p.dk == 8 || p.dk == 4 || p.dk == 2;
+    const bool dv_ok = p.dv == 4 || p.dv == 2 || (p.dv == 8 && p.D == 128);
+    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok &&
+           p.N * (long long)(p.D / 2) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
@@ -908,6 +952,13 @@ int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
     case 12822: return launch_typed<128, 2, 2, 8, true>(p, stream);
     case 12824: return launch_typed<128, 2, 4, 8, true>(p, stream);
     case 12842: return launch_typed<128, 4, 2, 8, true>(p, stream);
+    case 12888: return launch_typed<128, 8, 8, 8, true>(p, stream);
+    case 12884: return launch_typed<128, 8, 4, 8, true>(p, stream);
+    case 12882: return launch_typed<128, 8, 2, 8, true>(p, stream);
+    case 12848: return launch_typed<128, 4, 8, 8, true>(p, stream);
+    case 12828: return launch_typed<128, 2, 8, 8, true>(p, stream);
+    case 6484: return launch_typed<64, 8, 4, 8, true>(p, stream);
+    case 6482: return launch_typed<64, 8, 2, 8, true>(p, stream);
     case 6444: return launch_typed<64, 4, 4, 8, true>(p, stream);
     case 6422: return launch_typed<64, 2, 2, 8, true>(p, stream);
     case 6424: return launch_typed<64, 2, 4, 8, true>(p, stream);

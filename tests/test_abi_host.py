@@ -99,7 +99,7 @@ def test_decode_argument_errors():
     assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
     assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
-    # the matrix-core variant does not cover d = 8
+    # the matrix-core variant does not cover d_v = 8 at head dim 64
     assert _decode(cfg=vb.Config(64, 8, 1, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
 
 
@@ -134,7 +134,7 @@ def test_decode_step_argument_errors():
     assert step(N=0) == vb.EINVAL                               # the new token itself makes N >= 1
     assert step(N=2048) == vb.EINVAL
     assert step(cfg=vb.Config(128, 32, 8, 4, 4, k_bits=4)) == vb.EUNSUPPORTED
-    assert step(cfg=vb.Config(128, 8, 8, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert step(cfg=vb.Config(64, 8, 8, 4, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     need = vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, 4)
     assert step(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
 

@@ -16,8 +16,8 @@ VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
 
 
 def _supported(shape, variant):
-    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G <= 8 and shape.d_k in (2, 4)
-                                         and shape.d_v in (2, 4))
+    return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G <= 8 and shape.d_k in (2, 4, 8)
+                                         and (shape.d_v in (2, 4) or (shape.d_v == 8 and shape.D == 128)))
 
 
 # ------------------------------------------------------------------ decode, small shapes
@@ -44,6 +44,11 @@ SMALL = [
     synth.Shape(2, 8, 1, 64, 513, 2, 2),
     synth.Shape(1, 7, 1, 128, 900, 4, 4),         # G = 7, G = 3: spare head slots
     synth.Shape(1, 6, 2, 128, 600, 4, 2),
+    synth.Shape(2, 8, 2, 128, 777, 8, 8),         # d = 8 (one bit per element) on the matrix-core path
+    synth.Shape(1, 4, 1, 128, 1000, 4, 8),        # 2-bit keys, 1-bit values
+    synth.Shape(1, 8, 2, 64, 900, 8, 4),
+    synth.Shape(1, 16, 2, 128, 600, 8, 8),
+    synth.Shape(1, 4, 1, 128, 500, 2, 8),
 ]
 
 
@@ -272,6 +277,7 @@ RESIDUAL = [
     (synth.Shape(1, 3, 3, 128, 1000, 2, 2), 20),
     (synth.Shape(1, 16, 2, 128, 777, 4, 4), 128),
     (synth.Shape(1, 7, 1, 128, 900, 4, 4), 64),
+    (synth.Shape(1, 4, 1, 128, 1000, 4, 8), 128),
 ]
 
 
@@ -431,6 +437,8 @@ STEP_SHAPES = [
     synth.Shape(1, 8, 2, 128, 900, 4, 2),
     synth.Shape(1, 16, 2, 128, 777, 4, 4),
     synth.Shape(1, 7, 1, 64, 900, 4, 4),
+    synth.Shape(2, 8, 2, 128, 777, 8, 8),
+    synth.Shape(1, 8, 2, 64, 900, 8, 4),
 ]
 
 
