@@ -60,6 +60,15 @@ def _load():
                                                  C.c_int, dp, dp]
         lib.vo_decode_residual_batch.restype = C.c_int
         lib.vo_kmeans_update.argtypes = [dp, u8p, C.c_int64, C.c_int, C.c_int, C.c_int, dp, dp, i64p]
+        u16p = C.POINTER(C.c_uint16)
+        lib.vo_vq_encode_g.argtypes = [dp, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, dp, u16p, dp]
+        lib.vo_vq_dequantize_g.argtypes = [u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, dp, dp]
+        lib.vo_encode_batch_g.argtypes = [dp, dp, dp, C.c_int, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                          C.c_int, C.c_int, u16p, dp]
+        lib.vo_encode_batch_g.restype = C.c_int
+        lib.vo_decode_batch_g.argtypes = [dp, dp, dp, dp, u16p, u16p, i64p, C.c_int, C.c_int, C.c_int, C.c_int64,
+                                          C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, dp, dp]
+        lib.vo_decode_batch_g.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -74,6 +83,10 @@ def _dp(a):
 
 def _u8p(a):
     return a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def _u16p(a):
+    return a.ctypes.data_as(C.POINTER(C.c_uint16))
 
 
 def num_threads() -> int:
@@ -130,6 +143,13 @@ def vq_encode(X, cb, want_gap: bool = False):
     cb = _f64(cb)
     N, D = X.shape
     M, Cn, d = cb.shape
+    if M * d != D or Cn > 256:
+        # shared codebook ([1, C, d]) and / or more than 256 centroids: uint16 indices
+        assert M == 1 or M * d == D
+        idx = np.empty((N, D // d), dtype=np.uint16)
+        gap = np.empty((N, D // d), dtype=np.float64) if want_gap else None
+        _load().vo_vq_encode_g(_dp(X), N, D, d, Cn, M, _dp(cb), _u16p(idx), _dp(gap) if want_gap else None)
+        return (idx, gap) if want_gap else idx
     assert M * d == D
     idx = np.empty((N, M), dtype=np.uint8)
     gap = np.empty((N, M), dtype=np.float64) if want_gap else None
@@ -139,10 +159,17 @@ def vq_encode(X, cb, want_gap: bool = False):
 
 def vq_dequantize(idx, cb) -> np.ndarray:
     """VQ^{-1}: rows of concatenated centroids, idx [N, M], cb [M, C, d] -> [N, D]."""
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
     cb = _f64(cb)
-    N, M = idx.shape
+    N, M = np.asarray(idx).shape
     M2, Cn, d = cb.shape
+    if M2 != M or Cn > 256:
+        assert M2 in (1, M)
+        idx = np.ascontiguousarray(idx, dtype=np.uint16)
+        assert int(idx.max(initial=0)) < Cn
+        out = np.empty((N, M * d), dtype=np.float64)
+        _load().vo_vq_dequantize_g(_u16p(idx), N, M * d, d, Cn, M2, _dp(cb), _dp(out))
+        return out
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
     assert M == M2
     out = np.empty((N, M * d), dtype=np.float64)
     _load().vo_vq_dequantize(_u8p(idx), N, M * d, d, Cn, _dp(cb), _dp(out))
@@ -178,6 +205,8 @@ def _encode(x, lam, cb, transform, want_gap):
     cb = _f64(cb)
     B, Hkv, T, D = x.shape
     Hc, M, Cn, d = cb.shape
+    if M * d != D or Cn > 256:
+        return _encode_g(x, lam, cb, transform, want_gap)
     assert Hc == Hkv and M * d == D
     lam64 = _f64(lam) if transform else np.ones((Hkv, D), dtype=np.float64)
     assert lam64.shape == (Hkv, D)
@@ -190,6 +219,70 @@ def _encode(x, lam, cb, transform, want_gap):
     return (idx, gap) if want_gap else idx
 
 
+def _encode_g(x, lam, cb, transform, want_gap):
+    """General encode: cb [Hkv, Mcb, C, d] with Mcb = D / d (per sub-space) or 1 (one codebook shared by
+    the sub-spaces of a head, the form of Alg. 1 and Sec. 2.2), C up to 65536 -> uint16 [B, Hkv, T, M]."""
+    B, Hkv, T, D = x.shape
+    Hc, Mcb, Cn, d = cb.shape
+    M = D // d
+    assert Hc == Hkv and M * d == D and Mcb in (1, M)
+    lam64 = _f64(lam) if transform else np.ones((Hkv, D), dtype=np.float64)
+    assert lam64.shape == (Hkv, D)
+    idx = np.empty((B, Hkv, T, M), dtype=np.uint16)
+    gap = np.empty((B, Hkv, T, M), dtype=np.float64) if want_gap else None
+    rc = _load().vo_encode_batch_g(_dp(x), _dp(lam64), _dp(cb), B, Hkv, T, D, d, Cn, Mcb, transform,
+                                   _u16p(idx), _dp(gap) if want_gap else None)
+    if rc != 0:
+        raise ValueError("vo_encode_batch_g rejected the shapes")
+    return (idx, gap) if want_gap else idx
+
+
+def pack_codes(idx, bits: int) -> np.ndarray:
+    """Rows of M codes of `bits` bits each -> rows of M * bits / 8 bytes: the codes laid end to end
+    as one little-endian bit string (code m fills bits m * bits .. (m + 1) * bits - 1 of the row;
+    bit i of the row is bit i % 8 of byte i // 8).  This is the "(d_h / d) x (b / 8) bytes for the
+    indices" of Sec. 2.2.  idx [..., M] unsigned, every value < 2^bits."""
+    idx = np.asarray(idx)
+    M = idx.shape[-1]
+    assert (M * bits) % 8 == 0 and int(idx.max(initial=0)) < (1 << bits)
+    one = ((idx[..., None].astype(np.uint32) >> np.arange(bits, dtype=np.uint32)) & 1).astype(np.uint8)
+    return np.packbits(one.reshape(*idx.shape[:-1], M * bits), axis=-1, bitorder="little")
+
+
+def unpack_codes(packed, bits: int, M: int) -> np.ndarray:
+    """Inverse of pack_codes: uint8 [..., M * bits / 8] -> uint16 [..., M]."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.shape[-1] * 8 == M * bits
+    one = np.unpackbits(packed, axis=-1, bitorder="little").reshape(*packed.shape[:-1], M, bits)
+    out = np.zeros(one.shape[:-1], dtype=np.uint16)
+    for i in range(bits):
+        out |= one[..., i].astype(np.uint16) << np.uint16(i)
+    return out
+
+
+def _decode_g(q, lam, cb_k, cb_v, k_idx, v_idx, seq_lens):
+    B, Hq, D = q.shape
+    Hkv, Mcb_k, C_k, d_k = cb_k.shape
+    _, Mcb_v, C_v, d_v = cb_v.shape
+    Mk, Mv = D // d_k, D // d_v
+    k_idx = np.ascontiguousarray(k_idx, dtype=np.uint16)
+    v_idx = np.ascontiguousarray(v_idx, dtype=np.uint16)
+    assert Mcb_k in (1, Mk) and Mcb_v in (1, Mv)
+    assert k_idx.shape[:2] == (B, Hkv) and k_idx.shape[3] == Mk and v_idx.shape[3] == Mv
+    assert int(k_idx.max(initial=0)) < C_k and int(v_idx.max(initial=0)) < C_v
+    n_cap = k_idx.shape[2]
+    sl = np.full(B, n_cap, dtype=np.int64) if seq_lens is None else np.ascontiguousarray(seq_lens, dtype=np.int64)
+    assert sl.shape == (B,) and int(sl.max()) <= n_cap
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    rc = _load().vo_decode_batch_g(_dp(q), _dp(lam), _dp(cb_k), _dp(cb_v), _u16p(k_idx), _u16p(v_idx),
+                                   sl.ctypes.data_as(C.POINTER(C.c_int64)), B, Hq, Hkv, n_cap, D, d_k, C_k, Mcb_k,
+                                   d_v, C_v, Mcb_v, _dp(out), _dp(lse))
+    if rc != 0:
+        raise ValueError("vo_decode_batch_g rejected the inputs (empty sequence or bad shapes)")
+    return out, lse
+
+
 def decode_attention(q_f16, lam, cb_k, cb_v, k_idx, v_idx, seq_lens=None, *,
                      path: str = "eq10", tile: int = 64):
     """One decode step of VQ attention for a batch (Eq. 10; GQA by consecutive groups).
@@ -198,11 +291,18 @@ def decode_attention(q_f16, lam, cb_k, cb_v, k_idx, v_idx, seq_lens=None, *,
     k_idx [B, Hkv, n_cap, Mk]; v_idx [B, Hkv, n_cap, Mv]; seq_lens [B] or None (= n_cap).
     path "eq10": explicit dequantize-then-attend; "alg1": lookup table + online softmax
     over tiles of `tile` tokens.  Returns (out [B, Hq, D] f64, lse [B, Hq] f64).
+
+    A codebook may also be [Hkv, 1, C, d] (shared by the sub-spaces of a head) and C may exceed
+    256, with unpacked uint16 indices; keys and values may then differ in C (path "eq10" only).
     """
     q = _f64(q_f16)
     lam = _f64(lam)
     cb_k = _f64(cb_k)
     cb_v = _f64(cb_v)
+    if (cb_k.shape[1] * cb_k.shape[3] != q.shape[2] or cb_v.shape[1] * cb_v.shape[3] != q.shape[2]
+            or cb_k.shape[2] > 256 or cb_v.shape[2] > 256):
+        assert path == "eq10"
+        return _decode_g(q, lam, cb_k, cb_v, k_idx, v_idx, seq_lens)
     k_idx = np.ascontiguousarray(k_idx, dtype=np.uint8)
     v_idx = np.ascontiguousarray(v_idx, dtype=np.uint8)
     B, Hq, D = q.shape

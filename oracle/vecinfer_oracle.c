@@ -23,6 +23,12 @@
  *                          ("residual length ... 128"): recent tokens kept unquantized
  *   vo_kmeans_update       centroid update of one Lloyd iteration of the K-Means codebook training
  *                          (Sec. 2.2: the codebook is built by K-Means; Sec. 4.1: at most 30 iterations)
+ *   vo_vq_encode_g, vo_vq_dequantize_g, vo_vq_attention_g, vo_encode_batch_g, vo_decode_batch_g
+ *                          the same definitions (Eq. 2, VQ^{-1}, Eq. 10) for codes of up to 16 bits and
+ *                          for a codebook shared by all sub-spaces, as Alg. 1 states it (one C_k, one
+ *                          C_v of 2^b centroids; "codebook size 2^b x d x 2 bytes", Sec. 5.3), which the
+ *                          configurations with 10- and 12-bit codes (d8b12, d4b12, d4b10; Sec. 4.1,
+ *                          Tables 1-3) call for
  *   vo_merge_splits        log-sum-exp merge of per-split (o, L) pairs; the paper
  *                          returns L (Alg. 1 step 22) but does not print the merge
  *
@@ -484,4 +490,170 @@ void vo_kmeans_update(const double *X, const uint8_t *idx, int64_t N, int D, int
             }
         free(sum);
     }
+}
+
+
+/* ---- general forms: codes of up to 16 bits; per-sub-space or shared codebooks ----
+ *
+ * cb is [Mcb, C, d] with Mcb = M (sub-space m uses table m, as in the functions above) or
+ * Mcb = 1 (every sub-space uses the one table: Alg. 1's C in R^{2^b x D/M}).  Indices are
+ * uint16, one per sub-vector, unpacked; the packed b-bit stream the GPU library stores is
+ * formed from them by the caller. */
+
+static const double *table_of(const double *cb, int Mcb, int m, int C, int d)
+{
+    return cb + (Mcb == 1 ? (int64_t)0 : (int64_t)m * C * d);
+}
+
+/* Eq. 2, lowest index on ties; relgap as in vo_vq_encode. */
+void vo_vq_encode_g(const double *X, int64_t N, int D, int d, int C, int Mcb, const double *cb,
+                    uint16_t *idx, double *relgap)
+{
+    const int M = D / d;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int m = 0; m < M; ++m) {
+            const double *x = X + n * D + (int64_t)m * d;
+            const double *tab = table_of(cb, Mcb, m, C, d);
+            double best = INFINITY, second = INFINITY;
+            int arg = 0;
+            for (int c = 0; c < C; ++c) {
+                double dist = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    const double t = x[j] - tab[(int64_t)c * d + j];
+                    dist += t * t;
+                }
+                if (dist < best) {
+                    second = best;
+                    best = dist;
+                    arg = c;
+                } else if (dist < second) {
+                    second = dist;
+                }
+            }
+            idx[n * M + m] = (uint16_t)arg;
+            if (relgap) relgap[n * M + m] = (second - best) / (best > 1e-300 ? best : 1e-300);
+        }
+    }
+}
+
+/* VQ^{-1}: Xhat[n, m*d + j] = table(m)[idx[n,m]][j]. */
+void vo_vq_dequantize_g(const uint16_t *idx, int64_t N, int D, int d, int C, int Mcb,
+                        const double *cb, double *Xhat)
+{
+    const int M = D / d;
+    for (int64_t n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            const double *cen = table_of(cb, Mcb, m, C, d) + (int64_t)idx[n * M + m] * d;
+            for (int j = 0; j < d; ++j) Xhat[n * D + (int64_t)m * d + j] = cen[j];
+        }
+}
+
+/* Eq. 10 for one query row against one KV head; keys and values may differ in sub-vector
+ * dim, number of centroids and codebook sharing (Sec. 3.2: K and V are quantized separately). */
+int vo_vq_attention_g(const double *qt, const uint16_t *kidx, const uint16_t *vidx,
+                      const double *cb_k, const double *cb_v, int64_t N, int D, int d_k, int C_k,
+                      int Mcb_k, int d_v, int C_v, int Mcb_v, double *out, double *lse)
+{
+    if (N < 1) return -1;
+    double *Khat = (double *)malloc(sizeof(double) * (size_t)N * D);
+    double *Vhat = (double *)malloc(sizeof(double) * (size_t)N * D);
+    double *s = (double *)malloc(sizeof(double) * (size_t)N);
+    vo_vq_dequantize_g(kidx, N, D, d_k, C_k, Mcb_k, cb_k, Khat);
+    vo_vq_dequantize_g(vidx, N, D, d_v, C_v, Mcb_v, cb_v, Vhat);
+    const double scale = 1.0 / sqrt((double)D);
+    double mx = -INFINITY;
+    for (int64_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int i = 0; i < D; ++i) acc += qt[i] * Khat[n * D + i];
+        s[n] = acc * scale;
+        if (s[n] > mx) mx = s[n];
+    }
+    double denom = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        s[n] = exp(s[n] - mx);
+        denom += s[n];
+    }
+    for (int i = 0; i < D; ++i) out[i] = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        const double p = s[n] / denom;
+        for (int i = 0; i < D; ++i) out[i] += p * Vhat[n * D + i];
+    }
+    if (lse) *lse = mx + log(denom);
+    free(Khat);
+    free(Vhat);
+    free(s);
+    return 0;
+}
+
+/* X [B, Hkv, T, D], lam [Hkv, D], cb [Hkv, Mcb, C, d] -> idx [B, Hkv, T, M] (uint16). */
+int vo_encode_batch_g(const double *X, const double *lam, const double *cb, int B, int Hkv,
+                      int64_t T, int D, int d, int C, int Mcb, int transform, uint16_t *idx,
+                      double *relgap)
+{
+    if (D % d != 0 || (Mcb != 1 && Mcb != D / d) || C < 1 || C > 65536) return -1;
+    const int M = D / d;
+    double *H = NULL;
+    if (transform) {
+        H = (double *)malloc(sizeof(double) * (size_t)D * D);
+        if (vo_hadamard(D, H) != 0) {
+            free(H);
+            return -1;
+        }
+    }
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hkv; ++g) {
+            const int64_t row0 = ((int64_t)b * Hkv + g) * T;
+            const double *Xbg = X + row0 * D;
+            const double *cbg = cb + (int64_t)g * Mcb * C * d;
+            double *gap = relgap ? relgap + row0 * M : NULL;
+            if (transform) {
+                double *Kt = (double *)malloc(sizeof(double) * (size_t)T * D);
+                vo_transform_keys(Xbg, T, D, lam + (int64_t)g * D, H, Kt);
+                vo_vq_encode_g(Kt, T, D, d, C, Mcb, cbg, idx + row0 * M, gap);
+                free(Kt);
+            } else {
+                vo_vq_encode_g(Xbg, T, D, d, C, Mcb, cbg, idx + row0 * M, gap);
+            }
+        }
+    free(H);
+    return 0;
+}
+
+/* As vo_decode_batch (path 0), with cb_k [Hkv, Mcb_k, C_k, d_k], cb_v [Hkv, Mcb_v, C_v, d_v]
+ * and uint16 indices kidx [B, Hkv, n_cap, Mk], vidx [B, Hkv, n_cap, Mv]. */
+int vo_decode_batch_g(const double *q, const double *lam, const double *cb_k, const double *cb_v,
+                      const uint16_t *kidx, const uint16_t *vidx, const int64_t *seq_lens, int B,
+                      int Hq, int Hkv, int64_t n_cap, int D, int d_k, int C_k, int Mcb_k, int d_v,
+                      int C_v, int Mcb_v, double *out, double *lse)
+{
+    if (Hq % Hkv != 0 || D % d_k != 0 || D % d_v != 0) return -1;
+    const int G = Hq / Hkv, Mk = D / d_k, Mv = D / d_v;
+    if ((Mcb_k != 1 && Mcb_k != Mk) || (Mcb_v != 1 && Mcb_v != Mv)) return -1;
+    double *H = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if (vo_hadamard(D, H) != 0) {
+        free(H);
+        return -1;
+    }
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            double *qt = (double *)malloc(sizeof(double) * (size_t)D);
+            vo_transform_query(q + ((int64_t)b * Hq + h) * D, D, lam + (int64_t)g * D, H, qt);
+            const int64_t bg = (int64_t)b * Hkv + g;
+            const int rc = vo_vq_attention_g(qt, kidx + bg * n_cap * Mk, vidx + bg * n_cap * Mv,
+                                             cb_k + (int64_t)g * Mcb_k * C_k * d_k,
+                                             cb_v + (int64_t)g * Mcb_v * C_v * d_v, seq_lens[b], D, d_k,
+                                             C_k, Mcb_k, d_v, C_v, Mcb_v, out + ((int64_t)b * Hq + h) * D,
+                                             lse + ((int64_t)b * Hq + h));
+            if (rc != 0) {
+#pragma omp atomic write
+                err = -1;
+            }
+            free(qt);
+        }
+    free(H);
+    return err;
 }

@@ -482,6 +482,153 @@ def test_kmeans_step_never_increases_the_quantization_error(oracle):
     np.testing.assert_allclose(again, cb, rtol=1e-13, atol=1e-15)
 
 
+# --------------------------------------------------------------------------- codes wider than 8 bits, shared codebook
+# (Sec. 2.2: one codebook of 2^b centroids, (d_h / d) x (b / 8) bytes of indices per vector; Sec. 4.1 / Tables 1-3:
+#  d8b12, d4b12, K-d4b10 / V-d8b12; Sec. 4.4: codebook size 2^12 x 8 x 2 bytes for 1.5 bits)
+
+def test_pack_codes_worked_example_and_big_integer_definition(oracle):
+    """The row is one little-endian bit string: code m sits at bits m*b .. m*b + b - 1."""
+    # by hand: 0xABC then 0x123 at 12 bits = the 24-bit number 0x123ABC = bytes BC 3A 12
+    np.testing.assert_array_equal(oracle.pack_codes(np.array([[0xABC, 0x123]], dtype=np.uint16), 12),
+                                  np.array([[0xBC, 0x3A, 0x12]], dtype=np.uint8))
+    # 10 bits: 0x3FF, 0, 0x155, 0x2AA -> 0x2AA << 30 | 0x155 << 20 | 0 << 10 | 0x3FF
+    v = (0x2AA << 30) | (0x155 << 20) | 0x3FF
+    np.testing.assert_array_equal(oracle.pack_codes(np.array([0x3FF, 0, 0x155, 0x2AA], dtype=np.uint16), 10),
+                                  np.frombuffer(v.to_bytes(5, "little"), dtype=np.uint8))
+    g = synth.rng(77)
+    for bits, M in ((12, 16), (10, 32), (12, 32), (10, 16), (8, 32)):
+        idx = g.integers(0, 1 << bits, size=(3, 5, M), dtype=np.uint16)
+        packed = oracle.pack_codes(idx, bits)
+        assert packed.dtype == np.uint8 and packed.shape == (3, 5, M * bits // 8)
+        for row, prow in zip(idx.reshape(-1, M), packed.reshape(-1, M * bits // 8)):
+            big = sum(int(c) << (m * bits) for m, c in enumerate(row))         # Python big integer
+            assert bytes(prow) == big.to_bytes(M * bits // 8, "little")
+        np.testing.assert_array_equal(oracle.unpack_codes(packed, bits, M), idx)
+    # 8-bit codes: the packed row is the code row itself
+    idx8 = g.integers(0, 256, size=(4, 32), dtype=np.uint16)
+    np.testing.assert_array_equal(oracle.pack_codes(idx8, 8), idx8.astype(np.uint8))
+
+
+@pytest.mark.parametrize("d,C", [(8, 4096), (4, 1024), (4, 4096), (8, 1024)])
+def test_shared_codebook_encode_vs_cdist_brute_force(oracle, d, C):
+    """Eq. 2 with one codebook for every sub-space: each sub-vector against the same C centroids."""
+    g = synth.rng(300 + d + C)
+    D, N = 32, 40
+    M = D // d
+    X = g.standard_normal((N, D))
+    cb = g.standard_normal((1, C, d))
+    idx, gap = oracle.vq_encode(X, cb, want_gap=True)
+    assert idx.dtype == np.uint16 and idx.shape == (N, M)
+    dist = scipy.spatial.distance.cdist(X.reshape(N * M, d), cb[0], metric="sqeuclidean")
+    np.testing.assert_array_equal(idx.reshape(-1), dist.argmin(axis=1))
+    two = np.sort(dist, axis=1)[:, :2]
+    np.testing.assert_allclose(gap.reshape(-1), (two[:, 1] - two[:, 0]) / two[:, 0], rtol=1e-9)
+    # sub-vectors that are centroids come back as their own (lowest duplicate) index; ties -> lowest index
+    cb[0, 700] = cb[0, 5]
+    pick = g.integers(0, C, size=(N, M))
+    Xc = cb[0][pick].reshape(N, D)
+    back = oracle.vq_encode(Xc, cb)
+    np.testing.assert_array_equal(back, np.where(pick == 700, 5, pick))
+    # dequantization is the table lookup
+    np.testing.assert_array_equal(oracle.vq_dequantize(back, cb), cb[0][back].reshape(N, D))
+
+
+def test_general_encode_reduces_to_the_per_sub_space_one(oracle):
+    """A shared codebook replicated M times is a per-sub-space codebook: both forms must agree,
+    and the uint16 path with 256 centroids must reproduce the uint8 path."""
+    g = synth.rng(311)
+    D, d, C, N = 64, 4, 256, 33
+    M = D // d
+    X = g.standard_normal((N, D))
+    shared = g.standard_normal((1, C, d))
+    a = oracle.vq_encode(X, shared)                                     # general path (Mcb = 1)
+    b = oracle.vq_encode(X, np.repeat(shared, M, axis=0))               # uint8 path
+    assert a.dtype == np.uint16 and b.dtype == np.uint8
+    np.testing.assert_array_equal(a, b)
+
+
+def test_wide_encode_keys_vs_numpy_pipeline(oracle):
+    """Keys: smooth, rotate (library Hadamard), then the shared-codebook search, batch layout."""
+    g = synth.rng(312)
+    B, Hkv, T, D, d, C = 2, 2, 9, 128, 8, 4096
+    k = g.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    lam = np.exp(0.5 * g.standard_normal((Hkv, D))).astype(np.float32)
+    cb = g.standard_normal((Hkv, 1, C, d)).astype(np.float16)
+    got, gap = oracle.encode_keys(k, lam, cb, want_gap=True)
+    gotv = oracle.encode_values(k, cb)
+    assert got.dtype == np.uint16 and got.shape == (B, Hkv, T, D // d)
+    H = scipy.linalg.hadamard(D) / np.sqrt(D)
+    for b in range(B):
+        for h in range(Hkv):
+            Kt = (k[b, h].astype(np.float64) / lam[h].astype(np.float64)) @ H
+            dist = scipy.spatial.distance.cdist(Kt.reshape(-1, d), cb[h, 0].astype(np.float64), "sqeuclidean")
+            ok = (dist.argmin(axis=1) == got[b, h].reshape(-1)) | (gap[b, h].reshape(-1) < 1e-9)
+            assert ok.all()
+            dist = scipy.spatial.distance.cdist(k[b, h].astype(np.float64).reshape(-1, d),
+                                                cb[h, 0].astype(np.float64), "sqeuclidean")
+            np.testing.assert_array_equal(dist.argmin(axis=1), gotv[b, h].reshape(-1))
+
+
+@pytest.mark.parametrize("kcfg,vcfg", [((8, 4096, 1), (8, 4096, 1)), ((4, 1024, 1), (8, 4096, 1)),
+                                       ((8, 4096, 1), (8, 256, 16)), ((4, 256, 32), (4, 4096, 1))])
+def test_wide_decode_matches_torch_sdpa_on_dequantized_cache(oracle, kcfg, vcfg):
+    """Eq. 10 with wide codes / shared codebooks is textbook attention on the looked-up rows;
+    keys and values mix code widths and sharing."""
+    g = synth.rng(320 + kcfg[1] + vcfg[1])
+    B, Hq, Hkv, D, N = 2, 4, 2, 128, 61
+    G = Hq // Hkv
+    (d_k, C_k, Mcb_k), (d_v, C_v, Mcb_v) = kcfg, vcfg
+    Mk, Mv = D // d_k, D // d_v
+    cb_k = g.standard_normal((Hkv, Mcb_k, C_k, d_k)).astype(np.float16)
+    cb_v = g.standard_normal((Hkv, Mcb_v, C_v, d_v)).astype(np.float16)
+    k_idx = g.integers(0, C_k, size=(B, Hkv, N, Mk), dtype=np.uint16)
+    v_idx = g.integers(0, C_v, size=(B, Hkv, N, Mv), dtype=np.uint16)
+    q = g.standard_normal((B, Hq, D)).astype(np.float16)
+    lam = np.exp(0.5 * g.standard_normal((Hkv, D))).astype(np.float32)
+    seq = np.array([61, 17])
+    out, lse = oracle.decode_attention(q, lam, cb_k, cb_v, k_idx, v_idx, seq)
+    Hm = scipy.linalg.hadamard(D) / np.sqrt(D)
+
+    def rows(idx, cb):          # numpy fancy indexing, not the oracle's loop
+        M = idx.shape[1]
+        tab = cb.astype(np.float64)
+        return (tab[0][idx] if tab.shape[0] == 1 else tab[np.arange(M)[None, :], idx]).reshape(idx.shape[0], -1)
+
+    for b in range(B):
+        n = seq[b]
+        Kh = np.stack([rows(k_idx[b, h, :n], cb_k[h]) for h in range(Hkv)])
+        Vh = np.stack([rows(v_idx[b, h, :n], cb_v[h]) for h in range(Hkv)])
+        qt = (q[b].astype(np.float64) * np.repeat(lam.astype(np.float64), G, axis=0)) @ Hm
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qt)[None, :, None, :],
+            torch.from_numpy(Kh).repeat_interleave(G, dim=0)[None],
+            torch.from_numpy(Vh).repeat_interleave(G, dim=0)[None])[0, :, 0].numpy()
+        np.testing.assert_allclose(out[b], ref, rtol=1e-11, atol=1e-13)
+        scores = np.einsum("hd,hnd->hn", qt, np.repeat(Kh, G, axis=0)) / np.sqrt(D)
+        np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-12)
+
+
+def test_wide_decode_special_cases(oracle):
+    """q = 0: the mean of the looked-up value rows and L = ln N; N = 1: that token's value row."""
+    g = synth.rng(333)
+    B, Hq, Hkv, D, N, d, C = 1, 2, 1, 128, 23, 8, 4096
+    cb_k = g.standard_normal((Hkv, 1, C, d)).astype(np.float16)
+    cb_v = g.standard_normal((Hkv, 1, C, d)).astype(np.float16)
+    k_idx = g.integers(0, C, size=(B, Hkv, N, D // d), dtype=np.uint16)
+    v_idx = g.integers(0, C, size=(B, Hkv, N, D // d), dtype=np.uint16)
+    lam = np.ones((Hkv, D), dtype=np.float32)
+    Vh = cb_v[0, 0].astype(np.float64)[v_idx[0, 0]].reshape(N, D)
+    out, lse = oracle.decode_attention(np.zeros((B, Hq, D), np.float16), lam, cb_k, cb_v, k_idx, v_idx)
+    np.testing.assert_allclose(out[0, 0], Vh.mean(axis=0), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse, np.log(N), rtol=1e-13)
+    q = g.standard_normal((B, Hq, D)).astype(np.float16)
+    out1, lse1 = oracle.decode_attention(q, lam, cb_k, cb_v, k_idx, v_idx, np.array([1]))
+    np.testing.assert_allclose(out1[0, 1], Vh[0], rtol=1e-13)
+    Kh0 = cb_k[0, 0].astype(np.float64)[k_idx[0, 0, 0]].reshape(D)
+    H = scipy.linalg.hadamard(D) / np.sqrt(D)
+    np.testing.assert_allclose(lse1[0, 1], ((q[0, 1].astype(np.float64)) @ H) @ Kh0 / np.sqrt(D), rtol=1e-11)
+
+
 def test_decode_rejects_empty_sequence(oracle):
     s, x = _small_decode_case(28, B=2)
     with pytest.raises(ValueError):
