@@ -36,7 +36,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="196k-b2d4",
-                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-kd2vd4"])
+                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-kd2vd4", "196k-d8b12",
+                             "196k-d4b12", "196k-kd4b10-vd8b12", "196k-kd8b12-vd8b8"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
@@ -67,8 +68,13 @@ def main() -> int:
 
     shape = {"196k-b2d4": synth.LLAMA8B_196K, "196k-b4d2": synth.LLAMA8B_196K_B4D2,
              "32k": synth.LLAMA8B_32K, "batch32": synth.LLAMA8B_BATCH32,
-             "196k-d64": synth.HEADDIM64_196K, "196k-kd2vd4": synth.LLAMA8B_196K_KD2_VD4}[args.workload]
-    cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v)
+             "196k-d64": synth.HEADDIM64_196K, "196k-kd2vd4": synth.LLAMA8B_196K_KD2_VD4,
+             # codes wider than 8 bits, one shared codebook per KV head (side measurements, not the metric)
+             "196k-d8b12": synth.LLAMA8B_196K_D8B12,
+             "196k-d4b12": synth.Shape(1, 32, 8, 128, 196608, 4, 4, 12, 12),
+             "196k-kd4b10-vd8b12": synth.Shape(1, 32, 8, 128, 196608, 4, 8, 10, 12),
+             "196k-kd8b12-vd8b8": synth.Shape(1, 32, 8, 128, 196608, 8, 8, 12, 8)}[args.workload]
+    cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
     variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
     idx_bytes = shape.index_bytes()
     layers = args.layers or max(2, -(-768 * 2**20 // idx_bytes))   # working set >= 768 MB > Infinity Cache
@@ -81,8 +87,8 @@ def main() -> int:
     caches = [(dev(x0["k_idx"]), dev(x0["v_idx"]))]
     for layer in range(1, layers):
         g = synth.rng(1000 + layer)
-        caches.append((dev(synth.random_indices(g, shape.B, shape.Hkv, shape.N, shape.Mk)),
-                       dev(synth.random_indices(g, shape.B, shape.Hkv, shape.N, shape.Mv))))
+        caches.append((dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_k)),
+                       dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_v))))
     g = synth.rng(77)
     new_k = dev(synth.values(g, shape.B, shape.Hkv, 1, shape.D))
     new_v = dev(synth.values(g, shape.B, shape.Hkv, 1, shape.D))
@@ -156,7 +162,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "u8 codes, f16 tables, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"{'llama-3.1-8b' if shape.D == 128 else 'head-dim-64'} layer decode, B={shape.B}, Hq={shape.Hq}, Hkv={shape.Hkv}, "
-                               f"D={shape.D}, N={shape.N}, K d{shape.d_k}b8 / V d{shape.d_v}b8",
+                               f"D={shape.D}, N={shape.N}, K d{shape.d_k}b{shape.b_k} / V d{shape.d_v}b{shape.b_v}",
                    "step": f"attention over the code cache and a {args.residual}-token fp16 window" if args.residual
                    else "attention only" if args.decode_only
                    else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention, "
@@ -177,9 +183,14 @@ def main() -> int:
     # repeated until about 10 s of wall time have passed (bounded sample of the same workload)
     if not args.no_cpu_baseline:
         import oracle
+        ox = dict(x0)
+        for side, bits, M in (("k", shape.b_k, shape.Mk), ("v", shape.b_v, shape.Mv)):
+            if bits != 8:       # the oracle takes a shared codebook as [Hkv, 1, C, d] and unpacked indices
+                ox["cb_" + side] = x0["cb_" + side][:, None]
+                ox[side + "_idx"] = oracle.unpack_codes(x0[side + "_idx"], bits, M)
         reps, t0 = 0, time.perf_counter()
         while True:
-            oracle.decode_attention(x0["q"], x0["lam"], x0["cb_k"], x0["cb_v"], x0["k_idx"], x0["v_idx"])
+            oracle.decode_attention(ox["q"], ox["lam"], ox["cb_k"], ox["cb_v"], ox["k_idx"], ox["v_idx"])
             reps += 1
             dt = time.perf_counter() - t0
             if dt >= 10.0 or reps >= 64:

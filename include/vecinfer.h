@@ -18,18 +18,31 @@
  *     enqueued.  No exception crosses the boundary.
  *   - Thread-safe and stateless; decode needs a caller-provided scratch workspace.
  *
- * Notation (paper): D head dim, d sub-vector dim, M = D / d sub-spaces, 256
- * centroids per sub-space (8-bit codes), H_q query heads, H_kv KV heads,
- * G = H_q / H_kv, query head h reads KV head h / G (consecutive grouping).
+ * Notation (paper): D head dim, d sub-vector dim, M = D / d sub-spaces, b code bits
+ * (2^b centroids; the "dnbm" names of Sec. 4.1 are d = n, b = m), H_q query heads,
+ * H_kv KV heads, G = H_q / H_kv, query head h reads KV head h / G (consecutive grouping).
  *
  * Layouts (row-major, innermost last)
  *   keys / values      fp16  [B, H_kv, T, D]
  *   lambda             fp32  [H_kv, D]          smoothing factors, all > 0
+ *   queries / output   fp16  [B, H_q, D]
+ *   lse                fp32  [B, H_q]           natural-log sum of exp of the scores
+ *  8-bit codes (b = 8)
  *   codebooks          fp16  [H_kv, M, 256, d]  one codebook per (KV head, sub-space)
  *   code cache         uint8 [B, H_kv, n_cap, M] one byte per (token, sub-space): the
  *                                               paper's N x M code matrix per head
- *   queries / output   fp16  [B, H_q, D]
- *   lse                fp32  [B, H_q]           natural-log sum of exp of the scores
+ *  10- and 12-bit codes (d8b12, d4b12, d4b10, ... of Sec. 4.1; D = 128, d = 4 or 8)
+ *   codebooks          fp16  [H_kv, 2^b, d]     one codebook per KV head, shared by its M
+ *                                               sub-spaces: the single codebook of Sec. 2.2
+ *                                               and Alg. 1 (2^b x d x 2 bytes; 64 KB at d8b12,
+ *                                               Sec. 4.4)
+ *   code cache         uint8 [B, H_kv, n_cap, M b / 8]  a token's M codes end to end as one
+ *                                               little-endian bit string: code m fills bits
+ *                                               m b .. m b + b - 1 of the row, bit i of the row
+ *                                               being bit i % 8 of byte i / 8 (the
+ *                                               (D / d) x (b / 8) bytes per vector of Sec. 2.2)
+ *  Keys and values choose d and b independently (k_*, v_* of vecinfer_cfg); the layouts above
+ *  apply per side.  vecinfer_index_row_bytes / vecinfer_codebook_elems return the sizes.
  */
 #ifndef VECINFER_H
 #define VECINFER_H
@@ -63,7 +76,8 @@ enum {
     VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
                                     cores for both q.K and P.V; D in {64,128}, d_k and d_v
                                     in {2,4,8} (d_v = 8 only with D = 128), any G the cfg
-                                    allows                                                   */
+                                    allows; the only variant for 10- / 12-bit codes, which
+                                    need d = 4 or 8 on BOTH sides                            */
 };
 
 typedef struct vecinfer_cfg {
@@ -72,8 +86,10 @@ typedef struct vecinfer_cfg {
     int32_t num_kv_heads;  /* H_kv, divides H_q; G = H_q / H_kv in 1 .. 8                    */
     int32_t k_sub_dim;     /* d for keys: 2, 4 or 8                                          */
     int32_t v_sub_dim;     /* d for values: 2, 4 or 8 (keys and values may differ, Sec. 3.2)  */
-    int32_t k_bits;        /* code width for keys: 8 (uint8 index, 256 centroids)            */
-    int32_t v_bits;        /* code width for values: 8                                       */
+    int32_t k_bits;        /* code width b for keys: 8 (one byte per code, 256 centroids per
+                              sub-space), or 10 / 12 (packed rows, one shared codebook of 2^b
+                              centroids per KV head; needs D = 128 and d_k = 4 or 8)          */
+    int32_t v_bits;        /* code width for values: 8, 10 or 12, same rules with d_v        */
 } vecinfer_cfg;
 
 /*
@@ -85,6 +101,8 @@ typedef struct vecinfer_cfg {
  * T = 1 with pos0 = current length is the decode-time append of Eq. 9.
  *   k_f16   [B, H_kv, T, D] fp16      lambda [H_kv, D] fp32
  *   cb_k    [H_kv, M_k, 256, d_k]     k_idx  [B, H_kv, n_cap, M_k], rows pos0 .. pos0+T-1 written
+ * With k_bits = 10 or 12 the search runs over the one shared codebook cb_k [H_kv, 2^b, d_k] and
+ * the row written is the packed one, [B, H_kv, n_cap, M_k b / 8] (layouts at the top).
  * Errors: EINVAL for null pointers, B < 1, T < 1, pos0 < 0, pos0 + T > n_cap;
  * EUNSUPPORTED for a cfg outside the ranges above.
  */
@@ -125,8 +143,10 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
  *   x_f16  [B, H_kv, T, D] fp16       cb_in_f16, cb_out_f16 [H_kv, M, 256, d] (may not alias)
  *   codes  [B, H_kv, T, M] uint8 (written)    counts int32 [H_kv, M, 256] or NULL: cluster sizes
  *   workspace  vecinfer_kmeans_workspace_bytes(cfg, lambda != NULL) bytes, 256-byte aligned
- * d and M are the key values of cfg when lambda is given, else the value ones.
- * Errors: as vecinfer_encode_keys / _values, plus EWORKSPACE.
+ * d and M are the key values of cfg when lambda is given, else the value ones.  The step covers
+ * the 256-centroid tables of 8-bit codes only.
+ * Errors: as vecinfer_encode_keys / _values, plus EWORKSPACE, and EUNSUPPORTED for a side with
+ * 10- or 12-bit codes.
  */
 size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys);
 int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda,
@@ -217,7 +237,7 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
  * With VECINFER_VARIANT_MFMA (or AUTO when it covers cfg) nothing is launched in front of the
  * attention: its workgroups share out the sub-spaces of the new token while the code cache of
  * the older tokens streams, and the merge kernel joins the new token as one more partial.
- * Other configurations run the append kernel first.
+ * Other configurations (the lookup-table variant; 10- or 12-bit codes) run the append kernels first.
  *   k_new_f16, v_new_f16  fp16 [B, H_kv, 1, D]
  *   k_idx, v_idx          as in vecinfer_decode_attention, but written at row len_b - 1
  * Everything else, the workspace size and the errors as for vecinfer_decode_attention
@@ -228,6 +248,16 @@ int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void 
                          const void *cb_v_f16, uint8_t *k_idx, uint8_t *v_idx, const int32_t *seq_lens,
                          int32_t B, int64_t N, int64_t n_cap, int32_t num_splits, int32_t variant,
                          void *workspace, size_t workspace_bytes, void *out_f16, float *lse, void *stream);
+
+/*
+ * Sizes that follow from cfg (host-only; 0 for an invalid cfg).  keys != 0: the key side.
+ *   vecinfer_index_row_bytes  bytes of one token's code row, M b / 8 (Sec. 2.2): the innermost
+ *                             extent of k_idx / v_idx
+ *   vecinfer_codebook_elems   fp16 elements of the whole codebook tensor cb_k / cb_v:
+ *                             H_kv M 256 d at 8 bits, H_kv 2^b d above
+ */
+size_t vecinfer_index_row_bytes(const vecinfer_cfg *cfg, int32_t keys);
+size_t vecinfer_codebook_elems(const vecinfer_cfg *cfg, int32_t keys);
 
 /* Human-readable text for a return code (static storage). */
 const char *vecinfer_strerror(int code);

@@ -69,6 +69,10 @@ def _load():
         lib.vo_decode_batch_g.argtypes = [dp, dp, dp, dp, u16p, u16p, i64p, C.c_int, C.c_int, C.c_int, C.c_int64,
                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, dp, dp]
         lib.vo_decode_batch_g.restype = C.c_int
+        lib.vo_decode_residual_batch_g.argtypes = [dp, dp, dp, dp, u16p, u16p, i64p, dp, dp, i64p, C.c_int, C.c_int,
+                                                   C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                   C.c_int, C.c_int, C.c_int, dp, dp]
+        lib.vo_decode_residual_batch_g.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -339,12 +343,10 @@ def decode_attention_residual(q_f16, lam, cb_k, cb_v, k_idx, v_idx, k_res, v_res
     cb_v = _f64(cb_v)
     k_res = _f64(k_res)
     v_res = _f64(v_res)
-    k_idx = np.ascontiguousarray(k_idx, dtype=np.uint8)
-    v_idx = np.ascontiguousarray(v_idx, dtype=np.uint8)
     B, Hq, D = q.shape
     Hkv, Mk, Cn, d_k = cb_k.shape
-    _, Mv, _, d_v = cb_v.shape
-    n_cap = k_idx.shape[2]
+    _, Mv, Cv, d_v = cb_v.shape
+    n_cap = np.asarray(k_idx).shape[2]
     r_cap = k_res.shape[2]
     assert k_res.shape == (B, Hkv, r_cap, D) and v_res.shape == (B, Hkv, r_cap, D)
     sl = np.full(B, n_cap, dtype=np.int64) if seq_lens is None else np.ascontiguousarray(seq_lens, dtype=np.int64)
@@ -353,6 +355,22 @@ def decode_attention_residual(q_f16, lam, cb_k, cb_v, k_idx, v_idx, k_res, v_res
     out = np.empty((B, Hq, D), dtype=np.float64)
     lse = np.empty((B, Hq), dtype=np.float64)
     i64p = C.POINTER(C.c_int64)
+    if Mk * d_k != D or Mv * d_v != D or Cn > 256 or Cv > 256:
+        # shared codebooks ([Hkv, 1, C, d]) and / or more than 256 centroids: unpacked uint16 indices
+        k16 = np.ascontiguousarray(k_idx, dtype=np.uint16)
+        v16 = np.ascontiguousarray(v_idx, dtype=np.uint16)
+        assert Mk in (1, D // d_k) and Mv in (1, D // d_v)
+        assert k16.shape == (B, Hkv, n_cap, D // d_k) and v16.shape == (B, Hkv, n_cap, D // d_v)
+        assert int(k16.max(initial=0)) < Cn and int(v16.max(initial=0)) < Cv
+        rc = _load().vo_decode_residual_batch_g(_dp(q), _dp(lam), _dp(cb_k), _dp(cb_v), _u16p(k16), _u16p(v16),
+                                                sl.ctypes.data_as(i64p), _dp(k_res), _dp(v_res),
+                                                rl.ctypes.data_as(i64p), B, Hq, Hkv, n_cap, r_cap, D, d_k, Cn, Mk,
+                                                d_v, Cv, Mv, _dp(out), _dp(lse))
+        if rc != 0:
+            raise ValueError("vo_decode_residual_batch_g rejected the inputs")
+        return out, lse
+    k_idx = np.ascontiguousarray(k_idx, dtype=np.uint8)
+    v_idx = np.ascontiguousarray(v_idx, dtype=np.uint8)
     rc = _load().vo_decode_residual_batch(_dp(q), _dp(lam), _dp(cb_k), _dp(cb_v), _u8p(k_idx), _u8p(v_idx),
                                           sl.ctypes.data_as(i64p), _dp(k_res), _dp(v_res), rl.ctypes.data_as(i64p),
                                           B, Hq, Hkv, n_cap, r_cap, D, d_k, d_v, Cn, _dp(out), _dp(lse))

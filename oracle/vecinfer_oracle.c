@@ -657,3 +657,89 @@ int vo_decode_batch_g(const double *q, const double *lam, const double *cb_k, co
     free(H);
     return err;
 }
+
+/* Eq. 10 with the full-precision residual window (as vo_vq_attention_residual) in the general
+ * form: the N quantized tokens through (transformed query, looked-up transformed keys), the R
+ * window tokens through (raw query, raw keys), one softmax over all N + R scores. */
+int vo_vq_attention_residual_g(const double *qt, const double *q_raw, const uint16_t *kidx,
+                               const uint16_t *vidx, const double *cb_k, const double *cb_v, int64_t N,
+                               const double *kres, const double *vres, int64_t R, int D, int d_k,
+                               int C_k, int Mcb_k, int d_v, int C_v, int Mcb_v, double *out, double *lse)
+{
+    if (N < 0 || R < 0 || N + R < 1) return -1;
+    const int64_t T = N + R;
+    double *Kall = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * D);
+    double *Vall = (double *)malloc(sizeof(double) * (size_t)T * D);
+    double *s = (double *)malloc(sizeof(double) * (size_t)T);
+    if (N > 0) {
+        vo_vq_dequantize_g(kidx, N, D, d_k, C_k, Mcb_k, cb_k, Kall);
+        vo_vq_dequantize_g(vidx, N, D, d_v, C_v, Mcb_v, cb_v, Vall);
+    }
+    for (int64_t r = 0; r < R; ++r)
+        for (int i = 0; i < D; ++i) Vall[(N + r) * D + i] = vres[r * D + i];
+    const double scale = 1.0 / sqrt((double)D);
+    double mx = -INFINITY;
+    for (int64_t n = 0; n < T; ++n) {
+        double acc = 0.0;
+        if (n < N)
+            for (int i = 0; i < D; ++i) acc += qt[i] * Kall[n * D + i];
+        else
+            for (int i = 0; i < D; ++i) acc += q_raw[i] * kres[(n - N) * D + i];
+        s[n] = acc * scale;
+        if (s[n] > mx) mx = s[n];
+    }
+    double denom = 0.0;
+    for (int64_t n = 0; n < T; ++n) {
+        s[n] = exp(s[n] - mx);
+        denom += s[n];
+    }
+    for (int i = 0; i < D; ++i) out[i] = 0.0;
+    for (int64_t n = 0; n < T; ++n) {
+        const double p = s[n] / denom;
+        for (int i = 0; i < D; ++i) out[i] += p * Vall[n * D + i];
+    }
+    if (lse) *lse = mx + log(denom);
+    free(Kall);
+    free(Vall);
+    free(s);
+    return 0;
+}
+
+/* As vo_decode_residual_batch, general form. */
+int vo_decode_residual_batch_g(const double *q, const double *lam, const double *cb_k, const double *cb_v,
+                               const uint16_t *kidx, const uint16_t *vidx, const int64_t *seq_lens,
+                               const double *kres, const double *vres, const int64_t *res_lens, int B,
+                               int Hq, int Hkv, int64_t n_cap, int64_t r_cap, int D, int d_k, int C_k,
+                               int Mcb_k, int d_v, int C_v, int Mcb_v, double *out, double *lse)
+{
+    if (Hq % Hkv != 0 || D % d_k != 0 || D % d_v != 0) return -1;
+    const int G = Hq / Hkv, Mk = D / d_k, Mv = D / d_v;
+    if ((Mcb_k != 1 && Mcb_k != Mk) || (Mcb_v != 1 && Mcb_v != Mv)) return -1;
+    double *H = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if (vo_hadamard(D, H) != 0) {
+        free(H);
+        return -1;
+    }
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hq; ++h) {
+            const int g = h / G;
+            const double *qr = q + ((int64_t)b * Hq + h) * D;
+            double *qt = (double *)malloc(sizeof(double) * (size_t)D);
+            vo_transform_query(qr, D, lam + (int64_t)g * D, H, qt);
+            const int64_t bg = (int64_t)b * Hkv + g;
+            const int rc = vo_vq_attention_residual_g(
+                qt, qr, kidx + bg * n_cap * Mk, vidx + bg * n_cap * Mv, cb_k + (int64_t)g * Mcb_k * C_k * d_k,
+                cb_v + (int64_t)g * Mcb_v * C_v * d_v, seq_lens[b], kres + bg * r_cap * D, vres + bg * r_cap * D,
+                res_lens[b], D, d_k, C_k, Mcb_k, d_v, C_v, Mcb_v, out + ((int64_t)b * Hq + h) * D,
+                lse + ((int64_t)b * Hq + h));
+            if (rc != 0) {
+#pragma omp atomic write
+                err = -1;
+            }
+            free(qt);
+        }
+    free(H);
+    return err;
+}

@@ -26,6 +26,7 @@ EXPORTS = [
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
     "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
+    "vecinfer_index_row_bytes", "vecinfer_codebook_elems",
     "vecinfer_strerror", "vecinfer_version",
 ]
 
@@ -49,6 +50,19 @@ class Config:
     def c(self) -> _Cfg:
         return _Cfg(self.head_dim, self.num_q_heads, self.num_kv_heads, self.k_sub_dim,
                     self.v_sub_dim, self.k_bits, self.v_bits)
+
+    def cb_shape(self, keys: bool) -> tuple:
+        """Codebook tensor shape: one 256-entry table per (KV head, sub-space) for 8-bit codes, one
+        table of 2^bits entries per KV head for wider ones."""
+        d, bits = (self.k_sub_dim, self.k_bits) if keys else (self.v_sub_dim, self.v_bits)
+        if bits == 8:
+            return (self.num_kv_heads, self.head_dim // d, 256, d)
+        return (self.num_kv_heads, 1 << bits, d)
+
+    def row_bytes(self, keys: bool) -> int:
+        """Bytes of one token's code row: M codes of `bits` bits, end to end."""
+        d, bits = (self.k_sub_dim, self.k_bits) if keys else (self.v_sub_dim, self.v_bits)
+        return self.head_dim // d * bits // 8
 
 
 class VecInferError(RuntimeError):
@@ -94,6 +108,10 @@ def lib() -> C.CDLL:
         L.vecinfer_kmeans_workspace_bytes.restype = sz
         L.vecinfer_kmeans_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i32, i64, vp, sz, vp]
         L.vecinfer_kmeans_step.restype = C.c_int
+        L.vecinfer_index_row_bytes.argtypes = [cfgp, i32]
+        L.vecinfer_index_row_bytes.restype = sz
+        L.vecinfer_codebook_elems.argtypes = [cfgp, i32]
+        L.vecinfer_codebook_elems.restype = sz
         L.vecinfer_strerror.argtypes = [C.c_int]
         L.vecinfer_strerror.restype = C.c_char_p
         L.vecinfer_version.restype = C.c_int
@@ -132,12 +150,11 @@ def vecinfer_encode_keys(cfg: Config, k_f16, lam, cb_k, k_idx, pos0: int = 0, st
     """Smooth + Hadamard + VQ of T new keys into rows pos0.. of the code cache."""
     B, Hkv, T, D = k_f16.shape
     n_cap = k_idx.shape[2]
-    M = cfg.head_dim // cfg.k_sub_dim
     _check(lib().vecinfer_encode_keys(
         C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_k, torch.float16, (cfg.num_kv_heads, M, 256, cfg.k_sub_dim), "cb_k"),
-        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, M), "k_idx"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
         B, T, pos0, n_cap, _stream(stream)))
 
 
@@ -145,11 +162,10 @@ def vecinfer_encode_values(cfg: Config, v_f16, cb_v, v_idx, pos0: int = 0, strea
     """VQ of T new (untransformed) values into rows pos0.. of the code cache."""
     B, Hkv, T, D = v_f16.shape
     n_cap = v_idx.shape[2]
-    M = cfg.head_dim // cfg.v_sub_dim
     _check(lib().vecinfer_encode_values(
         C.byref(cfg.c()), _dev(v_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "v_f16"),
-        _dev(cb_v, torch.float16, (cfg.num_kv_heads, M, 256, cfg.v_sub_dim), "cb_v"),
-        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, M), "v_idx"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         B, T, pos0, n_cap, _stream(stream)))
 
 
@@ -157,16 +173,14 @@ def vecinfer_append_kv(cfg: Config, k_f16, v_f16, lam, cb_k, cb_v, k_idx, v_idx,
     """Decode-time append (Eq. 9): encode T <= 16 new keys and values in one launch."""
     B, Hkv, T, D = k_f16.shape
     n_cap = k_idx.shape[2]
-    Mk = cfg.head_dim // cfg.k_sub_dim
-    Mv = cfg.head_dim // cfg.v_sub_dim
     _check(lib().vecinfer_append_kv(
         C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
         _dev(v_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "v_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
-        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
-        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
-        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         B, T, pos0, n_cap, _stream(stream)))
 
 
@@ -193,15 +207,13 @@ def vecinfer_decode_attention(cfg: Config, q_f16, lam, cb_k, cb_v, k_idx, v_idx,
     B = q_f16.shape[0]
     n_cap = k_idx.shape[2]
     N = n_cap if N is None else N
-    Mk = cfg.head_dim // cfg.k_sub_dim
-    Mv = cfg.head_dim // cfg.v_sub_dim
     _check(lib().vecinfer_decode_attention(
         C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
-        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
-        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
-        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
         B, N, n_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
@@ -219,15 +231,13 @@ def vecinfer_decode_attention_residual(cfg: Config, q_f16, lam, cb_k, cb_v, k_id
     N = n_cap if N is None else N
     r_cap = k_res.shape[2]
     R = r_cap if R is None else R
-    Mk = cfg.head_dim // cfg.k_sub_dim
-    Mv = cfg.head_dim // cfg.v_sub_dim
     _check(lib().vecinfer_decode_attention_residual(
         C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
-        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
-        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
-        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
         B, N, n_cap,
         _dev(k_res, torch.float16, (B, cfg.num_kv_heads, r_cap, cfg.head_dim), "k_res"),
@@ -246,22 +256,28 @@ def vecinfer_decode_step(cfg: Config, q_f16, k_new, v_new, lam, cb_k, cb_v, k_id
     B = q_f16.shape[0]
     n_cap = k_idx.shape[2]
     N = n_cap if N is None else N
-    Mk = cfg.head_dim // cfg.k_sub_dim
-    Mv = cfg.head_dim // cfg.v_sub_dim
     _check(lib().vecinfer_decode_step(
         C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
         _dev(k_new, torch.float16, (B, cfg.num_kv_heads, 1, cfg.head_dim), "k_new"),
         _dev(v_new, torch.float16, (B, cfg.num_kv_heads, 1, cfg.head_dim), "v_new"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_k, torch.float16, (cfg.num_kv_heads, Mk, 256, cfg.k_sub_dim), "cb_k"),
-        _dev(cb_v, torch.float16, (cfg.num_kv_heads, Mv, 256, cfg.v_sub_dim), "cb_v"),
-        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mk), "k_idx"),
-        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, Mv), "v_idx"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
         B, N, n_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
         None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
         _stream(stream)))
+
+
+def vecinfer_index_row_bytes(cfg: Config, keys: bool) -> int:
+    return int(lib().vecinfer_index_row_bytes(C.byref(cfg.c()), 1 if keys else 0))
+
+
+def vecinfer_codebook_elems(cfg: Config, keys: bool) -> int:
+    return int(lib().vecinfer_codebook_elems(C.byref(cfg.c()), 1 if keys else 0))
 
 
 def vecinfer_kmeans_workspace_bytes(cfg: Config, keys: bool) -> int:

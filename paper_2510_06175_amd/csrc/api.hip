@@ -16,9 +16,14 @@ bool cfg_ok(const vecinfer_cfg *c)
     if (G > 8) return false;
     auto sub_ok = [](int d) { return d == 2 || d == 4 || d == 8; };
     if (!sub_ok(c->k_sub_dim) || !sub_ok(c->v_sub_dim)) return false;
-    if (c->k_bits != 8 || c->v_bits != 8) return false;
-    return true;
+    // 10- and 12-bit codes (shared codebook, packed rows): D = 128 and d = 4 or 8 on that side
+    auto bits_ok = [&](int bits, int d) {
+        return bits == 8 || ((bits == 10 || bits == 12) && c->head_dim == 128 && (d == 4 || d == 8));
+    };
+    return bits_ok(c->k_bits, c->k_sub_dim) && bits_ok(c->v_bits, c->v_sub_dim);
 }
+
+bool wide(const vecinfer_cfg *c) { return c->k_bits != 8 || c->v_bits != 8; }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -94,6 +99,7 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     p.D = cfg->head_dim;
     p.d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
     p.M = p.D / p.d;
+    p.bits = keys ? cfg->k_bits : cfg->v_bits;
     p.T = T;
     p.pos0 = pos0;
     p.n_cap = n_cap;
@@ -167,6 +173,8 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     p.dv = cfg->v_sub_dim;
     p.Mk = p.D / p.dk;
     p.Mv = p.D / p.dv;
+    p.bk = cfg->k_bits;
+    p.bv = cfg->v_bits;
     p.N = N;
     p.n_cap = n_cap;
     p.S = S;
@@ -189,8 +197,10 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     const bool mfma_ok = decode_mfma_supports(p);
     if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
     const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
+    // the lookup-table kernel reads one byte per code
+    if (!use_mfma && wide(cfg)) return VECINFER_EUNSUPPORTED;
     int rc = 0;
-    if (append && use_mfma) {           // the attention launch encodes the new token itself
+    if (append && use_mfma && !wide(cfg)) {   // the attention launch encodes the new token itself
         p.k_new = static_cast<const __half *>(k_new);
         p.v_new = static_cast<const __half *>(v_new);
         p.k_idx_w = const_cast<uint8_t *>(k_idx);
@@ -249,7 +259,7 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
 
 size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys)
 {
-    if (!cfg_ok(cfg)) return 0;
+    if (!cfg_ok(cfg) || (keys ? cfg->k_bits : cfg->v_bits) != 8) return 0;
     const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
     const size_t cen = (size_t)cfg->num_kv_heads * (cfg->head_dim / d) * kCentroids;
     return (cen * d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
@@ -264,6 +274,7 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
     const bool keys = lambda != nullptr;
     const int rc = encode_args(cfg, x_f16, lambda, keys, cb_in_f16, codes, B, T, 0, T, p);
     if (rc != VECINFER_OK) return rc;
+    if (p.bits != 8) return VECINFER_EUNSUPPORTED;       // the training step covers 256-centroid tables
     const size_t need = vecinfer_kmeans_workspace_bytes(cfg, keys ? 1 : 0);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return VECINFER_EWORKSPACE;
     const size_t cen = (size_t)p.Hkv * p.M * kCentroids;
@@ -327,6 +338,21 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
     return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, k_res_f16,
                          v_res_f16, res_lens, R, r_cap, nullptr, nullptr, num_splits, variant, workspace,
                          workspace_bytes, out_f16, lse, stream);
+}
+
+size_t vecinfer_index_row_bytes(const vecinfer_cfg *cfg, int32_t keys)
+{
+    if (!cfg_ok(cfg)) return 0;
+    const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim, bits = keys ? cfg->k_bits : cfg->v_bits;
+    return (size_t)cfg->head_dim / d * bits / 8;
+}
+
+size_t vecinfer_codebook_elems(const vecinfer_cfg *cfg, int32_t keys)
+{
+    if (!cfg_ok(cfg)) return 0;
+    const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim, bits = keys ? cfg->k_bits : cfg->v_bits;
+    const size_t per_head = bits == 8 ? (size_t)cfg->head_dim * kCentroids : ((size_t)1 << bits) * d;
+    return per_head * cfg->num_kv_heads;
 }
 
 const char *vecinfer_strerror(int code)

@@ -17,12 +17,13 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct DecodeParams {
     const __half *q;         // [B, Hq, D]
     const float *lam;        // [Hkv, D]
-    const __half *cb_k;      // [Hkv, Mk, 256, dk]
-    const __half *cb_v;      // [Hkv, Mv, 256, dv]
-    const uint8_t *k_idx;    // [B, Hkv, n_cap, Mk]
-    const uint8_t *v_idx;    // [B, Hkv, n_cap, Mv]
+    const __half *cb_k;      // [Hkv, Mk, 256, dk]; codes wider than 8 bits: [Hkv, 2^bk, dk]
+    const __half *cb_v;      // [Hkv, Mv, 256, dv]; codes wider than 8 bits: [Hkv, 2^bv, dv]
+    const uint8_t *k_idx;    // [B, Hkv, n_cap, Mk * bk / 8]: a token's codes end to end, bk bits each
+    const uint8_t *v_idx;    // [B, Hkv, n_cap, Mv * bv / 8]
     const int32_t *seq_lens; // [B] or nullptr
     int B, Hq, Hkv, G, D, dk, dv, Mk, Mv;
+    int bk, bv;              // code widths: 8, 10 or 12 bits
     long long N, n_cap;
     int S;                   // number of sequence splits
     float *part_o;           // [B, Hkv, S, G, D]  unnormalised partial outputs
@@ -170,14 +171,16 @@ constexpr int kMaxResidual = 128;                  // rows of the residual windo
 int launch_merge(const DecodeParams &p, hipStream_t stream);   // splits (+ residual window) -> out, lse
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
+int launch_decode_mfma_wide(const DecodeParams &p, hipStream_t stream);   // 10- / 12-bit codes
 bool decode_mfma_supports(const DecodeParams &p);
 
 struct EncodeParams {
     const __half *x;      // [B, Hkv, T, D]
     const float *lam;     // [Hkv, D] or nullptr (values: no transform)
-    const __half *cb;     // [Hkv, M, 256, d]
-    uint8_t *idx;         // [B, Hkv, n_cap, M]
+    const __half *cb;     // [Hkv, M, 256, d]; bits > 8: [Hkv, 2^bits, d], shared by the sub-spaces
+    uint8_t *idx;         // [B, Hkv, n_cap, M * bits / 8]
     int B, Hkv, D, d, M;
+    int bits;             // code width: 8, 10 or 12
     long long T, pos0, n_cap;
     // per-sequence append position (T = 1 only): when seq_lens != nullptr the token of sequence b
     // goes to row clamp(seq_lens[b], 0, len_max) - 1, and a sequence of length 0 is skipped

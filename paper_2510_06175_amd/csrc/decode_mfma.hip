@@ -1,933 +1,7 @@
-// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1, 2, 4 or 8 query heads
-// per KV head (8: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 8,
-// 4 or 2, chosen separately for keys and values (M = D / d = 8 .. 64 sub-spaces), 8-bit codes.
-//
-// Both codebooks of the KV head live in LDS for the whole kernel.  A token's dequantized
-// row is never assembled: each lane gathers a few centroids with ds_read and hands them
-// straight to v_mfma_f32_16x16x32_f16 as an operand, so the matrix cores do the
-// cross-lane summation that the lookup formulation needs.
-//
-//   scores (Eq. 10 / Alg. 1 step 11).  A 16-token tile is the A operand: lane (i, kg) owns
-//   token row i and the k-range [8kg, 8kg+8), which it fills with the centroids of 8/d
-//   consecutive sub-spaces of that token.  The B operand holds the transformed query:
-//   column j = 4h + t0 carries q~_h (the same vector for the four t0), so the product's
-//   column j is the score of head h and every lane ends up with the scores it will need as
-//   a P.V operand.  q~ is split into an fp16 high and low part so that the scores are
-//   fp32-accurate: columns t0 < 2 carry the high part, columns t0 >= 2 the low part, and one
-//   DPP add across the quad recombines them.  1/sqrt(D) and log2(e) are folded into q~.
-//
-//   P.V (Alg. 1 step 16).  Row 4h + t0 of the A operand holds p_h of 8/d tokens, placed
-//   only in the k-slots whose channel-in-sub-vector equals t0; the B operand's column n
-//   holds the gathered value centroids of those tokens for one sub-space.  The product's
-//   row (h, t0), column n is then o_h[channel d*m(n) + t0].  3/4 of the A operand is
-//   zero: the matrix cores have the headroom, and no cross-lane shuffle or transpose is
-//   needed anywhere.
-//
-// Each wavefront runs its own online softmax (steps 12-13) over the 64-token tiles it owns;
-// wavefronts are merged through LDS at the end of the split, splits through the workspace.
-#include "common.h"
+// Matrix-core decode attention, 8-bit codes: instantiations and dispatch (kernel: decode_mfma_kernel.h).
+#include "decode_mfma_kernel.h"
 
 namespace vecinfer {
-
-#ifdef VECINFER_PHASE_TIMING
-__device__ unsigned long long *g_phase_buf = nullptr;
-#define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); } while (0)
-// per-wavefront stamp: slot 8 * (j + 1) + wave, j in {0, 1, 2}
-#define STAMPW(j) do { if (g_phase_buf && (threadIdx.x & 63) == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 * ((j) + 1) + (threadIdx.x >> 6)] = wall_clock64(); } while (0)
-#else
-#define STAMP(i)
-#define STAMPW(j)
-#endif
-
-namespace {
-
-#define MFMA16(a, b, c, x, y, z) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, x, y, z)
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
-
-constexpr int kG = 4;              // head slots of one MFMA pass; spare slots (G not a multiple of 4) run on a zero query
-constexpr int kTile = 64;          // tokens per wavefront iteration (4 sub-tiles of 16)
-
-// loads from an absolute LDS byte address
-__device__ __forceinline__ uint2 lds_load_b64(unsigned addr)
-{
-    typedef uintx2 __attribute__((address_space(3))) *lds_ptr;
-    const uintx2 v = *(lds_ptr)(addr);
-    return make_uint2(v[0], v[1]);
-}
-__device__ __forceinline__ unsigned lds_load_b32(unsigned addr)
-{
-    typedef unsigned __attribute__((address_space(3))) *lds_ptr;
-    return *(lds_ptr)(addr);
-}
-
-__device__ __forceinline__ uintx4 lds_load_b128(unsigned addr)
-{
-    typedef uintx4 __attribute__((address_space(3))) *lds_ptr;
-    return *(lds_ptr)(addr);
-}
-
-__device__ __forceinline__ half8 as_half8(unsigned a, unsigned b, unsigned c, unsigned d)
-{
-    uintx4 u = {a, b, c, d};
-    return __builtin_bit_cast(half8, u);
-}
-
-// value of quad lane L (0..3) broadcast to the whole quad (DPP quad_perm:[L,L,L,L])
-template <int L>
-__device__ __forceinline__ unsigned quad_bcast(unsigned x)
-{
-    return (unsigned)__builtin_amdgcn_mov_dpp((int)x, L * 0x55, 0xf, 0xf, true);
-}
-
-// value of the lane whose index within the quad differs by XOR (1 or 2)
-template <int XOR>
-__device__ __forceinline__ float quad_xor(float x)
-{
-    constexpr int ctrl = XOR == 1 ? 0xB1 : 0x4E;     // quad_perm:[1,0,3,2] / [2,3,0,1]
-    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), ctrl, 0xf, 0xf, true));
-}
-
-// max over the four 16-lane rows of the wavefront, on the vector ALU (v_permlane16_swap /
-// v_permlane32_swap exchange rows between two copies of the value; no LDS round trip)
-__device__ __forceinline__ float rows_max(float x)
-{
-    const unsigned u = __builtin_bit_cast(unsigned, x);
-    auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    float m = fmaxf(__builtin_bit_cast(float, (unsigned)s16[0]), __builtin_bit_cast(float, (unsigned)s16[1]));
-    const unsigned w = __builtin_bit_cast(unsigned, m);
-    auto s32 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-    return fmaxf(__builtin_bit_cast(float, (unsigned)s32[0]), __builtin_bit_cast(float, (unsigned)s32[1]));
-}
-
-// unsigned minimum over the wavefront, in every lane: DPP inside the 16-lane rows
-// (quad_perm xor 1, 2, then row rotations by 4 and 8), row swaps across them
-__device__ __forceinline__ unsigned wave_umin(unsigned x)
-{
-    auto dpp = [](unsigned v, auto ctrl) {
-        return (unsigned)__builtin_amdgcn_mov_dpp((int)v, decltype(ctrl)::value, 0xf, 0xf, true);
-    };
-    x = min(x, dpp(x, std::integral_constant<int, 0xB1>{}));      // quad_perm:[1,0,3,2]
-    x = min(x, dpp(x, std::integral_constant<int, 0x4E>{}));      // quad_perm:[2,3,0,1]
-    x = min(x, dpp(x, std::integral_constant<int, 0x124>{}));     // row_ror:4
-    x = min(x, dpp(x, std::integral_constant<int, 0x128>{}));     // row_ror:8
-    auto s16 = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-    x = min((unsigned)s16[0], (unsigned)s16[1]);
-    auto s32 = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-    return min((unsigned)s32[0], (unsigned)s32[1]);
-}
-
-__device__ __forceinline__ unsigned pack_dup_f16(float p)
-{
-    // (p, p) as two fp16, round-to-nearest-even
-    const _Float16 h = (_Float16)p;
-    const unsigned short b = __builtin_bit_cast(unsigned short, h);
-    return (unsigned)b | ((unsigned)b << 16);
-}
-
-// DK, DV: sub-vector dims of the key and the value codebooks (keys and values may be quantized
-// differently, Sec. 3.2).
-// HG: head groups of 4 query heads that share the gathered key / value operands (G <= 4 HG).
-// At D = 128 the codebooks fill LDS, so a CU holds one workgroup = NW / 4 wavefronts per SIMD: say
-// so, or the compiler squeezes some instantiations under 168 registers for a third wavefront
-// that can never come, and serialises gathers to do it (58 -> 43 us for d_k = 4, d_v = 8).
-template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
-void decode_mfma_kernel(DecodeParams p)
-{
-    constexpr int KG = kG * HG;                        // head slots of the workgroup
-    static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DV == 8 || DV == 4 || DV == 2) &&
-                      (DV != 8 || kD == 128),
-                  "shapes this kernel is laid out for (d_v = 8 needs 16 value sub-spaces: D = 128)");
-    constexpr int BLOCK = NW * 64;
-    constexpr int MK = kD / DK, MV = kD / DV;          // sub-spaces: 16, 32 or 64
-    constexpr int CB_BYTES = kCentroids * kD * 2;      // one codebook set of a KV head: 64 or 32 KB
-    constexpr int ENTRY_K = DK * 2, ENTRY_V = DV * 2;  // bytes per centroid: 8 or 4
-    constexpr int SUB_K = kCentroids * ENTRY_K;        // one sub-space table: 2048 or 1024 bytes
-    constexpr int SUB_V = kCentroids * ENTRY_V;
-    constexpr int NR = kD / 32;                        // score MFMA rounds (32 channels each): 4 or 2;
-                                                       // also the P.V operands (and MFMAs) per sub-tile
-    constexpr int H = NR / 2;                          // rounds per pipeline stage
-    constexpr int KW = (MK / 4 + 3) / 4;               // key-code dwords per lane per sub-tile (MK / 4 bytes)
-    constexpr int NROUND_V = MV / 16;                  // value sub-spaces per MFMA column: 1, 2 or 4
-    constexpr int VW = NROUND_V;                       // value-code dwords per lane per sub-tile (4 tokens x NROUND_V bytes)
-    // P.V accumulators per head group: one per value sub-space of the lane's column, except at
-    // d_v = 8, where the one sub-space is covered in two halves of 4 channels (the four t0 rows of
-    // a head serve channels t0 and t0 + 4 in turn).  Register v of accumulator a is channel
-    // kChanBlock * (NACC * col + a) + v.
-    constexpr int NACC = DV == 8 ? 2 : NROUND_V;
-    constexpr int kChanBlock = DV == 8 ? 4 : DV;
-    // LDS layout of the value codebook: [r][code][col] with sub-space m = NROUND_V * col + r.
-    // LDS serves a gather 16 lanes at a time, and the 16 lanes of such a group read the same r
-    // and 16 different col: with the 16 entries of a code in one ROW_V-byte row they fall on
-    // disjoint banks whatever their codes are (4.4 instead of 6.7 cycles per gather).  The key
-    // codebook keeps the [m][code] order: the 16 lanes of a group all read one sub-space there.
-    constexpr int ROW_V = 16 * ENTRY_V;                // 128 or 64 bytes
-    constexpr int PLANE_V = kCentroids * ROW_V;        // one r: 32768 or 16384 bytes
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *const sm_k = smem;
-    unsigned char *const sm_v = smem + CB_BYTES;
-    float *const sm_qt = reinterpret_cast<float *>(smem + 2 * CB_BYTES);   // [KG][D]
-    float *const sm_new = sm_qt + KG * kD;                                 // [2][D]: k~ and v of the new token
-    float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][KG]: its score shares (log2 units)
-    float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
-    // fastest: with 8 KV heads every XCD serves one head and its L2 fetches one codebook set
-    // (128 KB) instead of all of them.
-    const int lin = blockIdx.x + gridDim.x * blockIdx.y;
-    const int g = lin % p.Hkv, s = lin / p.Hkv, b = blockIdx.z;
-    const int col = lane & 15;       // MFMA row (A) / column (B, D) index of this lane
-    const int kg = lane >> 4;        // k-group (A, B) / row group (D) of this lane
-    const size_t bg = (size_t)b * p.Hkv + g;
-
-    // With a fused append the new token is the sequence's last one: its codes are produced in
-    // this launch (below), so the tile loop covers the len - 1 older tokens only.  Workgroup s
-    // encodes sub-spaces s, s + S, ... of the new token's key and value.
-    const long long len = seq_len_of(p, b);
-    const bool fused = p.k_new != nullptr && len > 0;
-    const bool has_new = fused && s < (MK > MV ? MK : MV);
-    long long n0, n1;
-    split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
-
-    if (n0 >= n1 && !has_new) {                        // empty split: neutral partial
-        for (int e = tid; e < p.G * kD; e += BLOCK) p.part_o[(bg * p.S + s) * p.G * kD + e] = 0.f;
-        if (tid < p.G) {
-            p.part_m[(bg * p.S + s) * p.G + tid] = -INFINITY;
-            p.part_l[(bg * p.S + s) * p.G + tid] = 0.f;
-        }
-        finish_split<BLOCK>(p, b, g);
-        return;
-    }
-
-    // ---- per-lane constants
-    const int t0 = col & 3;                              // channel-in-sub-vector this A row serves
-    unsigned mask_a, mask_b;                             // select the fp16 slot(s) of (p, p)
-    if (DV == 4 || DV == 8) {
-        // d_v = 8: the same two masks pick channel t0 in the first dword pair of the operand
-        // (channels 0-3) or channel t0 + 4 in the second pair (channels 4-7)
-        mask_a = t0 == 0 ? 0x0000ffffu : (t0 == 1 ? 0xffff0000u : 0u);
-        mask_b = t0 == 2 ? 0x0000ffffu : (t0 == 3 ? 0xffff0000u : 0u);
-    } else {
-        mask_a = t0 == 0 ? 0x0000ffffu : (t0 == 1 ? 0xffff0000u : 0u);
-        mask_b = 0u;
-    }
-    unsigned sel[4];                                     // sel[i] = all ones iff t0 == i
-#pragma unroll
-    for (int i = 0; i < 4; ++i) sel[i] = t0 == i ? 0xffffffffu : 0u;
-    // LDS byte offsets: keys  MK/4 sub-spaces per kg
-    //                   values sub-space NROUND_V*col + r
-    const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
-    const unsigned lds_k = lds_base + (unsigned)(kg * (MK / 4) * SUB_K);
-    const unsigned lds_v = lds_base + (unsigned)(CB_BYTES + col * ENTRY_V);
-
-    const uint8_t *krow = p.k_idx + bg * p.n_cap * MK;
-    const uint8_t *vrow = p.v_idx + bg * p.n_cap * MV;
-    const long long last = n1 - 1;
-
-    // token owned by A-row i of sub-tile st: base + 16 st + 4 (i % 4) + i / 4, so that D-register v
-    // of row group rg is token base + 16 st + 4 v + rg
-    const int krow_tok = 4 * (col & 3) + (col >> 2);
-
-    // Codes of one 64-token tile as this lane needs them: kc = the key-code bytes of the lane's
-    // A row in each sub-tile, vc = the value-code bytes of the 4 tokens of its k-group.
-    struct Codes {
-        unsigned kc[4][KW];
-        unsigned vc[4][VW];
-    };
-    // The code rows of (b, g) are read through buffer descriptors whose extent ends at the
-    // split's last token: a lane's address is one loop-invariant VGPR offset plus the tile's
-    // base plus an instruction immediate, and loads past the end of the split return 0 (a
-    // valid code) instead of needing a clamp.  The host checks N * M < 2^31.
-    const __amdgpu_buffer_rsrc_t rsrc_k =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(krow), 0, (int)((unsigned)n1 * MK), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_v =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(vrow), 0, (int)((unsigned)n1 * MV), 0x00020000);
-    const unsigned koff_lane = (unsigned)(krow_tok * MK + kg * (MK / 4));
-    const unsigned voff_lane = (unsigned)(kg * MV + col * NROUND_V);
-
-    auto load_codes = [&](Codes &cd, long long tb) {
-        const unsigned ko = (unsigned)tb * MK + koff_lane, vo = (unsigned)tb * MV + voff_lane;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            // keys: the MK / 4 code bytes of the lane's k-slot range of its token
-            if constexpr (MK / 4 == 2) {
-                cd.kc[st][0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_k, ko + 16 * st * MK, 0, 0);
-            } else if constexpr (MK / 4 == 4) {
-                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * MK, 0, 0);
-            } else if constexpr (MK / 4 == 8) {
-                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, 0);
-                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1];
-            } else {
-                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, 0);
-                cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][2] = w[2]; cd.kc[st][3] = w[3];
-            }
-            // values: NROUND_V bytes (sub-spaces NROUND_V col ..) of each of the tokens 4 v + kg,
-            // packed token after token: byte v * NROUND_V + r
-            if constexpr (NROUND_V == 1) {
-                unsigned w = 0;
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0) << (8 * v);
-                cd.vc[st][0] = w;
-            } else if constexpr (NROUND_V == 2) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    ushortx2 t;
-                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, 0);
-                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, 0);
-                    cd.vc[st][u] = __builtin_bit_cast(unsigned, t);
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0);
-            }
-        }
-    };
-
-    // Which tiles a wavefront owns.  The two wavefronts of a SIMD do not run at the same speed:
-    // the one launched first (wavefronts 0 .. NW/2-1) wins the issue arbitration and gets through
-    // a tile about 13 % sooner, so an even deal leaves it idle at the end of a long split.  Tiles
-    // are therefore dealt in periods of 12 rounds: 11 rounds to every wavefront in turn and one
-    // round shared by the first half only, two tiles each (13 : 11).  Short splits (under 11
-    // rounds) see the plain round-robin.  The deal is static, so results are reproducible.
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto tile_base = [&](int k) -> long long {          // first token of this wavefront's k-th tile
-        constexpr int kFull = 11, kPeriod = (kFull + 1) * NW;
-        int per, off;
-        if (NW != 8) {
-            per = 0;
-            off = k * NW + wave_u;                          // plain round-robin
-        } else if (wave_u < NW / 2) {
-            per = k / (kFull + 2);
-            const int i = k % (kFull + 2);
-            off = i < kFull ? i * NW + wave_u : kFull * NW + (i - kFull) * (NW / 2) + wave_u;
-        } else {
-            per = k / kFull;
-            off = (k % kFull) * NW + wave_u;
-        }
-        return n0 + ((long long)per * kPeriod + off) * kTile;
-    };
-    Codes ca, cb;
-
-    STAMP(0);
-#ifdef VECINFER_PROLOGUE_STAMPS
-    STAMPW(0);
-#endif
-    constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
-    // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
-    constexpr int kStageItems = CB_BYTES / 1024, kStagePerWave = (kStageItems + NW - 1) / NW;
-    static_assert(NROUND_V * (kCentroids / (4 * CPL)) == kStageItems, "value items: (code group, r)");
-    const int vq = lane >> 4, vcol = lane & 15;
-    uintx4 vreg[kStagePerWave];
-    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise), through
-    // registers: all 16 loads of a wavefront (16 KB) are issued back to back and share one trip
-    // to memory with the first code tiles and the query; the LDS writes come after the q~ section.
-    // (Direct global->LDS loads measured slower here: a wavefront got through its 8 of them at
-    // about one L2 latency each.)
-    uintx4 kreg[kStagePerWave];
-    {
-        const unsigned char *srck = reinterpret_cast<const unsigned char *>(p.cb_k + (size_t)g * kCentroids * kD);
-        const unsigned char *srcv = reinterpret_cast<const unsigned char *>(p.cb_v + (size_t)g * kCentroids * kD);
-        // keys keep the [m][code] order: item = 1 KB chunk, 16 bytes per lane
-#pragma unroll
-        for (int j = 0; j < kStagePerWave; ++j) {
-            const int it = wave + NW * j;
-            if (kStageItems % NW == 0 || it < kStageItems)
-                kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
-        }
-        // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
-        // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
-        // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
-        // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
-        // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
-        // group it / NROUND_V.
-#pragma unroll
-        for (int j = 0; j < kStagePerWave; ++j) {
-            const int it = wave + NW * j;
-            const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
-            if (kStageItems % NW == 0 || it < kStageItems)
-                vreg[j] = *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
-        }
-    }
-    // The first two tiles' codes start their trip from HBM now, under the prologue.  They are
-    // requested after the codebooks: loads return in order, and the first touch of the code stream
-    // is the slowest load of the kernel, so the other way round the staging would wait behind it.
-    load_codes(ca, tile_base(0));
-    load_codes(cb, tile_base(1));
-#ifdef VECINFER_PROLOGUE_STAMPS
-    STAMPW(2);
-#endif
-    // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
-    // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
-    // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
-    static_assert(KG <= NW && NW >= 2, "one wavefront per head slot for the query transform");
-    if (wave < KG && wave >= p.G) {
-        // spare head slot (G < 4): a zero query; its scores and outputs are never written out
-        sm_qt[wave * kD + lane] = 0.f;
-        if (kD == 128) sm_qt[wave * kD + 64 + lane] = 0.f;
-    } else if (wave < KG && kD == 64) {
-        // D = 64: one channel per lane, six butterfly stages across lanes
-        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
-        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const float o0 = __shfl_xor(x0, st);
-            x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
-        }
-        sm_qt[wave * kD + lane] = x0;
-    } else if (wave < KG) {
-        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
-        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
-        float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
-        {
-            const float a = x0 + x1, d = x0 - x1;
-            x0 = a;
-            x1 = d;
-        }
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const float o0 = __shfl_xor(x0, st), o1 = __shfl_xor(x1, st);
-            const bool up = (lane & st) != 0;
-            x0 = up ? (o0 - x0) : (x0 + o0);
-            x1 = up ? (o1 - x1) : (x1 + o1);
-        }
-        sm_qt[wave * kD + lane] = x0;
-        sm_qt[wave * kD + 64 + lane] = x1;
-    }
-    // the new token's key and value (fused append): the last two wavefronts
-    if (has_new && wave == NW - 2 && kD == 64) {
-        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const float o0 = __shfl_xor(x0, st);
-            x0 = (lane & st) != 0 ? (o0 - x0) : (x0 + o0);
-        }
-        sm_new[lane] = x0 * (1.0f / sqrtf((float)kD));
-    } else if (has_new && wave == NW - 2) {
-        // k~ = (k / lambda) H_D of the new token (Eq. 9), operation for operation what the
-        // cache-fill kernels compute (true division, butterfly stages at distance 1, 2, .. 64,
-        // then 1/sqrt D), so that the fused step writes the codes a separate append would
-        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
-        float x1 = __half2float(p.k_new[bg * kD + 64 + lane]) / p.lam[(size_t)g * kD + 64 + lane];
-#pragma unroll
-        for (int st = 1; st < 64; st <<= 1) {
-            const float o0 = __shfl_xor(x0, st), o1 = __shfl_xor(x1, st);
-            const bool up = (lane & st) != 0;
-            x0 = up ? (o0 - x0) : (x0 + o0);
-            x1 = up ? (o1 - x1) : (x1 + o1);
-        }
-        const float hs = 1.0f / sqrtf((float)kD);
-        sm_new[lane] = (x0 + x1) * hs;
-        sm_new[64 + lane] = (x0 - x1) * hs;
-    } else if (has_new && wave == NW - 1) {
-        sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
-        if (kD == 128) sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
-    }
-    // second half of the codebook staging: registers -> LDS
-#pragma unroll
-    for (int j = 0; j < kStagePerWave; ++j) {
-        const int it = wave + NW * j;
-        if (kStageItems % NW == 0 || it < kStageItems)
-            *reinterpret_cast<uintx4 *>(sm_k + it * 1024 + lane * 16) = kreg[j];
-    }
-#pragma unroll
-    for (int j = 0; j < kStagePerWave; ++j) {
-        const int it = wave + NW * j;
-        const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
-        if (kStageItems % NW == 0 || it < kStageItems) {
-#pragma unroll
-            for (int e = 0; e < CPL; ++e) {
-                unsigned char *const d = sm_v + r * PLANE_V + (code + e) * ROW_V + vcol * ENTRY_V;
-                if constexpr (DV == 8)
-                    *reinterpret_cast<uintx4 *>(d) = vreg[j];
-                else if constexpr (DV == 4)
-                    *reinterpret_cast<uintx2 *>(d) = uintx2{vreg[j][2 * e], vreg[j][2 * e + 1]};
-                else
-                    *reinterpret_cast<unsigned *>(d) = vreg[j][e];
-            }
-        }
-    }
-    __syncthreads();
-    STAMP(1);
-
-    // ---- B operands of the score MFMAs: q~_h[(D/4) kg + 8r .. +8); columns with t0 < 2 take the
-    // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
-    // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq[HG][NR];
-    {
-        const float fold = kLog2e / (float)kD;
-#pragma unroll
-        for (int hg = 0; hg < HG; ++hg) {
-            const int hh = kG * hg + (col >> 2);
-#pragma unroll
-            for (int r = 0; r < NR; ++r)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float x = sm_qt[hh * kD + (kD / 4) * kg + 8 * r + e] * fold;
-                    const _Float16 hi = (_Float16)x;
-                    const _Float16 lo = (_Float16)(x - (float)hi);
-                    bq[hg][r][e] = (SPLITQ && (col & 2)) ? lo : hi;
-                }
-        }
-    }
-
-    // ---- fused append: this workgroup's sub-spaces of the new token, dealt to the wavefronts as
-    // (sub-space, key | value) items.  Eq. 2 by exhaustive search over the table already in LDS: a lane
-    // scans centroids lane, lane + 64, ..; squared distances summed in channel order in fp32; the
-    // lowest index among the centroids at minimum distance wins.  The key item
-    // also leaves the new token's score share of its sub-space for the 4 heads, the value item
-    // the dequantized channels, for the merge kernel.
-    if (has_new) {
-        const long long pos = len - 1;
-        const float fold = kLog2e / (float)kD;
-        // A wavefront takes up to four items of one kind at a time (items i0, i0 + NW, ..): their
-        // chains of LDS reads, distance arithmetic and cross-lane reductions are independent, so
-        // they overlap instead of paying their latencies one after the other.
-        auto new_items = [&](auto kv_c, int i0) {
-            constexpr int kv = decltype(kv_c)::value;          // 0: key sub-spaces, 1: value sub-spaces
-            constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS, MX = kv == 0 ? MK : MV, NB = 4;
-            // entry c of a sub-space sits at tab + c * stride (value tables are transposed)
-            constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
-            int m[NB];
-            bool ok[NB];
-            const unsigned char *tab[NB];
-            float best[NB];
-            unsigned arg[NB];
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                const int mm = s + (i0 + NW * b4) * p.S;
-                ok[b4] = mm < MX;
-                m[b4] = ok[b4] ? mm : 0;                        // a surplus slot redoes sub-space 0 and writes nothing
-                tab[b4] = kv == 0 ? sm_k + m[b4] * SUB_K
-                                  : sm_v + (m[b4] % NROUND_V) * PLANE_V + (m[b4] / NROUND_V) * ENTRY_V;
-                best[b4] = INFINITY;
-                arg[b4] = 0;
-            }
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                float x[DS];
-#pragma unroll
-                for (int jj = 0; jj < DS; ++jj) x[jj] = sm_new[kv * kD + m[b4] * DS + jj];
-#pragma unroll
-                for (int i = 0; i < kCentroids / 64; ++i) {
-                    const unsigned c = lane + 64 * i;
-                    _Float16 cen[DS];
-                    __builtin_memcpy(cen, tab[b4] + c * stride, EN);
-                    float dist = 0.f;
-#pragma unroll
-                    for (int jj = 0; jj < DS; ++jj) {
-                        const float tdiff = x[jj] - (float)cen[jj];
-                        dist = fmaf(tdiff, tdiff, dist);
-                    }
-                    if (dist < best[b4]) {
-                        best[b4] = dist;
-                        arg[b4] = c;
-                    }
-                }
-            }
-            unsigned code[NB];
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                // a non-negative fp32 orders like its bit pattern
-                const unsigned dmin = wave_umin(__float_as_uint(best[b4]));
-                code[b4] = wave_umin(__float_as_uint(best[b4]) == dmin ? arg[b4] : 0xffffffffu);
-            }
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                if (!ok[b4]) continue;                          // wave-uniform
-                _Float16 win[DS];
-                __builtin_memcpy(win, tab[b4] + code[b4] * stride, EN);
-                if (kv == 0) {
-                    if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m[b4]] = (uint8_t)code[b4];
-                    if (lane < p.G) {
-                        float sc = 0.f;
-#pragma unroll
-                        for (int jj = 0; jj < DS; ++jj)
-                            sc = fmaf(sm_qt[lane * kD + m[b4] * DS + jj] * fold, (float)win[jj], sc);
-                        p.new_sc[((size_t)bg * MK + m[b4]) * p.G + lane] = sc;
-                        sm_nsc[m[b4] * KG + lane] = sc;
-                    }
-                } else {
-                    if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m[b4]] = (uint8_t)code[b4];
-                    float mine = (float)win[0];
-#pragma unroll
-                    for (int jj = 1; jj < DS; ++jj) mine = lane == jj ? (float)win[jj] : mine;
-                    if (lane < DS) {
-                        p.new_v[(size_t)bg * kD + m[b4] * DS + lane] = mine;
-                        sm_nv[m[b4] * DS + lane] = mine;
-                    }
-                }
-            }
-        };
-        // key item i (sub-space s + i S) goes to wavefront i % NW, value item i to wavefront (i + 1) % NW
-        for (int i0 = wave_u; s + i0 * p.S < MK; i0 += 4 * NW) new_items(std::integral_constant<int, 0>{}, i0);
-        for (int i0 = (wave_u + NW - 1) % NW; s + i0 * p.S < MV; i0 += 4 * NW)
-            new_items(std::integral_constant<int, 1>{}, i0);
-    }
-
-    STAMP(2);
-    float m_run[HG];                  // running max of head 4 hg + col/4 (log2 units), same in all its lanes
-    float l_part[HG];                 // this lane's share of the running sum
-    floatx4 acc_o[HG][NACC];
-#pragma unroll
-    for (int hg = 0; hg < HG; ++hg) {
-        m_run[hg] = -INFINITY;
-        l_part[hg] = 0.f;
-#pragma unroll
-        for (int r = 0; r < NACC; ++r) acc_o[hg][r] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    // LDS byte address of centroid `code byte k of w` in the sub-space table at `base`:
-    // one v_dot4_u32_u8 (w . (ENTRY_K << 8k) + base) instead of a bit-field extract and a shift-add.
-    auto lds_addr = [&](unsigned w, int k, unsigned base) -> unsigned {
-        return __builtin_amdgcn_udot4(w, (unsigned)ENTRY_K << (8 * k), base, false);
-    };
-    auto lds_addr_v = [&](unsigned w, int k, unsigned base) -> unsigned {   // code * ROW_V + base
-        if constexpr (ROW_V > 255)                  // the multiplier of v_dot4 is one byte: halve, then double
-            return __builtin_amdgcn_udot4(w, (unsigned)(ROW_V / 2) << (8 * k), base >> 1, false) << 1;
-        else
-            return __builtin_amdgcn_udot4(w, (unsigned)ROW_V << (8 * k), base, false);
-    };
-    // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
-    // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
-    auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
-        if constexpr (DK == 8) {
-            // sub-space (MK/4) kg + r: one 16-byte entry is the whole operand
-            return __builtin_bit_cast(half8, lds_load_b128(lds_addr(cd.kc[st][0], r, lds_k) + r * SUB_K));
-        } else if (DK == 4) {
-            // sub-spaces (MK/4) kg + 2r, + 2r + 1: code bytes 2r, 2r+1 of the lane's MK / 4
-            const unsigned w = cd.kc[st][r >> 1];
-            const int k0 = 2 * (r & 1);
-            const uint2 x0 = lds_load_b64(lds_addr(w, k0, lds_k) + (2 * r) * SUB_K);
-            const uint2 x1 = lds_load_b64(lds_addr(w, k0 + 1, lds_k) + (2 * r + 1) * SUB_K);
-            return as_half8(x0.x, x0.y, x1.x, x1.y);
-        } else {
-            // sub-spaces (MK/4) kg + 4r .. +3: the 4 code bytes of dword r
-            const unsigned w = cd.kc[st][r];
-            unsigned x[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                x[q] = lds_load_b32(lds_addr(w, q, lds_k) + (4 * r + q) * SUB_K);
-            return as_half8(x[0], x[1], x[2], x[3]);
-        }
-    };
-    // B operand q (0 .. NR-1) of the P.V MFMAs of sub-tile st; the code of (token v of the
-    // k-group, round r) is byte v * NROUND_V + r of the packed value codes.  d = 4:
-    // q = u * NROUND_V + r (step u, round r): centroids of sub-space NROUND_V col + r for tokens
-    // 2u, 2u+1.  d = 2: q = r: centroids of sub-space NROUND_V col + r for the 4 tokens.
-    auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
-        if constexpr (DV == 8) {
-            // q = token v of the k-group: the 8 channels of sub-space col of that token
-            return __builtin_bit_cast(half8, lds_load_b128(lds_addr_v(cd.vc[st][0], q, lds_v)));
-        } else if (DV == 4) {
-            const int u = q / NROUND_V, r = q % NROUND_V;
-            const int b0 = 2 * u * NROUND_V + r, b1 = (2 * u + 1) * NROUND_V + r;
-            const uint2 x0 = lds_load_b64(lds_addr_v(cd.vc[st][b0 >> 2], b0 & 3, lds_v) + r * PLANE_V);
-            const uint2 x1 = lds_load_b64(lds_addr_v(cd.vc[st][b1 >> 2], b1 & 3, lds_v) + r * PLANE_V);
-            return as_half8(x0.x, x0.y, x1.x, x1.y);
-        } else {
-            unsigned x[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int bi = v * NROUND_V + q;
-                x[v] = lds_load_b32(lds_addr_v(cd.vc[st][bi >> 2], bi & 3, lds_v) + q * PLANE_V);
-            }
-            return as_half8(x[0], x[1], x[2], x[3]);
-        }
-    };
-
-    half8 ka[4 * H];                 // score operands of the first H rounds of the tile about to be processed
-    // One tile, as five stages.  In every stage but the softmax the matrix cores work on
-    // operands gathered in the previous stage while the vector ALU forms the addresses of, and
-    // LDS serves, the gathers of the next one; the scheduling hints interleave the three
-    // instruction kinds so that each MFMA's 16 busy cycles are filled:
-    //   1  MFMA K first H rounds  | gather K last H rounds          (H = 2 at D = 128, 1 at D = 64)
-    //   2  MFMA K last H rounds   | gather V sub-tiles 0-1
-    //   3  online softmax         | gather V sub-tiles 2-3 (issued first, lands under the softmax)
-    //   4  MFMA P.V sub-tiles 0-1 | gather K first H rounds of the NEXT tile
-    //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
-    // Every stage pairs 4 H MFMAs with 4 H operand gathers.
-    constexpr int kReadsK = 8 / DK;                   // ds_reads (and address ops) per gathered half8
-    constexpr int kReadsV = 8 / DV;
-    // 4 H groups of: MF MFMAs, RD + XV vector-ALU ops, RD LDS reads
-#define VI_GROUPS8(MF, RD, XV)                                                             \
-    _Pragma("unroll") for (int gi = 0; gi < 4 * H; ++gi) {                                    \
-        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);                                 \
-        __builtin_amdgcn_sched_group_barrier(0x002, (RD) + (XV), 0);                        \
-        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);                                 \
-    }
-    auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
-        half8 kb[4 * H], va[2 * NR], vb[2 * NR];
-        const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
-        floatx4 sacc[HG][4];
-
-        // ---- stage 1
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int hr = 0; hr < H; ++hr)
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-#pragma unroll
-                for (int hg = 0; hg < HG; ++hg)
-                    sacc[hg][st] = MFMA16(ka[H * st + hr], bq[hg][hr], hr == 0 ? kZero4 : sacc[hg][st], 0, 0, 0);
-                kb[H * st + hr] = gather_k(cd, st, H + hr);
-            }
-        VI_GROUPS8(HG, kReadsK, 0)
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- stage 2
-#pragma unroll
-        for (int hr = 0; hr < H; ++hr)
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-#pragma unroll
-                for (int hg = 0; hg < HG; ++hg)
-                    sacc[hg][st] = MFMA16(kb[H * st + hr], bq[hg][H + hr], sacc[hg][st], 0, 0, 0);
-                va[4 * hr + st] = gather_v(cd, (4 * hr + st) / NR, (4 * hr + st) % NR);   // sub-tiles 0, 1
-            }
-        VI_GROUPS8(HG, kReadsV, 0)
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- stage 3: online softmax of this wavefront (Alg. 1 steps 12-13).
-        // The four lanes of a quad (same head, t0 = 0..3) hold identical copies of all 16 scores
-        // of their row group.  Lane t0 keeps only sub-tile t0's four, so the quad does each
-        // exp once; the P.V operand build below fetches them back across the quad with DPP.
-#pragma unroll
-        for (int q = 0; q < NR; ++q) {
-            vb[q] = gather_v(cd, 2, q);
-            vb[NR + q] = gather_v(cd, 3, q);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        unsigned pp[HG][4];                      // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
-#pragma unroll
-        for (int hg = 0; hg < HG; ++hg) {
-            if (SPLITQ) {
-                // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
-                // of the quad so that all four lanes hold the full-precision score again
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) sacc[hg][st][v] += quad_xor<2>(sacc[hg][st][v]);
-            }
-            float sc[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                // branch-free per-lane pick of sacc[t0][v] (bit masks: exactly one of sel[] is all ones)
-                const float s0 = sacc[hg][0][v], s1 = sacc[hg][1][v], s2 = sacc[hg][2][v], s3 = sacc[hg][3][v];
-                const unsigned u = (__float_as_uint(s0) & sel[0]) | (__float_as_uint(s1) & sel[1]) |
-                                   (__float_as_uint(s2) & sel[2]) | (__float_as_uint(s3) & sel[3]);
-                sc[v] = __uint_as_float(u);
-            }
-            if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (tb + 16 * t0 + 4 * v + kg > last) sc[v] = -INFINITY;
-            }
-            float tmax = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-            tmax = fmaxf(tmax, quad_xor<1>(tmax));
-            tmax = fmaxf(tmax, quad_xor<2>(tmax));
-            tmax = rows_max(tmax);
-            const float m_new = fmaxf(m_run[hg], tmax);
-            if (__any(m_new > m_run[hg])) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run[hg] - m_new);   // 0 on the first tile
-                l_part[hg] *= alpha;
-                const float alpha_o = __shfl(alpha, 4 * kg);                     // lane 4kg serves head kg
-#pragma unroll
-                for (int r = 0; r < NACC; ++r) acc_o[hg][r] *= alpha_o;
-                m_run[hg] = m_new;
-            }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run[hg]);
-                l_part[hg] += pr;
-                pp[hg][v] = pack_dup_f16(pr);
-            }
-        }
-
-        // ---- o += P . VQ^-1(V_q)  (step 16)
-        auto pv = [&](auto st_c, const half8 *vops) {
-            constexpr int st = decltype(st_c)::value;
-#pragma unroll
-            for (int hg = 0; hg < HG; ++hg) {
-                // p of sub-tile st lives in quad lane st
-                const unsigned p0 = quad_bcast<st>(pp[hg][0]), p1 = quad_bcast<st>(pp[hg][1]);
-                const unsigned p2 = quad_bcast<st>(pp[hg][2]), p3 = quad_bcast<st>(pp[hg][3]);
-                if constexpr (DV == 8) {
-                    // one token per step; channels t0 (first accumulator) and t0 + 4 (second)
-                    const unsigned pt[4] = {p0, p1, p2, p3};
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const half8 alo = as_half8(pt[v] & mask_a, pt[v] & mask_b, 0u, 0u);
-                        const half8 ahi = as_half8(0u, 0u, pt[v] & mask_a, pt[v] & mask_b);
-                        acc_o[hg][0] = MFMA16(alo, vops[v], acc_o[hg][0], 0, 0, 0);
-                        acc_o[hg][1] = MFMA16(ahi, vops[v], acc_o[hg][1], 0, 0, 0);
-                    }
-                } else if (DV == 4) {
-                    const half8 a0 = as_half8(p0 & mask_a, p0 & mask_b, p1 & mask_a, p1 & mask_b);
-                    const half8 a1 = as_half8(p2 & mask_a, p2 & mask_b, p3 & mask_a, p3 & mask_b);
-#pragma unroll
-                    for (int r = 0; r < NROUND_V; ++r) acc_o[hg][r] = MFMA16(a0, vops[r], acc_o[hg][r], 0, 0, 0);
-#pragma unroll
-                    for (int r = 0; r < NROUND_V; ++r)
-                        acc_o[hg][r] = MFMA16(a1, vops[NROUND_V + r], acc_o[hg][r], 0, 0, 0);
-                } else {
-                    const half8 a = as_half8(p0 & mask_a, p1 & mask_a, p2 & mask_a, p3 & mask_a);
-#pragma unroll
-                    for (int r = 0; r < NROUND_V; ++r)
-                        acc_o[hg][r] = MFMA16(a, vops[r], acc_o[hg][r], 0, 0, 0);
-                }
-            }
-        };
-        // ---- stage 4
-        __builtin_amdgcn_sched_barrier(0);
-        pv(std::integral_constant<int, 0>{}, va);
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
-        pv(std::integral_constant<int, 1>{}, va + NR);
-#pragma unroll
-        for (int st = 2; st < 4; ++st)
-#pragma unroll
-            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(next, st, hr);
-        VI_GROUPS8(HG * (DV == 8 ? 2 : 1), kReadsK, 3 * HG)
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- stage 5
-        pv(std::integral_constant<int, 2>{}, vb);
-        load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
-        pv(std::integral_constant<int, 3>{}, vb + NR);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-#undef VI_GROUPS8
-
-    // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
-    // its last gather has been issued.  Loads past the end of the split return code 0 (buffer
-    // range check), so the refill and the look-ahead gathers need no bounds branch.
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(0);
-#endif
-    {
-#pragma unroll
-        for (int st = 0; st < 4; ++st)
-#pragma unroll
-            for (int hr = 0; hr < H; ++hr) ka[H * st + hr] = gather_k(ca, st, hr);
-        // a wavefront's tile bases increase with k: once one is past the end, all later ones are
-        long long ta = tile_base(0), tb = tile_base(1);
-        for (int k = 2; ta < n1; k += 2) {
-            const long long tc = tile_base(k), td = tile_base(k + 1);
-            process_tile(ca, cb, ta, tc);
-            if (tb < n1) process_tile(cb, ca, tb, td);
-            ta = tc;
-            tb = td;
-        }
-    }
-
-    STAMP(3);
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(1);
-#endif
-    // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
-    float l_head[HG];
-#pragma unroll
-    for (int hg = 0; hg < HG; ++hg) {
-        l_head[hg] = l_part[hg] + quad_xor<1>(l_part[hg]);
-        l_head[hg] += quad_xor<2>(l_head[hg]);
-        l_head[hg] += __shfl_xor(l_head[hg], 16);
-        l_head[hg] += __shfl_xor(l_head[hg], 32);
-    }
-    __syncthreads();
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(2);
-#endif
-    float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][KG][D]
-    float *const sm_m = sm_o + NW * KG * kD;                              // [NW][KG]
-    float *const sm_l = sm_m + NW * KG;                                   // [NW][KG]
-#pragma unroll
-    for (int hg = 0; hg < HG; ++hg) {
-        // acc_o[hg][r] register v of lane (col, kg): head 4 hg + kg, channel kChanBlock * (NACC * col + r) + v
-#pragma unroll
-        for (int r = 0; r < NACC; ++r)
-#pragma unroll
-            for (int v = 0; v < kChanBlock; ++v)
-                sm_o[(wave * KG + kG * hg + kg) * kD + kChanBlock * (NACC * col + r) + v] = acc_o[hg][r][v];
-        if (kg == 0 && (col & 3) == 0) {
-            sm_m[wave * KG + kG * hg + (col >> 2)] = m_run[hg];
-            sm_l[wave * KG + kG * hg + (col >> 2)] = l_head[hg];
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < p.G * kD; e += BLOCK) {
-        const int hh = e / kD, c = e % kD;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, sm_m[w * KG + hh]);
-        float o = 0.f, l = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float mw = sm_m[w * KG + hh];
-            const float f = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - mx) : 0.f;
-            o += f * sm_o[w * KG * kD + e];
-            l += f * sm_l[w * KG + hh];
-        }
-        if (p.S == 1 && !p.k_res) {
-            // the workgroup holds the whole answer (a single split also encoded every sub-space of
-            // a fused new token): fold the new token in and write the output rows
-            if (has_new) {
-                float s_new = 0.f;
-                for (int m = 0; m < MK; ++m) s_new += sm_nsc[m * KG + hh];
-                const float mt = fmaxf(mx, s_new);
-                const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
-                o = f * o + wgt * sm_nv[c];
-                l = f * l + wgt;
-                mx = mt;
-            }
-            const size_t row = (size_t)b * p.Hq + g * p.G + hh;
-            p.out[row * kD + c] = __float2half(l > 0.f ? o / l : 0.f);
-            if (c == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
-        } else {
-            const size_t pi = (bg * p.S + s) * p.G;
-            p.part_o[pi * kD + e] = o;
-            if (c == 0) {
-                p.part_m[pi + hh] = mx;
-                p.part_l[pi + hh] = l;
-            }
-        }
-    }
-    STAMP(4);
-    STAMP(5);
-}
-
-template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ>
-int launch_hg(const DecodeParams &p, hipStream_t stream)
-{
-    constexpr int KG = kG * HG;
-    constexpr size_t smem = 2 * (size_t)kCentroids * kD * 2 + sizeof(float) * ((KG + 3) * kD + (kD / DK) * KG) + 16;
-    // once per process and instantiation (function-local static: initialised thread-safely)
-    static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
-    if (!configured) return -4;
-    dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ>), grid, dim3(NW * 64), smem, stream, p);
-    return hipGetLastError() == hipSuccess ? 0 : -4;
-}
-
-template <int kD, int DK, int DV, int NW, bool SPLITQ>
-int launch_typed(const DecodeParams &p, hipStream_t stream)
-{
-    return p.G <= kG ? launch_hg<kD, DK, DV, 1, NW, SPLITQ>(p, stream) : launch_hg<kD, DK, DV, 2, NW, SPLITQ>(p, stream);
-}
-
-} // namespace
 
 #ifdef VECINFER_PHASE_TIMING
 extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol(HIP_SYMBOL(g_phase_buf), &buf, sizeof(buf)) == hipSuccess ? 0 : -4; }
@@ -935,16 +9,22 @@ extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol
 
 bool decode_mfma_supports(const DecodeParams &p)
 {
-    // code rows are addressed with 32-bit byte offsets
     const bool dk_ok = p.dk == 8 || p.dk == 4 || p.dk == 2;
     const bool dv_ok = p.dv == 4 || p.dv == 2 || (p.dv == 8 && p.D == 128);
-    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok &&
+    // 10- and 12-bit codes: D = 128 and d = 4 or 8 on that side, d = 4 or 8 on the other side too
+    auto wide = [](int b) { return b == 10 || b == 12; };
+    bool bits_ok = p.bk == 8 && p.bv == 8;
+    if (wide(p.bk) || wide(p.bv))
+        bits_ok = p.D == 128 && (wide(p.bk) || p.bk == 8) && (wide(p.bv) || p.bv == 8) && p.dk >= 4 && p.dv >= 4;
+    // code rows are addressed with 32-bit byte offsets (a row is at most D / 2 bytes)
+    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok && bits_ok &&
            p.N * (long long)(p.D / 2) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
+    if (p.bk != 8 || p.bv != 8) return launch_decode_mfma_wide(p, stream);
     // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster (LDS-bound), 4 is latency-bound
     const int key = p.D * 100 + p.dk * 10 + p.dv;
     switch (key) {

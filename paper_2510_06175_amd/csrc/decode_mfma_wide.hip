@@ -1,0 +1,53 @@
+// Matrix-core decode attention with 10- or 12-bit codes on the key side, the value side or both
+// (d8b12, d4b12, K-d4b10 / V-d8b12, K-d8b12 / V-d8b8, ... of Sec. 4.1): instantiations and dispatch
+// (kernel: decode_mfma_kernel.h).  D = 128, d = 4 or 8 on both sides.
+#undef VECINFER_PHASE_TIMING
+#include "decode_mfma_kernel.h"
+
+namespace vecinfer {
+
+namespace {
+
+template <int DK, int BK, int DV>
+int pick_bv(const DecodeParams &p, hipStream_t stream)
+{
+    switch (p.bv) {
+    case 8:
+        if constexpr (BK != 8) return launch_typed<128, DK, DV, 8, true, BK, 8>(p, stream);
+        else return -2;                                    // both sides 8 bits: not this file's
+    case 10: return launch_typed<128, DK, DV, 8, true, BK, 10>(p, stream);
+    case 12: return launch_typed<128, DK, DV, 8, true, BK, 12>(p, stream);
+    default: return -2;
+    }
+}
+
+template <int DK, int BK>
+int pick_dv(const DecodeParams &p, hipStream_t stream)
+{
+    if (p.dv == 4) return pick_bv<DK, BK, 4>(p, stream);
+    if (p.dv == 8) return pick_bv<DK, BK, 8>(p, stream);
+    return -2;
+}
+
+template <int DK>
+int pick_bk(const DecodeParams &p, hipStream_t stream)
+{
+    switch (p.bk) {
+    case 8: return pick_dv<DK, 8>(p, stream);
+    case 10: return pick_dv<DK, 10>(p, stream);
+    case 12: return pick_dv<DK, 12>(p, stream);
+    default: return -2;
+    }
+}
+
+} // namespace
+
+int launch_decode_mfma_wide(const DecodeParams &p, hipStream_t stream)
+{
+    if (p.D != 128) return -2;
+    if (p.dk == 4) return pick_bk<4>(p, stream);
+    if (p.dk == 8) return pick_bk<8>(p, stream);
+    return -2;
+}
+
+} // namespace vecinfer

@@ -27,28 +27,17 @@ constexpr int kEncBlock = 256;
 constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
 constexpr int kChunkSub = 4;       // sub-spaces searched per pass: one per wavefront
 
-template <int D, int d, bool kTransform>
-__global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
+// Phase 1 of the tiled kernels: the 64 tokens of the tile, smoothed and Hadamard-transformed
+// (kTransform) or just widened (values), as fp32 rows of x_s (row stride D + 4 floats).  A lane
+// owns 4 consecutive channels of one token; the first two butterfly stages run inside the lane,
+// the others across lanes with wavefront shuffles.
+template <int D, bool kTransform>
+__device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float *x_s, long long t0, int bg, int g)
 {
-    constexpr int M = D / d;
-    constexpr int MS = kChunkSub;              // sub-spaces per chunk
-    constexpr int kChunkCh = MS * d;           // channels per chunk
-    constexpr int NCHUNK = M / MS;             // chunks per token row
-    constexpr int LPT = D / 4;                 // lanes per token in phase 1
-    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass in phase 1
+    constexpr int LPT = D / 4;                 // lanes per token
+    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass
     constexpr int XS = D + 4;                  // padded row stride of the LDS tile (floats)
-
-    __shared__ __align__(16) float cb_s[MS * kCentroids * d];      // 4096 d bytes: fp32 copies of one chunk's centroids
-    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 33 KB (D = 128): the transformed tile
-    __shared__ __align__(16) uint8_t idx_s[kEncTokens * M];        // codes of the tile
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long t0 = (long long)blockIdx.x * kEncTokens;
-    const int bg = blockIdx.z;
-    const int g = bg % p.Hkv;
-
-    // ---- phase 1: the whole transformed tile -> LDS (once per workgroup)
-    {
         const int sub = lane % LPT;            // which 4 channels of the token
         const int tw = lane / LPT;             // which token of this pass
         const int c0 = 4 * sub;
@@ -108,7 +97,30 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
             float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
             *reinterpret_cast<float4 *>(&x_s[tl * XS + c0]) = w;
         }
-    }
+}
+
+template <int D, int d, bool kTransform>
+__global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
+{
+    constexpr int M = D / d;
+    constexpr int MS = kChunkSub;              // sub-spaces per chunk
+    constexpr int kChunkCh = MS * d;           // channels per chunk
+    constexpr int NCHUNK = M / MS;             // chunks per token row
+    constexpr int LPT = D / 4;                 // lanes per token in phase 1
+    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass in phase 1
+    constexpr int XS = D + 4;                  // padded row stride of the LDS tile (floats)
+
+    __shared__ __align__(16) float cb_s[MS * kCentroids * d];      // 4096 d bytes: fp32 copies of one chunk's centroids
+    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 33 KB (D = 128): the transformed tile
+    __shared__ __align__(16) uint8_t idx_s[kEncTokens * M];        // codes of the tile
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long t0 = (long long)blockIdx.x * kEncTokens;
+    const int bg = blockIdx.z;
+    const int g = bg % p.Hkv;
+
+    // ---- phase 1: the whole transformed tile -> LDS (once per workgroup)
+    load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
 
     auto dist_bits = [&](const float (&x)[d], const float *cen) -> unsigned {
         float dist = 0.f;
@@ -330,6 +342,339 @@ __global__ __launch_bounds__(kCentroids) void append_kv_kernel(EncodeParams pk, 
 
 constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b, g) the per-token kernel wins
 
+// ---------------------------------------------------------------------------------------------
+// Codes wider than 8 bits (10 or 12; d8b12, d4b12, d4b10 of Sec. 4.1): one table of C = 2^b
+// centroids per KV head, shared by its sub-spaces (the codebook of Sec. 2.2 and Alg. 1), and a
+// token's M codes packed end to end, b bits each, in M b / 8 bytes.  D = 128.
+//
+// Tiled kernel: 64 tokens of one (batch, KV head) per workgroup.  The whole table stays in LDS as
+// fp16 (up to 64 KB) next to the transformed tile.  A lane owns one token, a wavefront M / 4
+// sub-spaces of it, so a centroid is read once (an LDS broadcast), widened to fp32 and tried
+// against all of the wavefront's sub-vectors.  The search is the one of the 8-bit kernel:
+// squared distances summed directly in channel order in fp32, group minima on the bit patterns,
+// strict "<" between groups, and the winning group looked at again for the lowest index.
+constexpr int kWideTokens = 64;
+
+template <int d>
+__device__ __forceinline__ void load_centroid(const __half *tab, unsigned c, float (&cen)[d])
+{
+    if constexpr (d == 8) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(tab + (size_t)c * 8);
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            cen[2 * j] = __low2float(h[j]);
+            cen[2 * j + 1] = __high2float(h[j]);
+        }
+    } else {
+        const uint2 raw = *reinterpret_cast<const uint2 *>(tab + (size_t)c * 4);
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+        cen[0] = __low2float(h[0]); cen[1] = __high2float(h[0]);
+        cen[2] = __low2float(h[1]); cen[3] = __high2float(h[1]);
+    }
+}
+
+template <int d>
+__device__ __forceinline__ unsigned dist_bits_of(const float (&x)[d], const float (&cen)[d])
+{
+    float dist = 0.f;
+#pragma unroll
+    for (int j = 0; j < d; ++j) {
+        const float t = x[j] - cen[j];
+        dist = fmaf(t, t, dist);
+    }
+    return __float_as_uint(dist);      // a non-negative fp32 orders like its bit pattern
+}
+
+// Packs the M codes of each of `rows` tokens (LDS, uint16 [rows][M]) into the token's row of
+// M BITS / 8 bytes and writes whole 32-bit words; word w of a row holds bits 32 w .. 32 w + 31.
+template <int M, int BITS>
+__device__ __forceinline__ void store_packed_rows(const EncodeParams &p, const unsigned short *idx_s, long long t0,
+                                                  int rows, int bg, int nthreads)
+{
+    constexpr int WPT = M * BITS / 32;         // words per token row
+    for (int e = threadIdx.x; e < rows * WPT; e += nthreads) {
+        const int tl = e / WPT, w = e - tl * WPT;
+        const long long t = t0 + tl;
+        if (t >= p.T) continue;
+        unsigned word = 0;
+        const int m_lo = 32 * w / BITS, m_hi = (32 * w + 31) / BITS;
+        for (int m = m_lo; m <= m_hi && m < M; ++m) {
+            const int sh = m * BITS - 32 * w;  // position of the code's bit 0 inside this word
+            const unsigned c = idx_s[tl * M + m];
+            word |= sh >= 0 ? c << sh : c >> (-sh);
+        }
+        reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t) * (M * BITS / 8))[w] = word;
+    }
+}
+
+template <int d, int BITS, bool kTransform>
+__global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
+{
+    constexpr int D = 128, M = D / d, C = 1 << BITS;
+    constexpr int XS = D + 4;
+    constexpr int SPW = M / (kEncBlock / 64);      // sub-spaces per wavefront: 4 (d = 8) or 8 (d = 4)
+    extern __shared__ __align__(16) unsigned char smem_w[];
+    __half *const tab = reinterpret_cast<__half *>(smem_w);                          // [C][d] fp16
+    float *const x_s = reinterpret_cast<float *>(smem_w + (size_t)C * d * 2);        // [64][XS]
+    unsigned short *const idx_s = reinterpret_cast<unsigned short *>(x_s + kWideTokens * XS);   // [64][M]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long t0 = (long long)blockIdx.x * kWideTokens;
+    const int bg = blockIdx.z;
+    const int g = bg % p.Hkv;
+
+    {
+        const uint4 *src = reinterpret_cast<const uint4 *>(p.cb + (size_t)g * C * d);
+        uint4 *dst = reinterpret_cast<uint4 *>(tab);
+        for (int e = tid; e < C * d / 8; e += kEncBlock) dst[e] = src[e];
+    }
+    load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
+    __syncthreads();
+
+    float x[SPW][d];
+#pragma unroll
+    for (int i = 0; i < SPW; ++i)
+#pragma unroll
+        for (int j = 0; j < d; ++j) x[i][j] = x_s[lane * XS + (wave * SPW + i) * d + j];
+    unsigned best[SPW];
+    int best_group[SPW];
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+        best[i] = 0x7f800000u;                     // +inf
+        best_group[i] = 0;
+    }
+    for (int c0 = 0; c0 < C; c0 += 8) {
+        unsigned gmin[SPW];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float cen[d];
+            load_centroid<d>(tab, c0 + k, cen);    // same address in every lane: broadcast
+#pragma unroll
+            for (int i = 0; i < SPW; ++i) {
+                const unsigned v = dist_bits_of<d>(x[i], cen);
+                gmin[i] = k == 0 ? v : (v < gmin[i] ? v : gmin[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < SPW; ++i)
+            if (gmin[i] < best[i]) {
+                best[i] = gmin[i];
+                best_group[i] = c0;
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+        int arg = best_group[i];
+#pragma unroll
+        for (int k = 7; k >= 0; --k) {
+            float cen[d];
+            load_centroid<d>(tab, best_group[i] + k, cen);
+            if (dist_bits_of<d>(x[i], cen) == best[i]) arg = best_group[i] + k;
+        }
+        idx_s[lane * M + wave * SPW + i] = (unsigned short)arg;
+    }
+    __syncthreads();
+    store_packed_rows<M, BITS>(p, idx_s, t0, kWideTokens, bg, kEncBlock);
+}
+
+// Decode-time append and other short inputs with wide codes: one workgroup per (token, group of
+// 4 sub-spaces, batch x KV head).  The token is transformed as in encode_token (same butterfly
+// order: bit-identical k~).  Thread c tries centroids c, c + 256, ... (increasing, strict "<":
+// its lowest index wins) against the 4 sub-vectors; the threads combine through 64-bit
+// (distance bits, index) keys, and the group's 4 b bits (a whole number of bytes) go out as bytes.
+constexpr int kTokWideSub = 4;
+
+template <int d, int BITS, bool kTransform>
+__device__ __forceinline__ void encode_token_wide(const EncodeParams &p, int group, float *x_s,
+                                                  unsigned long long (*key_s)[kTokWideSub], unsigned *code_s)
+{
+    constexpr int D = 128, M = D / d, C = 1 << BITS, MS = kTokWideSub;
+    const int tid = threadIdx.x;
+    const long long t = blockIdx.x;
+    const int m0 = group * MS;
+    const int bg = blockIdx.z;
+    const int g = bg % p.Hkv;
+    long long pos = p.pos0 + t;
+    if (p.seq_lens) {                          // per-sequence position: the last token of the sequence
+        const long long v = p.seq_lens[bg / p.Hkv];
+        const long long len = v < 0 ? 0 : (v > p.len_max ? p.len_max : v);
+        if (len == 0) return;                  // uniform over the workgroup
+        pos = len - 1;
+    }
+
+    if (tid < D) {
+        float v = __half2float(p.x[((size_t)bg * p.T + t) * D + tid]);
+        if (kTransform) v = v / p.lam[(size_t)g * D + tid];
+        x_s[tid] = v;
+    }
+    __syncthreads();
+    if (kTransform) {
+        for (int st = 1; st < D; st <<= 1) {
+            float mine = 0.f, other = 0.f;
+            if (tid < D) {
+                mine = x_s[tid];
+                other = x_s[tid ^ st];
+            }
+            __syncthreads();
+            if (tid < D) x_s[tid] = (tid & st) ? (other - mine) : (mine + other);
+            __syncthreads();
+        }
+        const float hs = 1.0f / sqrtf((float)D);
+        if (tid < D) x_s[tid] *= hs;
+        __syncthreads();
+    }
+
+    float x[MS][d];
+#pragma unroll
+    for (int i = 0; i < MS; ++i)
+#pragma unroll
+        for (int j = 0; j < d; ++j) x[i][j] = x_s[(m0 + i) * d + j];
+    unsigned best[MS], arg[MS];
+#pragma unroll
+    for (int i = 0; i < MS; ++i) {
+        best[i] = 0x7f800000u;
+        arg[i] = 0;
+    }
+    const __half *tab = p.cb + (size_t)g * C * d;
+#pragma unroll 4
+    for (int c = tid; c < C; c += kCentroids) {
+        float cen[d];
+        load_centroid<d>(tab, c, cen);
+#pragma unroll
+        for (int i = 0; i < MS; ++i) {
+            const unsigned v = dist_bits_of<d>(x[i], cen);
+            if (v < best[i]) {
+                best[i] = v;
+                arg[i] = c;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < MS; ++i) {
+        unsigned long long key = ((unsigned long long)best[i] << 32) | arg[i];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long other = __shfl_xor(key, o);
+            key = other < key ? other : key;
+        }
+        if ((tid & 63) == 0) key_s[tid >> 6][i] = key;
+    }
+    __syncthreads();
+    if (tid < MS) {
+        unsigned long long key = key_s[0][tid];
+#pragma unroll
+        for (int w = 1; w < kCentroids / 64; ++w) key = key_s[w][tid] < key ? key_s[w][tid] : key;
+        code_s[tid] = (unsigned)(key & 0xffffffffu);
+    }
+    __syncthreads();
+    // the group's MS codes = MS BITS / 8 whole bytes at byte m0 BITS / 8 of the row
+    constexpr int GB = MS * BITS / 8;
+    if (tid < GB) {
+        unsigned long long bits = 0;
+#pragma unroll
+        for (int i = 0; i < MS; ++i) bits |= (unsigned long long)code_s[i] << (i * BITS);
+        p.idx[((size_t)bg * p.n_cap + pos) * (M * BITS / 8) + (size_t)m0 * BITS / 8 + tid] = (uint8_t)(bits >> (8 * tid));
+    }
+}
+
+template <int d, int BITS, bool kTransform>
+__global__ __launch_bounds__(kCentroids) void encode_token_wide_kernel(EncodeParams p)
+{
+    __shared__ float x_s[128];
+    __shared__ unsigned long long key_s[kCentroids / 64][kTokWideSub];
+    __shared__ unsigned code_s[kTokWideSub];
+    encode_token_wide<d, BITS, kTransform>(p, blockIdx.y, x_s, key_s, code_s);
+}
+
+// Eq. 9 with wide codes on both sides in one launch: the first M_k / 4 workgroups along y take the
+// key's sub-space groups, the others the value's.
+template <int dk, int BK, int dv, int BV>
+__global__ __launch_bounds__(kCentroids) void append_wide_kernel(EncodeParams pk, EncodeParams pv)
+{
+    __shared__ float x_s[128];
+    __shared__ unsigned long long key_s[kCentroids / 64][kTokWideSub];
+    __shared__ unsigned code_s[kTokWideSub];
+    constexpr int GK = 128 / dk / kTokWideSub;
+    if (blockIdx.y < GK)
+        encode_token_wide<dk, BK, true>(pk, blockIdx.y, x_s, key_s, code_s);
+    else
+        encode_token_wide<dv, BV, false>(pv, blockIdx.y - GK, x_s, key_s, code_s);
+}
+
+template <int dk, int BK, int dv, int BV>
+int launch_append_wide_typed(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    dim3 grid((unsigned)pk.T, (128 / dk + 128 / dv) / kTokWideSub, pk.B * pk.Hkv);
+    hipLaunchKernelGGL((append_wide_kernel<dk, BK, dv, BV>), grid, dim3(kCentroids), 0, stream, pk, pv);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+template <int dk, int BK>
+int launch_append_wide_v(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    switch (pv.d * 100 + pv.bits) {
+    case 810: return launch_append_wide_typed<dk, BK, 8, 10>(pk, pv, stream);
+    case 812: return launch_append_wide_typed<dk, BK, 8, 12>(pk, pv, stream);
+    case 410: return launch_append_wide_typed<dk, BK, 4, 10>(pk, pv, stream);
+    case 412: return launch_append_wide_typed<dk, BK, 4, 12>(pk, pv, stream);
+    default: return -2;
+    }
+}
+
+// both sides wide (D = 128): one launch
+int launch_append_wide(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    if (pk.D != 128) return -2;
+    switch (pk.d * 100 + pk.bits) {
+    case 810: return launch_append_wide_v<8, 10>(pk, pv, stream);
+    case 812: return launch_append_wide_v<8, 12>(pk, pv, stream);
+    case 410: return launch_append_wide_v<4, 10>(pk, pv, stream);
+    case 412: return launch_append_wide_v<4, 12>(pk, pv, stream);
+    default: return -2;
+    }
+}
+
+template <int d, int BITS>
+int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
+{
+    constexpr int M = 128 / d;
+    if (p.T <= kTokenKernelMaxT) {
+        dim3 tgrid((unsigned)p.T, M / kTokWideSub, p.B * p.Hkv);
+        if (p.lam)
+            hipLaunchKernelGGL((encode_token_wide_kernel<d, BITS, true>), tgrid, dim3(kCentroids), 0, stream, p);
+        else
+            hipLaunchKernelGGL((encode_token_wide_kernel<d, BITS, false>), tgrid, dim3(kCentroids), 0, stream, p);
+        return hipGetLastError() == hipSuccess ? 0 : -4;
+    }
+    constexpr size_t smem = ((size_t)1 << BITS) * d * 2 + sizeof(float) * kWideTokens * (128 + 4) + 2 * kWideTokens * M;
+    static const bool configured =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<d, BITS, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<d, BITS, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!configured) return -4;
+    dim3 grid((unsigned)((p.T + kWideTokens - 1) / kWideTokens), 1, p.B * p.Hkv);
+    if (p.lam)
+        hipLaunchKernelGGL((encode_wide_kernel<d, BITS, true>), grid, dim3(kEncBlock), smem, stream, p);
+    else
+        hipLaunchKernelGGL((encode_wide_kernel<d, BITS, false>), grid, dim3(kEncBlock), smem, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+int launch_encode_wide(const EncodeParams &p, hipStream_t stream)
+{
+    if (p.D != 128 || p.km_sums) return -2;
+    const int key = p.d * 100 + p.bits;
+    switch (key) {
+    case 810: return launch_wide_typed<8, 10>(p, stream);
+    case 812: return launch_wide_typed<8, 12>(p, stream);
+    case 410: return launch_wide_typed<4, 10>(p, stream);
+    case 412: return launch_wide_typed<4, 12>(p, stream);
+    default: return -2;
+    }
+}
+
 template <int D, int d>
 int launch_typed(const EncodeParams &p, hipStream_t stream)
 {
@@ -396,6 +741,13 @@ int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __hal
 int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
 {
     if (pk.T > kTokenKernelMaxT) return -2;
+    if (pk.bits != 8 && pv.bits != 8) return launch_append_wide(pk, pv, stream);
+    if (pk.bits != 8 || pv.bits != 8) {
+        // one wide side, one 8-bit side: each has its own per-token kernel (launch_encode picks
+        // it for T <= kTokenKernelMaxT), so keys and values go out as two launches
+        const int rc = launch_encode(pk, stream);
+        return rc != 0 ? rc : launch_encode(pv, stream);
+    }
     if (pk.D == 128) return launch_append_dk<128>(pk, pv, stream);
     if (pk.D == 64) return launch_append_dk<64>(pk, pv, stream);
     return -2;
@@ -403,6 +755,7 @@ int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t st
 
 int launch_encode(const EncodeParams &p, hipStream_t stream)
 {
+    if (p.bits != 8) return launch_encode_wide(p, stream);
     if (p.D == 128) {
         if (p.d == 2) return launch_typed<128, 2>(p, stream);
         if (p.d == 4) return launch_typed<128, 4>(p, stream);

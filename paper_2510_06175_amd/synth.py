@@ -28,6 +28,8 @@ class Shape:
     N: int            # tokens in the cache
     d_k: int          # key sub-vector dim
     d_v: int          # value sub-vector dim
+    b_k: int = 8      # key code width in bits (the m of the paper's "dnbm" names)
+    b_v: int = 8      # value code width in bits
 
     @property
     def Mk(self) -> int:
@@ -41,9 +43,18 @@ class Shape:
     def G(self) -> int:
         return self.Hq // self.Hkv
 
+    @property
+    def row_bytes_k(self) -> int:
+        """Bytes of one token's key codes (Mk codes of b_k bits, end to end)."""
+        return self.Mk * self.b_k // 8
+
+    @property
+    def row_bytes_v(self) -> int:
+        return self.Mv * self.b_v // 8
+
     def index_bytes(self) -> int:
         """Compressed-KV bytes one decode step has to read."""
-        return self.B * self.Hkv * self.N * (self.Mk + self.Mv)
+        return self.B * self.Hkv * self.N * (self.row_bytes_k + self.row_bytes_v)
 
 
 # BASELINE configurations (b2d4 = d 4, b4d2 = d 2; 8-bit codes in both)
@@ -56,6 +67,8 @@ LLAMA8B_196K_B4D2 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=2)
 HEADDIM64_196K = Shape(1, 32, 8, 64, 196608, 4, 4)
 # keys at 4 bits per element (d = 2), values at 2 (d = 4): "more bits for the keys", Sec. 3.2
 LLAMA8B_196K_KD2_VD4 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=2, d_v=4)
+# 1.5 bits per element: d = 8, 12-bit codes, one 4096-entry codebook per KV head (Sec. 4.1, Sec. 4.4)
+LLAMA8B_196K_D8B12 = Shape(B=1, Hq=32, Hkv=8, D=128, N=196608, d_k=8, d_v=8, b_k=12, b_v=12)
 ENCODE_64K = Shape(B=1, Hq=32, Hkv=8, D=128, N=65536, d_k=4, d_v=4)
 
 
@@ -66,6 +79,16 @@ def rng(seed: int) -> np.random.Generator:
 def codebooks(g: np.random.Generator, Hkv: int, M: int, d: int) -> np.ndarray:
     """Per-(KV head, sub-space) codebooks [Hkv, M, 256, d], fp16, centroids ~ N(0, 1)."""
     return g.standard_normal((Hkv, M, NUM_CENTROIDS, d), dtype=np.float32).astype(np.float16)
+
+
+def shared_codebooks(g: np.random.Generator, Hkv: int, bits: int, d: int) -> np.ndarray:
+    """One codebook of 2^bits centroids per KV head, shared by its sub-spaces: [Hkv, 2^bits, d], fp16 ~ N(0, 1)."""
+    return g.standard_normal((Hkv, 1 << bits, d), dtype=np.float32).astype(np.float16)
+
+
+def codebooks_for(g: np.random.Generator, Hkv: int, M: int, d: int, bits: int) -> np.ndarray:
+    """The codebook tensor a side with `bits`-bit codes uses: per sub-space at 8 bits, shared above."""
+    return codebooks(g, Hkv, M, d) if bits == 8 else shared_codebooks(g, Hkv, bits, d)
 
 
 def queries(g: np.random.Generator, B: int, Hq: int, D: int) -> np.ndarray:
@@ -81,6 +104,12 @@ def lognormal_lambda(g: np.random.Generator, Hkv: int, D: int, sigma: float = 0.
 def random_indices(g: np.random.Generator, B: int, Hkv: int, n_cap: int, M: int) -> np.ndarray:
     """Uniform random uint8 codes [B, Hkv, n_cap, M]."""
     return g.integers(0, NUM_CENTROIDS, size=(B, Hkv, n_cap, M), dtype=np.uint8)
+
+
+def random_code_rows(g: np.random.Generator, B: int, Hkv: int, n_cap: int, row_bytes: int) -> np.ndarray:
+    """Uniform random code rows [B, Hkv, n_cap, row_bytes] as bytes.  With 2^b centroids every b-bit
+    pattern is a valid code, so uniform random bytes are uniform random codes at any code width."""
+    return g.integers(0, 256, size=(B, Hkv, n_cap, row_bytes), dtype=np.uint8)
 
 
 def keys_with_outlier_channels(g: np.random.Generator, B: int, Hkv: int, T: int, D: int,
@@ -108,10 +137,10 @@ def decode_inputs(shape: Shape, seed: int, n_cap: int | None = None) -> dict:
     return {
         "q": queries(g, shape.B, shape.Hq, shape.D),
         "lam": lognormal_lambda(g, shape.Hkv, shape.D),
-        "cb_k": codebooks(g, shape.Hkv, shape.Mk, shape.d_k),
-        "cb_v": codebooks(g, shape.Hkv, shape.Mv, shape.d_v),
-        "k_idx": random_indices(g, shape.B, shape.Hkv, n_cap, shape.Mk),
-        "v_idx": random_indices(g, shape.B, shape.Hkv, n_cap, shape.Mv),
+        "cb_k": codebooks_for(g, shape.Hkv, shape.Mk, shape.d_k, shape.b_k),
+        "cb_v": codebooks_for(g, shape.Hkv, shape.Mv, shape.d_v, shape.b_v),
+        "k_idx": random_code_rows(g, shape.B, shape.Hkv, n_cap, shape.row_bytes_k),
+        "v_idx": random_code_rows(g, shape.B, shape.Hkv, n_cap, shape.row_bytes_v),
     }
 
 
@@ -133,7 +162,7 @@ def encode_inputs(shape: Shape, seed: int, n_outlier: int) -> dict:
         "k": k,
         "outlier_channels": ch,
         "v": values(g, shape.B, shape.Hkv, shape.N, shape.D),
-        "cb_k": codebooks(g, shape.Hkv, shape.Mk, shape.d_k),
-        "cb_v": codebooks(g, shape.Hkv, shape.Mv, shape.d_v),
+        "cb_k": codebooks_for(g, shape.Hkv, shape.Mk, shape.d_k, shape.b_k),
+        "cb_v": codebooks_for(g, shape.Hkv, shape.Mv, shape.d_v, shape.b_v),
         "q": queries(rng(0), shape.B, shape.Hq, shape.D),
     }

@@ -14,7 +14,20 @@ NEAR_TIE = 1e-6     # relative distance gap under which an index mismatch is a l
 
 
 def cfg_of(shape):
-    return vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v)
+    return vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
+
+
+def oracle_view(shape, x):
+    """GPU-layout inputs as the oracle takes them: codebooks [Hkv, Mcb, C, d] (Mcb = 1 for the shared
+    table of codes wider than 8 bits) and one unpacked index per sub-vector (uint16 when packed)."""
+    import oracle
+    y = dict(x)
+    for side, bits, M in (("k", shape.b_k, shape.Mk), ("v", shape.b_v, shape.Mv)):
+        if bits != 8:
+            y["cb_" + side] = np.asarray(x["cb_" + side])[:, None]
+            if side + "_idx" in x:
+                y[side + "_idx"] = oracle.unpack_codes(np.asarray(x[side + "_idx"]), bits, M)
+    return y
 
 
 def dev(a):
@@ -77,19 +90,19 @@ def assert_decode_close(got_out, got_lse, ref_out, ref_lse, what=""):
 
 
 def gpu_encode(shape, k=None, lam=None, cb_k=None, v=None, cb_v=None, pos0=0, n_cap=None):
-    """Encode keys and/or values on the GPU; returns uint8 numpy arrays [B, Hkv, n_cap, M]."""
+    """Encode keys and/or values on the GPU; returns uint8 numpy arrays [B, Hkv, n_cap, row bytes]."""
     cfg = cfg_of(shape)
     res = []
     if k is not None:
         B, Hkv, T, D = k.shape
         cap = T + pos0 if n_cap is None else n_cap
-        idx = torch.full((B, Hkv, cap, shape.Mk), 0xEE, dtype=torch.uint8, device="cuda")
+        idx = torch.full((B, Hkv, cap, shape.row_bytes_k), 0xEE, dtype=torch.uint8, device="cuda")
         vb.vecinfer_encode_keys(cfg, dev(k), dev(lam), dev(cb_k), idx, pos0=pos0)
         res.append(idx)
     if v is not None:
         B, Hkv, T, D = v.shape
         cap = T + pos0 if n_cap is None else n_cap
-        idx = torch.full((B, Hkv, cap, shape.Mv), 0xEE, dtype=torch.uint8, device="cuda")
+        idx = torch.full((B, Hkv, cap, shape.row_bytes_v), 0xEE, dtype=torch.uint8, device="cuda")
         vb.vecinfer_encode_values(cfg, dev(v), dev(cb_v), idx, pos0=pos0)
         res.append(idx)
     torch.cuda.synchronize()

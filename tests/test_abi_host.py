@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2510_06175_amd import binding as vb
@@ -57,7 +58,8 @@ def test_encode_argument_errors():
     assert _enc_vals(v=None) == vb.EINVAL
     assert _enc_vals(T=9) == vb.EINVAL
     for bad in (vb.Config(96, 32, 8, 4, 4), vb.Config(128, 32, 5, 4, 4), vb.Config(128, 32, 8, 3, 4),
-                vb.Config(128, 32, 8, 4, 4, k_bits=12), vb.Config(128, 128, 8, 4, 4),
+                vb.Config(128, 32, 8, 4, 4, k_bits=16), vb.Config(128, 32, 8, 2, 4, k_bits=12),
+                vb.Config(64, 32, 8, 4, 4, v_bits=10), vb.Config(128, 32, 8, 4, 4, k_bits=9), vb.Config(128, 128, 8, 4, 4),
                 vb.Config(128, 32, 8, 4, 16)):
         assert _enc_keys(cfg=bad) == vb.EUNSUPPORTED
         assert _enc_vals(cfg=bad) == vb.EUNSUPPORTED
@@ -155,6 +157,29 @@ def test_kmeans_argument_errors():
     mixed = vb.Config(128, 32, 8, 2, 8)
     assert vb.vecinfer_kmeans_workspace_bytes(mixed, True) > vb.vecinfer_kmeans_workspace_bytes(mixed, False)
     assert vb.vecinfer_kmeans_workspace_bytes(vb.Config(96, 32, 8, 4, 4), True) == 0
+
+
+def test_wide_code_sizes_and_argument_errors():
+    """10- and 12-bit codes: row bytes M b / 8 and one 2^b-entry codebook per KV head (Sec. 2.2)."""
+    d8b12 = vb.Config(128, 32, 8, 8, 8, 12, 12)
+    assert vb.vecinfer_index_row_bytes(d8b12, True) == 24 == d8b12.row_bytes(True)
+    assert vb.vecinfer_codebook_elems(d8b12, False) == 8 * 4096 * 8 == int(np.prod(d8b12.cb_shape(False)))
+    mixed = vb.Config(128, 32, 8, 4, 8, 10, 8)                       # K-d4b10 / V-d8b8
+    assert vb.vecinfer_index_row_bytes(mixed, True) == 40 and vb.vecinfer_index_row_bytes(mixed, False) == 16
+    assert vb.vecinfer_codebook_elems(mixed, True) == 8 * 1024 * 4
+    assert vb.vecinfer_codebook_elems(mixed, False) == 8 * 16 * 256 * 8 == int(np.prod(mixed.cb_shape(False)))
+    assert vb.vecinfer_index_row_bytes(CFG, True) == 32 and vb.vecinfer_codebook_elems(CFG, True) == 8 * 32 * 256 * 4
+    assert vb.vecinfer_index_row_bytes(vb.Config(128, 32, 8, 2, 4, k_bits=12), True) == 0     # d = 2 has no wide form
+    assert vb.vecinfer_decode_workspace_bytes(d8b12, 1, 196608, 32) == vb.vecinfer_decode_workspace_bytes(
+        vb.Config(128, 32, 8, 8, 8), 1, 196608, 32)
+    # the lookup-table variant reads one byte per code; the training step covers 256-centroid tables
+    assert _decode(cfg=d8b12, variant=vb.VARIANT_LUT, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # wide codes on one side need d = 4 or 8 on the other side too
+    assert _decode(cfg=vb.Config(128, 32, 8, 8, 2, 12, 8), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert vb.vecinfer_kmeans_workspace_bytes(d8b12, True) == 0
+    assert vb.lib().vecinfer_kmeans_step(C.byref(d8b12.c()), FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, FAKE, 1 << 30,
+                                         None) == vb.EUNSUPPORTED
+    assert _enc_keys(cfg=d8b12, k=None) == vb.EINVAL
 
 
 def test_workspace_size_and_auto_splits():

@@ -608,6 +608,41 @@ def test_wide_decode_matches_torch_sdpa_on_dequantized_cache(oracle, kcfg, vcfg)
         np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-12)
 
 
+def test_wide_residual_window_matches_sdpa_on_concatenated_cache(oracle):
+    """Sec. 4.1's full-precision window with a wide-code cache: attention over the looked-up rows
+    followed by the raw window rows, window keys carried into the transformed domain (Eq. 7)."""
+    g = synth.rng(341)
+    B, Hq, Hkv, D, N, R = 2, 4, 2, 128, 37, 9
+    G = Hq // Hkv
+    cb_k = g.standard_normal((Hkv, 1, 4096, 8)).astype(np.float16)
+    cb_v = g.standard_normal((Hkv, 16, 256, 8)).astype(np.float16)
+    k_idx = g.integers(0, 4096, size=(B, Hkv, N, 16), dtype=np.uint16)
+    v_idx = g.integers(0, 256, size=(B, Hkv, N, 16), dtype=np.uint16)
+    q = g.standard_normal((B, Hq, D)).astype(np.float16)
+    lam = np.exp(0.5 * g.standard_normal((Hkv, D))).astype(np.float32)
+    k_res = g.standard_normal((B, Hkv, R, D)).astype(np.float16)
+    v_res = g.standard_normal((B, Hkv, R, D)).astype(np.float16)
+    seq, res = np.array([37, 12]), np.array([9, 4])
+    out, lse = oracle.decode_attention_residual(q, lam, cb_k, cb_v, k_idx, v_idx, k_res, v_res, seq, res)
+    Hm = scipy.linalg.hadamard(D) / np.sqrt(D)
+    for b in range(B):
+        n, r = seq[b], res[b]
+        Kh = np.stack([cb_k[h, 0].astype(np.float64)[k_idx[b, h, :n]].reshape(n, D) for h in range(Hkv)])
+        Vh = np.stack([cb_v[h].astype(np.float64)[np.arange(16)[None, :], v_idx[b, h, :n]].reshape(n, D)
+                       for h in range(Hkv)])
+        Kw = np.stack([(k_res[b, h, :r].astype(np.float64) / lam[h].astype(np.float64)) @ Hm for h in range(Hkv)])
+        Kall = np.concatenate([Kh, Kw], axis=1)
+        Vall = np.concatenate([Vh, v_res[b, :, :r].astype(np.float64)], axis=1)
+        qt = (q[b].astype(np.float64) * np.repeat(lam.astype(np.float64), G, axis=0)) @ Hm
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(qt)[None, :, None, :],
+            torch.from_numpy(Kall).repeat_interleave(G, dim=0)[None],
+            torch.from_numpy(Vall).repeat_interleave(G, dim=0)[None])[0, :, 0].numpy()
+        np.testing.assert_allclose(out[b], ref, rtol=1e-10, atol=1e-12)
+        scores = np.einsum("hd,hnd->hn", qt, np.repeat(Kall, G, axis=0)) / np.sqrt(D)
+        np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-11)
+
+
 def test_wide_decode_special_cases(oracle):
     """q = 0: the mean of the looked-up value rows and L = ln N; N = 1: that token's value row."""
     g = synth.rng(333)
