@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused VQ decode-attention hot path on one MI355X.
 
-Workload (BASELINE configs[3], the one the metric is quoted on): Llama-3.1-8B layer shape,
+Workload (the long-context configuration the metric is quoted on): Llama-3.1-8B layer shape,
 batch 1, 32 query / 8 KV heads, head dim 128, 196608 cached tokens, b2d4 codes for K and V.
 One step = one decode step of one layer (vecinfer_decode_step): append the new token's key and
 value codes (smooth + FWHT + nearest centroid) and run the fused VQ attention over the cache.
@@ -9,7 +9,9 @@ Steps rotate over several distinct layer caches so that the index stream comes f
 from the 256 MB Infinity Cache.  Inputs are seeded and synthetic and are resident in HBM
 before the timed region.
 
-Prints ONE JSON line; see the design doc for how each field is computed.
+Prints ONE JSON line: `value` = index bytes per step / step time; `roofline.achieved` = index bytes /
+average duration of the attention call, timed by its own event pairs; `cpu_baseline` = the float64
+oracle on the host cores.
 """
 from __future__ import annotations
 
@@ -57,7 +59,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1 "
-              "(sharding by KV head / sequence is described in DESIGN.md, not built).", file=sys.stderr)
+              "(the path shards by KV head, batch or sequence with one log-sum-exp merge; not built).", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -57,7 +57,7 @@ class Shape:
         return self.B * self.Hkv * self.N * (self.row_bytes_k + self.row_bytes_v)
 
 
-# BASELINE configurations (b2d4 = d 4, b4d2 = d 2; 8-bit codes in both)
+# benchmark configurations (b2d4 = d 4, b4d2 = d 2; 8-bit codes in both)
 TINY = Shape(B=1, Hq=1, Hkv=1, D=128, N=4096, d_k=4, d_v=4)
 LLAMA8B_32K = Shape(B=1, Hq=32, Hkv=8, D=128, N=32768, d_k=4, d_v=4)
 LLAMA8B_BATCH32 = Shape(B=32, Hq=32, Hkv=8, D=128, N=8192, d_k=4, d_v=4)

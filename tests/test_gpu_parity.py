@@ -210,7 +210,7 @@ def test_encode_planted_codes_and_ties():
     np.testing.assert_array_equal(got_v, expect)
 
 
-# ------------------------------------------------------------------ the BASELINE configurations
+# ------------------------------------------------------------------ the benchmark configurations at full size
 
 def test_config1_tiny_encode_then_decode():
     """Config 1: 1 head, N 4096, keys with 4 outlier channels x20, lambda by Eq. 4, b2d4."""
