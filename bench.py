@@ -5,7 +5,7 @@ Workload (the long-context configuration the metric is quoted on): Llama-3.1-8B 
 batch 1, 32 query / 8 KV heads, head dim 128, 196608 cached tokens, b2d4 codes for K and V.
 One step = one decode step of one layer (vecinfer_decode_step): append the new token's key and
 value codes (smooth + FWHT + nearest centroid) and run the fused VQ attention over the cache.
-Steps rotate over several distinct layer caches so that the index stream comes from HBM, not
+Steps rotate over several distinct layers (code caches, codebooks, smoothing factors) so that the index stream comes from HBM, not
 from the 256 MB Infinity Cache.  Inputs are seeded and synthetic and are resident in HBM
 before the timed region.
 
@@ -85,12 +85,17 @@ def main() -> int:
 
     # ---- inputs, resident in HBM
     x0 = synth.decode_inputs(shape, seed=4)
-    base = {k: dev(v) for k, v in x0.items() if k in ("q", "lam", "cb_k", "cb_v")}
-    caches = [(dev(x0["k_idx"]), dev(x0["v_idx"]))]
+    # every layer has its own code cache, codebooks and smoothing factors (layer 0 = x0, which the
+    # oracle leg also uses); the query is the same tensor for all
+    q = dev(x0["q"])
+    caches = [tuple(dev(x0[k]) for k in ("k_idx", "v_idx", "cb_k", "cb_v", "lam"))]
     for layer in range(1, layers):
         g = synth.rng(1000 + layer)
         caches.append((dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_k)),
-                       dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_v))))
+                       dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_v)),
+                       dev(synth.codebooks_for(g, shape.Hkv, shape.Mk, shape.d_k, shape.b_k)),
+                       dev(synth.codebooks_for(g, shape.Hkv, shape.Mv, shape.d_v, shape.b_v)),
+                       dev(synth.lognormal_lambda(g, shape.Hkv, shape.D))))
     g = synth.rng(77)
     new_k = dev(synth.values(g, shape.B, shape.Hkv, 1, shape.D))
     new_v = dev(synth.values(g, shape.B, shape.Hkv, 1, shape.D))
@@ -104,27 +109,25 @@ def main() -> int:
         win = {k: dev(v) for k, v in synth.residual_window(shape, seed=78, r_cap=args.residual).items()}
 
     def attend(i):
-        k_idx, v_idx = caches[i % layers]
+        k_idx, v_idx, cb_k, cb_v, lam = caches[i % layers]
         if args.residual:
-            vb.vecinfer_decode_attention_residual(cfg, base["q"], base["lam"], base["cb_k"], base["cb_v"], k_idx,
-                                                  v_idx, win["k_res"], win["v_res"], ws, out, lse=lse,
-                                                  num_splits=args.splits, variant=variant)
+            vb.vecinfer_decode_attention_residual(cfg, q, lam, cb_k, cb_v, k_idx, v_idx, win["k_res"], win["v_res"],
+                                                  ws, out, lse=lse, num_splits=args.splits, variant=variant)
             return
-        vb.vecinfer_decode_attention(cfg, base["q"], base["lam"], base["cb_k"], base["cb_v"], k_idx, v_idx,
-                                     ws, out, lse=lse, num_splits=args.splits, variant=variant)
+        vb.vecinfer_decode_attention(cfg, q, lam, cb_k, cb_v, k_idx, v_idx, ws, out, lse=lse,
+                                     num_splits=args.splits, variant=variant)
 
     def step(i):
         if args.decode_only:
             attend(i)
             return
-        k_idx, v_idx = caches[i % layers]
+        k_idx, v_idx, cb_k, cb_v, lam = caches[i % layers]
         if args.separate_append:
-            vb.vecinfer_append_kv(cfg, new_k, new_v, base["lam"], base["cb_k"], base["cb_v"], k_idx, v_idx,
-                                  pos0=shape.N - 1)
+            vb.vecinfer_append_kv(cfg, new_k, new_v, lam, cb_k, cb_v, k_idx, v_idx, pos0=shape.N - 1)
             attend(i)
         else:
-            vb.vecinfer_decode_step(cfg, base["q"], new_k, new_v, base["lam"], base["cb_k"], base["cb_v"], k_idx,
-                                    v_idx, ws, out, lse=lse, num_splits=args.splits, variant=variant)
+            vb.vecinfer_decode_step(cfg, q, new_k, new_v, lam, cb_k, cb_v, k_idx, v_idx, ws, out, lse=lse,
+                                    num_splits=args.splits, variant=variant)
 
     if args.traffic_probe:
         src = torch.empty(256 * 2**20, dtype=torch.uint8, device="cuda").random_(0, 256)
