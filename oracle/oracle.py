@@ -73,6 +73,7 @@ def _load():
                                                    C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                                    C.c_int, C.c_int, C.c_int, dp, dp]
         lib.vo_decode_residual_batch_g.restype = C.c_int
+        lib.vo_kmeans_update_g.argtypes = [dp, u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, dp, dp, i64p]
         _lib = lib
     return _lib
 
@@ -385,9 +386,19 @@ def kmeans_update(X, idx, cb_in):
     Returns (cb_out [M, C, d] f64, counts [M, C] int64); an empty cluster keeps its centroid."""
     X = _f64(X)
     cb_in = _f64(cb_in)
-    idx = np.ascontiguousarray(idx, dtype=np.uint8)
     N, D = X.shape
     M, Cn, d = cb_in.shape
+    if M * d != D or Cn > 256:
+        # one codebook shared by the sub-spaces ([1, C, d]): trained on their sub-vectors pooled
+        assert M in (1, D // d)
+        idx = np.ascontiguousarray(idx, dtype=np.uint16)
+        assert idx.shape == (N, D // d) and int(idx.max(initial=0)) < Cn
+        cb_out = np.empty_like(cb_in)
+        counts = np.empty((M, Cn), dtype=np.int64)
+        _load().vo_kmeans_update_g(_dp(X), _u16p(idx), N, D, d, Cn, M, _dp(cb_in), _dp(cb_out),
+                                   counts.ctypes.data_as(C.POINTER(C.c_int64)))
+        return cb_out, counts
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
     assert M * d == D and idx.shape == (N, M)
     cb_out = np.empty_like(cb_in)
     counts = np.empty((M, Cn), dtype=np.int64)
@@ -399,8 +410,8 @@ def kmeans_update(X, idx, cb_in):
 def kmeans_step(x_f16, lam, cb):
     """One Lloyd iteration per (KV head, sub-space) over all tokens of all sequences:
     x_f16 [B, Hkv, T, D]; lam [Hkv, D] (keys: trained on the transformed keys, Sec. 3.2) or None
-    (values: raw); cb [Hkv, M, C, d].  Returns (cb_new [Hkv, M, C, d] f64, counts [Hkv, M, C],
-    idx [B, Hkv, T, M])."""
+    (values: raw); cb [Hkv, M, C, d], or [Hkv, 1, C, d] for a codebook shared by the sub-spaces.
+    Returns (cb_new like cb, f64; counts [Hkv, M or 1, C]; idx [B, Hkv, T, M])."""
     x = _f64(x_f16)
     cb = _f64(cb)
     B, Hkv, T, D = x.shape

@@ -29,6 +29,7 @@
  *                          C_v of 2^b centroids; "codebook size 2^b x d x 2 bytes", Sec. 5.3), which the
  *                          configurations with 10- and 12-bit codes (d8b12, d4b12, d4b10; Sec. 4.1,
  *                          Tables 1-3) call for
+ *   vo_kmeans_update_g     the same update for a codebook shared by the sub-spaces (pooled sub-vectors)
  *   vo_merge_splits        log-sum-exp merge of per-split (o, L) pairs; the paper
  *                          returns L (Alg. 1 step 22) but does not print the merge
  *
@@ -742,4 +743,27 @@ int vo_decode_residual_batch_g(const double *q, const double *lam, const double 
         }
     free(H);
     return err;
+}
+
+/* Centroid update of one Lloyd iteration in the general form.  Mcb = M: as vo_kmeans_update, one
+ * table per sub-space.  Mcb = 1: the one table shared by all sub-spaces is trained on the
+ * sub-vectors of all of them pooled (Sec. 2.2: K-Means constructs the codebook C of 2^b
+ * centroids of dimension d from the sub-vectors).  idx is uint16; cb_in, cb_out [Mcb, C, d];
+ * counts [Mcb, C]; a centroid nobody was assigned to keeps its old value. */
+void vo_kmeans_update_g(const double *X, const uint16_t *idx, int64_t N, int D, int d, int C, int Mcb,
+                        const double *cb_in, double *cb_out, int64_t *counts)
+{
+    const int M = D / d;
+    double *sum = (double *)calloc((size_t)Mcb * C * d, sizeof(double));
+    for (int64_t e = 0; e < (int64_t)Mcb * C; ++e) counts[e] = 0;
+    for (int64_t n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            const int64_t t = (Mcb == 1 ? 0 : (int64_t)m * C) + idx[n * M + m];
+            counts[t] += 1;
+            for (int j = 0; j < d; ++j) sum[t * d + j] += X[n * D + m * d + j];
+        }
+    for (int64_t t = 0; t < (int64_t)Mcb * C; ++t)
+        for (int j = 0; j < d; ++j)
+            cb_out[t * d + j] = counts[t] > 0 ? sum[t * d + j] / (double)counts[t] : cb_in[t * d + j];
+    free(sum);
 }

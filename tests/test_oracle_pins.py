@@ -643,6 +643,48 @@ def test_wide_residual_window_matches_sdpa_on_concatenated_cache(oracle):
         np.testing.assert_allclose(lse[b], scipy.special.logsumexp(scores, axis=1), rtol=1e-11)
 
 
+def test_shared_codebook_kmeans_update_matches_scipy_on_pooled_sub_vectors(oracle):
+    """One Lloyd iteration for a codebook shared by the sub-spaces = scipy's kmeans2 (one iteration,
+    given initial centroids) on the sub-vectors of all sub-spaces pooled; empty clusters keep theirs."""
+    import scipy.cluster.vq
+    g = synth.rng(351)
+    N, D, d, C = 90, 32, 8, 1024
+    M = D // d
+    X = g.standard_normal((N, D))
+    cb = g.standard_normal((1, C, d))
+    idx = oracle.vq_encode(X, cb)
+    new, counts = oracle.kmeans_update(X, idx, cb)
+    assert new.shape == (1, C, d) and counts.shape == (1, C) and counts.sum() == N * M
+    import warnings
+    with warnings.catch_warnings():
+        warnings.simplefilter("ignore")                 # scipy warns about the empty clusters
+        ref, labels = scipy.cluster.vq.kmeans2(X.reshape(N * M, d), cb[0].copy(), iter=1, minit="matrix",
+                                               missing="warn")
+    np.testing.assert_array_equal(labels, idx.reshape(-1))
+    np.testing.assert_array_equal(counts[0], np.bincount(labels, minlength=C))
+    used = counts[0] > 0
+    assert used.sum() < C                               # the case has empty clusters
+    np.testing.assert_allclose(new[0][used], ref[used], rtol=1e-12, atol=1e-14)
+    np.testing.assert_array_equal(new[0][~used], cb[0][~used])
+    # batch driver: per KV head, keys transformed first; monotone error over iterations
+    B, Hkv, T, Dk = 1, 2, 300, 128
+    k, _ = synth.keys_with_outlier_channels(g, B, Hkv, T, Dk, 2)
+    lam = np.stack([oracle.smoothing_factors(k[:, h]) for h in range(Hkv)])
+    cbk = g.standard_normal((Hkv, 1, 1024, 8))
+
+    def error(cbx):
+        idx = oracle.encode_keys(k, lam, cbx)
+        return sum(((oracle.transform_keys(k[0, h].astype(np.float64), lam[h])
+                     - oracle.vq_dequantize(idx[0, h], cbx[h])) ** 2).sum() for h in range(Hkv))
+
+    errs = [error(cbk)]
+    for _ in range(3):
+        cbk, cnt, _ = oracle.kmeans_step(k, lam, cbk)
+        assert cnt.shape == (Hkv, 1, 1024) and cnt.sum() == Hkv * T * 16
+        errs.append(error(cbk))
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(errs, errs[1:])) and errs[-1] < 0.9 * errs[0]
+
+
 def test_wide_decode_special_cases(oracle):
     """q = 0: the mean of the looked-up value rows and L = ln N; N = 1: that token's value row."""
     g = synth.rng(333)
