@@ -143,10 +143,11 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
  *   x_f16  [B, H_kv, T, D] fp16       cb_in_f16, cb_out_f16 [H_kv, M, 256, d] (may not alias)
  *   codes  [B, H_kv, T, M] uint8 (written)    counts int32 [H_kv, M, 256] or NULL: cluster sizes
  *   workspace  vecinfer_kmeans_workspace_bytes(cfg, lambda != NULL) bytes, 256-byte aligned
- * d and M are the key values of cfg when lambda is given, else the value ones.  The step covers
- * the 256-centroid tables of 8-bit codes only.
- * Errors: as vecinfer_encode_keys / _values, plus EWORKSPACE, and EUNSUPPORTED for a side with
- * 10- or 12-bit codes.
+ * d and M are the key values of cfg when lambda is given, else the value ones.
+ * With 10- or 12-bit codes on that side the one codebook of a KV head, [H_kv, 2^b, d], is trained on
+ * the sub-vectors of all its sub-spaces pooled (Sec. 2.2); codes are the packed rows
+ * [B, H_kv, T, M b / 8] and counts is [H_kv, 2^b].
+ * Errors: as vecinfer_encode_keys / _values, plus EWORKSPACE.
  */
 size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys);
 int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda,

@@ -290,17 +290,17 @@ def new_kmeans_workspace(cfg: Config, keys: bool, device="cuda") -> torch.Tensor
 
 def vecinfer_kmeans_step(cfg: Config, x_f16, lam, cb_in, cb_out, codes, workspace, counts=None, stream=None) -> None:
     """One Lloyd iteration of the codebook training on x_f16 [B, Hkv, T, D]; lam = None trains a
-    value codebook (no transform).  Writes cb_out, codes [B, Hkv, T, M] and, if given, counts."""
+    value codebook (no transform).  Writes cb_out, codes [B, Hkv, T, row bytes] and, if given, counts
+    (one per centroid: the codebook's shape without its last axis)."""
     B, Hkv, T, D = x_f16.shape
     keys = lam is not None
-    d = cfg.k_sub_dim if keys else cfg.v_sub_dim
-    M = cfg.head_dim // d
     ws = workspace
+    cb_shape = cfg.cb_shape(keys)
     _check(lib().vecinfer_kmeans_step(
         C.byref(cfg.c()), _dev(x_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "x_f16"),
         None if lam is None else _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
-        _dev(cb_in, torch.float16, (cfg.num_kv_heads, M, 256, d), "cb_in"),
-        _dev(cb_out, torch.float16, (cfg.num_kv_heads, M, 256, d), "cb_out"),
-        _dev(codes, torch.uint8, (B, cfg.num_kv_heads, T, M), "codes"),
-        None if counts is None else _dev(counts, torch.int32, (cfg.num_kv_heads, M, 256), "counts"),
+        _dev(cb_in, torch.float16, cb_shape, "cb_in"),
+        _dev(cb_out, torch.float16, cb_shape, "cb_out"),
+        _dev(codes, torch.uint8, (B, cfg.num_kv_heads, T, cfg.row_bytes(keys)), "codes"),
+        None if counts is None else _dev(counts, torch.int32, cb_shape[:-1], "counts"),
         B, T, ws.data_ptr(), ws.numel(), _stream(stream)))

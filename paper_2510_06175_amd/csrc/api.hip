@@ -259,9 +259,9 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
 
 size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys)
 {
-    if (!cfg_ok(cfg) || (keys ? cfg->k_bits : cfg->v_bits) != 8) return 0;
+    if (!cfg_ok(cfg)) return 0;
     const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
-    const size_t cen = (size_t)cfg->num_kv_heads * (cfg->head_dim / d) * kCentroids;
+    const size_t cen = vecinfer_codebook_elems(cfg, keys) / d;     // centroids of the whole tensor
     return (cen * d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
 }
 
@@ -274,10 +274,9 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
     const bool keys = lambda != nullptr;
     const int rc = encode_args(cfg, x_f16, lambda, keys, cb_in_f16, codes, B, T, 0, T, p);
     if (rc != VECINFER_OK) return rc;
-    if (p.bits != 8) return VECINFER_EUNSUPPORTED;       // the training step covers 256-centroid tables
     const size_t need = vecinfer_kmeans_workspace_bytes(cfg, keys ? 1 : 0);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return VECINFER_EWORKSPACE;
-    const size_t cen = (size_t)p.Hkv * p.M * kCentroids;
+    const size_t cen = vecinfer_codebook_elems(cfg, keys ? 1 : 0) / p.d;
     p.km_sums = static_cast<float *>(workspace);
     p.km_counts = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(workspace) +
                                               (cen * p.d * sizeof(float) + 255) / 256 * 256);

@@ -476,6 +476,20 @@ __global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
     }
     __syncthreads();
     store_packed_rows<M, BITS>(p, idx_s, t0, kWideTokens, bg, kEncBlock);
+
+    // ---- K-Means training only: every sub-vector of the tile joins the sum of its centroid in the
+    // head's one table (fp32 hardware atomics, order of the additions not fixed)
+    if (p.km_sums) {
+        for (int e = tid; e < kWideTokens * M; e += kEncBlock) {
+            const int tl = e / M, m = e - tl * M;
+            if (t0 + tl < p.T) {
+                const size_t cen = (size_t)g * C + idx_s[tl * M + m];
+#pragma unroll
+                for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
+                atomicAdd(p.km_counts + cen, 1);
+            }
+        }
+    }
 }
 
 // Decode-time append and other short inputs with wide codes: one workgroup per (token, group of
@@ -639,7 +653,7 @@ template <int d, int BITS>
 int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
 {
     constexpr int M = 128 / d;
-    if (p.T <= kTokenKernelMaxT) {
+    if (p.T <= kTokenKernelMaxT && !p.km_sums) {
         dim3 tgrid((unsigned)p.T, M / kTokWideSub, p.B * p.Hkv);
         if (p.lam)
             hipLaunchKernelGGL((encode_token_wide_kernel<d, BITS, true>), tgrid, dim3(kCentroids), 0, stream, p);
@@ -664,7 +678,7 @@ int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
 
 int launch_encode_wide(const EncodeParams &p, hipStream_t stream)
 {
-    if (p.D != 128 || p.km_sums) return -2;
+    if (p.D != 128) return -2;
     const int key = p.d * 100 + p.bits;
     switch (key) {
     case 810: return launch_wide_typed<8, 10>(p, stream);

@@ -172,13 +172,14 @@ def test_wide_code_sizes_and_argument_errors():
     assert vb.vecinfer_index_row_bytes(vb.Config(128, 32, 8, 2, 4, k_bits=12), True) == 0     # d = 2 has no wide form
     assert vb.vecinfer_decode_workspace_bytes(d8b12, 1, 196608, 32) == vb.vecinfer_decode_workspace_bytes(
         vb.Config(128, 32, 8, 8, 8), 1, 196608, 32)
-    # the lookup-table variant reads one byte per code; the training step covers 256-centroid tables
+    # the lookup-table variant reads one byte per code
     assert _decode(cfg=d8b12, variant=vb.VARIANT_LUT, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     # wide codes on one side need d = 4 or 8 on the other side too
     assert _decode(cfg=vb.Config(128, 32, 8, 8, 2, 12, 8), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
-    assert vb.vecinfer_kmeans_workspace_bytes(d8b12, True) == 0
-    assert vb.lib().vecinfer_kmeans_step(C.byref(d8b12.c()), FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, FAKE, 1 << 30,
-                                         None) == vb.EUNSUPPORTED
+    # the training step: fp32 sums and int32 counts for the head's one table
+    assert vb.vecinfer_kmeans_workspace_bytes(d8b12, True) == 8 * 4096 * (8 * 4 + 4)
+    assert vb.lib().vecinfer_kmeans_step(C.byref(d8b12.c()), FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, FAKE, 1024,
+                                         None) == vb.EWORKSPACE
     assert _enc_keys(cfg=d8b12, k=None) == vb.EINVAL
 
 

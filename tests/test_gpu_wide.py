@@ -222,3 +222,45 @@ def test_decode_step_wide_equals_append_then_attend_and_the_oracle():
     ref = _oracle_decode(shape, dict(x, k_idx=k_idx, v_idx=v_idx), lens)
     assert_decode_close(out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), *ref,
                         what="wide step")
+
+
+# ------------------------------------------------------------------ K-Means step on a shared codebook
+
+@pytest.mark.parametrize("kind", ["keys", "values"])
+@pytest.mark.parametrize("shape", [synth.Shape(2, 2, 2, 128, 500, 8, 8, 12, 12), synth.Shape(1, 2, 2, 128, 330, 4, 8, 10, 12)],
+                         ids=_id)
+def test_kmeans_step_wide(shape, kind):
+    """One Lloyd iteration of a KV head's one codebook over the pooled sub-vectors (Sec. 2.2):
+    assignment against the oracle's Eq. 2, counts exact, centroids against the oracle's means for
+    the GPU's own assignment (fp32 atomic sums, fp16 result), empty clusters bit for bit."""
+    e = synth.encode_inputs(shape, seed=shape.N + 7, n_outlier=3)
+    keys = kind == "keys"
+    if keys:
+        lam = np.stack([oracle.smoothing_factors(e["k"][:, h]) for h in range(shape.Hkv)]).astype(np.float32)
+        x, cb, bits, M = e["k"], e["cb_k"], shape.b_k, shape.Mk
+    else:
+        lam, x, cb, bits, M = None, e["v"], e["cb_v"], shape.b_v, shape.Mv
+    cfg = cfg_of(shape)
+    B, Hkv, T, D = x.shape
+    cb_out = torch.full(cb.shape, float("nan"), dtype=torch.float16, device="cuda")
+    codes = torch.full((B, Hkv, T, M * bits // 8), 0xEE, dtype=torch.uint8, device="cuda")
+    counts = torch.full(cb.shape[:-1], -1, dtype=torch.int32, device="cuda")
+    ws = vb.new_kmeans_workspace(cfg, keys)
+    vb.vecinfer_kmeans_step(cfg, dev(x), None if lam is None else dev(lam), dev(cb), cb_out, codes, ws, counts=counts)
+    torch.cuda.synchronize()
+    cb_out, counts = cb_out.cpu().numpy(), counts.cpu().numpy()
+    got_idx = oracle.unpack_codes(codes.cpu().numpy(), bits, M)
+    ocb = cb[:, None]
+    ref_idx, gap = (oracle.encode_keys(x, lam, ocb, want_gap=True) if keys else
+                    oracle.encode_values(x, ocb, want_gap=True))
+    assert_indices_match(got_idx, ref_idx, gap, f"kmeans wide {kind}: assignment")
+    for g in range(Hkv):
+        rows = x[:, g].reshape(B * T, D).astype(np.float64)
+        if keys:
+            rows = oracle.transform_keys(rows, lam[g])
+        ref_cb, ref_counts = oracle.kmeans_update(rows, got_idx[:, g].reshape(B * T, M), ocb[g])
+        np.testing.assert_array_equal(counts[g], ref_counts[0])
+        assert ref_counts.sum() == B * T * M and (ref_counts == 0).any()
+        np.testing.assert_allclose(cb_out[g].astype(np.float64), ref_cb[0], rtol=1.5e-3, atol=1e-6)
+        empty = ref_counts[0] == 0
+        np.testing.assert_array_equal(cb_out[g][empty], cb[g][empty])
