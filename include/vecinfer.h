@@ -58,6 +58,7 @@ extern "C" {
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
 #define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
 #define VECINFER_MAX_RESIDUAL 128     /* most rows of the full-precision residual window */
+#define VECINFER_LAMBDA_FLOOR 1e-5f    /* smallest smoothing factor vecinfer_calibrate_lambda returns */
 
 enum {
     VECINFER_OK = 0,
@@ -127,6 +128,18 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
                        const float *lambda, const void *cb_k_f16, const void *cb_v_f16,
                        uint8_t *k_idx, uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0,
                        int64_t n_cap, void *stream);
+
+/*
+ * Calibration of the smoothing factors, Eq. 4: per KV head g and channel i
+ *   lambda[g, i] = max( sqrt( max over b, t of |k[b, g, t, i]| ), VECINFER_LAMBDA_FLOOR )
+ * over the T calibration tokens of all B sequences (the paper calibrates offline on 256 samples
+ * of 512 tokens, Sec. 4.1).  The floor keeps a channel that is zero in every calibration token
+ * usable (every other call needs lambda > 0); Eq. 4 itself has none.
+ *   k_f16  [B, H_kv, T, D] fp16 raw keys     lambda [H_kv, D] fp32 (fully overwritten)
+ * Errors: EINVAL for null pointers, B < 1, T < 1; EUNSUPPORTED for a cfg outside the ranges above.
+ */
+int vecinfer_calibrate_lambda(const vecinfer_cfg *cfg, const void *k_f16, float *lambda, int32_t B,
+                              int64_t T, void *stream);
 
 /*
  * One Lloyd iteration of the K-Means codebook training.  The paper builds the codebooks by

@@ -26,7 +26,7 @@ EXPORTS = [
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
     "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
-    "vecinfer_index_row_bytes", "vecinfer_codebook_elems",
+    "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda",
     "vecinfer_strerror", "vecinfer_version",
 ]
 
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
         L.vecinfer_kmeans_workspace_bytes.restype = sz
         L.vecinfer_kmeans_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i32, i64, vp, sz, vp]
         L.vecinfer_kmeans_step.restype = C.c_int
+        L.vecinfer_calibrate_lambda.argtypes = [cfgp, vp, vp, i32, i64, vp]
+        L.vecinfer_calibrate_lambda.restype = C.c_int
         L.vecinfer_index_row_bytes.argtypes = [cfgp, i32]
         L.vecinfer_index_row_bytes.restype = sz
         L.vecinfer_codebook_elems.argtypes = [cfgp, i32]
@@ -278,6 +280,17 @@ def vecinfer_index_row_bytes(cfg: Config, keys: bool) -> int:
 
 def vecinfer_codebook_elems(cfg: Config, keys: bool) -> int:
     return int(lib().vecinfer_codebook_elems(C.byref(cfg.c()), 1 if keys else 0))
+
+
+LAMBDA_FLOOR = 1e-5
+
+
+def vecinfer_calibrate_lambda(cfg: Config, k_f16, lam, stream=None) -> None:
+    """Eq. 4: lam [Hkv, D] = sqrt(max |k|) over all tokens of k_f16 [B, Hkv, T, D], floored at LAMBDA_FLOOR."""
+    B, Hkv, T, D = k_f16.shape
+    _check(lib().vecinfer_calibrate_lambda(
+        C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"), B, T, _stream(stream)))
 
 
 def vecinfer_kmeans_workspace_bytes(cfg: Config, keys: bool) -> int:

@@ -257,6 +257,19 @@ int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v
     return launch_status(launch_append(pk, pv, static_cast<hipStream_t>(stream)));
 }
 
+int vecinfer_calibrate_lambda(const vecinfer_cfg *cfg, const void *k_f16, float *lambda, int32_t B, int64_t T,
+                              void *stream)
+{
+    if (!cfg || !k_f16 || !lambda) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    if (B < 1 || T < 1) return VECINFER_EINVAL;
+    if (B > 65535 || cfg->num_kv_heads > 65535 || (T + 255) / 256 > 0x7fffffffLL) return VECINFER_EUNSUPPORTED;
+    if (!aligned(k_f16, 16) || !aligned(lambda, 16)) return VECINFER_EINVAL;
+    return launch_status(launch_calibrate_lambda(static_cast<const __half *>(k_f16), lambda, B, cfg->num_kv_heads,
+                                                 cfg->head_dim, T, VECINFER_LAMBDA_FLOOR,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
 size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys)
 {
     if (!cfg_ok(cfg)) return 0;

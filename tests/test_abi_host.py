@@ -159,6 +159,17 @@ def test_kmeans_argument_errors():
     assert vb.vecinfer_kmeans_workspace_bytes(vb.Config(96, 32, 8, 4, 4), True) == 0
 
 
+def test_calibrate_lambda_argument_errors():
+    def cal(cfg=CFG, k=FAKE, lam=FAKE, B=1, T=64):
+        return vb.lib().vecinfer_calibrate_lambda(C.byref(cfg.c()), k, lam, B, T, None)
+    assert cal(k=None) == vb.EINVAL
+    assert cal(lam=None) == vb.EINVAL
+    assert cal(B=0) == vb.EINVAL
+    assert cal(T=0) == vb.EINVAL
+    assert cal(k=FAKE + 2) == vb.EINVAL
+    assert cal(cfg=vb.Config(96, 32, 8, 4, 4)) == vb.EUNSUPPORTED
+
+
 def test_wide_code_sizes_and_argument_errors():
     """10- and 12-bit codes: row bytes M b / 8 and one 2^b-entry codebook per KV head (Sec. 2.2)."""
     d8b12 = vb.Config(128, 32, 8, 8, 8, 12, 12)

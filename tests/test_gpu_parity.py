@@ -584,3 +584,29 @@ def test_kmeans_iterations_reduce_the_quantization_error():
         errs.append(error(cb))
     assert all(b <= a * (1 + 1e-3) for a, b in zip(errs, errs[1:])), errs
     assert errs[-1] < 0.8 * errs[0]
+
+
+# ------------------------------------------------------------------ smoothing-factor calibration (Eq. 4)
+
+@pytest.mark.parametrize("shape", [synth.Shape(3, 4, 2, 128, 700, 4, 4), synth.Shape(1, 8, 8, 64, 1, 4, 4),
+                                   synth.Shape(2, 2, 1, 128, 513, 8, 8, 12, 12)],
+                         ids=lambda s: f"B{s.B}g{s.Hkv}D{s.D}T{s.N}")
+def test_calibrate_lambda(shape):
+    """lambda = sqrt(max |K|) per (KV head, channel) over every token of every sequence; the maximum
+    is exact, the square root is one fp32 rounding; an all-zero channel gets the floor."""
+    k, _ = synth.keys_with_outlier_channels(synth.rng(shape.N + 3), shape.B, shape.Hkv, shape.N, shape.D, 3)
+    k[:, 0, :, 5] = 0                                         # a channel with no signal at all
+    lam = torch.full((shape.Hkv, shape.D), float("nan"), dtype=torch.float32, device="cuda")
+    vb.vecinfer_calibrate_lambda(cfg_of(shape), dev(k), lam)
+    torch.cuda.synchronize()
+    got = lam.cpu().numpy()
+    ref = np.stack([oracle.smoothing_factors(k[:, h]) for h in range(shape.Hkv)])
+    assert ref[0, 5] == 0 and got[0, 5] == np.float32(vb.LAMBDA_FLOOR)
+    ref[0, 5] = vb.LAMBDA_FLOOR
+    np.testing.assert_allclose(got, ref, rtol=1.2e-7, atol=0)
+    # the calibrated factors are usable as they are: encode with them and compare with the oracle
+    if shape.b_k == 8 and shape.N > 1:
+        cb = synth.codebooks(synth.rng(1), shape.Hkv, shape.Mk, shape.d_k)
+        (got_k,) = gpu_encode(shape, k=k, lam=got, cb_k=cb)
+        ref_k, gap = oracle.encode_keys(k, got, cb, want_gap=True)
+        assert_indices_match(got_k, ref_k, gap, "encode with calibrated lambda")
