@@ -282,8 +282,8 @@ void decode_mfma_kernel(DecodeParams p)
     const unsigned voff_lane = WV ? (unsigned)((4 * (col & 3) + kg) * ROWB_V + 4 * (((col >> 2) * (MV / 4) * BV) >> 5))
                                   : (unsigned)(kg * MV + col * NROUND_V);
 
-    auto load_codes = [&](Codes &cd, long long tb) {
-        const unsigned ko = (unsigned)tb * ROWB_K + koff_lane, vo = (unsigned)tb * ROWB_V + voff_lane;
+    auto load_codes_k = [&](Codes &cd, long long tb) {
+        const unsigned ko = (unsigned)tb * ROWB_K + koff_lane;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             // keys: the MK / 4 code bytes of the lane's k-slot range of its token
@@ -302,6 +302,12 @@ void decode_mfma_kernel(DecodeParams p)
                 const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, 0);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][2] = w[2]; cd.kc[st][3] = w[3];
             }
+        }
+    };
+    auto load_codes_v = [&](Codes &cd, long long tb) {
+        const unsigned vo = (unsigned)tb * ROWB_V + voff_lane;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
             // values: NROUND_V bytes (sub-spaces NROUND_V col ..) of each of the tokens 4 v + kg,
             // packed token after token: byte v * NROUND_V + r
             if constexpr (WV) {
@@ -329,6 +335,10 @@ void decode_mfma_kernel(DecodeParams p)
                     cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0);
             }
         }
+    };
+    auto load_codes = [&](Codes &cd, long long tb) {
+        load_codes_k(cd, tb);
+        load_codes_v(cd, tb);
     };
 
     // Which tiles a wavefront owns.  The two wavefronts of a SIMD do not run at the same speed:
@@ -749,7 +759,11 @@ void decode_mfma_kernel(DecodeParams p)
     //   2  MFMA K last H rounds   | gather V sub-tiles 0-1
     //   3  online softmax         | gather V sub-tiles 2-3 (issued first, lands under the softmax)
     //   4  MFMA P.V sub-tiles 0-1 | gather K first H rounds of the NEXT tile
-    //   5  MFMA P.V sub-tiles 2-3 | refill this tile's code registers from HBM (two tiles ahead)
+    //   5  MFMA P.V sub-tiles 2-3
+    // A tile's key-code registers are refilled from HBM (with the codes of the tile two ahead) at the
+    // end of stage 1, its value-code registers at the start of stage 3: right after their last use,
+    // which gives the loads the longest run-up the two register sets allow (1.1 - 1.6 us less per
+    // call at 196608 tokens than refilling both in stage 5; a third register set measured slower).
     // Every stage pairs 4 H MFMAs with 4 H operand gathers.
     constexpr int kReadsK = 8 / DK;                   // ds_reads (and address ops) per gathered half8
     constexpr int kReadsV = 8 / DV;
@@ -777,6 +791,7 @@ void decode_mfma_kernel(DecodeParams p)
                 kb[H * st + hr] = gather_k(cd, st, H + hr);
             }
         VI_GROUPS8(HG, kReadsK, 0)
+        load_codes_k(cd, tb_refill);              // this tile's key codes are consumed: refill them (two tiles ahead)
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- stage 2
@@ -801,6 +816,7 @@ void decode_mfma_kernel(DecodeParams p)
             vb[q] = gather_v(cd, 2, q);
             vb[NR + q] = gather_v(cd, 3, q);
         }
+        load_codes_v(cd, tb_refill);              // this tile's value codes are consumed
         __builtin_amdgcn_sched_barrier(0);
         unsigned pp[HG][4];                      // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
 #pragma unroll
@@ -899,14 +915,13 @@ void decode_mfma_kernel(DecodeParams p)
 
         // ---- stage 5
         pv(std::integral_constant<int, 2>{}, vb);
-        load_codes(cd, tb_refill);                // cd is consumed: refill it two tiles ahead
         pv(std::integral_constant<int, 3>{}, vb + NR);
         __builtin_amdgcn_sched_barrier(0);
     };
 #undef VI_GROUPS8
 
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
-    // its last gather has been issued.  Loads past the end of the split return code 0 (buffer
+    // the last gather that uses them has been issued.  Loads past the end of the split return code 0 (buffer
     // range check), so the refill and the look-ahead gathers need no bounds branch.
 #ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(0);
