@@ -202,6 +202,15 @@ void decode_mfma_kernel(DecodeParams p)
     float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Every argument the prologue uses is read here, in one batch of scalar loads: left to itself
+    // the compiler fetches them where they are first needed, one cold trip to the argument buffer
+    // after the other along the prologue.
+#define VECINFER_PIN(x) asm volatile("" ::"s"(x))
+    VECINFER_PIN(p.q); VECINFER_PIN(p.lam); VECINFER_PIN(p.cb_k); VECINFER_PIN(p.cb_v);
+    VECINFER_PIN(p.k_idx); VECINFER_PIN(p.v_idx); VECINFER_PIN(p.seq_lens);
+    VECINFER_PIN(p.Hq); VECINFER_PIN(p.Hkv); VECINFER_PIN(p.G); VECINFER_PIN(p.N); VECINFER_PIN(p.n_cap);
+    VECINFER_PIN(p.S); VECINFER_PIN(p.k_new); VECINFER_PIN(p.v_new);
+#undef VECINFER_PIN
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
     // fastest: with 8 KV heads every XCD serves one head and its L2 fetches one codebook set
     // (128 KB) instead of all of them.
@@ -370,6 +379,23 @@ void decode_mfma_kernel(DecodeParams p)
 #ifdef VECINFER_PROLOGUE_STAMPS
     STAMPW(0);
 #endif
+    // ---- the wavefront's small input rows are requested first: loads come back in order, so the
+    // query transform below runs while the codebooks and the first code tiles are still on their way
+    // (wavefront hh < G: query head hh; the last two wavefronts: key and value of a fused new token)
+    // Every wavefront issues the same six loads (a wavefront without a query head, or a launch
+    // without a new token, reads a row that exists anyway and ignores it), and the fp16 rows are
+    // kept as raw bits until they are used: neither a branch nor a conversion makes the wavefront
+    // wait here for data it has only just requested.
+    auto raw16 = [](const __half *src) -> unsigned { return *reinterpret_cast<const unsigned short *>(src); };
+    auto widen = [](unsigned bits) { return (float)__builtin_bit_cast(_Float16, (unsigned short)bits); };
+    const bool q_role = wave < KG && wave < p.G;
+    const __half *const qsrc = p.q + ((size_t)b * p.Hq + g * p.G + (q_role ? wave : 0)) * kD;
+    const __half *const nsrc = has_new ? (wave == NW - 1 ? p.v_new : p.k_new) + bg * kD : qsrc;
+    const unsigned qh0 = raw16(qsrc + lane), qh1 = raw16(qsrc + (kD == 128 ? 64 : 0) + lane);
+    const float ql0 = p.lam[(size_t)g * kD + lane], ql1 = p.lam[(size_t)g * kD + (kD == 128 ? 64 : 0) + lane];
+    const unsigned nh0 = raw16(nsrc + lane), nh1 = raw16(nsrc + (kD == 128 ? 64 : 0) + lane);
+    const float nl0 = ql0, nl1 = ql1;
+    asm volatile("" ::: "memory");                 // keep these six loads ahead of the big ones below
     constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
     // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
     constexpr int kStageK = CBK_BYTES / 1024, kStageKPerWave = (kStageK + NW - 1) / NW;
@@ -393,6 +419,9 @@ void decode_mfma_kernel(DecodeParams p)
             if (kStageK % NW == 0 || it < kStageK)
                 kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
         }
+#ifdef VECINFER_PROLOGUE_STAMPS
+        STAMPW(1);
+#endif
         // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
         // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
         // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
@@ -426,8 +455,7 @@ void decode_mfma_kernel(DecodeParams p)
         if (kD == 128) sm_qt[wave * kD + 64 + lane] = 0.f;
     } else if (wave < KG && kD == 64) {
         // D = 64: one channel per lane, six butterfly stages across lanes
-        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
-        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
+        float x0 = widen(qh0) * ql0;
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) {
             const float o0 = __shfl_xor(x0, st);
@@ -435,9 +463,7 @@ void decode_mfma_kernel(DecodeParams p)
         }
         sm_qt[wave * kD + lane] = x0;
     } else if (wave < KG) {
-        const size_t qrow = ((size_t)b * p.Hq + g * p.G + wave) * kD;
-        float x0 = __half2float(p.q[qrow + lane]) * p.lam[(size_t)g * kD + lane];
-        float x1 = __half2float(p.q[qrow + 64 + lane]) * p.lam[(size_t)g * kD + 64 + lane];
+        float x0 = widen(qh0) * ql0, x1 = widen(qh1) * ql1;
         {
             const float a = x0 + x1, d = x0 - x1;
             x0 = a;
@@ -455,7 +481,7 @@ void decode_mfma_kernel(DecodeParams p)
     }
     // the new token's key and value (fused append): the last two wavefronts
     if (has_new && wave == NW - 2 && kD == 64) {
-        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
+        float x0 = widen(nh0) / nl0;
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) {
             const float o0 = __shfl_xor(x0, st);
@@ -466,8 +492,7 @@ void decode_mfma_kernel(DecodeParams p)
         // k~ = (k / lambda) H_D of the new token (Eq. 9), operation for operation what the
         // cache-fill kernels compute (true division, butterfly stages at distance 1, 2, .. 64,
         // then 1/sqrt D), so that the fused step writes the codes a separate append would
-        float x0 = __half2float(p.k_new[bg * kD + lane]) / p.lam[(size_t)g * kD + lane];
-        float x1 = __half2float(p.k_new[bg * kD + 64 + lane]) / p.lam[(size_t)g * kD + 64 + lane];
+        float x0 = widen(nh0) / nl0, x1 = widen(nh1) / nl1;
 #pragma unroll
         for (int st = 1; st < 64; st <<= 1) {
             const float o0 = __shfl_xor(x0, st), o1 = __shfl_xor(x1, st);
@@ -479,8 +504,8 @@ void decode_mfma_kernel(DecodeParams p)
         sm_new[lane] = (x0 + x1) * hs;
         sm_new[64 + lane] = (x0 - x1) * hs;
     } else if (has_new && wave == NW - 1) {
-        sm_new[kD + lane] = __half2float(p.v_new[bg * kD + lane]);
-        if (kD == 128) sm_new[kD + 64 + lane] = __half2float(p.v_new[bg * kD + 64 + lane]);
+        sm_new[kD + lane] = widen(nh0);
+        if (kD == 128) sm_new[kD + 64 + lane] = widen(nh1);
     }
     // second half of the codebook staging: registers -> LDS
 #pragma unroll
