@@ -1,0 +1,100 @@
+"""GPU parity on seeded random configurations: every supported head dim, GQA group, sub-vector
+dim and code width (8-bit per-sub-space tables, 10- / 12-bit shared tables), ragged batches, split
+counts, cache-fill lengths and offsets.  Through the C ABI, against the float64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_06175_amd import synth
+
+from helpers import assert_decode_close, assert_indices_match, gpu_decode, gpu_encode, oracle_view
+
+pytestmark = pytest.mark.gpu
+
+
+def _id(s):
+    return f"B{s.B}h{s.Hq}-{s.Hkv}N{s.N}k{s.d_k}b{s.b_k}v{s.d_v}b{s.b_v}"
+
+
+def _oracle_decode(shape, x, seq_lens=None):
+    y = oracle_view(shape, x)
+    return oracle.decode_attention(y["q"], y["lam"], y["cb_k"], y["cb_v"], y["k_idx"], y["v_idx"], seq_lens)
+
+
+# ------------------------------------------------------------------ seeded random sweep over the whole configuration space
+
+def _random_cases(n, seed):
+    """Seeded random configurations: head dim, GQA group, sub-vector dims, code widths, batch,
+    lengths (ragged, with tails that are not a multiple of any tile), split counts."""
+    g = synth.rng(seed)
+    sides = [(2, 8), (4, 8), (8, 8), (4, 10), (4, 12), (8, 10), (8, 12)]
+    cases = []
+    while len(cases) < n:
+        D = int(g.choice([64, 128]))
+        (dk, bk), (dv, bv) = sides[int(g.integers(len(sides)))], sides[int(g.integers(len(sides)))]
+        wide = bk != 8 or bv != 8
+        if wide and (D != 128 or dk < 4 or dv < 4):
+            continue
+        if dv == 8 and D != 128:
+            continue
+        G = int(g.choice([1, 2, 3, 4, 5, 8]))
+        Hkv = int(g.choice([1, 2, 3]))
+        B = int(g.choice([1, 2, 3]))
+        N = int(g.integers(1, 2500))
+        S = int(g.choice([0, 1, 2, 3, 7, 32]))
+        lens = [int(g.integers(0, N + 1)) for _ in range(B)] if g.random() < 0.5 else None
+        cases.append((synth.Shape(B, G * Hkv, Hkv, D, N, dk, dv, bk, bv), S, lens, int(g.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(48, seed=2024),
+                         ids=lambda c: f"{_id(c[0])}D{c[0].D}S{c[1]}{'r' if c[2] else ''}")
+def test_decode_random_configurations(case):
+    shape, S, lens, seed = case
+    x = synth.decode_inputs(shape, seed=seed)
+    got_o, got_l = gpu_decode(shape, x, seq_lens=lens, num_splits=S)
+    lens_a = np.full(shape.B, shape.N) if lens is None else np.asarray(lens)
+    keep = [b for b in range(shape.B) if lens_a[b] > 0]
+    for b in range(shape.B):
+        if lens_a[b] == 0:
+            assert (got_o[b] == 0).all() and np.isneginf(got_l[b]).all()
+    if keep:
+        sub = {k: (v[keep] if k in ("q", "k_idx", "v_idx") else v) for k, v in x.items()}
+        ref_o, ref_l = _oracle_decode(shape, sub, lens_a[keep])
+        assert_decode_close(got_o[keep], got_l[keep], ref_o, ref_l, what=f"random {_id(shape)} S={S}")
+
+
+def _random_encode_cases(n, seed):
+    g = synth.rng(seed)
+    sides = [(2, 8), (4, 8), (8, 8), (4, 10), (4, 12), (8, 10), (8, 12)]
+    cases = []
+    while len(cases) < n:
+        D = int(g.choice([64, 128]))
+        (dk, bk), (dv, bv) = sides[int(g.integers(len(sides)))], sides[int(g.integers(len(sides)))]
+        if (bk != 8 or bv != 8) and D != 128:
+            continue
+        T = int(g.choice([1, 2, 15, 16, 17, 63, 64, 65, 200, 333]))
+        cases.append((synth.Shape(int(g.choice([1, 2])), 2, int(g.choice([1, 2])), D, T, dk, dv, bk, bv),
+                      int(g.integers(0, 40)), int(g.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_encode_cases(24, seed=77),
+                         ids=lambda c: f"{_id(c[0])}D{c[0].D}T{c[0].N}p{c[1]}")
+def test_encode_random_configurations(case):
+    """Cache fill at random shapes, lengths around the kernels' switch-over points (16 / 17 tokens,
+    64-token tiles) and offsets: codes against the oracle, untouched rows stay untouched."""
+    shape, pos0, seed = case
+    shape = synth.Shape(shape.B, 2 * shape.Hkv, shape.Hkv, shape.D, shape.N, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
+    e = synth.encode_inputs(shape, seed=seed, n_outlier=3)
+    lam = synth.lognormal_lambda(synth.rng(seed + 1), shape.Hkv, shape.D)
+    cap = pos0 + shape.N + 5
+    got_k, got_v = gpu_encode(shape, k=e["k"], lam=lam, cb_k=e["cb_k"], v=e["v"], cb_v=e["cb_v"], pos0=pos0, n_cap=cap)
+    y = oracle_view(shape, {"cb_k": e["cb_k"], "cb_v": e["cb_v"]})
+    ref_k, gap_k = oracle.encode_keys(e["k"], lam, y["cb_k"], want_gap=True)
+    ref_v, gap_v = oracle.encode_values(e["v"], y["cb_v"], want_gap=True)
+    rows = slice(pos0, pos0 + shape.N)
+    assert_indices_match(oracle.unpack_codes(got_k[:, :, rows], shape.b_k, shape.Mk), ref_k, gap_k, "random keys")
+    assert_indices_match(oracle.unpack_codes(got_v[:, :, rows], shape.b_v, shape.Mv), ref_v, gap_v, "random values")
+    for got in (got_k, got_v):
+        assert (got[:, :, :pos0] == 0xEE).all() and (got[:, :, pos0 + shape.N:] == 0xEE).all()
