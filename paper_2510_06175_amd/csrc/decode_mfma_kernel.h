@@ -792,12 +792,15 @@ void decode_mfma_kernel(DecodeParams p)
     // Every stage pairs 4 H MFMAs with 4 H operand gathers.
     constexpr int kReadsK = 8 / DK;                   // ds_reads (and address ops) per gathered half8
     constexpr int kReadsV = 8 / DV;
-    // 4 H groups of: MF MFMAs, RD + XV vector-ALU ops, RD LDS reads
+    // H groups of: the address (and other vector-ALU) ops of four operand gathers, then four
+    // rounds of MFMAs, then the four gathers' LDS reads.  The address op (v_dot4) needs a few wait
+    // states before an LDS instruction may read its result: with the MFMAs in between they are
+    // free, and groups of four measured 1 us per call faster than alternating one by one.
 #define VI_GROUPS8(MF, RD, XV)                                                             \
-    _Pragma("unroll") for (int gi = 0; gi < 4 * H; ++gi) {                                    \
-        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);                                 \
-        __builtin_amdgcn_sched_group_barrier(0x002, (RD) + (XV), 0);                        \
-        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);                                 \
+    _Pragma("unroll") for (int gi = 0; gi < H; ++gi) {                                        \
+        __builtin_amdgcn_sched_group_barrier(0x002, 4 * ((RD) + (XV)), 0);                  \
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * (MF), 0);                           \
+        __builtin_amdgcn_sched_group_barrier(0x100, 4 * (RD), 0);                           \
     }
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
         half8 kb[4 * H], va[2 * NR], vb[2 * NR];
