@@ -251,7 +251,7 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
  * With VECINFER_VARIANT_MFMA (or AUTO when it covers cfg) nothing is launched in front of the
  * attention: its workgroups share out the sub-spaces of the new token while the code cache of
  * the older tokens streams, and the merge kernel joins the new token as one more partial.
- * Other configurations (the lookup-table variant; 10- or 12-bit codes) run the append kernels first.
+ * The lookup-table variant runs the append kernel first.
  *   k_new_f16, v_new_f16  fp16 [B, H_kv, 1, D]
  *   k_idx, v_idx          as in vecinfer_decode_attention, but written at row len_b - 1
  * Everything else, the workspace size and the errors as for vecinfer_decode_attention

@@ -200,7 +200,7 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     // the lookup-table kernel reads one byte per code
     if (!use_mfma && wide(cfg)) return VECINFER_EUNSUPPORTED;
     int rc = 0;
-    if (append && use_mfma && !wide(cfg)) {   // the attention launch encodes the new token itself
+    if (append && use_mfma) {           // the attention launch encodes the new token itself
         p.k_new = static_cast<const __half *>(k_new);
         p.v_new = static_cast<const __half *>(v_new);
         p.k_idx_w = const_cast<uint8_t *>(k_idx);

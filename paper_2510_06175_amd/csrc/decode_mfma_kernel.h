@@ -200,6 +200,7 @@ void decode_mfma_kernel(DecodeParams p)
     float *const sm_new = sm_qt + KG * kD;                                 // [2][D]: k~ and v of the new token
     float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][KG]: its score shares (log2 units)
     float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
+    unsigned long long *const sm_red = reinterpret_cast<unsigned long long *>(sm_nv + kD);   // [4][NW] (wide codes)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Every argument the prologue uses is read here, in one batch of scalar loads: left to itself
@@ -224,8 +225,14 @@ void decode_mfma_kernel(DecodeParams p)
     // this launch (below), so the tile loop covers the len - 1 older tokens only.  Workgroup s
     // encodes sub-spaces s, s + S, ... of the new token's key and value.
     const long long len = seq_len_of(p, b);
-    const bool fused = !WK && !WV && p.k_new != nullptr && len > 0;     // (wide codes: the host appends separately)
-    const bool has_new = fused && s < (MK > MV ? MK : MV);
+    const bool fused = p.k_new != nullptr && len > 0;
+    // items of the new token that are shared out: sub-spaces (8-bit codes), or groups of four
+    // sub-spaces whose codes fill a whole number of bytes (10- and 12-bit codes)
+    constexpr int ITEMS_K = WK ? MK / 4 : MK, ITEMS_V = WV ? MV / 4 : MV;
+    // workgroup s takes key items s, s + S, ...; value sub-spaces likewise, value groups (wide codes)
+    // starting behind the key items: group j goes to workgroup (j + ITEMS_K) % S
+    const int vgrp0 = (s + p.S - ITEMS_K % p.S) % p.S;        // first value group of this workgroup
+    const bool has_new = fused && (s < ITEMS_K || (WV ? vgrp0 < ITEMS_V : s < ITEMS_V));
     long long n0, n1;
     split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
 
@@ -646,10 +653,108 @@ void decode_mfma_kernel(DecodeParams p)
                 }
             }
         };
-        // key item i (sub-space s + i S) goes to wavefront i % NW, value item i to wavefront (i + 1) % NW
-        for (int i0 = wave_u; s + i0 * p.S < MK; i0 += 4 * NW) new_items(std::integral_constant<int, 0>{}, i0);
-        for (int i0 = (wave_u + NW - 1) % NW; s + i0 * p.S < MV; i0 += 4 * NW)
-            new_items(std::integral_constant<int, 1>{}, i0);
+        // Wide codes: an item is a group of four sub-spaces (4 b bits = whole bytes of the packed
+        // row) and the whole workgroup works on it: wavefront w scans centroids
+        // [w C / NW, (w + 1) C / NW) of the one table for the four sub-vectors at once, a lane taking
+        // every 64th of them in increasing order (strict "<": its lowest index wins); the
+        // wavefronts' (distance bits, index) keys meet in LDS and the smallest key wins, which is the
+        // lowest index at the minimum distance.  Same distance arithmetic as the append kernels.
+        auto wide_item = [&](auto kv_c, int grp) {
+            constexpr int kv = decltype(kv_c)::value;
+            constexpr int DS = kv == 0 ? DK : DV, BITS = kv == 0 ? BK : BV, MX = kv == 0 ? MK : MV;
+            constexpr int C = 1 << BITS, PER_WAVE = C / NW, EN = 2 * DS;
+            const unsigned char *const tab = kv == 0 ? sm_k : sm_v;
+            float x[4][DS];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < DS; ++jj) x[i][jj] = sm_new[kv * kD + (4 * grp + i) * DS + jj];
+            unsigned best[4], arg[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                best[i] = 0x7f800000u;                         // +inf
+                arg[i] = 0;
+            }
+#pragma unroll 2
+            for (int it = 0; it < PER_WAVE / 64; ++it) {
+                const unsigned c = (unsigned)(wave_u * PER_WAVE + it * 64 + lane);
+                _Float16 cen[DS];
+                __builtin_memcpy(cen, tab + c * EN, EN);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float dist = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < DS; ++jj) {
+                        const float tdiff = x[i][jj] - (float)cen[jj];
+                        dist = fmaf(tdiff, tdiff, dist);
+                    }
+                    const unsigned v = __float_as_uint(dist);  // a non-negative fp32 orders like its bit pattern
+                    if (v < best[i]) {
+                        best[i] = v;
+                        arg[i] = c;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned dmin = wave_umin(best[i]);
+                const unsigned code = wave_umin(best[i] == dmin ? arg[i] : 0xffffffffu);
+                if (lane == 0) sm_red[i * NW + wave_u] = ((unsigned long long)dmin << 32) | code;
+            }
+            __syncthreads();
+            if (wave_u == 0) {
+                // lanes 16 i .. 16 i + 15 look after sub-vector i of the group
+                const int i = lane >> 4, l16 = lane & 15, m = 4 * grp + i;
+                unsigned long long key = sm_red[i * NW];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) key = sm_red[i * NW + w] < key ? sm_red[i * NW + w] : key;
+                const unsigned code = (unsigned)key;
+                _Float16 win[DS];
+                __builtin_memcpy(win, tab + code * EN, EN);
+                if (kv == 0) {
+                    if (l16 < p.G) {
+                        float sc = 0.f;
+#pragma unroll
+                        for (int jj = 0; jj < DS; ++jj)
+                            sc = fmaf(sm_qt[l16 * kD + m * DS + jj] * fold, (float)win[jj], sc);
+                        p.new_sc[((size_t)bg * MK + m) * p.G + l16] = sc;
+                        sm_nsc[m * KG + l16] = sc;
+                    }
+                } else {
+                    float mine = (float)win[0];
+#pragma unroll
+                    for (int jj = 1; jj < DS; ++jj) mine = l16 == jj ? (float)win[jj] : mine;
+                    if (l16 < DS) {
+                        p.new_v[(size_t)bg * kD + m * DS + l16] = mine;
+                        sm_nv[m * DS + l16] = mine;
+                    }
+                }
+                // the group's four codes, end to end, are bytes [grp 4 b / 8, (grp + 1) 4 b / 8) of the row
+                const unsigned c0 = (unsigned)__shfl(code, 0), c1 = (unsigned)__shfl(code, 16);
+                const unsigned c2 = (unsigned)__shfl(code, 32), c3 = (unsigned)__shfl(code, 48);
+                const unsigned long long bits = (unsigned long long)c0 | ((unsigned long long)c1 << BITS) |
+                                                ((unsigned long long)c2 << (2 * BITS)) |
+                                                ((unsigned long long)c3 << (3 * BITS));
+                constexpr int GB = 4 * BITS / 8;
+                uint8_t *const row = (kv == 0 ? p.k_idx_w : p.v_idx_w) + ((size_t)bg * p.n_cap + pos) * (MX * BITS / 8);
+                if (lane < GB) row[grp * GB + lane] = (uint8_t)(bits >> (8 * lane));
+            }
+            __syncthreads();                                   // sm_red is free for the next item
+        };
+        if constexpr (WK) {
+            for (int grp = s; grp < ITEMS_K; grp += p.S) wide_item(std::integral_constant<int, 0>{}, grp);
+        } else {
+            // key item i (sub-space s + i S) goes to wavefront i % NW, value item i to wavefront (i + 1) % NW
+            for (int i0 = wave_u; s + i0 * p.S < MK; i0 += 4 * NW) new_items(std::integral_constant<int, 0>{}, i0);
+        }
+        if constexpr (WV) {
+            // value groups start where the key items end, so that other workgroups take them
+            for (int grp = vgrp0; grp < ITEMS_V; grp += p.S)
+                wide_item(std::integral_constant<int, 1>{}, grp);
+        } else {
+            for (int i0 = (wave_u + NW - 1) % NW; s + i0 * p.S < MV; i0 += 4 * NW)
+                new_items(std::integral_constant<int, 1>{}, i0);
+        }
     }
 
     STAMP(2);
@@ -1052,7 +1157,7 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
     constexpr size_t cbk = BK > 8 ? ((size_t)1 << BK) * DK * 2 : (size_t)kCentroids * kD * 2;
     constexpr size_t cbv = BV > 8 ? ((size_t)1 << BV) * DV * 2 : (size_t)kCentroids * kD * 2;
     // the tables, q~ and the new token's scratch during the tile loop; the wavefronts' partials after it
-    constexpr size_t loop_bytes = cbk + cbv + sizeof(float) * ((KG + 3) * kD + (kD / DK) * KG) + 16;
+    constexpr size_t loop_bytes = cbk + cbv + sizeof(float) * ((KG + 3) * kD + (kD / DK) * KG) + 8 * 4 * NW + 16;
     constexpr size_t merge_bytes = sizeof(float) * (NW * KG * kD + 2 * NW * KG);
     constexpr size_t smem = loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
     // once per process and instantiation (function-local static: initialised thread-safely)

@@ -264,3 +264,49 @@ def test_kmeans_step_wide(shape, kind):
         np.testing.assert_allclose(cb_out[g].astype(np.float64), ref_cb[0], rtol=1.5e-3, atol=1e-6)
         empty = ref_counts[0] == 0
         np.testing.assert_array_equal(cb_out[g][empty], cb[g][empty])
+
+
+STEP_WIDE = [
+    synth.Shape(2, 8, 2, 128, 1200, 8, 8, 12, 12),
+    synth.Shape(1, 8, 2, 128, 2100, 4, 8, 10, 12),
+    synth.Shape(2, 4, 1, 128, 700, 4, 4, 12, 12),
+    synth.Shape(1, 16, 2, 128, 900, 8, 8, 10, 10),       # G = 8
+    synth.Shape(2, 8, 2, 128, 800, 8, 8, 12, 8),         # keys wide, values 8-bit
+    synth.Shape(1, 6, 2, 128, 650, 4, 8, 8, 12),         # keys 8-bit, values wide, G = 3
+    synth.Shape(1, 8, 2, 128, 1, 8, 8, 12, 12),          # the new token is the only one
+]
+
+
+@pytest.mark.parametrize("shape", STEP_WIDE, ids=_id)
+@pytest.mark.parametrize("splits", [1, 5, 64, 0])
+def test_decode_step_wide_fused_equals_append_then_attend(shape, splits):
+    """The whole step with wide codes encodes the new token inside the attention launch: the
+    packed rows must be bit-identical to what vecinfer_append_kv writes, and the output equal to
+    vecinfer_decode_attention on the result (and to the oracle)."""
+    x = synth.decode_inputs(shape, seed=shape.N + 5, n_cap=shape.N + 3)
+    g = synth.rng(shape.N + 6)
+    k_new, _ = synth.keys_with_outlier_channels(g, shape.B, shape.Hkv, 1, shape.D, 3)
+    v_new = synth.values(g, shape.B, shape.Hkv, 1, shape.D)
+    lens = np.array([shape.N] + [max(1, shape.N // 3)] * (shape.B - 1))
+    sl = torch.as_tensor(lens, dtype=torch.int32).cuda()
+    cfg = cfg_of(shape)
+    t = {k: dev(v) for k, v in x.items()}
+    ws = vb.new_workspace(cfg, shape.B, shape.N, splits)
+    out = torch.full((shape.B, shape.Hq, shape.D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((shape.B, shape.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    vb.vecinfer_decode_step(cfg, t["q"], dev(k_new), dev(v_new), t["lam"], t["cb_k"], t["cb_v"], t["k_idx"],
+                            t["v_idx"], ws, out, lse=lse, seq_lens=sl, N=shape.N, num_splits=splits)
+    torch.cuda.synchronize()
+    # the same append by the append kernels, one sequence at a time (each has its own position)
+    k2, v2 = dev(x["k_idx"]), dev(x["v_idx"])
+    for b in range(shape.B):
+        vb.vecinfer_append_kv(cfg, dev(k_new[b:b + 1]), dev(v_new[b:b + 1]), t["lam"], t["cb_k"], t["cb_v"],
+                              k2[b:b + 1], v2[b:b + 1], pos0=int(lens[b]) - 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t["k_idx"].cpu().numpy(), k2.cpu().numpy())
+    np.testing.assert_array_equal(t["v_idx"].cpu().numpy(), v2.cpu().numpy())
+    got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+    ref_gpu = gpu_decode(shape, dict(x, k_idx=k2, v_idx=v2), seq_lens=lens, N=shape.N, num_splits=splits)
+    assert_decode_close(*got, *ref_gpu, what="fused wide step vs append + attend")
+    ref = _oracle_decode(shape, dict(x, k_idx=k2.cpu().numpy(), v_idx=v2.cpu().numpy()), lens)
+    assert_decode_close(*got, *ref, what="fused wide step vs oracle")
