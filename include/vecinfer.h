@@ -78,7 +78,10 @@ enum {
                                     cores for both q.K and P.V; D in {64,128}, d_k and d_v
                                     in {2,4,8} (d_v = 8 only with D = 128), any G the cfg
                                     allows; the only variant for 10- / 12-bit codes, which
-                                    need d = 4 or 8 on BOTH sides                            */
+                                    need d = 4 or 8 on BOTH sides.  Code rows are addressed
+                                    with 32-bit byte offsets: N * D / 2 < 2^31 (N < 33 554 432
+                                    tokens at D = 128); longer caches fall to the lookup-table
+                                    variant under AUTO                                       */
 };
 
 typedef struct vecinfer_cfg {

@@ -1,8 +1,8 @@
 // Kernel template of the matrix-core decode attention; included by the translation units that
 // instantiate it (8-bit codes: decode_mfma.hip; 10- and 12-bit codes: decode_mfma_wide.hip).
 //
-// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1, 2, 4 or 8 query heads
-// per KV head (8: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 8,
+// Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1 .. 8 query heads
+// per KV head (more than 4: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 8,
 // 4 or 2, chosen separately for keys and values (M = D / d = 8 .. 64 sub-spaces), 8-bit codes
 // with one table per sub-space, or (D = 128, d = 8 or 4) 10- / 12-bit codes packed bit by bit,
 // with one table of 2^b centroids shared by the sub-spaces of the head (the codebook of Sec. 2.2

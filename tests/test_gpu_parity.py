@@ -610,3 +610,53 @@ def test_calibrate_lambda(shape):
         (got_k,) = gpu_encode(shape, k=k, lam=got, cb_k=cb)
         ref_k, gap = oracle.encode_keys(k, got, cb, want_gap=True)
         assert_indices_match(got_k, ref_k, gap, "encode with calibrated lambda")
+
+
+# ------------------------------------------------------------------ the longest cache the matrix-core path takes
+
+def test_decode_at_the_maximum_length():
+    """N just under the 32-bit row-offset limit (N * D / 2 < 2^31: 33.5 M tokens at D = 128, 1 GiB of
+    codes per side).  The bulk of the cache is one repeated token (every code 7), the last 3000
+    tokens are random: the oracle attends to the tail, the bulk has the closed form
+    L = s_0 + ln N_0, o = its one value row, and the two are joined by the log-sum-exp merge.
+    The query is scaled so that bulk and tail weigh about the same: a wrong offset anywhere near
+    the end of the buffers, or a lost stretch of the bulk, changes the result."""
+    shape = synth.Shape(1, 1, 1, 128, (1 << 25) - 5, 4, 4)
+    tail = 3000
+    x = synth.decode_inputs(synth.Shape(1, 1, 1, 128, tail, 4, 4), seed=99)
+    N0 = shape.N - tail
+    one = np.full((1, 1, 1, 32), 7, dtype=np.uint8)
+
+    def parts(scale):
+        q = (x["q"].astype(np.float32) * scale).astype(np.float16)
+        t_o, t_l = oracle.decode_attention(q, x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+        b_o, b_l = oracle.decode_attention(q, x["lam"], x["cb_k"], x["cb_v"], one, one)       # a single token
+        return q, t_o, t_l, b_o, b_l + np.log(N0)
+
+    lo, hi = 0.0, 16.0                         # tail log-weight minus bulk log-weight grows with the scale
+    for _ in range(30):
+        mid = 0.5 * (lo + hi)
+        _, _, t_l, _, b_l = parts(mid)
+        lo, hi = (mid, hi) if t_l[0, 0] < b_l[0, 0] else (lo, mid)
+    q, t_o, t_l, b_o, b_l = parts(hi)
+    ref_o, ref_l = oracle.merge_splits(np.stack([b_o[0, 0], t_o[0, 0]]), np.array([b_l[0, 0], t_l[0, 0]]))
+    share = np.exp(t_l[0, 0] - ref_l)          # weight of the tail in the softmax
+    assert 0.2 < share < 0.8, share
+
+    k_idx = torch.full((1, 1, shape.N, 32), 7, dtype=torch.uint8, device="cuda")
+    v_idx = torch.full((1, 1, shape.N, 32), 7, dtype=torch.uint8, device="cuda")
+    k_idx[:, :, N0:] = dev(x["k_idx"])
+    v_idx[:, :, N0:] = dev(x["v_idx"])
+    got_o, got_l = gpu_decode(shape, dict(x, q=q, k_idx=k_idx, v_idx=v_idx), variant=vb.VARIANT_MFMA)
+    assert_decode_close(got_o, got_l, ref_o[None, None], np.array([[ref_l]]), what="N = 2^25 - 5")
+    del k_idx, v_idx
+    # one token more than the limit is refused by this variant, not mis-addressed
+    cfg = cfg_of(shape)
+    n_big = 1 << 25
+    ws = vb.new_workspace(cfg, 1, n_big)
+    out = torch.empty((1, 1, 128), dtype=torch.float16, device="cuda")
+    kb = torch.empty((1, 1, n_big, 32), dtype=torch.uint8, device="cuda")
+    with pytest.raises(vb.VecInferError) as e:
+        vb.vecinfer_decode_attention(cfg, dev(q), dev(x["lam"]), dev(x["cb_k"]), dev(x["cb_v"]), kb, kb, ws, out,
+                                     variant=vb.VARIANT_MFMA)
+    assert e.value.code == vb.EUNSUPPORTED
