@@ -62,6 +62,20 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
     __shared__ float ns_s[MODE == kNewToken ? kMaxM * HB : 1];      // [m][hh] score shares of the new token
     __shared__ float nv_s[MODE == kNewToken ? D : 1];
 
+    // Every argument the kernel uses is read here, in one batch of scalar loads (left to itself the
+    // compiler fetches them where they are first needed: several cold trips to the argument buffer
+    // in a kernel whose whole run is a few of them long).
+#define VECINFER_PIN(x) asm volatile("" ::"s"(x))
+    VECINFER_PIN(p.part_o); VECINFER_PIN(p.part_m); VECINFER_PIN(p.part_l); VECINFER_PIN(p.out); VECINFER_PIN(p.lse);
+    VECINFER_PIN(p.S); VECINFER_PIN(p.G); VECINFER_PIN(p.Hq); VECINFER_PIN(p.Hkv);
+    if (MODE == kWindow) {
+        VECINFER_PIN(p.q); VECINFER_PIN(p.k_res); VECINFER_PIN(p.v_res); VECINFER_PIN(p.res_lens);
+        VECINFER_PIN(p.R); VECINFER_PIN(p.r_cap);
+    }
+    if (MODE == kNewToken) {
+        VECINFER_PIN(p.new_sc); VECINFER_PIN(p.new_v); VECINFER_PIN(p.Mk); VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N);
+    }
+#undef VECINFER_PIN
     const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int w = t >> 6, lane = t & 63;
     const int G = p.G, GD = G * D, S = p.S;
