@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--workload", default="196k-b2d4",
                     choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-kd2vd4", "196k-d8b12",
                              "196k-d4b12", "196k-kd4b10-vd8b12", "196k-kd8b12-vd8b8"])
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the workload's cache length N (the 32k .. 196k ladder); a side measurement")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
@@ -76,6 +78,8 @@ def main() -> int:
              "196k-d4b12": synth.Shape(1, 32, 8, 128, 196608, 4, 4, 12, 12),
              "196k-kd4b10-vd8b12": synth.Shape(1, 32, 8, 128, 196608, 4, 8, 10, 12),
              "196k-kd8b12-vd8b8": synth.Shape(1, 32, 8, 128, 196608, 8, 8, 12, 8)}[args.workload]
+    if args.tokens:
+        shape = synth.Shape(shape.B, shape.Hq, shape.Hkv, shape.D, args.tokens, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
     cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
     variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
     idx_bytes = shape.index_bytes()
@@ -169,6 +173,22 @@ def main() -> int:
     torch.cuda.synchronize()
     kern_ms = sorted(a.elapsed_time(b) for a, b in pairs)
 
+    # ---- what a plain read reaches on this machine: vecinfer_read_probe (a kernel that only loads) over
+    # one 1 GiB buffer, so that neither launch costs nor the Infinity Cache flatter or hurt it
+    big = torch.empty(2**30, dtype=torch.uint8, device="cuda").random_(0, 256)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        vb.vecinfer_read_probe(big, sink)
+    torch.cuda.synchronize()
+    probe_n = 20
+    e0.record()
+    for _ in range(probe_n):
+        vb.vecinfer_read_probe(big, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_gbs = big.numel() * probe_n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del big
+
     rec = {
         "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True,
@@ -189,7 +209,9 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant != vb.VARIANT_LUT else None,
                      "algorithmic_bytes": idx_bytes, "kernel_us_avg": round(kern_avg_ms * 1e3, 3),
                      "event_pair_us_median": round(kern_ms[len(kern_ms) // 2] * 1e3, 3),
-                     "event_pair_us_min": round(kern_ms[0] * 1e3, 3)},
+                     "event_pair_us_min": round(kern_ms[0] * 1e3, 3),
+                     "plain_read_probe_gbs": round(probe_gbs, 1),
+                     "frac_of_plain_read_probe": round(achieved / probe_gbs, 4)},
     }
 
     # ---- the oracle (as it stands) on the host cores: the same attention step on layer cache 0,

@@ -276,6 +276,16 @@ int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void 
 size_t vecinfer_index_row_bytes(const vecinfer_cfg *cfg, int32_t keys);
 size_t vecinfer_codebook_elems(const vecinfer_cfg *cfg, int32_t keys);
 
+/*
+ * Measurement aid: a plain streaming read of `bytes` bytes at `src` (16-byte loads from every CU,
+ * nothing else), i.e. the read rate HBM delivers on this device to a kernel with no other work.
+ * Benchmarks print it beside the attention kernel's rate (the roofline's measured counterpart of
+ * the published peak).  The result of the reads is discarded; `sink` (device, 4 bytes) is written
+ * at most in the unlikely case of one particular checksum.
+ * Errors: EINVAL for null or misaligned pointers (src 16, sink 4 bytes) or bytes < 16.
+ */
+int vecinfer_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 /* Human-readable text for a return code (static storage). */
 const char *vecinfer_strerror(int code);
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
     "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
-    "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda",
+    "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda", "vecinfer_read_probe",
     "vecinfer_strerror", "vecinfer_version",
 ]
 
@@ -110,6 +110,8 @@ def lib() -> C.CDLL:
         L.vecinfer_kmeans_step.restype = C.c_int
         L.vecinfer_calibrate_lambda.argtypes = [cfgp, vp, vp, i32, i64, vp]
         L.vecinfer_calibrate_lambda.restype = C.c_int
+        L.vecinfer_read_probe.argtypes = [vp, sz, vp, vp]
+        L.vecinfer_read_probe.restype = C.c_int
         L.vecinfer_index_row_bytes.argtypes = [cfgp, i32]
         L.vecinfer_index_row_bytes.restype = sz
         L.vecinfer_codebook_elems.argtypes = [cfgp, i32]
@@ -291,6 +293,14 @@ def vecinfer_calibrate_lambda(cfg: Config, k_f16, lam, stream=None) -> None:
     _check(lib().vecinfer_calibrate_lambda(
         C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"), B, T, _stream(stream)))
+
+
+def vecinfer_read_probe(src, sink, stream=None) -> None:
+    """Plain streaming read of the whole tensor `src` (measurement aid); `sink`: any device tensor of >= 4 bytes."""
+    if not src.is_cuda or not sink.is_cuda or not src.is_contiguous():
+        raise TypeError("read probe: expected contiguous device tensors")
+    _check(lib().vecinfer_read_probe(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                     _stream(stream)))
 
 
 def vecinfer_kmeans_workspace_bytes(cfg: Config, keys: bool) -> int:

@@ -352,6 +352,13 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
                          workspace_bytes, out_f16, lse, stream);
 }
 
+int vecinfer_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16) return VECINFER_EINVAL;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return VECINFER_EINVAL;
+    return launch_status(launch_read_probe(src, bytes, sink, num_cus(), static_cast<hipStream_t>(stream)));
+}
+
 size_t vecinfer_index_row_bytes(const vecinfer_cfg *cfg, int32_t keys)
 {
     if (!cfg_ok(cfg)) return 0;

@@ -195,6 +195,7 @@ int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_cou
 int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
                            int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream);
 int launch_encode(const EncodeParams &p, hipStream_t stream);
+int launch_read_probe(const void *src, size_t bytes, unsigned *sink, int num_cus, hipStream_t stream);
 int launch_calibrate_lambda(const __half *k, float *lam, int B, int Hkv, int D, long long T, float floor_value,
                             hipStream_t stream);
 int launch_append(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream);

@@ -159,6 +159,14 @@ def test_kmeans_argument_errors():
     assert vb.vecinfer_kmeans_workspace_bytes(vb.Config(96, 32, 8, 4, 4), True) == 0
 
 
+def test_read_probe_argument_errors():
+    probe = lambda src=FAKE, n=1 << 20, sink=FAKE: vb.lib().vecinfer_read_probe(src, n, sink, None)
+    assert probe(src=None) == vb.EINVAL
+    assert probe(sink=None) == vb.EINVAL
+    assert probe(n=8) == vb.EINVAL
+    assert probe(src=FAKE + 4) == vb.EINVAL
+
+
 def test_calibrate_lambda_argument_errors():
     def cal(cfg=CFG, k=FAKE, lam=FAKE, B=1, T=64):
         return vb.lib().vecinfer_calibrate_lambda(C.byref(cfg.c()), k, lam, B, T, None)

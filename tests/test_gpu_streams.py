@@ -96,3 +96,16 @@ def test_decode_step_in_a_hip_graph(shape):
             ref = oracle.decode_attention(y["q"], y["lam"], y["cb_k"], y["cb_v"], y["k_idx"], y["v_idx"],
                                           np.full(shape.B, shape.N + 4))
             assert_decode_close(*got, *ref, what="graph replay vs oracle")
+
+
+def test_read_probe_reads_and_writes_nothing():
+    """The measurement aid: a plain read of a buffer whose size is not a multiple of anything nice;
+    the sink keeps its value and the source is untouched."""
+    src = torch.arange(3_000_017, dtype=torch.int32, device="cuda")
+    before = src.clone()
+    sink = torch.full((1,), 1234, dtype=torch.int32, device="cuda")
+    view = src.view(torch.uint8)[: (src.numel() * 4) // 16 * 16 - 16]
+    vb.vecinfer_read_probe(view, sink)
+    vb.vecinfer_read_probe(src.view(torch.uint8)[:64], sink)        # fewer 16-byte pieces than workgroups
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 1234 and torch.equal(src, before)
