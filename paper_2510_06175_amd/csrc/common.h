@@ -67,7 +67,10 @@ __device__ __forceinline__ long long seq_len_of(const DecodeParams &p, int b)
 {
     long long len = p.N;
     if (p.seq_lens) {
-        long long v = p.seq_lens[b];
+        // b is the same for the whole workgroup: read through the constant address space, i.e. by a
+        // scalar load, which does not queue behind the wavefront's vector loads
+        typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+        long long v = ((const_i32_ptr)(uintptr_t)p.seq_lens)[b];
         len = v < 0 ? 0 : (v > p.N ? p.N : v);
     }
     return len;

@@ -41,9 +41,14 @@ __device__ unsigned long long *g_phase_buf = nullptr;
 #define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); } while (0)
 // per-wavefront stamp: slot 8 * (j + 1) + wave, j in {0, 1, 2}
 #define STAMPW(j) do { if (g_phase_buf && (threadIdx.x & 63) == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 * ((j) + 1) + (threadIdx.x >> 6)] = wall_clock64(); } while (0)
+// time of entry, taken before the first memory access and written out with the last stamp (slot 6)
+#define STAMP_ENTRY() const unsigned long long t_entry = wall_clock64()
+#define STAMP_ENTRY_OUT() do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 6] = t_entry; } while (0)
 #else
 #define STAMP(i)
 #define STAMPW(j)
+#define STAMP_ENTRY()
+#define STAMP_ENTRY_OUT()
 #endif
 
 namespace {
@@ -146,7 +151,8 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
 // codes packed end to end in the token's row, one table of 2^b centroids for all sub-spaces.
 template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
-void decode_mfma_kernel(DecodeParams p)
+void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half *cb_k_arg, const __half *cb_v_arg,
+                        const uint8_t *k_idx_arg, const uint8_t *v_idx_arg, unsigned hkv_g_arg, int S_, DecodeParams p)
 {
     constexpr int KG = kG * HG;                        // head slots of the workgroup
     static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DV == 8 || DV == 4 || DV == 2) &&
@@ -202,24 +208,85 @@ void decode_mfma_kernel(DecodeParams p)
     float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
     unsigned long long *const sm_red = reinterpret_cast<unsigned long long *>(sm_nv + kD);   // [4][NW] (wide codes)
 
+    STAMP_ENTRY();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // Every argument the prologue uses is read here, in one batch of scalar loads: left to itself
-    // the compiler fetches them where they are first needed, one cold trip to the argument buffer
-    // after the other along the prologue.
-#define VECINFER_PIN(x) asm volatile("" ::"s"(x))
-    VECINFER_PIN(p.q); VECINFER_PIN(p.lam); VECINFER_PIN(p.cb_k); VECINFER_PIN(p.cb_v);
-    VECINFER_PIN(p.k_idx); VECINFER_PIN(p.v_idx); VECINFER_PIN(p.seq_lens);
-    VECINFER_PIN(p.Hq); VECINFER_PIN(p.Hkv); VECINFER_PIN(p.G); VECINFER_PIN(p.N); VECINFER_PIN(p.n_cap);
-    VECINFER_PIN(p.S); VECINFER_PIN(p.k_new); VECINFER_PIN(p.v_new);
-#undef VECINFER_PIN
+    const int Hkv_ = (int)(hkv_g_arg & 0xffffffu), G_ = (int)(hkv_g_arg >> 24);   // = p.Hkv, p.G
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
     // fastest: with 8 KV heads every XCD serves one head and its L2 fetches one codebook set
-    // (128 KB) instead of all of them.
-    const int lin = blockIdx.x + gridDim.x * blockIdx.y;
-    const int g = lin % p.Hkv, s = lin / p.Hkv, b = blockIdx.z;
+    // (128 KB) instead of all of them.  (The grid is (S, Hkv, B).)
+    const int lin = blockIdx.x + S_ * blockIdx.y;
+    const int g = lin % Hkv_, s = lin / Hkv_, b = blockIdx.z;
     const int col = lane & 15;       // MFMA row (A) / column (B, D) index of this lane
     const int kg = lane >> 4;        // k-group (A, B) / row group (D) of this lane
-    const size_t bg = (size_t)b * p.Hkv + g;
+    const size_t bg = (size_t)b * Hkv_ + g;
+    STAMP(0);
+#ifdef VECINFER_PROLOGUE_STAMPS
+    STAMPW(0);
+#endif
+    // ---- The kernel's first memory requests use nothing but the leading arguments, which the
+    // command processor can place in scalar registers before the wavefront starts (kernel-argument
+    // preloading); everything else of `p` takes a trip to the argument buffer, which now runs
+    // beside these requests instead of ahead of them.
+    // The wavefront's small input rows are requested first: loads come back in order, so the
+    // query transform below runs while the codebooks and the first code tiles are still on their way
+    // (wavefront hh < G: query head hh).  Every wavefront issues the same loads (a wavefront
+    // without a query head reads a row that exists anyway and ignores it), and the fp16 rows are
+    // kept as raw bits until they are used: neither a branch nor a conversion makes the wavefront
+    // wait here for data it has only just requested.
+    auto raw16 = [](const __half *src) -> unsigned { return *reinterpret_cast<const unsigned short *>(src); };
+    auto widen = [](unsigned bits) { return (float)__builtin_bit_cast(_Float16, (unsigned short)bits); };
+    const bool q_role = wave < KG && wave < G_;
+    const __half *const qsrc = q_arg + (((size_t)b * Hkv_ + g) * G_ + (q_role ? wave : 0)) * kD;
+    const unsigned qh0 = raw16(qsrc + lane), qh1 = raw16(qsrc + (kD == 128 ? 64 : 0) + lane);
+    const float ql0 = lam_arg[(size_t)g * kD + lane], ql1 = lam_arg[(size_t)g * kD + (kD == 128 ? 64 : 0) + lane];
+    asm volatile("" ::: "memory");                 // keep these loads ahead of the big ones below
+    constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
+    // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
+    constexpr int kStageK = CBK_BYTES / 1024, kStageKPerWave = (kStageK + NW - 1) / NW;
+    constexpr int kStageV = CBV_BYTES / 1024, kStageVPerWave = (kStageV + NW - 1) / NW;
+    static_assert(WV || NROUND_V * (kCentroids / (4 * CPL)) == kStageV, "value items: (code group, r)");
+    const int vq = lane >> 4, vcol = lane & 15;
+    uintx4 vreg[kStageVPerWave];
+    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise), through
+    // registers: all 16 loads of a wavefront (16 KB) are issued back to back right behind the query
+    // rows; the LDS writes come after the q~ section.
+    // (Direct global->LDS loads measured slower here: a wavefront got through its 8 of them at
+    // about one L2 latency each.)
+    uintx4 kreg[kStageKPerWave];
+    {
+        const unsigned char *srck = reinterpret_cast<const unsigned char *>(cb_k_arg) + (size_t)g * CBK_BYTES;
+        const unsigned char *srcv = reinterpret_cast<const unsigned char *>(cb_v_arg) + (size_t)g * CBV_BYTES;
+        // keys keep the [m][code] order (a shared table its one order): item = 1 KB chunk, 16 bytes per lane
+#pragma unroll
+        for (int j = 0; j < kStageKPerWave; ++j) {
+            const int it = wave + NW * j;
+            if (kStageK % NW == 0 || it < kStageK)
+                kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
+        }
+#ifdef VECINFER_PROLOGUE_STAMPS
+        STAMPW(1);
+#endif
+        // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
+        // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
+        // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
+        // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
+        // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
+        // group it / NROUND_V.
+#pragma unroll
+        for (int j = 0; j < kStageVPerWave; ++j) {
+            const int it = wave + NW * j;
+            const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
+            if (kStageV % NW == 0 || it < kStageV)
+                vreg[j] = WV ? *reinterpret_cast<const uintx4 *>(srcv + it * 1024 + lane * 16)   // shared table: as is
+                             : *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
+        }
+    }
+    // Every other argument the prologue uses is read here, in one batch of scalar loads: left to
+    // itself the compiler fetches them where they are first needed, one cold trip to the argument
+    // buffer after the other along the prologue.
+#define VECINFER_PIN(x) asm volatile("" ::"s"(x))
+    VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N); VECINFER_PIN(p.n_cap); VECINFER_PIN(p.k_new); VECINFER_PIN(p.v_new);
+#undef VECINFER_PIN
 
     // With a fused append the new token is the sequence's last one: its codes are produced in
     // this launch (below), so the tile loop covers the len - 1 older tokens only.  Workgroup s
@@ -231,16 +298,16 @@ void decode_mfma_kernel(DecodeParams p)
     constexpr int ITEMS_K = WK ? MK / 4 : MK, ITEMS_V = WV ? MV / 4 : MV;
     // workgroup s takes key items s, s + S, ...; value sub-spaces likewise, value groups (wide codes)
     // starting behind the key items: group j goes to workgroup (j + ITEMS_K) % S
-    const int vgrp0 = (s + p.S - ITEMS_K % p.S) % p.S;        // first value group of this workgroup
+    const int vgrp0 = (s + S_ - ITEMS_K % S_) % S_;        // first value group of this workgroup
     const bool has_new = fused && (s < ITEMS_K || (WV ? vgrp0 < ITEMS_V : s < ITEMS_V));
     long long n0, n1;
-    split_range(fused ? len - 1 : len, p.S, s, kTile, n0, n1);
+    split_range(fused ? len - 1 : len, S_, s, kTile, n0, n1);
 
     if (n0 >= n1 && !has_new) {                        // empty split: neutral partial
-        for (int e = tid; e < p.G * kD; e += BLOCK) p.part_o[(bg * p.S + s) * p.G * kD + e] = 0.f;
-        if (tid < p.G) {
-            p.part_m[(bg * p.S + s) * p.G + tid] = -INFINITY;
-            p.part_l[(bg * p.S + s) * p.G + tid] = 0.f;
+        for (int e = tid; e < G_ * kD; e += BLOCK) p.part_o[(bg * S_ + s) * G_ * kD + e] = 0.f;
+        if (tid < G_) {
+            p.part_m[(bg * S_ + s) * G_ + tid] = -INFINITY;
+            p.part_l[(bg * S_ + s) * G_ + tid] = 0.f;
         }
         finish_split<BLOCK>(p, b, g);
         return;
@@ -271,8 +338,8 @@ void decode_mfma_kernel(DecodeParams p)
     const unsigned pos_k = (unsigned)(kg * (MK / 4) * BK) & 31u;
     const unsigned pos_v = ((unsigned)((col >> 2) * (MV / 4) * BV) & 31u) + (unsigned)((col & 3) * NROUND_V * BV);
 
-    const uint8_t *krow = p.k_idx + bg * p.n_cap * ROWB_K;
-    const uint8_t *vrow = p.v_idx + bg * p.n_cap * ROWB_V;
+    const uint8_t *krow = k_idx_arg + bg * p.n_cap * ROWB_K;
+    const uint8_t *vrow = v_idx_arg + bg * p.n_cap * ROWB_V;
     const long long last = n1 - 1;
 
     // token owned by A-row i of sub-tile st: base + 16 st + 4 (i % 4) + i / 4, so that D-register v
@@ -382,68 +449,12 @@ void decode_mfma_kernel(DecodeParams p)
     };
     Codes ca, cb;
 
-    STAMP(0);
-#ifdef VECINFER_PROLOGUE_STAMPS
-    STAMPW(0);
-#endif
-    // ---- the wavefront's small input rows are requested first: loads come back in order, so the
-    // query transform below runs while the codebooks and the first code tiles are still on their way
-    // (wavefront hh < G: query head hh; the last two wavefronts: key and value of a fused new token)
-    // Every wavefront issues the same six loads (a wavefront without a query head, or a launch
-    // without a new token, reads a row that exists anyway and ignores it), and the fp16 rows are
-    // kept as raw bits until they are used: neither a branch nor a conversion makes the wavefront
-    // wait here for data it has only just requested.
-    auto raw16 = [](const __half *src) -> unsigned { return *reinterpret_cast<const unsigned short *>(src); };
-    auto widen = [](unsigned bits) { return (float)__builtin_bit_cast(_Float16, (unsigned short)bits); };
-    const bool q_role = wave < KG && wave < p.G;
-    const __half *const qsrc = p.q + ((size_t)b * p.Hq + g * p.G + (q_role ? wave : 0)) * kD;
+    // the last two wavefronts: key and value row of a fused new token (any other wavefront, or a
+    // launch without one, re-reads its query row and ignores it)
     const __half *const nsrc = has_new ? (wave == NW - 1 ? p.v_new : p.k_new) + bg * kD : qsrc;
-    const unsigned qh0 = raw16(qsrc + lane), qh1 = raw16(qsrc + (kD == 128 ? 64 : 0) + lane);
-    const float ql0 = p.lam[(size_t)g * kD + lane], ql1 = p.lam[(size_t)g * kD + (kD == 128 ? 64 : 0) + lane];
     const unsigned nh0 = raw16(nsrc + lane), nh1 = raw16(nsrc + (kD == 128 ? 64 : 0) + lane);
     const float nl0 = ql0, nl1 = ql1;
-    asm volatile("" ::: "memory");                 // keep these six loads ahead of the big ones below
-    constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
-    // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
-    constexpr int kStageK = CBK_BYTES / 1024, kStageKPerWave = (kStageK + NW - 1) / NW;
-    constexpr int kStageV = CBV_BYTES / 1024, kStageVPerWave = (kStageV + NW - 1) / NW;
-    static_assert(WV || NROUND_V * (kCentroids / (4 * CPL)) == kStageV, "value items: (code group, r)");
-    const int vq = lane >> 4, vcol = lane & 15;
-    uintx4 vreg[kStageVPerWave];
-    // ---- stage both codebooks of this KV head in LDS (Alg. 1 step 7, and C_k likewise), through
-    // registers: all 16 loads of a wavefront (16 KB) are issued back to back and share one trip
-    // to memory with the first code tiles and the query; the LDS writes come after the q~ section.
-    // (Direct global->LDS loads measured slower here: a wavefront got through its 8 of them at
-    // about one L2 latency each.)
-    uintx4 kreg[kStageKPerWave];
-    {
-        const unsigned char *srck = reinterpret_cast<const unsigned char *>(p.cb_k) + (size_t)g * CBK_BYTES;
-        const unsigned char *srcv = reinterpret_cast<const unsigned char *>(p.cb_v) + (size_t)g * CBV_BYTES;
-        // keys keep the [m][code] order (a shared table its one order): item = 1 KB chunk, 16 bytes per lane
-#pragma unroll
-        for (int j = 0; j < kStageKPerWave; ++j) {
-            const int it = wave + NW * j;
-            if (kStageK % NW == 0 || it < kStageK)
-                kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
-        }
-#ifdef VECINFER_PROLOGUE_STAMPS
-        STAMPW(1);
-#endif
-        // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
-        // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
-        // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
-        // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
-        // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
-        // group it / NROUND_V.
-#pragma unroll
-        for (int j = 0; j < kStageVPerWave; ++j) {
-            const int it = wave + NW * j;
-            const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
-            if (kStageV % NW == 0 || it < kStageV)
-                vreg[j] = WV ? *reinterpret_cast<const uintx4 *>(srcv + it * 1024 + lane * 16)   // shared table: as is
-                             : *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
-        }
-    }
+    asm volatile("" ::: "memory");                 // ahead of the code tiles
     // The first two tiles' codes start their trip from HBM now, under the prologue.  They are
     // requested after the codebooks: loads return in order, and the first touch of the code stream
     // is the slowest load of the kernel, so the other way round the staging would wait behind it.
@@ -456,7 +467,7 @@ void decode_mfma_kernel(DecodeParams p)
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
     static_assert(KG <= NW && NW >= 2, "one wavefront per head slot for the query transform");
-    if (wave < KG && wave >= p.G) {
+    if (wave < KG && wave >= G_) {
         // spare head slot (G < 4): a zero query; its scores and outputs are never written out
         sm_qt[wave * kD + lane] = 0.f;
         if (kD == 128) sm_qt[wave * kD + 64 + lane] = 0.f;
@@ -571,191 +582,197 @@ void decode_mfma_kernel(DecodeParams p)
     // lowest index among the centroids at minimum distance wins.  The key item
     // also leaves the new token's score share of its sub-space for the 4 heads, the value item
     // the dequantized channels, for the merge kernel.
-    if (has_new) {
-        const long long pos = len - 1;
-        const float fold = kLog2e / (float)kD;
-        // A wavefront takes up to four items of one kind at a time (items i0, i0 + NW, ..): their
-        // chains of LDS reads, distance arithmetic and cross-lane reductions are independent, so
-        // they overlap instead of paying their latencies one after the other.
-        auto new_items = [&](auto kv_c, int i0) {
-            constexpr int kv = decltype(kv_c)::value;          // 0: key sub-spaces, 1: value sub-spaces
-            constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS, MX = kv == 0 ? MK : MV, NB = 4;
-            // entry c of a sub-space sits at tab + c * stride (value tables are transposed)
-            constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
-            int m[NB];
-            bool ok[NB];
-            const unsigned char *tab[NB];
-            float best[NB];
-            unsigned arg[NB];
+    const long long pos = len - 1;
+    const float fold = kLog2e / (float)kD;
+    // A wavefront takes up to four items of one kind at a time (items i0, i0 + NW, ..): their
+    // chains of LDS reads, distance arithmetic and cross-lane reductions are independent, so
+    // they overlap instead of paying their latencies one after the other.
+    auto new_items = [&](auto kv_c, auto nb_c, int i0) {
+        constexpr int kv = decltype(kv_c)::value;          // 0: key sub-spaces, 1: value sub-spaces
+        constexpr int NB = decltype(nb_c)::value;          // items taken at a time
+        constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS, MX = kv == 0 ? MK : MV;
+        // entry c of a sub-space sits at tab + c * stride (value tables are transposed)
+        constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
+        int m[NB];
+        bool ok[NB];
+        const unsigned char *tab[NB];
+        float best[NB];
+        unsigned arg[NB];
 #pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                const int mm = s + (i0 + NW * b4) * p.S;
-                ok[b4] = mm < MX;
-                m[b4] = ok[b4] ? mm : 0;                        // a surplus slot redoes sub-space 0 and writes nothing
-                tab[b4] = kv == 0 ? sm_k + m[b4] * SUB_K
-                                  : sm_v + (m[b4] % NROUND_V) * PLANE_V + (m[b4] / NROUND_V) * ENTRY_V;
-                best[b4] = INFINITY;
-                arg[b4] = 0;
-            }
+        for (int b4 = 0; b4 < NB; ++b4) {
+            const int mm = s + (i0 + NW * b4) * S_;
+            ok[b4] = mm < MX;
+            m[b4] = ok[b4] ? mm : 0;                        // a surplus slot redoes sub-space 0 and writes nothing
+            tab[b4] = kv == 0 ? sm_k + m[b4] * SUB_K
+                              : sm_v + (m[b4] % NROUND_V) * PLANE_V + (m[b4] / NROUND_V) * ENTRY_V;
+            best[b4] = INFINITY;
+            arg[b4] = 0;
+        }
 #pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                float x[DS];
+        for (int b4 = 0; b4 < NB; ++b4) {
+            float x[DS];
 #pragma unroll
-                for (int jj = 0; jj < DS; ++jj) x[jj] = sm_new[kv * kD + m[b4] * DS + jj];
+            for (int jj = 0; jj < DS; ++jj) x[jj] = sm_new[kv * kD + m[b4] * DS + jj];
 #pragma unroll
-                for (int i = 0; i < kCentroids / 64; ++i) {
-                    const unsigned c = lane + 64 * i;
-                    _Float16 cen[DS];
-                    __builtin_memcpy(cen, tab[b4] + c * stride, EN);
-                    float dist = 0.f;
-#pragma unroll
-                    for (int jj = 0; jj < DS; ++jj) {
-                        const float tdiff = x[jj] - (float)cen[jj];
-                        dist = fmaf(tdiff, tdiff, dist);
-                    }
-                    if (dist < best[b4]) {
-                        best[b4] = dist;
-                        arg[b4] = c;
-                    }
-                }
-            }
-            unsigned code[NB];
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                // a non-negative fp32 orders like its bit pattern
-                const unsigned dmin = wave_umin(__float_as_uint(best[b4]));
-                code[b4] = wave_umin(__float_as_uint(best[b4]) == dmin ? arg[b4] : 0xffffffffu);
-            }
-#pragma unroll
-            for (int b4 = 0; b4 < NB; ++b4) {
-                if (!ok[b4]) continue;                          // wave-uniform
-                _Float16 win[DS];
-                __builtin_memcpy(win, tab[b4] + code[b4] * stride, EN);
-                if (kv == 0) {
-                    if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m[b4]] = (uint8_t)code[b4];
-                    if (lane < p.G) {
-                        float sc = 0.f;
-#pragma unroll
-                        for (int jj = 0; jj < DS; ++jj)
-                            sc = fmaf(sm_qt[lane * kD + m[b4] * DS + jj] * fold, (float)win[jj], sc);
-                        p.new_sc[((size_t)bg * MK + m[b4]) * p.G + lane] = sc;
-                        sm_nsc[m[b4] * KG + lane] = sc;
-                    }
-                } else {
-                    if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m[b4]] = (uint8_t)code[b4];
-                    float mine = (float)win[0];
-#pragma unroll
-                    for (int jj = 1; jj < DS; ++jj) mine = lane == jj ? (float)win[jj] : mine;
-                    if (lane < DS) {
-                        p.new_v[(size_t)bg * kD + m[b4] * DS + lane] = mine;
-                        sm_nv[m[b4] * DS + lane] = mine;
-                    }
-                }
-            }
-        };
-        // Wide codes: an item is a group of four sub-spaces (4 b bits = whole bytes of the packed
-        // row) and the whole workgroup works on it: wavefront w scans centroids
-        // [w C / NW, (w + 1) C / NW) of the one table for the four sub-vectors at once, a lane taking
-        // every 64th of them in increasing order (strict "<": its lowest index wins); the
-        // wavefronts' (distance bits, index) keys meet in LDS and the smallest key wins, which is the
-        // lowest index at the minimum distance.  Same distance arithmetic as the append kernels.
-        auto wide_item = [&](auto kv_c, int grp) {
-            constexpr int kv = decltype(kv_c)::value;
-            constexpr int DS = kv == 0 ? DK : DV, BITS = kv == 0 ? BK : BV, MX = kv == 0 ? MK : MV;
-            constexpr int C = 1 << BITS, PER_WAVE = C / NW, EN = 2 * DS;
-            const unsigned char *const tab = kv == 0 ? sm_k : sm_v;
-            float x[4][DS];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < DS; ++jj) x[i][jj] = sm_new[kv * kD + (4 * grp + i) * DS + jj];
-            unsigned best[4], arg[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                best[i] = 0x7f800000u;                         // +inf
-                arg[i] = 0;
-            }
-#pragma unroll 2
-            for (int it = 0; it < PER_WAVE / 64; ++it) {
-                const unsigned c = (unsigned)(wave_u * PER_WAVE + it * 64 + lane);
+            for (int i = 0; i < kCentroids / 64; ++i) {
+                const unsigned c = lane + 64 * i;
                 _Float16 cen[DS];
-                __builtin_memcpy(cen, tab + c * EN, EN);
+                __builtin_memcpy(cen, tab[b4] + c * stride, EN);
+                float dist = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float dist = 0.f;
-#pragma unroll
-                    for (int jj = 0; jj < DS; ++jj) {
-                        const float tdiff = x[i][jj] - (float)cen[jj];
-                        dist = fmaf(tdiff, tdiff, dist);
-                    }
-                    const unsigned v = __float_as_uint(dist);  // a non-negative fp32 orders like its bit pattern
-                    if (v < best[i]) {
-                        best[i] = v;
-                        arg[i] = c;
-                    }
+                for (int jj = 0; jj < DS; ++jj) {
+                    const float tdiff = x[jj] - (float)cen[jj];
+                    dist = fmaf(tdiff, tdiff, dist);
+                }
+                if (dist < best[b4]) {
+                    best[b4] = dist;
+                    arg[b4] = c;
                 }
             }
+        }
+        unsigned code[NB];
+#pragma unroll
+        for (int b4 = 0; b4 < NB; ++b4) {
+            // a non-negative fp32 orders like its bit pattern
+            const unsigned dmin = wave_umin(__float_as_uint(best[b4]));
+            code[b4] = wave_umin(__float_as_uint(best[b4]) == dmin ? arg[b4] : 0xffffffffu);
+        }
+#pragma unroll
+        for (int b4 = 0; b4 < NB; ++b4) {
+            if (!ok[b4]) continue;                          // wave-uniform
+            _Float16 win[DS];
+            __builtin_memcpy(win, tab[b4] + code[b4] * stride, EN);
+            if (kv == 0) {
+                if (lane == 0) p.k_idx_w[((size_t)bg * p.n_cap + pos) * MK + m[b4]] = (uint8_t)code[b4];
+                if (lane < G_) {
+                    float sc = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < DS; ++jj)
+                        sc = fmaf(sm_qt[lane * kD + m[b4] * DS + jj] * fold, (float)win[jj], sc);
+                    p.new_sc[((size_t)bg * MK + m[b4]) * G_ + lane] = sc;
+                    sm_nsc[m[b4] * KG + lane] = sc;
+                }
+            } else {
+                if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m[b4]] = (uint8_t)code[b4];
+                float mine = (float)win[0];
+#pragma unroll
+                for (int jj = 1; jj < DS; ++jj) mine = lane == jj ? (float)win[jj] : mine;
+                if (lane < DS) {
+                    p.new_v[(size_t)bg * kD + m[b4] * DS + lane] = mine;
+                    sm_nv[m[b4] * DS + lane] = mine;
+                }
+            }
+        }
+    };
+    // Wide codes: an item is a group of four sub-spaces (4 b bits = whole bytes of the packed
+    // row) and the whole workgroup works on it: wavefront w scans centroids
+    // [w C / NW, (w + 1) C / NW) of the one table for the four sub-vectors at once, a lane taking
+    // every 64th of them in increasing order (strict "<": its lowest index wins); the
+    // wavefronts' (distance bits, index) keys meet in LDS and the smallest key wins, which is the
+    // lowest index at the minimum distance.  Same distance arithmetic as the append kernels.
+    auto wide_item = [&](auto kv_c, int grp) {
+        constexpr int kv = decltype(kv_c)::value;
+        constexpr int DS = kv == 0 ? DK : DV, BITS = kv == 0 ? BK : BV, MX = kv == 0 ? MK : MV;
+        constexpr int C = 1 << BITS, PER_WAVE = C / NW, EN = 2 * DS;
+        const unsigned char *const tab = kv == 0 ? sm_k : sm_v;
+        float x[4][DS];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int jj = 0; jj < DS; ++jj) x[i][jj] = sm_new[kv * kD + (4 * grp + i) * DS + jj];
+        unsigned best[4], arg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            best[i] = 0x7f800000u;                         // +inf
+            arg[i] = 0;
+        }
+#pragma unroll 2
+        for (int it = 0; it < PER_WAVE / 64; ++it) {
+            const unsigned c = (unsigned)(wave_u * PER_WAVE + it * 64 + lane);
+            _Float16 cen[DS];
+            __builtin_memcpy(cen, tab + c * EN, EN);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const unsigned dmin = wave_umin(best[i]);
-                const unsigned code = wave_umin(best[i] == dmin ? arg[i] : 0xffffffffu);
-                if (lane == 0) sm_red[i * NW + wave_u] = ((unsigned long long)dmin << 32) | code;
-            }
-            __syncthreads();
-            if (wave_u == 0) {
-                // lanes 16 i .. 16 i + 15 look after sub-vector i of the group
-                const int i = lane >> 4, l16 = lane & 15, m = 4 * grp + i;
-                unsigned long long key = sm_red[i * NW];
+                float dist = 0.f;
 #pragma unroll
-                for (int w = 1; w < NW; ++w) key = sm_red[i * NW + w] < key ? sm_red[i * NW + w] : key;
-                const unsigned code = (unsigned)key;
-                _Float16 win[DS];
-                __builtin_memcpy(win, tab + code * EN, EN);
-                if (kv == 0) {
-                    if (l16 < p.G) {
-                        float sc = 0.f;
-#pragma unroll
-                        for (int jj = 0; jj < DS; ++jj)
-                            sc = fmaf(sm_qt[l16 * kD + m * DS + jj] * fold, (float)win[jj], sc);
-                        p.new_sc[((size_t)bg * MK + m) * p.G + l16] = sc;
-                        sm_nsc[m * KG + l16] = sc;
-                    }
-                } else {
-                    float mine = (float)win[0];
-#pragma unroll
-                    for (int jj = 1; jj < DS; ++jj) mine = l16 == jj ? (float)win[jj] : mine;
-                    if (l16 < DS) {
-                        p.new_v[(size_t)bg * kD + m * DS + l16] = mine;
-                        sm_nv[m * DS + l16] = mine;
-                    }
+                for (int jj = 0; jj < DS; ++jj) {
+                    const float tdiff = x[i][jj] - (float)cen[jj];
+                    dist = fmaf(tdiff, tdiff, dist);
                 }
-                // the group's four codes, end to end, are bytes [grp 4 b / 8, (grp + 1) 4 b / 8) of the row
-                const unsigned c0 = (unsigned)__shfl(code, 0), c1 = (unsigned)__shfl(code, 16);
-                const unsigned c2 = (unsigned)__shfl(code, 32), c3 = (unsigned)__shfl(code, 48);
-                const unsigned long long bits = (unsigned long long)c0 | ((unsigned long long)c1 << BITS) |
-                                                ((unsigned long long)c2 << (2 * BITS)) |
-                                                ((unsigned long long)c3 << (3 * BITS));
-                constexpr int GB = 4 * BITS / 8;
-                uint8_t *const row = (kv == 0 ? p.k_idx_w : p.v_idx_w) + ((size_t)bg * p.n_cap + pos) * (MX * BITS / 8);
-                if (lane < GB) row[grp * GB + lane] = (uint8_t)(bits >> (8 * lane));
+                const unsigned v = __float_as_uint(dist);  // a non-negative fp32 orders like its bit pattern
+                if (v < best[i]) {
+                    best[i] = v;
+                    arg[i] = c;
+                }
             }
-            __syncthreads();                                   // sm_red is free for the next item
-        };
-        if constexpr (WK) {
-            for (int grp = s; grp < ITEMS_K; grp += p.S) wide_item(std::integral_constant<int, 0>{}, grp);
-        } else {
-            // key item i (sub-space s + i S) goes to wavefront i % NW, value item i to wavefront (i + 1) % NW
-            for (int i0 = wave_u; s + i0 * p.S < MK; i0 += 4 * NW) new_items(std::integral_constant<int, 0>{}, i0);
         }
-        if constexpr (WV) {
-            // value groups start where the key items end, so that other workgroups take them
-            for (int grp = vgrp0; grp < ITEMS_V; grp += p.S)
-                wide_item(std::integral_constant<int, 1>{}, grp);
-        } else {
-            for (int i0 = (wave_u + NW - 1) % NW; s + i0 * p.S < MV; i0 += 4 * NW)
-                new_items(std::integral_constant<int, 1>{}, i0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned dmin = wave_umin(best[i]);
+            const unsigned code = wave_umin(best[i] == dmin ? arg[i] : 0xffffffffu);
+            if (lane == 0) sm_red[i * NW + wave_u] = ((unsigned long long)dmin << 32) | code;
         }
+        __syncthreads();
+        if (wave_u == 0) {
+            // lanes 16 i .. 16 i + 15 look after sub-vector i of the group
+            const int i = lane >> 4, l16 = lane & 15, m = 4 * grp + i;
+            unsigned long long key = sm_red[i * NW];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) key = sm_red[i * NW + w] < key ? sm_red[i * NW + w] : key;
+            const unsigned code = (unsigned)key;
+            _Float16 win[DS];
+            __builtin_memcpy(win, tab + code * EN, EN);
+            if (kv == 0) {
+                if (l16 < G_) {
+                    float sc = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < DS; ++jj)
+                        sc = fmaf(sm_qt[l16 * kD + m * DS + jj] * fold, (float)win[jj], sc);
+                    p.new_sc[((size_t)bg * MK + m) * G_ + l16] = sc;
+                    sm_nsc[m * KG + l16] = sc;
+                }
+            } else {
+                float mine = (float)win[0];
+#pragma unroll
+                for (int jj = 1; jj < DS; ++jj) mine = l16 == jj ? (float)win[jj] : mine;
+                if (l16 < DS) {
+                    p.new_v[(size_t)bg * kD + m * DS + l16] = mine;
+                    sm_nv[m * DS + l16] = mine;
+                }
+            }
+            // the group's four codes, end to end, are bytes [grp 4 b / 8, (grp + 1) 4 b / 8) of the row
+            const unsigned c0 = (unsigned)__shfl(code, 0), c1 = (unsigned)__shfl(code, 16);
+            const unsigned c2 = (unsigned)__shfl(code, 32), c3 = (unsigned)__shfl(code, 48);
+            const unsigned long long bits = (unsigned long long)c0 | ((unsigned long long)c1 << BITS) |
+                                            ((unsigned long long)c2 << (2 * BITS)) |
+                                            ((unsigned long long)c3 << (3 * BITS));
+            constexpr int GB = 4 * BITS / 8;
+            uint8_t *const row = (kv == 0 ? p.k_idx_w : p.v_idx_w) + ((size_t)bg * p.n_cap + pos) * (MX * BITS / 8);
+            if (lane < GB) row[grp * GB + lane] = (uint8_t)(bits >> (8 * lane));
+        }
+        __syncthreads();                                   // sm_red is free for the next item
+    };
+    if constexpr (WK) {
+        if (has_new)
+            for (int grp = s; grp < ITEMS_K; grp += S_) wide_item(std::integral_constant<int, 0>{}, grp);
     }
+    if constexpr (WV) {
+        // value groups start where the key items end, so that other workgroups take them
+        if (has_new)
+            for (int grp = vgrp0; grp < ITEMS_V; grp += S_) wide_item(std::integral_constant<int, 1>{}, grp);
+    }
+    // 8-bit codes: key item i (sub-space s + i S) goes to wavefront i % NW, value item i to
+    // wavefront (i + 1) % NW; a wavefront with one item of a kind (the usual case: at least as
+    // many splits as sub-spaces) takes it alone, otherwise four at a time
+    auto items8 = [&](auto kv_c) {
+        constexpr int kv = decltype(kv_c)::value, MX = kv == 0 ? MK : MV;
+        const int first = kv == 0 ? wave_u : (wave_u + NW - 1) % NW;
+        if (s + (first + NW) * S_ < MX) {
+            for (int i0 = first; s + i0 * S_ < MX; i0 += 4 * NW) new_items(kv_c, std::integral_constant<int, 4>{}, i0);
+        } else if (s + first * S_ < MX) {
+            new_items(kv_c, std::integral_constant<int, 1>{}, first);
+        }
+    };
 
     STAMP(2);
     float m_run[HG];                  // running max of head 4 hg + col/4 (log2 units), same in all its lanes
@@ -1075,6 +1092,14 @@ void decode_mfma_kernel(DecodeParams p)
         }
     }
 
+    // 8-bit codes: the new token's items come after the wavefront's tiles.  The wavefronts that take
+    // them (the first ones of the workgroup) are the ones that finish their tiles first, so the
+    // items fill time in which the workgroup waits for its slower wavefronts anyway; the tables are
+    // still in LDS until the barrier below.
+    if (has_new) {
+        if constexpr (!WK) items8(std::integral_constant<int, 0>{});
+        if constexpr (!WV) items8(std::integral_constant<int, 1>{});
+    }
     STAMP(3);
 #ifndef VECINFER_PROLOGUE_STAMPS
     STAMPW(1);
@@ -1109,7 +1134,7 @@ void decode_mfma_kernel(DecodeParams p)
         }
     }
     __syncthreads();
-    for (int e = tid; e < p.G * kD; e += BLOCK) {
+    for (int e = tid; e < G_ * kD; e += BLOCK) {
         const int hh = e / kD, c = e % kD;
         float mx = -INFINITY;
 #pragma unroll
@@ -1122,7 +1147,7 @@ void decode_mfma_kernel(DecodeParams p)
             o += f * sm_o[w * KG * kD + e];
             l += f * sm_l[w * KG + hh];
         }
-        if (p.S == 1 && !p.k_res) {
+        if (S_ == 1 && !p.k_res) {
             // the workgroup holds the whole answer (a single split also encoded every sub-space of
             // a fused new token): fold the new token in and write the output rows
             if (has_new) {
@@ -1134,11 +1159,11 @@ void decode_mfma_kernel(DecodeParams p)
                 l = f * l + wgt;
                 mx = mt;
             }
-            const size_t row = (size_t)b * p.Hq + g * p.G + hh;
+            const size_t row = ((size_t)b * Hkv_ + g) * G_ + hh;
             p.out[row * kD + c] = __float2half(l > 0.f ? o / l : 0.f);
             if (c == 0 && p.lse) p.lse[row] = l > 0.f ? (mx + log2f(l)) * kLn2 : -INFINITY;
         } else {
-            const size_t pi = (bg * p.S + s) * p.G;
+            const size_t pi = (bg * S_ + s) * G_;
             p.part_o[pi * kD + e] = o;
             if (c == 0) {
                 p.part_m[pi + hh] = mx;
@@ -1148,6 +1173,7 @@ void decode_mfma_kernel(DecodeParams p)
     }
     STAMP(4);
     STAMP(5);
+    STAMP_ENTRY_OUT();
 }
 
 template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK, int BV>
@@ -1166,7 +1192,8 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
     if (!configured) return -4;
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV>), grid, dim3(NW * 64), smem, stream, p);
+    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV>), grid, dim3(NW * 64), smem, stream,
+                       p.q, p.lam, p.cb_k, p.cb_v, p.k_idx, p.v_idx, (unsigned)p.Hkv | (unsigned)p.G << 24, p.S, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

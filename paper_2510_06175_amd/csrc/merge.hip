@@ -49,7 +49,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 enum { kPlain = 0, kWindow = 1, kNewToken = 2 };
 
 template <int D, int HB, int MODE>
-__global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
+__global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, const float *part_m, const float *part_l,
+                                                         __half *out, float *lse, int S, int G, int Hq, int Hkv,
+                                                         DecodeParams p)
 {
     constexpr bool WINDOW = MODE == kWindow;
     constexpr int kMaxM = D / 2;                                      // key sub-spaces at d = 2
@@ -66,8 +68,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
     // compiler fetches them where they are first needed: several cold trips to the argument buffer
     // in a kernel whose whole run is a few of them long).
 #define VECINFER_PIN(x) asm volatile("" ::"s"(x))
-    VECINFER_PIN(p.part_o); VECINFER_PIN(p.part_m); VECINFER_PIN(p.part_l); VECINFER_PIN(p.out); VECINFER_PIN(p.lse);
-    VECINFER_PIN(p.S); VECINFER_PIN(p.G); VECINFER_PIN(p.Hq); VECINFER_PIN(p.Hkv);
+    VECINFER_PIN(part_o); VECINFER_PIN(part_m); VECINFER_PIN(part_l); VECINFER_PIN(out); VECINFER_PIN(lse);
+    VECINFER_PIN(S); VECINFER_PIN(G); VECINFER_PIN(Hq); VECINFER_PIN(Hkv);
     if (MODE == kWindow) {
         VECINFER_PIN(p.q); VECINFER_PIN(p.k_res); VECINFER_PIN(p.v_res); VECINFER_PIN(p.res_lens);
         VECINFER_PIN(p.R); VECINFER_PIN(p.r_cap);
@@ -78,8 +80,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
 #undef VECINFER_PIN
     const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int w = t >> 6, lane = t & 63;
-    const int G = p.G, GD = G * D, S = p.S;
-    const size_t bg = (size_t)b * p.Hkv + g;
+    const int GD = G * D;
+    const size_t bg = (size_t)b * Hkv + g;
 
     // ---- 1. window operands -> registers
     half8 qa[kSteps], kb[kSteps];
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
         if (wave_loads) {
             const __half *kg = p.k_res + bg * p.r_cap * D;
             const __half *vg = p.v_res + bg * p.r_cap * D;
-            const __half *qg = p.q + ((size_t)b * p.Hq + (size_t)g * G) * D;
+            const __half *qg = p.q + ((size_t)b * Hq + (size_t)g * G) * D;
             const int last = p.R - 1;
             const int qrow = (lane & 15) < G ? (lane & 15) : 0;
             const int krow = row0 + (lane & 15) < last ? row0 + (lane & 15) : last;
@@ -127,9 +129,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
     float vo[kElems][kBatch], tm[kML], tl[kML];
     const int SG = S * G;
     if (S > 0) {
-        const float *po = p.part_o + bg * S * GD;
-        const float *pm = p.part_m + bg * SG;
-        const float *pl = p.part_l + bg * SG;
+        const float *po = part_o + bg * S * GD;
+        const float *pm = part_m + bg * SG;
+        const float *pl = part_l + bg * SG;
 #pragma unroll
         for (int i = 0; i < kElems; ++i) {
             const int e = t + i * kThreads < GD ? t + i * kThreads : 0;
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
                 den = fmaf(wgt, pl_s[j * G + hh], den);
                 acc = fmaf(wgt, vo[i][j], acc);
             }
-            const float *po = p.part_o + bg * S * GD;
+            const float *po = part_o + bg * S * GD;
             for (int s0 = kBatch; s0 < S; s0 += kBatch) {    // more than kBatch splits: further rounds
                 float vx[kBatch];
 #pragma unroll
@@ -255,9 +257,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(DecodeParams p)
             den += wgt;
             acc = fmaf(wgt, nv_s[c], acc);
         }
-        const size_t row = (size_t)b * p.Hq + g * G + hh;
-        p.out[row * D + c] = __float2half(den > 0.f ? acc / den : 0.f);
-        if (c == 0 && p.lse) p.lse[row] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
+        const size_t row = (size_t)b * Hq + g * G + hh;
+        out[row * D + c] = __float2half(den > 0.f ? acc / den : 0.f);
+        if (c == 0 && lse) lse[row] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
     }
 }
 
@@ -266,11 +268,11 @@ int launch_for(const DecodeParams &p, hipStream_t stream)
 {
     const dim3 grid(p.Hkv, p.B), block(kThreads);
     if (p.k_res)
-        hipLaunchKernelGGL((merge_kernel<D, HB, kWindow>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kWindow>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
     else if (p.k_new)
-        hipLaunchKernelGGL((merge_kernel<D, HB, kNewToken>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kNewToken>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
     else
-        hipLaunchKernelGGL((merge_kernel<D, HB, kPlain>), grid, block, 0, stream, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kPlain>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
