@@ -64,12 +64,39 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
     __shared__ float ns_s[MODE == kNewToken ? kMaxM * HB : 1];      // [m][hh] score shares of the new token
     __shared__ float nv_s[MODE == kNewToken ? D : 1];
 
-    // Every argument the kernel uses is read here, in one batch of scalar loads (left to itself the
-    // compiler fetches them where they are first needed: several cold trips to the argument buffer
-    // in a kernel whose whole run is a few of them long).
+    const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
+    const int w = t >> 6, lane = t & 63;
+    const int GD = G * D;
+    const size_t bg = (size_t)b * Hkv + g;
+
+    // ---- 1. split partials: this thread's o_s of the first kBatch splits, and its share of the (m, l)
+    // table.  These requests use the leading kernel arguments only, which the command processor can
+    // hand over in scalar registers (kernel-argument preloading): they leave before the rest of
+    // `p` has made its trip from the argument buffer.
+    float vo[kElems][kBatch], tm[kML], tl[kML];
+    const int SG = S * G;
+    if (S > 0) {
+        const float *po = part_o + bg * S * GD;
+        const float *pm = part_m + bg * SG;
+        const float *pl = part_l + bg * SG;
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+            const int e = t + i * kThreads < GD ? t + i * kThreads : 0;
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) vo[i][j] = po[(size_t)(j < S ? j : S - 1) * GD + e];
+        }
+#pragma unroll
+        for (int i = 0; i < kML; ++i) {
+            const int idx = t + i * kThreads < SG ? t + i * kThreads : SG - 1;
+            tm[i] = pm[idx];
+            tl[i] = pl[idx];
+        }
+    }
+
+    // Every other argument is read here, in one batch of scalar loads (left to itself the compiler
+    // fetches them where they are first needed: several cold trips to the argument buffer in a
+    // kernel whose whole run is a few of them long).
 #define VECINFER_PIN(x) asm volatile("" ::"s"(x))
-    VECINFER_PIN(part_o); VECINFER_PIN(part_m); VECINFER_PIN(part_l); VECINFER_PIN(out); VECINFER_PIN(lse);
-    VECINFER_PIN(S); VECINFER_PIN(G); VECINFER_PIN(Hq); VECINFER_PIN(Hkv);
     if (MODE == kWindow) {
         VECINFER_PIN(p.q); VECINFER_PIN(p.k_res); VECINFER_PIN(p.v_res); VECINFER_PIN(p.res_lens);
         VECINFER_PIN(p.R); VECINFER_PIN(p.r_cap);
@@ -78,12 +105,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
         VECINFER_PIN(p.new_sc); VECINFER_PIN(p.new_v); VECINFER_PIN(p.Mk); VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N);
     }
 #undef VECINFER_PIN
-    const int g = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
-    const int w = t >> 6, lane = t & 63;
-    const int GD = G * D;
-    const size_t bg = (size_t)b * Hkv + g;
-
-    // ---- 1. window operands -> registers
+    // ---- 2. window operands -> registers
     half8 qa[kSteps], kb[kSteps];
     unsigned vv[kRowsPerWave];
     const int row0 = w * kRowsPerWave;
@@ -123,27 +145,6 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
     if (MODE == kNewToken) {
         if (t < p.Mk * G) nsc = p.new_sc[bg * p.Mk * G + t];
         if (t < D) nvv = p.new_v[bg * D + t];
-    }
-
-    // ---- 2. split partials: this thread's o_s of the first kBatch splits, and its share of the (m, l) table
-    float vo[kElems][kBatch], tm[kML], tl[kML];
-    const int SG = S * G;
-    if (S > 0) {
-        const float *po = part_o + bg * S * GD;
-        const float *pm = part_m + bg * SG;
-        const float *pl = part_l + bg * SG;
-#pragma unroll
-        for (int i = 0; i < kElems; ++i) {
-            const int e = t + i * kThreads < GD ? t + i * kThreads : 0;
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) vo[i][j] = po[(size_t)(j < S ? j : S - 1) * GD + e];
-        }
-#pragma unroll
-        for (int i = 0; i < kML; ++i) {
-            const int idx = t + i * kThreads < SG ? t + i * kThreads : SG - 1;
-            tm[i] = pm[idx];
-            tl[i] = pl[idx];
-        }
     }
 
     // ---- 3. the wave's window partial -> LDS
