@@ -206,7 +206,7 @@ size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64
  *             calls that share a workspace must be ordered on one stream
  *   out_f16   [B, H_q, D] fp16          lse  [B, H_q] fp32 or NULL
  * Errors: EINVAL (null pointers, B < 1, N < 1, N > n_cap, num_splits out of range),
- * EUNSUPPORTED (cfg, or variant that does not cover cfg), EWORKSPACE, ELAUNCH.
+ * EUNSUPPORTED (cfg, variant that does not cover cfg, B or H_kv above 65535), EWORKSPACE, ELAUNCH.
  */
 int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
                               const void *cb_k_f16, const void *cb_v_f16,

@@ -29,14 +29,15 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 int num_cus()
 {
-    static int cached = 0;
-    if (cached == 0) {
+    // queried once per process (function-local static: initialised thread-safely); the library is
+    // built for one chip, so the first device's count serves every device
+    static const int cached = [] {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
             n = 256;                     // MI355X; used only to size the grid
-        cached = n;
-    }
+        return n;
+    }();
     return cached;
 }
 
@@ -148,7 +149,7 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     if (num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
     if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA)
         return VECINFER_EINVAL;
-    if (B > 65535) return VECINFER_EUNSUPPORTED;
+    if (B > 65535 || cfg->num_kv_heads > 65535) return VECINFER_EUNSUPPORTED;      // grid dimensions
     if (!aligned(q_f16, 16) || !aligned(lambda, 16) || !aligned(cb_k_f16, 16) || !aligned(cb_v_f16, 16) ||
         !aligned(k_idx, 16) || !aligned(v_idx, 16) || !aligned(out_f16, 16))
         return VECINFER_EINVAL;

@@ -25,7 +25,7 @@ int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
     if (p.bk != 8 || p.bv != 8) return launch_decode_mfma_wide(p, stream);
-    // 8 wavefronts per workgroup (2 per SIMD): 12 measured no faster (LDS-bound), 4 is latency-bound
+    // 8 wavefronts per workgroup (2 per SIMD): 12 measured slower, 4 is latency-bound
     const int key = p.D * 100 + p.dk * 10 + p.dv;
     switch (key) {
     case 12844: return launch_typed<128, 4, 4, 8, true>(p, stream);

@@ -103,6 +103,9 @@ def test_decode_argument_errors():
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
     # the matrix-core variant does not cover d_v = 8 at head dim 64
     assert _decode(cfg=vb.Config(64, 8, 1, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # more KV heads (or sequences) than a grid dimension holds
+    assert _decode(cfg=vb.Config(128, 70000, 70000, 4, 4), ws=FAKE, ws_bytes=1 << 40) == vb.EUNSUPPORTED
+    assert _decode(B=70000, ws=FAKE, ws_bytes=1 << 40) == vb.EUNSUPPORTED
 
 
 def test_decode_residual_argument_errors():
