@@ -204,7 +204,12 @@ def main() -> int:
                    "num_splits": splits, "variant": args.variant,
                    "us_per_step": round(ms_per_step * 1e3, 3),
                    "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},
-        "roofline": {"bound": "hbm", "kernel": "vecinfer_decode_attention", "achieved": round(achieved, 2),
+        # `kernel` is the call the events bracket: the attention kernel plus, with more than one split,
+        # the merge kernel right behind it (rocprofv3 lists the two separately, see profiles/)
+        "roofline": {"bound": "hbm", "kernel": "vecinfer_decode_attention",
+                     "launches_per_call": ["decode_lut_kernel" if variant == vb.VARIANT_LUT else "decode_mfma_kernel"]
+                     + (["merge_kernel"] if splits > 1 else []),
+                     "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if variant != vb.VARIANT_LUT else None,
                      "algorithmic_bytes": idx_bytes, "kernel_us_avg": round(kern_avg_ms * 1e3, 3),
