@@ -45,6 +45,10 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
+    ap.add_argument("--v-layout", default="auto", choices=["auto", "rows", "tiled"],
+                    help="physical layout of the value code cache: rows [n_cap, M_v], or tiles of 64 tokens "
+                         "in the attention kernel's own order (cfg.v_tiled); auto = tiled where it applies "
+                         "(8-bit codes on both sides, matrix-core kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run 8 plain 256 MiB device copies first: a kernel of known HBM traffic "
@@ -80,8 +84,14 @@ def main() -> int:
              "196k-kd8b12-vd8b8": synth.Shape(1, 32, 8, 128, 196608, 8, 8, 12, 8)}[args.workload]
     if args.tokens:
         shape = synth.Shape(shape.B, shape.Hq, shape.Hkv, shape.D, args.tokens, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
-    cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
     variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
+    can_tile = shape.b_k == 8 and shape.b_v == 8 and variant != vb.VARIANT_LUT and shape.N % 64 == 0
+    if args.v_layout == "tiled" and not can_tile:
+        print("bench.py: --v-layout tiled needs 8-bit codes on both sides, the matrix-core kernel and "
+              "a cache length that is a multiple of 64", file=sys.stderr)
+        return 2
+    v_tiled = 1 if (args.v_layout == "tiled" or (args.v_layout == "auto" and can_tile)) else 0
+    cfg = vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v, v_tiled)
     idx_bytes = shape.index_bytes()
     layers = args.layers or max(2, -(-768 * 2**20 // idx_bytes))   # working set >= 768 MB > Infinity Cache
     torch.cuda.set_device(0)
@@ -93,6 +103,14 @@ def main() -> int:
     # oracle leg also uses); the query is the same tensor for all
     q = dev(x0["q"])
     caches = [tuple(dev(x0[k]) for k in ("k_idx", "v_idx", "cb_k", "cb_v", "lam"))]
+    if v_tiled:
+        # the random bytes of layer 0's value cache are taken as a tiled cache; the oracle leg gets
+        # the N x M_v code matrix they hold (codes are uniform random either way)
+        rows = torch.empty_like(caches[0][1])
+        vb.vecinfer_export_value_codes(cfg, caches[0][1], rows)
+        torch.cuda.synchronize()
+        x0["v_idx"] = rows.cpu().numpy()
+        del rows
     for layer in range(1, layers):
         g = synth.rng(1000 + layer)
         caches.append((dev(synth.random_code_rows(g, shape.B, shape.Hkv, shape.N, shape.row_bytes_k)),
@@ -201,6 +219,7 @@ def main() -> int:
                    else "append 1 token (smooth+FWHT+VQ of k, VQ of v) + fused VQ attention, "
                         + ("two calls" if args.separate_append else "one call (vecinfer_decode_step)"),
                    "index_bytes_per_step": idx_bytes, "layer_caches_rotated": layers,
+                   "value_code_layout": "tiles of 64 tokens" if v_tiled else "rows",
                    "num_splits": splits, "variant": args.variant,
                    "us_per_step": round(ms_per_step * 1e3, 3),
                    "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2)},

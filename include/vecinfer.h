@@ -94,7 +94,25 @@ typedef struct vecinfer_cfg {
                               sub-space), or 10 / 12 (packed rows, one shared codebook of 2^b
                               centroids per KV head; needs D = 128 and d_k = 4 or 8)          */
     int32_t v_bits;        /* code width for values: 8, 10 or 12, same rules with d_v        */
+    int32_t v_tiled;       /* physical layout of the value code cache (8-bit value codes only):
+                              0 = rows, [B, H_kv, n_cap, M_v] as above;
+                              1 = tiles of 64 tokens, see "Tiled value codes" below           */
 } vecinfer_cfg;
+
+/*
+ * Tiled value codes (cfg.v_tiled = 1; v_bits = 8; n_cap a multiple of 64).
+ * The cache holds the same N x M_v code matrix of a (sequence, KV head), stored in blocks of
+ * 64 tokens (64 M_v bytes each, block t / 64 of token t) in the order in which the lanes of the
+ * matrix-core attention kernel consume them, so that a lane fetches its share of a block with
+ * 16-byte loads instead of one narrow load per token (about 1 us per call at 196608 tokens).
+ * With R = M_v / 16, i = t % 64, sub-space m and j = ((i / 16) * 4 + (i % 16) / 4) * R + m % R,
+ * the byte of (t, m) sits at offset
+ *     (t / 64) * 64 M_v  +  (j / 16) * 1024  +  ((i % 4) * 16 + m / R) * 16  +  j % 16
+ * of the (sequence, KV head)'s cache.  vecinfer_encode_values, vecinfer_append_kv and
+ * vecinfer_decode_step write this layout and the matrix-core attention reads it when the flag is
+ * set; vecinfer_export_value_codes returns the rows form.  The lookup-table variant and
+ * vecinfer_kmeans_step (whose `codes` output is always rows) do not take it.
+ */
 
 /*
  * Cache fill for keys: Alg. 1 "Preprocessing" + "Quantization" (Eq. 3, 6, 8):
@@ -275,6 +293,18 @@ int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void 
  */
 size_t vecinfer_index_row_bytes(const vecinfer_cfg *cfg, int32_t keys);
 size_t vecinfer_codebook_elems(const vecinfer_cfg *cfg, int32_t keys);
+
+/*
+ * Tiled value codes -> rows: writes the N x M_v code matrix of every (sequence, KV head) of a cache
+ * kept in the tiled layout (cfg.v_tiled, see "Tiled value codes") as rows, [B, H_kv, n_cap, M_v],
+ * rows 0 .. N-1.  For callers that inspect or move a cache (and for the parity tests); the attention
+ * path never needs it.  The flag in cfg is not consulted: the source is taken to be tiled.
+ *   v_idx_tiled  [B, H_kv, n_cap * M_v] bytes, tiled     v_idx_rows  [B, H_kv, n_cap, M_v], another buffer
+ * Errors: EINVAL (null or identical pointers, B < 1, N < 1, N > n_cap, n_cap not a multiple of 64),
+ * EUNSUPPORTED (cfg; v_bits other than 8).
+ */
+int vecinfer_export_value_codes(const vecinfer_cfg *cfg, const uint8_t *v_idx_tiled, uint8_t *v_idx_rows,
+                                int32_t B, int64_t N, int64_t n_cap, void *stream);
 
 /*
  * Measurement aid: a plain streaming read of `bytes` bytes at `src` (16-byte loads from every CU,

@@ -27,13 +27,14 @@ EXPORTS = [
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
     "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
     "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda", "vecinfer_read_probe",
+    "vecinfer_export_value_codes",
     "vecinfer_strerror", "vecinfer_version",
 ]
 
 
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_dim", "num_q_heads", "num_kv_heads", "k_sub_dim",
-                                         "v_sub_dim", "k_bits", "v_bits")]
+                                         "v_sub_dim", "k_bits", "v_bits", "v_tiled")]
 
 
 @dataclass(frozen=True)
@@ -46,10 +47,11 @@ class Config:
     v_sub_dim: int
     k_bits: int = 8
     v_bits: int = 8
+    v_tiled: int = 0            # 1: value codes stored in tiles of 64 tokens (8-bit value codes)
 
     def c(self) -> _Cfg:
         return _Cfg(self.head_dim, self.num_q_heads, self.num_kv_heads, self.k_sub_dim,
-                    self.v_sub_dim, self.k_bits, self.v_bits)
+                    self.v_sub_dim, self.k_bits, self.v_bits, self.v_tiled)
 
     def cb_shape(self, keys: bool) -> tuple:
         """Codebook tensor shape: one 256-entry table per (KV head, sub-space) for 8-bit codes, one
@@ -112,6 +114,8 @@ def lib() -> C.CDLL:
         L.vecinfer_calibrate_lambda.restype = C.c_int
         L.vecinfer_read_probe.argtypes = [vp, sz, vp, vp]
         L.vecinfer_read_probe.restype = C.c_int
+        L.vecinfer_export_value_codes.argtypes = [cfgp, vp, vp, i32, i64, i64, vp]
+        L.vecinfer_export_value_codes.restype = C.c_int
         L.vecinfer_index_row_bytes.argtypes = [cfgp, i32]
         L.vecinfer_index_row_bytes.restype = sz
         L.vecinfer_codebook_elems.argtypes = [cfgp, i32]
@@ -293,6 +297,15 @@ def vecinfer_calibrate_lambda(cfg: Config, k_f16, lam, stream=None) -> None:
     _check(lib().vecinfer_calibrate_lambda(
         C.byref(cfg.c()), _dev(k_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "k_f16"),
         _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"), B, T, _stream(stream)))
+
+
+def vecinfer_export_value_codes(cfg: Config, v_idx_tiled, v_idx_rows, N: int | None = None, stream=None) -> None:
+    """Rows form [B, Hkv, n_cap, M_v] (rows 0 .. N-1) of a value code cache kept in the tiled layout."""
+    B, n_cap = v_idx_rows.shape[0], v_idx_rows.shape[2]
+    shape = (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False))
+    _check(lib().vecinfer_export_value_codes(
+        C.byref(cfg.c()), _dev(v_idx_tiled, torch.uint8, shape, "v_idx_tiled"),
+        _dev(v_idx_rows, torch.uint8, shape, "v_idx_rows"), B, n_cap if N is None else N, n_cap, _stream(stream)))
 
 
 def vecinfer_read_probe(src, sink, stream=None) -> None:

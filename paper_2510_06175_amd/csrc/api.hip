@@ -20,7 +20,9 @@ bool cfg_ok(const vecinfer_cfg *c)
     auto bits_ok = [&](int bits, int d) {
         return bits == 8 || ((bits == 10 || bits == 12) && c->head_dim == 128 && (d == 4 || d == 8));
     };
-    return bits_ok(c->k_bits, c->k_sub_dim) && bits_ok(c->v_bits, c->v_sub_dim);
+    if (!bits_ok(c->k_bits, c->k_sub_dim) || !bits_ok(c->v_bits, c->v_sub_dim)) return false;
+    // tiled value codes: one byte per code
+    return c->v_tiled == 0 || (c->v_tiled == 1 && c->v_bits == 8);
 }
 
 bool wide(const vecinfer_cfg *c) { return c->k_bits != 8 || c->v_bits != 8; }
@@ -87,6 +89,7 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     if (!cfg || !x || !cb || !idx || (keys && !lambda)) return VECINFER_EINVAL;
     if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
     if (B < 1 || T < 1 || pos0 < 0 || n_cap < 1 || pos0 + T > n_cap) return VECINFER_EINVAL;
+    if (!keys && cfg->v_tiled && n_cap % 64 != 0) return VECINFER_EINVAL;       // whole 64-token blocks
     if ((int64_t)B * cfg->num_kv_heads > 65535) return VECINFER_EUNSUPPORTED;
     if ((T + 63) / 64 > 0x7fffffffLL) return VECINFER_EUNSUPPORTED;
     if (!aligned(x, 16) || !aligned(cb, 16) || !aligned(idx, 16) || (keys && !aligned(lambda, 16)))
@@ -101,6 +104,7 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     p.d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
     p.M = p.D / p.d;
     p.bits = keys ? cfg->k_bits : cfg->v_bits;
+    p.tiled = keys ? 0 : cfg->v_tiled;
     p.T = T;
     p.pos0 = pos0;
     p.n_cap = n_cap;
@@ -140,6 +144,7 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     const bool append = k_new != nullptr;
     if (append && (!v_new || !aligned(k_new, 16) || !aligned(v_new, 16))) return VECINFER_EINVAL;
     if (B < 1 || N < (window ? 0 : 1) || n_cap < N) return VECINFER_EINVAL;
+    if (cfg->v_tiled && n_cap % 64 != 0) return VECINFER_EINVAL;                  // whole 64-token blocks
     if (N > 0 && (!k_idx || !v_idx)) return VECINFER_EINVAL;
     if (window) {
         if (!v_res || R < 0 || R > r_cap || N + R < 1) return VECINFER_EINVAL;
@@ -176,6 +181,7 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     p.Mv = p.D / p.dv;
     p.bk = cfg->k_bits;
     p.bv = cfg->v_bits;
+    p.v_tiled = cfg->v_tiled;
     p.N = N;
     p.n_cap = n_cap;
     p.S = S;
@@ -198,8 +204,8 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
     const bool mfma_ok = decode_mfma_supports(p);
     if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
     const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
-    // the lookup-table kernel reads one byte per code
-    if (!use_mfma && wide(cfg)) return VECINFER_EUNSUPPORTED;
+    // the lookup-table kernel reads one byte per code, from rows
+    if (!use_mfma && (wide(cfg) || cfg->v_tiled)) return VECINFER_EUNSUPPORTED;
     int rc = 0;
     if (append && use_mfma) {           // the attention launch encodes the new token itself
         p.k_new = static_cast<const __half *>(k_new);
@@ -283,7 +289,10 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
                          void *cb_out_f16, uint8_t *codes, int32_t *counts, int32_t B, int64_t T, void *workspace,
                          size_t workspace_bytes, void *stream)
 {
-    if (!cb_out_f16 || !aligned(cb_out_f16, 16)) return VECINFER_EINVAL;
+    if (!cfg || !cb_out_f16 || !aligned(cb_out_f16, 16)) return VECINFER_EINVAL;
+    vecinfer_cfg rows_cfg = *cfg;
+    rows_cfg.v_tiled = 0;                  // the assignment output is always rows
+    cfg = &rows_cfg;
     EncodeParams p;
     const bool keys = lambda != nullptr;
     const int rc = encode_args(cfg, x_f16, lambda, keys, cb_in_f16, codes, B, T, 0, T, p);
@@ -351,6 +360,18 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
     return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, k_res_f16,
                          v_res_f16, res_lens, R, r_cap, nullptr, nullptr, num_splits, variant, workspace,
                          workspace_bytes, out_f16, lse, stream);
+}
+
+int vecinfer_export_value_codes(const vecinfer_cfg *cfg, const uint8_t *v_idx_tiled, uint8_t *v_idx_rows, int32_t B,
+                                int64_t N, int64_t n_cap, void *stream)
+{
+    if (!cfg || !v_idx_tiled || !v_idx_rows || v_idx_tiled == v_idx_rows) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg) || cfg->v_bits != 8) return VECINFER_EUNSUPPORTED;
+    if (B < 1 || N < 1 || n_cap < N || n_cap % 64 != 0) return VECINFER_EINVAL;
+    if ((int64_t)B * cfg->num_kv_heads > 65535) return VECINFER_EUNSUPPORTED;
+    return launch_status(launch_export_value_codes(v_idx_tiled, v_idx_rows, B * cfg->num_kv_heads,
+                                                   cfg->head_dim / cfg->v_sub_dim, N, n_cap,
+                                                   static_cast<hipStream_t>(stream)));
 }
 
 int vecinfer_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream)

@@ -24,6 +24,7 @@ struct DecodeParams {
     const int32_t *seq_lens; // [B] or nullptr
     int B, Hq, Hkv, G, D, dk, dv, Mk, Mv;
     int bk, bv;              // code widths: 8, 10 or 12 bits
+    int v_tiled;             // value codes stored in tiles of 64 tokens (v_tiled_offset), 8-bit codes only
     long long N, n_cap;
     int S;                   // number of sequence splits
     float *part_o;           // [B, Hkv, S, G, D]  unnormalised partial outputs
@@ -49,6 +50,20 @@ struct DecodeParams {
     float *new_sc;           // [B, Hkv, Mk, G] score share of each key sub-space (log2 units)
     float *new_v;            // [B, Hkv, D]     dequantized value of the new token
 };
+
+// Tiled value codes: byte offset of (token n, sub-space m) in the cache of one (sequence, KV head).
+// Blocks of 64 tokens.  Lane (k-group kg, column col) of the matrix-core kernel consumes, of a
+// block, 16 R bytes (R = M / 16): for sub-tile st and token 4 v + kg of it, the bytes of sub-spaces
+// R col .. R col + R - 1, in the order j = (st, v, r).  The block is stored as R slabs of 1 KB: slab
+// j / 16 holds bytes j % 16 .. of every lane, lane after lane, so that one 16-byte load per lane
+// reads a whole slab (8 full cache lines).
+__host__ __device__ __forceinline__ size_t v_tiled_offset(long long n, int m, int M)
+{
+    const int R = M / 16, i = (int)(n & 63);
+    const int st = i >> 4, v = (i & 15) >> 2, kg = i & 3, col = m / R, r = m % R;
+    const int j = (st * 4 + v) * R + r;
+    return (size_t)(n >> 6) * 64 * M + (size_t)(j >> 4) * 1024 + (kg * 16 + col) * 16 + (j & 15);
+}
 
 // Token range [n0, n1) of split s for a sequence of `len` tokens: equal chunks rounded
 // up to a multiple of `align` tokens; trailing splits may be empty.
@@ -175,6 +190,7 @@ int launch_merge(const DecodeParams &p, hipStream_t stream);   // splits (+ resi
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma_wide(const DecodeParams &p, hipStream_t stream);   // 10- / 12-bit codes
+int launch_decode_mfma_tiled(const DecodeParams &p, hipStream_t stream);  // 8-bit codes, tiled value codes
 bool decode_mfma_supports(const DecodeParams &p);
 
 struct EncodeParams {
@@ -184,6 +200,7 @@ struct EncodeParams {
     uint8_t *idx;         // [B, Hkv, n_cap, M * bits / 8]
     int B, Hkv, D, d, M;
     int bits;             // code width: 8, 10 or 12
+    int tiled;            // 8-bit value codes written in tiles of 64 tokens (v_tiled_offset)
     long long T, pos0, n_cap;
     // per-sequence append position (T = 1 only): when seq_lens != nullptr the token of sequence b
     // goes to row clamp(seq_lens[b], 0, len_max) - 1, and a sequence of length 0 is skipped
@@ -198,6 +215,8 @@ int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_cou
 int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
                            int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream);
 int launch_encode(const EncodeParams &p, hipStream_t stream);
+int launch_export_value_codes(const uint8_t *tiled, uint8_t *rows, int BH, int M, long long N, long long n_cap,
+                              hipStream_t stream);
 int launch_read_probe(const void *src, size_t bytes, unsigned *sink, int num_cus, hipStream_t stream);
 int launch_calibrate_lambda(const __half *k, float *lam, int B, int Hkv, int D, long long T, float floor_value,
                             hipStream_t stream);

@@ -17,14 +17,17 @@ bool decode_mfma_supports(const DecodeParams &p)
     if (wide(p.bk) || wide(p.bv))
         bits_ok = p.D == 128 && (wide(p.bk) || p.bk == 8) && (wide(p.bv) || p.bv == 8) && p.dk >= 4 && p.dv >= 4;
     // code rows are addressed with 32-bit byte offsets (a row is at most D / 2 bytes)
-    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok && bits_ok &&
-           p.N * (long long)(p.D / 2) < (1LL << 31);
+    // tiled value codes: 8-bit codes on both sides (the instantiations built)
+    const bool tiled_ok = !p.v_tiled || (p.bk == 8 && p.bv == 8 && p.n_cap % 64 == 0);
+    return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok && bits_ok && tiled_ok &&
+           (p.v_tiled ? (p.N + 63) / 64 * 64 : p.N) * (long long)(p.D / 2) < (1LL << 31);
 }
 
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
     if (p.bk != 8 || p.bv != 8) return launch_decode_mfma_wide(p, stream);
+    if (p.v_tiled) return launch_decode_mfma_tiled(p, stream);
     // 8 wavefronts per workgroup (2 per SIMD): 12 measured slower, 4 is latency-bound
     const int key = p.D * 100 + p.dk * 10 + p.dv;
     switch (key) {

@@ -149,7 +149,9 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
 // that can never come, and serialises gathers to do it (58 -> 43 us for d_k = 4, d_v = 8).
 // BK, BV: code widths.  8: one byte per code, one table of 256 centroids per sub-space.  10 or 12:
 // codes packed end to end in the token's row, one table of 2^b centroids for all sub-spaces.
-template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8>
+// VT: 8-bit value codes stored in tiles of 64 tokens (v_tiled_offset): a lane's share of a tile is
+// 16 NROUND_V bytes, fetched with NROUND_V 16-byte loads.
+template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8, bool VT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
 void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half *cb_k_arg, const __half *cb_v_arg,
                         const uint8_t *k_idx_arg, const uint8_t *v_idx_arg, unsigned hkv_g_arg, int S_, DecodeParams p)
@@ -159,6 +161,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                       (DV != 8 || kD == 128),
                   "shapes this kernel is laid out for (d_v = 8 needs 16 value sub-spaces: D = 128)");
     constexpr bool WK = BK > 8, WV = BV > 8;           // wide codes: shared table, packed rows
+    static_assert(!VT || !WV, "tiled value codes are 8-bit codes");
     static_assert((BK == 8 || ((BK == 10 || BK == 12) && kD == 128 && DK >= 4)) &&
                       (BV == 8 || ((BV == 10 || BV == 12) && kD == 128 && DV >= 4)),
                   "wide codes: 10 or 12 bits, D = 128, d = 4 or 8");
@@ -358,12 +361,14 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // valid code) instead of needing a clamp.  The host checks N * M < 2^31.
     const __amdgpu_buffer_rsrc_t rsrc_k =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(krow), 0, (int)((unsigned)n1 * ROWB_K), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_v =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(vrow), 0, (int)((unsigned)n1 * ROWB_V), 0x00020000);
+    // (tiled value codes: whole 64-token blocks; n_cap is a multiple of 64, so the last block exists)
+    const __amdgpu_buffer_rsrc_t rsrc_v = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t *>(vrow), 0, (int)((unsigned)(VT ? (n1 + 63) / 64 * 64 : n1) * ROWB_V), 0x00020000);
     const unsigned koff_lane = WK ? (unsigned)(krow_tok * ROWB_K + 4 * ((kg * (MK / 4) * BK) >> 5))
                                   : (unsigned)(krow_tok * MK + kg * (MK / 4));
     const unsigned voff_lane = WV ? (unsigned)((4 * (col & 3) + kg) * ROWB_V + 4 * (((col >> 2) * (MV / 4) * BV) >> 5))
-                                  : (unsigned)(kg * MV + col * NROUND_V);
+                               : VT ? (unsigned)(lane * 16)
+                                    : (unsigned)(kg * MV + col * NROUND_V);
 
     auto load_codes_k = [&](Codes &cd, long long tb) {
         const unsigned ko = (unsigned)tb * ROWB_K + koff_lane;
@@ -389,6 +394,21 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     };
     auto load_codes_v = [&](Codes &cd, long long tb) {
         const unsigned vo = (unsigned)tb * ROWB_V + voff_lane;
+        if constexpr (VT) {
+            // the lane's 16 NROUND_V bytes of the tile, in the order (sub-tile, token v, round r), 16
+            // from each of the block's NROUND_V slabs of 1 KB: dword j of them is cd.vc[j / NROUND_V][j % NROUND_V]
+            unsigned w[4 * NROUND_V];
+#pragma unroll
+            for (int j = 0; j < NROUND_V; ++j) {
+                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, vo + 1024 * j, 0, 0);
+                w[4 * j] = x[0]; w[4 * j + 1] = x[1]; w[4 * j + 2] = x[2]; w[4 * j + 3] = x[3];
+            }
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int j = 0; j < NROUND_V; ++j) cd.vc[st][j] = w[st * NROUND_V + j];
+            return;
+        }
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             // values: NROUND_V bytes (sub-spaces NROUND_V col ..) of each of the tokens 4 v + kg,
@@ -653,7 +673,9 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                     sm_nsc[m[b4] * KG + lane] = sc;
                 }
             } else {
-                if (lane == 0) p.v_idx_w[((size_t)bg * p.n_cap + pos) * MV + m[b4]] = (uint8_t)code[b4];
+                if (lane == 0)
+                    p.v_idx_w[(size_t)bg * p.n_cap * MV + (VT ? v_tiled_offset(pos, m[b4], MV) : (size_t)pos * MV + m[b4])] =
+                        (uint8_t)code[b4];
                 float mine = (float)win[0];
 #pragma unroll
                 for (int jj = 1; jj < DS; ++jj) mine = lane == jj ? (float)win[jj] : mine;
@@ -1176,7 +1198,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     STAMP_ENTRY_OUT();
 }
 
-template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK, int BV>
+template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK, int BV, bool VT>
 int launch_hg(const DecodeParams &p, hipStream_t stream)
 {
     constexpr int KG = kG * HG;
@@ -1188,20 +1210,20 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
     constexpr size_t smem = loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
     // once per process and instantiation (function-local static: initialised thread-safely)
     static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
     if (!configured) return -4;
     dim3 grid(p.S, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV>), grid, dim3(NW * 64), smem, stream,
+    hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>), grid, dim3(NW * 64), smem, stream,
                        p.q, p.lam, p.cb_k, p.cb_v, p.k_idx, p.v_idx, (unsigned)p.Hkv | (unsigned)p.G << 24, p.S, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
-template <int kD, int DK, int DV, int NW, bool SPLITQ, int BK = 8, int BV = 8>
+template <int kD, int DK, int DV, int NW, bool SPLITQ, int BK = 8, int BV = 8, bool VT = false>
 int launch_typed(const DecodeParams &p, hipStream_t stream)
 {
-    return p.G <= kG ? launch_hg<kD, DK, DV, 1, NW, SPLITQ, BK, BV>(p, stream)
-                     : launch_hg<kD, DK, DV, 2, NW, SPLITQ, BK, BV>(p, stream);
+    return p.G <= kG ? launch_hg<kD, DK, DV, 1, NW, SPLITQ, BK, BV, VT>(p, stream)
+                     : launch_hg<kD, DK, DV, 2, NW, SPLITQ, BK, BV, VT>(p, stream);
 }
 
 } // namespace

@@ -178,8 +178,15 @@ __global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
     }
     __syncthreads();
 
-    // ---- phase 3: M bytes per token, written as 32-bit words (whole rows: coalesced)
-    {
+    // ---- phase 3: M bytes per token, written as 32-bit words (whole rows: coalesced); tiled value
+    // codes byte by byte, each at its place in the token's 64-token block
+    if (p.tiled) {
+        for (int e = tid; e < kEncTokens * M; e += kEncBlock) {
+            const int tl = e / M, m = e - tl * M;
+            const long long t = t0 + tl;
+            if (t < p.T) p.idx[(size_t)bg * p.n_cap * M + v_tiled_offset(p.pos0 + t, m, M)] = idx_s[tl * M + m];
+        }
+    } else {
         constexpr int WPT = M / 4;             // words per token
         for (int e = tid; e < kEncTokens * WPT; e += kEncBlock) {
             const int tl = e / WPT, w = e - tl * WPT;
@@ -314,7 +321,8 @@ __device__ __forceinline__ void encode_token(const EncodeParams &p, float *x_s, 
                 key = other < key ? other : key;
             }
             if (part == 0 && mm < MC)
-                p.idx[((size_t)bg * p.n_cap + pos) * M + m0 + mm] = (uint8_t)(key & 255u);
+                p.idx[(size_t)bg * p.n_cap * M + (p.tiled ? v_tiled_offset(pos, m0 + mm, M) : (size_t)pos * M + m0 + mm)] =
+                    (uint8_t)(key & 255u);
         }
         __syncthreads();
     }
@@ -733,6 +741,28 @@ int launch_append_dk(const EncodeParams &pk, const EncodeParams &pv, hipStream_t
 }
 
 } // namespace
+
+// Tiled value codes -> rows (the N x M code matrix of each (sequence, KV head)).
+namespace {
+__global__ void export_value_codes_kernel(const uint8_t *tiled, uint8_t *rows, int M, long long N, long long n_cap)
+{
+    const size_t bg = blockIdx.y;
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;      // byte of the rows form
+    if (e >= N * M) return;
+    const long long n = e / M;
+    const int m = (int)(e - n * M);
+    rows[bg * (size_t)n_cap * M + e] = tiled[bg * (size_t)n_cap * M + v_tiled_offset(n, m, M)];
+}
+} // namespace
+
+int launch_export_value_codes(const uint8_t *tiled, uint8_t *rows, int BH, int M, long long N, long long n_cap,
+                              hipStream_t stream)
+{
+    const long long blocks = (N * M + 255) / 256;
+    if (BH < 1 || BH > 65535 || blocks > 0x7fffffffLL) return -2;
+    hipLaunchKernelGGL(export_value_codes_kernel, dim3((unsigned)blocks, BH), dim3(256), 0, stream, tiled, rows, M, N, n_cap);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
 
 int append_max_tokens() { return (int)kTokenKernelMaxT; }
 

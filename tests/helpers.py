@@ -13,8 +13,27 @@ LSE_ATOL = 1e-3
 NEAR_TIE = 1e-6     # relative distance gap under which an index mismatch is a logged near-tie
 
 
-def cfg_of(shape):
-    return vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
+def cfg_of(shape, v_tiled=0):
+    return vb.Config(shape.D, shape.Hq, shape.Hkv, shape.d_k, shape.d_v, shape.b_k, shape.b_v, v_tiled)
+
+
+def tile_value_codes(rows):
+    """Value codes [B, Hkv, n_cap, M] (n_cap a multiple of 64) -> the tiled layout of the C header
+    ("Tiled value codes"), written out from its formula: byte of (t, m) at
+    (t/64) 64M + (j/16) 1024 + ((i%4) 16 + m/R) 16 + j%16 with i = t % 64, R = M/16,
+    j = ((i/16) 4 + (i%16)/4) R + m%R."""
+    rows = np.asarray(rows)
+    B, H, n_cap, M = rows.shape
+    assert n_cap % 64 == 0 and M % 16 == 0
+    R = M // 16
+    t = np.arange(n_cap)[:, None]
+    m = np.arange(M)[None, :]
+    i = t % 64
+    j = ((i // 16) * 4 + (i % 16) // 4) * R + m % R
+    off = (t // 64) * 64 * M + (j // 16) * 1024 + ((i % 4) * 16 + m // R) * 16 + j % 16
+    out = np.empty((B, H, n_cap * M), dtype=rows.dtype)
+    out[:, :, off.reshape(-1)] = rows.reshape(B, H, -1)
+    return out.reshape(B, H, n_cap, M)
 
 
 def oracle_view(shape, x):
@@ -34,9 +53,10 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def gpu_decode(shape, x, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT_AUTO, ws=None, want_lse=True):
+def gpu_decode(shape, x, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT_AUTO, ws=None, want_lse=True,
+               v_tiled=0):
     """x: dict of numpy arrays (q, lam, cb_k, cb_v, k_idx, v_idx) -> (out fp16 as f64, lse f64)."""
-    cfg = cfg_of(shape)
+    cfg = cfg_of(shape, v_tiled)
     t = {k: (v if isinstance(v, torch.Tensor) else dev(v)) for k, v in x.items()
          if k in ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx")}
     B = t["q"].shape[0]
@@ -89,9 +109,9 @@ def assert_decode_close(got_out, got_lse, ref_out, ref_lse, what=""):
     return worst
 
 
-def gpu_encode(shape, k=None, lam=None, cb_k=None, v=None, cb_v=None, pos0=0, n_cap=None):
+def gpu_encode(shape, k=None, lam=None, cb_k=None, v=None, cb_v=None, pos0=0, n_cap=None, v_tiled=0):
     """Encode keys and/or values on the GPU; returns uint8 numpy arrays [B, Hkv, n_cap, row bytes]."""
-    cfg = cfg_of(shape)
+    cfg = cfg_of(shape, v_tiled)
     res = []
     if k is not None:
         B, Hkv, T, D = k.shape

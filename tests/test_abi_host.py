@@ -226,3 +226,46 @@ def test_binding_refuses_host_tensors():
         vb.vecinfer_encode_values(CFG, torch.zeros(1, 8, 4, 128, dtype=torch.float16),
                                   torch.zeros(8, 32, 256, 4, dtype=torch.float16),
                                   torch.zeros(1, 8, 8, 32, dtype=torch.uint8))
+
+
+def test_tiled_value_codes_argument_errors():
+    tiled = vb.Config(128, 32, 8, 4, 4, v_tiled=1)
+    # tiled value codes are one byte per code
+    assert _decode(cfg=vb.Config(128, 32, 8, 8, 8, 12, 12, 1), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert _decode(cfg=vb.Config(128, 32, 8, 4, 4, v_tiled=2), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # whole 64-token blocks
+    assert _decode(cfg=tiled, N=1000, n_cap=1000, ws=FAKE, ws_bytes=1 << 30) == vb.EINVAL
+    assert _enc_vals(cfg=tiled, T=4, n_cap=100) == vb.EINVAL
+    # the lookup-table variant reads rows
+    assert _decode(cfg=tiled, variant=vb.VARIANT_LUT, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # export
+    exp = lambda cfg=tiled, src=FAKE, dst=FAKE + 4096, B=1, N=64, n_cap=64: vb.lib().vecinfer_export_value_codes(
+        C.byref(cfg.c()), src, dst, B, N, n_cap, None)
+    assert exp(src=None) == vb.EINVAL
+    assert exp(dst=FAKE) == vb.EINVAL                       # in place
+    assert exp(N=0) == vb.EINVAL
+    assert exp(N=65) == vb.EINVAL
+    assert exp(N=60, n_cap=100) == vb.EINVAL
+    assert exp(cfg=vb.Config(128, 32, 8, 8, 8, 8, 12)) == vb.EUNSUPPORTED
+
+
+def test_tiled_layout_formula():
+    """The test-side tiling (written from the header's formula) is a permutation of each 64-token
+    block, and a lane finds its 16 R bytes as 16 from each of the block's R slabs of 1 KB: the bytes
+    the header promises."""
+    from helpers import tile_value_codes
+    for M in (16, 32, 64):
+        R = M // 16
+        rows = np.arange(2 * 128 * M, dtype=np.int64).reshape(1, 2, 128, M)
+        tiled = tile_value_codes(rows).reshape(1, 2, 128 * M)
+        for h in range(2):
+            for blk in range(2):
+                got = np.sort(tiled[0, h, blk * 64 * M:(blk + 1) * 64 * M])
+                np.testing.assert_array_equal(got, np.sort(rows[0, h, blk * 64:(blk + 1) * 64].reshape(-1)))
+        # lane (kg, col) of block 1: tokens 64 + 16 st + 4 v + kg, sub-spaces R col .. R col + R - 1
+        kg, col = 2, 5
+        lane = kg * 16 + col
+        run = np.concatenate([tiled[0, 1, 64 * M + s * 1024 + lane * 16: 64 * M + s * 1024 + lane * 16 + 16]
+                              for s in range(R)])
+        want = [rows[0, 1, 64 + 16 * st + 4 * v + kg, R * col + r] for st in range(4) for v in range(4) for r in range(R)]
+        np.testing.assert_array_equal(run, np.array(want))
