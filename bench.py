@@ -29,7 +29,7 @@ METRIC = "fused VQ decode-attn: compressed-KV GB/s (% HBM peak) + µs/step, 8B @
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per attention launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a copy
 # kernel of known size); see profiles/decode_attention_b2d4_196k_hbm_traffic.txt.  Not measured live.
-MEASURED_TRAFFIC_BYTES = {"196k-b2d4": 102.01e6 + 0.54e6}
+MEASURED_TRAFFIC_BYTES = {"196k-b2d4": 101.99e6 + 0.54e6}
 
 
 def main() -> int:
