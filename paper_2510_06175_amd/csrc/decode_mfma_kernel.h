@@ -154,7 +154,7 @@ __device__ __forceinline__ unsigned pack_dup_f16(float p)
 template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8, bool VT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
 void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half *cb_k_arg, const __half *cb_v_arg,
-                        const uint8_t *k_idx_arg, const uint8_t *v_idx_arg, unsigned hkv_g_arg, int S_, DecodeParams p)
+                        const __half *k_new_arg, const __half *v_new_arg, unsigned hkv_g_arg, int S_, DecodeParams p)
 {
     constexpr int KG = kG * HG;                        // head slots of the workgroup
     static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DV == 8 || DV == 4 || DV == 2) &&
@@ -232,16 +232,20 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // beside these requests instead of ahead of them.
     // The wavefront's small input rows are requested first: loads come back in order, so the
     // query transform below runs while the codebooks and the first code tiles are still on their way
-    // (wavefront hh < G: query head hh).  Every wavefront issues the same loads (a wavefront
-    // without a query head reads a row that exists anyway and ignores it), and the fp16 rows are
-    // kept as raw bits until they are used: neither a branch nor a conversion makes the wavefront
-    // wait here for data it has only just requested.
+    // (wavefront hh < G: query head hh; the last two wavefronts: key and value row of a fused new
+    // token).  Every wavefront issues the same six loads (a wavefront without a query head, or a
+    // launch without a new token, reads a row that exists anyway and ignores it), and the fp16
+    // rows are kept as raw bits until they are used: neither a branch nor a conversion makes the
+    // wavefront wait here for data it has only just requested.
     auto raw16 = [](const __half *src) -> unsigned { return *reinterpret_cast<const unsigned short *>(src); };
     auto widen = [](unsigned bits) { return (float)__builtin_bit_cast(_Float16, (unsigned short)bits); };
     const bool q_role = wave < KG && wave < G_;
     const __half *const qsrc = q_arg + (((size_t)b * Hkv_ + g) * G_ + (q_role ? wave : 0)) * kD;
     const unsigned qh0 = raw16(qsrc + lane), qh1 = raw16(qsrc + (kD == 128 ? 64 : 0) + lane);
     const float ql0 = lam_arg[(size_t)g * kD + lane], ql1 = lam_arg[(size_t)g * kD + (kD == 128 ? 64 : 0) + lane];
+    const __half *const nsrc = k_new_arg ? (wave == NW - 1 ? v_new_arg : k_new_arg) + bg * kD : qsrc;
+    const unsigned nh0 = raw16(nsrc + lane), nh1 = raw16(nsrc + (kD == 128 ? 64 : 0) + lane);
+    const float nl0 = ql0, nl1 = ql1;
     asm volatile("" ::: "memory");                 // keep these loads ahead of the big ones below
     constexpr int CPL = 16 / ENTRY_V;                  // codes per 16-byte load of the value codebook
     // each codebook is staged as items of 1 KB (one wavefront instruction each), dealt round-robin
@@ -288,14 +292,14 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // itself the compiler fetches them where they are first needed, one cold trip to the argument
     // buffer after the other along the prologue.
 #define VECINFER_PIN(x) asm volatile("" ::"s"(x))
-    VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N); VECINFER_PIN(p.n_cap); VECINFER_PIN(p.k_new); VECINFER_PIN(p.v_new);
+    VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N); VECINFER_PIN(p.n_cap); VECINFER_PIN(p.k_idx); VECINFER_PIN(p.v_idx);
 #undef VECINFER_PIN
 
     // With a fused append the new token is the sequence's last one: its codes are produced in
     // this launch (below), so the tile loop covers the len - 1 older tokens only.  Workgroup s
     // encodes sub-spaces s, s + S, ... of the new token's key and value.
     const long long len = seq_len_of(p, b);
-    const bool fused = p.k_new != nullptr && len > 0;
+    const bool fused = k_new_arg != nullptr && len > 0;
     // items of the new token that are shared out: sub-spaces (8-bit codes), or groups of four
     // sub-spaces whose codes fill a whole number of bytes (10- and 12-bit codes)
     constexpr int ITEMS_K = WK ? MK / 4 : MK, ITEMS_V = WV ? MV / 4 : MV;
@@ -341,8 +345,8 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     const unsigned pos_k = (unsigned)(kg * (MK / 4) * BK) & 31u;
     const unsigned pos_v = ((unsigned)((col >> 2) * (MV / 4) * BV) & 31u) + (unsigned)((col & 3) * NROUND_V * BV);
 
-    const uint8_t *krow = k_idx_arg + bg * p.n_cap * ROWB_K;
-    const uint8_t *vrow = v_idx_arg + bg * p.n_cap * ROWB_V;
+    const uint8_t *krow = p.k_idx + bg * p.n_cap * ROWB_K;
+    const uint8_t *vrow = p.v_idx + bg * p.n_cap * ROWB_V;
     const long long last = n1 - 1;
 
     // token owned by A-row i of sub-tile st: base + 16 st + 4 (i % 4) + i / 4, so that D-register v
@@ -469,12 +473,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     };
     Codes ca, cb;
 
-    // the last two wavefronts: key and value row of a fused new token (any other wavefront, or a
-    // launch without one, re-reads its query row and ignores it)
-    const __half *const nsrc = has_new ? (wave == NW - 1 ? p.v_new : p.k_new) + bg * kD : qsrc;
-    const unsigned nh0 = raw16(nsrc + lane), nh1 = raw16(nsrc + (kD == 128 ? 64 : 0) + lane);
-    const float nl0 = ql0, nl1 = ql1;
-    asm volatile("" ::: "memory");                 // ahead of the code tiles
     // The first two tiles' codes start their trip from HBM now, under the prologue.  They are
     // requested after the codebooks: loads return in order, and the first touch of the code stream
     // is the slowest load of the kernel, so the other way round the staging would wait behind it.
@@ -1215,7 +1213,7 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
     if (!configured) return -4;
     dim3 grid(p.S, p.Hkv, p.B);
     hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>), grid, dim3(NW * 64), smem, stream,
-                       p.q, p.lam, p.cb_k, p.cb_v, p.k_idx, p.v_idx, (unsigned)p.Hkv | (unsigned)p.G << 24, p.S, p);
+                       p.q, p.lam, p.cb_k, p.cb_v, p.k_new, p.v_new, (unsigned)p.Hkv | (unsigned)p.G << 24, p.S, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
