@@ -54,7 +54,7 @@
 extern "C" {
 #endif
 
-#define VECINFER_VERSION 100          /* major*10000 + minor*100 + patch */
+#define VECINFER_VERSION 200          /* major*10000 + minor*100 + patch */
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
 #define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
 #define VECINFER_MAX_RESIDUAL 128     /* most rows of the full-precision residual window */

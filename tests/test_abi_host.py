@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_strerror():
-    assert vb.vecinfer_version() == 100
+    assert vb.vecinfer_version() == 200
     assert vb.strerror(0) == "ok"
     for code in (vb.EINVAL, vb.EUNSUPPORTED, vb.EWORKSPACE, vb.ELAUNCH):
         assert vb.strerror(code) not in ("ok", "unknown error code")
