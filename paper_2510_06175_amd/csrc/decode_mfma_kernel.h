@@ -1,5 +1,6 @@
 // Kernel template of the matrix-core decode attention; included by the translation units that
-// instantiate it (8-bit codes: decode_mfma.hip; 10- and 12-bit codes: decode_mfma_wide.hip).
+// instantiate it (8-bit codes: decode_mfma.hip; 8-bit codes with the value codes in the tiled
+// layout: decode_mfma_tiled.hip; 10- and 12-bit codes: decode_mfma_wide.hip).
 //
 // Matrix-core decode attention for gfx950: head dim D = 128 or 64, G = 1 .. 8 query heads
 // per KV head (more than 4: two passes of 4 over the same gathered operands), sub-vector dims d_k, d_v = 8,
