@@ -177,6 +177,23 @@ def test_decode_step_tiled(shape, splits):
     assert_decode_close(t[0].astype(np.float64), t[1].astype(np.float64), *ref, what=f"tiled step {_id(shape)}")
 
 
+def test_decode_step_tiled_full_size_196k():
+    """The configuration bench.py times (32 / 8 heads, 196608 tokens, b2d4, tiled value codes): the
+    whole step equals the step on the rows cache bit for bit (which the parity tests check against
+    the oracle at this size), and the new token's codes sit at their tiled places."""
+    shape = synth.LLAMA8B_196K
+    x = synth.decode_inputs(shape, seed=4)
+    g = synth.rng(45)
+    k_new = synth.values(g, shape.B, shape.Hkv, 1, shape.D)
+    v_new = synth.values(g, shape.B, shape.Hkv, 1, shape.D)
+    r = _step(shape, x, k_new, v_new, 0)
+    t = _step(shape, x, k_new, v_new, 1)
+    np.testing.assert_array_equal(t[0], r[0])
+    np.testing.assert_array_equal(t[1], r[1])
+    np.testing.assert_array_equal(t[2], r[2])
+    np.testing.assert_array_equal(t[3], tile_value_codes(r[3]))
+
+
 def test_decode_step_tiled_ragged():
     shape = synth.Shape(4, 8, 2, 128, 900, 4, 4)
     x = synth.decode_inputs(shape, seed=41, n_cap=1024)
