@@ -7,7 +7,8 @@ import pytest
 import oracle
 from paper_2510_06175_amd import synth
 
-from helpers import assert_decode_close, assert_indices_match, gpu_decode, gpu_encode, oracle_view
+from helpers import (assert_decode_close, assert_indices_match, gpu_decode, gpu_encode, oracle_view,
+                     tile_value_codes)
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +63,15 @@ def test_decode_random_configurations(case):
         sub = {k: (v[keep] if k in ("q", "k_idx", "v_idx") else v) for k, v in x.items()}
         ref_o, ref_l = _oracle_decode(shape, sub, lens_a[keep])
         assert_decode_close(got_o[keep], got_l[keep], ref_o, ref_l, what=f"random {_id(shape)} S={S}")
+    if shape.b_k == 8 and shape.b_v == 8:
+        # the tiled layout of the value codes feeds the same arithmetic: same bits out
+        cap = (shape.N + 63) // 64 * 64
+        x2 = synth.decode_inputs(shape, seed=seed + 1, n_cap=cap)
+        rows = gpu_decode(shape, x2, seq_lens=lens, N=shape.N, num_splits=S)
+        tiled = gpu_decode(shape, dict(x2, v_idx=tile_value_codes(x2["v_idx"])), seq_lens=lens, N=shape.N,
+                           num_splits=S, v_tiled=1)
+        np.testing.assert_array_equal(tiled[0], rows[0])
+        np.testing.assert_array_equal(tiled[1], rows[1])
 
 
 def _random_encode_cases(n, seed):
