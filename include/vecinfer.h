@@ -134,7 +134,9 @@ int vecinfer_encode_keys(const vecinfer_cfg *cfg, const void *k_f16, const float
 
 /*
  * Cache fill for values: Eq. 8 on the untransformed values (no smoothing, no Hadamard).
- * Same argmin rule, layouts and errors as vecinfer_encode_keys, with d_v / M_v.
+ * Same argmin rule, layouts and errors as vecinfer_encode_keys, with d_v / M_v.  With
+ * cfg.v_tiled = 1 each code goes to its place in the tiled layout ("Tiled value codes"; EINVAL
+ * unless n_cap is a multiple of 64); bytes of other tokens of a block are left as they are.
  */
 int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const void *cb_v_f16,
                            uint8_t *v_idx, int32_t B, int64_t T, int64_t pos0,
@@ -142,7 +144,8 @@ int vecinfer_encode_values(const vecinfer_cfg *cfg, const void *v_f16, const voi
 
 /*
  * Decode-time append of Eq. 9 in one launch: the same result as vecinfer_encode_keys followed
- * by vecinfer_encode_values on the T new tokens (identical codes), for 1 <= T <= VECINFER_MAX_APPEND.
+ * by vecinfer_encode_values on the T new tokens (identical codes, value codes tiled when
+ * cfg.v_tiled is set), for 1 <= T <= VECINFER_MAX_APPEND.
  * Arguments and errors as for those two calls; EINVAL if T > VECINFER_MAX_APPEND.
  */
 int vecinfer_append_kv(const vecinfer_cfg *cfg, const void *k_f16, const void *v_f16,
@@ -213,7 +216,8 @@ size_t vecinfer_decode_workspace_bytes(const vecinfer_cfg *cfg, int32_t B, int64
  * is cut into `num_splits` chunks handled by different workgroups; their (o, m, l)
  * partials go through `workspace` and are merged by log-sum-exp by a second small kernel
  * enqueued right behind (with one split the attention kernel finalises by itself).
- * The result does not depend on num_splits beyond fp32 rounding.
+ * The result does not depend on num_splits beyond fp32 rounding, and not at all on the layout
+ * of the value codes (cfg.v_tiled: v_idx is then read as tiles; n_cap a multiple of 64, else EINVAL).
  *   seq_lens  int32 [B] on the device, or NULL: every sequence has N tokens.  Values are
  *             clamped to [0, N]; a sequence of length 0 yields o = 0 and L = -inf.
  *   N         tokens attended (upper bound when seq_lens is given), 1 <= N <= n_cap
@@ -274,7 +278,8 @@ int vecinfer_decode_attention_residual(const vecinfer_cfg *cfg, const void *q_f1
  * the older tokens streams, and the merge kernel joins the new token as one more partial.
  * The lookup-table variant runs the append kernel first.
  *   k_new_f16, v_new_f16  fp16 [B, H_kv, 1, D]
- *   k_idx, v_idx          as in vecinfer_decode_attention, but written at row len_b - 1
+ *   k_idx, v_idx          as in vecinfer_decode_attention, but written at row len_b - 1 (with
+ *                         cfg.v_tiled the value codes of that token go to their tiled places)
  * Everything else, the workspace size and the errors as for vecinfer_decode_attention
  * (EINVAL also for NULL k_new_f16 / v_new_f16).
  */
