@@ -3,10 +3,6 @@
 
 namespace vecinfer {
 
-#ifdef VECINFER_PHASE_TIMING
-extern "C" int vecinfer_debug_phase_buffer(void *buf) { return hipMemcpyToSymbol(HIP_SYMBOL(g_phase_buf), &buf, sizeof(buf)) == hipSuccess ? 0 : -4; }
-#endif
-
 bool decode_mfma_supports(const DecodeParams &p)
 {
     const bool dk_ok = p.dk == 8 || p.dk == 4 || p.dk == 2;

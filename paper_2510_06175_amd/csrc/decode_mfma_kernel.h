@@ -37,20 +37,6 @@
 
 namespace vecinfer {
 
-#ifdef VECINFER_PHASE_TIMING
-__device__ unsigned long long *g_phase_buf = nullptr;
-#define STAMP(i) do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + (i)] = wall_clock64(); } while (0)
-// per-wavefront stamp: slot 8 * (j + 1) + wave, j in {0, 1, 2}
-#define STAMPW(j) do { if (g_phase_buf && (threadIdx.x & 63) == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 8 * ((j) + 1) + (threadIdx.x >> 6)] = wall_clock64(); } while (0)
-// time of entry, taken before the first memory access and written out with the last stamp (slot 6)
-#define STAMP_ENTRY() const unsigned long long t_entry = wall_clock64()
-#define STAMP_ENTRY_OUT() do { if (g_phase_buf && threadIdx.x == 0) g_phase_buf[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 32 + 6] = t_entry; } while (0)
-#else
-#define STAMP(i)
-#define STAMPW(j)
-#define STAMP_ENTRY()
-#define STAMP_ENTRY_OUT()
-#endif
 
 namespace {
 
@@ -211,8 +197,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     float *const sm_nsc = sm_new + 2 * kD;                                 // [MK][KG]: its score shares (log2 units)
     float *const sm_nv = sm_nsc + MK * KG;                                 // [D]:    its dequantized value
     unsigned long long *const sm_red = reinterpret_cast<unsigned long long *>(sm_nv + kD);   // [4][NW] (wide codes)
-
-    STAMP_ENTRY();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int Hkv_ = (int)(hkv_g_arg & 0xffffffu), G_ = (int)(hkv_g_arg >> 24);   // = p.Hkv, p.G
     // Workgroups are dealt to the 8 XCDs round-robin in linear order, so the KV head varies
@@ -223,10 +207,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     const int col = lane & 15;       // MFMA row (A) / column (B, D) index of this lane
     const int kg = lane >> 4;        // k-group (A, B) / row group (D) of this lane
     const size_t bg = (size_t)b * Hkv_ + g;
-    STAMP(0);
-#ifdef VECINFER_PROLOGUE_STAMPS
-    STAMPW(0);
-#endif
     // ---- The kernel's first memory requests use nothing but the leading arguments, which the
     // command processor can place in scalar registers before the wavefront starts (kernel-argument
     // preloading); everything else of `p` takes a trip to the argument buffer, which now runs
@@ -271,9 +251,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             if (kStageK % NW == 0 || it < kStageK)
                 kreg[j] = *reinterpret_cast<const uintx4 *>(srck + it * 1024 + lane * 16);
         }
-#ifdef VECINFER_PROLOGUE_STAMPS
-        STAMPW(1);
-#endif
         // The value codebook is transposed on the way, through registers: a lane loads 16 bytes
         // (CPL = 16 / ENTRY_V consecutive codes of one sub-space) and writes them entry by entry.
         // The 16 lanes of a quarter-wavefront hold 16 different col (distinct banks on the write);
@@ -512,9 +489,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // is the slowest load of the kernel, so the other way round the staging would wait behind it.
     load_codes(ca, tile_base(0));
     load_codes(cb, tile_base(1));
-#ifdef VECINFER_PROLOGUE_STAMPS
-    STAMPW(2);
-#endif
     // ---- q~ = (q * lambda) H_D for the 4 heads of the group (un-normalised butterflies):
     // wavefront hh transforms head hh in registers, a lane holding channels `lane` and
     // `lane + 64`: one in-lane butterfly (partner distance 64), six across lanes.
@@ -605,7 +579,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         }
     }
     __syncthreads();
-    STAMP(1);
 
     // ---- B operands of the score MFMAs: q~_h[(D/4) kg + 8r .. +8); columns with t0 < 2 take the
     // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
@@ -827,8 +800,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             new_items(kv_c, std::integral_constant<int, 1>{}, first);
         }
     };
-
-    STAMP(2);
     float m_run[HG];                  // running max of head 4 hg + col/4 (log2 units), same in all its lanes
     float l_part[HG];                 // this lane's share of the running sum
     floatx4 acc_o[HG][NACC];
@@ -1127,9 +1098,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // Two tiles of codes in flight: a tile's registers are refilled (two tiles ahead) as soon as
     // the last gather that uses them has been issued.  Loads past the end of the split return code 0 (buffer
     // range check), so the refill and the look-ahead gathers need no bounds branch.
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(0);
-#endif
     {
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -1154,10 +1122,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         if constexpr (!WK) items8(std::integral_constant<int, 0>{});
         if constexpr (!WV) items8(std::integral_constant<int, 1>{});
     }
-    STAMP(3);
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(1);
-#endif
     // ---- merge the wavefronts of this split through LDS (the codebooks are no longer needed)
     float l_head[HG];
 #pragma unroll
@@ -1167,10 +1131,27 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         l_head[hg] += __shfl_xor(l_head[hg], 16);
         l_head[hg] += __shfl_xor(l_head[hg], 32);
     }
+    // A single split folds the fused new token in below.  Its score shares and dequantized value
+    // sit in the scratch behind the tables, and with small shared tables (10-bit codes on both
+    // sides, two head groups) the wavefronts' partials written next reach into that scratch:
+    // every thread takes what it will need into registers first.
+    constexpr int kMergeIters = (KG * kD + BLOCK - 1) / BLOCK;
+    const bool fold_new = S_ == 1 && !p.k_res && has_new;
+    float new_s[kMergeIters], new_val[kMergeIters];
+    if (fold_new) {
+        __syncthreads();                                   // the items' scratch writes
+#pragma unroll
+        for (int i = 0; i < kMergeIters; ++i) {
+            const int e = tid + i * BLOCK, hh = e / kD, c = e % kD;
+            new_s[i] = 0.f;
+            new_val[i] = 0.f;
+            if (e < G_ * kD) {
+                for (int m = 0; m < MK; ++m) new_s[i] += sm_nsc[m * KG + hh];
+                new_val[i] = sm_nv[c];
+            }
+        }
+    }
     __syncthreads();
-#ifndef VECINFER_PROLOGUE_STAMPS
-    STAMPW(2);
-#endif
     float *const sm_o = reinterpret_cast<float *>(smem);                  // [NW][KG][D]
     float *const sm_m = sm_o + NW * KG * kD;                              // [NW][KG]
     float *const sm_l = sm_m + NW * KG;                                   // [NW][KG]
@@ -1188,7 +1169,10 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         }
     }
     __syncthreads();
-    for (int e = tid; e < G_ * kD; e += BLOCK) {
+#pragma unroll
+    for (int it = 0; it < kMergeIters; ++it) {
+        const int e = tid + it * BLOCK;
+        if (e >= G_ * kD) break;
         const int hh = e / kD, c = e % kD;
         float mx = -INFINITY;
 #pragma unroll
@@ -1205,11 +1189,10 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             // the workgroup holds the whole answer (a single split also encoded every sub-space of
             // a fused new token): fold the new token in and write the output rows
             if (has_new) {
-                float s_new = 0.f;
-                for (int m = 0; m < MK; ++m) s_new += sm_nsc[m * KG + hh];
+                const float s_new = new_s[it];
                 const float mt = fmaxf(mx, s_new);
                 const float f = __builtin_amdgcn_exp2f(mx - mt), wgt = __builtin_amdgcn_exp2f(s_new - mt);
-                o = f * o + wgt * sm_nv[c];
+                o = f * o + wgt * new_val[it];
                 l = f * l + wgt;
                 mx = mt;
             }
@@ -1225,9 +1208,6 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             }
         }
     }
-    STAMP(4);
-    STAMP(5);
-    STAMP_ENTRY_OUT();
 }
 
 template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK, int BV, bool VT>

@@ -1,6 +1,5 @@
 // Matrix-core decode attention, 8-bit codes with the value codes stored in tiles of 64 tokens
 // (cfg.v_tiled): instantiations and dispatch (kernel: decode_mfma_kernel.h).
-#undef VECINFER_PHASE_TIMING
 #include "decode_mfma_kernel.h"
 
 namespace vecinfer {

@@ -1,7 +1,6 @@
 // Matrix-core decode attention with 10- or 12-bit codes on the key side, the value side or both
 // (d8b12, d4b12, K-d4b10 / V-d8b12, K-d8b12 / V-d8b8, ... of Sec. 4.1): instantiations and dispatch
 // (kernel: decode_mfma_kernel.h).  D = 128, d = 4 or 8 on both sides.
-#undef VECINFER_PHASE_TIMING
 #include "decode_mfma_kernel.h"
 
 namespace vecinfer {

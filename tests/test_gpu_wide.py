@@ -271,6 +271,11 @@ STEP_WIDE = [
     synth.Shape(1, 8, 2, 128, 2100, 4, 8, 10, 12),
     synth.Shape(2, 4, 1, 128, 700, 4, 4, 12, 12),
     synth.Shape(1, 16, 2, 128, 900, 8, 8, 10, 10),       # G = 8
+    # G = 8 with small shared tables: with one split the wavefronts' partials (32 KB) reach past the
+    # tables into the new token's scratch, which must have been read by then
+    synth.Shape(1, 16, 2, 128, 900, 4, 4, 10, 10),
+    synth.Shape(1, 16, 2, 128, 900, 4, 8, 10, 10),
+    synth.Shape(2, 12, 2, 128, 333, 4, 4, 10, 10),       # G = 6
     synth.Shape(2, 8, 2, 128, 800, 8, 8, 12, 8),         # keys wide, values 8-bit
     synth.Shape(1, 6, 2, 128, 650, 4, 8, 8, 12),         # keys 8-bit, values wide, G = 3
     synth.Shape(1, 8, 2, 128, 1, 8, 8, 12, 12),          # the new token is the only one
