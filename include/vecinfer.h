@@ -58,6 +58,7 @@ extern "C" {
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
 #define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
 #define VECINFER_MAX_RESIDUAL 128     /* most rows of the full-precision residual window */
+#define VECINFER_STATIC_SCRATCH_BYTES (4u << 20) /* workspace limit of vecinfer_decode_attention_static */
 #define VECINFER_LAMBDA_FLOOR 1e-5f    /* smallest smoothing factor vecinfer_calibrate_lambda returns */
 
 enum {
@@ -236,6 +237,31 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
                               const int32_t *seq_lens, int32_t B, int64_t N, int64_t n_cap,
                               int32_t num_splits, int32_t variant, void *workspace,
                               size_t workspace_bytes, void *out_f16, float *lse, void *stream);
+
+/*
+ * vecinfer_decode_attention for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (minus the workspace), same kernels, same results bit for bit.
+ * The split partials go to a fixed array of VECINFER_STATIC_SCRATCH_BYTES (4 MiB) inside the
+ * library's device code; every GPU the library runs on holds its own copy until the process ends.
+ * The call allocates and frees nothing, on the device or through any library; the first call
+ * on a device looks the array's address up once (make that first call outside a capture).
+ *   - A request whose workspace (vecinfer_decode_workspace_bytes for the same cfg, B, N,
+ *     num_splits) exceeds VECINFER_STATIC_SCRATCH_BYTES returns EWORKSPACE; nothing is enqueued.
+ *     (Llama-3.1-8B shapes: B = 1 with 32 splits needs 0.55 MiB; B x H_q x splits x (D + 2)
+ *     floats in general.)
+ *   - All calls on one GPU share that GPU's array.  It needs no clearing (every partial a merge
+ *     reads was written by the attention kernel of the same call), but calls that overlap on one
+ *     GPU - different streams without ordering, or different host threads - race on it: order them.
+ * Errors: as vecinfer_decode_attention, EWORKSPACE as above, ELAUNCH if the device query or the
+ * address lookup fails.
+ */
+int vecinfer_decode_attention_static(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                                     const void *cb_k_f16, const void *cb_v_f16,
+                                     const uint8_t *k_idx, const uint8_t *v_idx,
+                                     const int32_t *seq_lens, int32_t B, int64_t N, int64_t n_cap,
+                                     int32_t num_splits, int32_t variant, void *out_f16, float *lse,
+                                     void *stream);
 
 /*
  * Decode step with a full-precision residual window.  The paper's runs keep the most recent

@@ -25,6 +25,7 @@ EXPORTS = [
     "vecinfer_encode_keys", "vecinfer_encode_values", "vecinfer_append_kv", "vecinfer_decode_auto_splits",
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
+    "vecinfer_decode_attention_static",
     "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
     "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda", "vecinfer_read_probe",
     "vecinfer_export_value_codes",
@@ -100,6 +101,9 @@ def lib() -> C.CDLL:
         L.vecinfer_decode_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32,
                                                 i32, vp, sz, vp, vp, vp]
         L.vecinfer_decode_attention.restype = C.c_int
+        L.vecinfer_decode_attention_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, i32,
+                                                       i32, vp, vp, vp]
+        L.vecinfer_decode_attention_static.restype = C.c_int
         L.vecinfer_decode_attention_residual.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64, vp, vp,
                                                          vp, i32, i64, i32, i32, vp, sz, vp, vp, vp]
         L.vecinfer_decode_attention_residual.restype = C.c_int
@@ -224,6 +228,31 @@ def vecinfer_decode_attention(cfg: Config, q_f16, lam, cb_k, cb_v, k_idx, v_idx,
         _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
         None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
         B, N, n_cap, num_splits, variant, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
+        None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
+        _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def vecinfer_decode_attention_static(cfg: Config, q_f16, lam, cb_k, cb_v, k_idx, v_idx, out_f16,
+                                     lse=None, seq_lens=None, N: int | None = None, num_splits: int = 0,
+                                     variant: int = VARIANT_AUTO, stream=None) -> None:
+    """vecinfer_decode_attention without a workspace argument: the split partials live in a fixed
+    array inside the library (STATIC_SCRATCH_BYTES per GPU); the call allocates nothing."""
+    B = q_f16.shape[0]
+    n_cap = k_idx.shape[2]
+    N = n_cap if N is None else N
+    _check(lib().vecinfer_decode_attention_static(
+        C.byref(cfg.c()), _dev(q_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "q_f16"),
+        _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb_k, torch.float16, cfg.cb_shape(True), "cb_k"),
+        _dev(cb_v, torch.float16, cfg.cb_shape(False), "cb_v"),
+        _dev(k_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(True)), "k_idx"),
+        _dev(v_idx, torch.uint8, (B, cfg.num_kv_heads, n_cap, cfg.row_bytes(False)), "v_idx"),
+        None if seq_lens is None else _dev(seq_lens, torch.int32, (B,), "seq_lens"),
+        B, N, n_cap, num_splits, variant,
         _dev(out_f16, torch.float16, (B, cfg.num_q_heads, cfg.head_dim), "out_f16"),
         None if lse is None else _dev(lse, torch.float32, (B, cfg.num_q_heads), "lse"),
         _stream(stream)))

@@ -3,7 +3,16 @@
 
 #include "common.h"
 
+#include <atomic>
+#include <mutex>
+
 using namespace vecinfer;
+
+// Split partials of vecinfer_decode_attention_static: one fixed array per GPU (every device the
+// library's code object is loaded on holds its own copy, at its own address, until the process
+// ends).  In host code the name is only a handle for hipGetSymbolAddress; the address that call
+// returns is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[VECINFER_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -55,6 +64,28 @@ int32_t auto_splits(const vecinfer_cfg *c, int32_t B, int64_t N)
     if (s > VECINFER_MAX_SPLITS) s = VECINFER_MAX_SPLITS;
     if (s < 1) s = 1;
     return (int32_t)s;
+}
+
+// Device address of `scratch` on the current device, resolved once per device.
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VECINFER_ELAUNCH;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return VECINFER_ELAUNCH;
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *ptr = p;
+    return VECINFER_OK;
 }
 
 struct WorkspaceLayout {
@@ -334,6 +365,26 @@ int vecinfer_decode_attention(const vecinfer_cfg *cfg, const void *q_f16, const 
     return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, nullptr,
                          nullptr, nullptr, 0, 0, nullptr, nullptr, num_splits, variant, workspace,
                          workspace_bytes, out_f16, lse, stream);
+}
+
+int vecinfer_decode_attention_static(const vecinfer_cfg *cfg, const void *q_f16, const float *lambda,
+                                     const void *cb_k_f16, const void *cb_v_f16, const uint8_t *k_idx,
+                                     const uint8_t *v_idx, const int32_t *seq_lens, int32_t B, int64_t N,
+                                     int64_t n_cap, int32_t num_splits, int32_t variant, void *out_f16, float *lse,
+                                     void *stream)
+{
+    // the size check comes first: a request that does not fit is refused before anything else happens
+    if (!cfg) return VECINFER_EINVAL;
+    if (!cfg_ok(cfg)) return VECINFER_EUNSUPPORTED;
+    if (B < 1 || N < 1 || num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
+    const int32_t S = num_splits ? num_splits : auto_splits(cfg, B, N);
+    if (ws_layout(cfg, B, S).total > (size_t)VECINFER_STATIC_SCRATCH_BYTES) return VECINFER_EWORKSPACE;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != VECINFER_OK) return rc;
+    return decode_common(cfg, q_f16, lambda, cb_k_f16, cb_v_f16, k_idx, v_idx, seq_lens, B, N, n_cap, nullptr,
+                         nullptr, nullptr, 0, 0, nullptr, nullptr, num_splits, variant, ws,
+                         VECINFER_STATIC_SCRATCH_BYTES, out_f16, lse, stream);
 }
 
 int vecinfer_decode_step(const vecinfer_cfg *cfg, const void *q_f16, const void *k_new_f16,

@@ -269,3 +269,22 @@ def test_tiled_layout_formula():
                               for s in range(R)])
         want = [rows[0, 1, 64 + 16 * st + 4 * v + kg, R * col + r] for st in range(4) for v in range(4) for r in range(R)]
         np.testing.assert_array_equal(run, np.array(want))
+
+
+def test_static_entry_refuses_before_any_device_call():
+    """vecinfer_decode_attention_static: argument and size checks come before the device is
+    touched, so they can be exercised on the host."""
+    def call(cfg=CFG, B=1, N=1024, splits=4, q=FAKE):
+        return vb.lib().vecinfer_decode_attention_static(C.byref(cfg.c()), q, FAKE, FAKE, FAKE, FAKE, FAKE, None,
+                                                         B, N, N, splits, vb.VARIANT_AUTO, FAKE, None, None)
+    assert vb.lib().vecinfer_decode_attention_static(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, 64, 1,
+                                                     vb.VARIANT_AUTO, FAKE, None, None) == vb.EINVAL
+    assert call(cfg=vb.Config(96, 32, 8, 4, 4)) == vb.EUNSUPPORTED
+    assert call(B=0) == vb.EINVAL
+    assert call(N=0) == vb.EINVAL
+    assert call(splits=vb.MAX_SPLITS + 1) == vb.EINVAL
+    # 8 sequences x 32 heads x 64 splits x 130 floats = 8.5 MB of partials: over the 4 MiB array
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 8, 4096, 64) > vb.STATIC_SCRATCH_BYTES
+    assert call(B=8, N=4096, splits=64) == vb.EWORKSPACE
+    # the headline shape fits with room to spare
+    assert vb.vecinfer_decode_workspace_bytes(CFG, 1, 196608, 32) < vb.STATIC_SCRATCH_BYTES // 4
