@@ -65,7 +65,7 @@ def main() -> int:
                     help="override the workload's cache length N (the 32k .. 196k ladder); a side measurement")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = auto)")
     ap.add_argument("--splits", type=int, default=0)
-    ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "lut", "mfma", "roles"])
     ap.add_argument("--v-layout", default="auto", choices=["auto", "rows", "tiled"],
                     help="physical layout of the value code cache: rows [n_cap, M_v], or tiles of 64 tokens "
                          "in the attention kernel's own order (cfg.v_tiled); auto = tiled where it applies "
@@ -105,7 +105,7 @@ def main() -> int:
              "196k-kd8b12-vd8b8": synth.Shape(1, 32, 8, 128, 196608, 8, 8, 12, 8)}[args.workload]
     if args.tokens:
         shape = synth.Shape(shape.B, shape.Hq, shape.Hkv, shape.D, args.tokens, shape.d_k, shape.d_v, shape.b_k, shape.b_v)
-    variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}[args.variant]
+    variant = {"auto": vb.VARIANT_AUTO, "lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA, "roles": vb.VARIANT_ROLES}[args.variant]
     can_tile = shape.b_k == 8 and shape.b_v == 8 and variant != vb.VARIANT_LUT and shape.N % 64 == 0
     if args.v_layout == "tiled" and not can_tile:
         print("bench.py: --v-layout tiled needs 8-bit codes on both sides, the matrix-core kernel and "
@@ -261,7 +261,7 @@ def main() -> int:
         # `kernel` is the call the events bracket: the attention kernel plus, with more than one split,
         # the merge kernel right behind it (rocprofv3 lists the two separately, see profiles/)
         "roofline": {"bound": "hbm", "kernel": "vecinfer_decode_attention",
-                     "launches_per_call": ["decode_lut_kernel" if variant == vb.VARIANT_LUT else "decode_mfma_kernel"]
+                     "launches_per_call": [{vb.VARIANT_LUT: "decode_lut_kernel", vb.VARIANT_ROLES: "decode_roles_kernel"}.get(variant, "decode_mfma_kernel")]
                      + (["merge_kernel"] if splits > 1 else []),
                      "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -83,6 +83,17 @@ enum {
                                     with 32-bit byte offsets: N * D / 2 < 2^31 (N < 33 554 432
                                     tokens at D = 128); longer caches fall to the lookup-table
                                     variant under AUTO                                       */
+    ,
+    VECINFER_VARIANT_ROLES = 3   /* the matrix-core kernel with the work of a tile split between
+                                    score wavefronts (q.K, online softmax) and value wavefronts
+                                    (P.V), 16 wavefronts per workgroup, probabilities handed over
+                                    through LDS; same arithmetic, results equal to MFMA's up to
+                                    fp32 summation order.  8-bit codes, D = 128, G <= 4, d_k and
+                                    d_v in {2, 4}, value codes in rows or tiles.  Never chosen by AUTO: it
+                                    measures 1 - 2 us slower per call than MFMA at 196608 tokens
+                                    (the tile loop is bound by LDS and issue throughput, not by
+                                    latency, so more wavefronts per SIMD buy nothing); kept as
+                                    the measured alternative                                 */
 };
 
 typedef struct vecinfer_cfg {

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvecinfer.so")
 
-VARIANT_AUTO, VARIANT_LUT, VARIANT_MFMA = 0, 1, 2
+VARIANT_AUTO, VARIANT_LUT, VARIANT_MFMA, VARIANT_ROLES = 0, 1, 2, 3
 MAX_SPLITS = 256
 MAX_RESIDUAL = 128
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4

@@ -183,7 +183,8 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
         if (!aligned(k_res, 16) || !aligned(v_res, 16)) return VECINFER_EINVAL;
     }
     if (num_splits < 0 || num_splits > VECINFER_MAX_SPLITS) return VECINFER_EINVAL;
-    if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA)
+    if (variant != VECINFER_VARIANT_AUTO && variant != VECINFER_VARIANT_LUT && variant != VECINFER_VARIANT_MFMA &&
+        variant != VECINFER_VARIANT_ROLES)
         return VECINFER_EINVAL;
     if (B > 65535 || cfg->num_kv_heads > 65535) return VECINFER_EUNSUPPORTED;      // grid dimensions
     if (!aligned(q_f16, 16) || !aligned(lambda, 16) || !aligned(cb_k_f16, 16) || !aligned(cb_v_f16, 16) ||
@@ -234,7 +235,9 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
 
     const bool mfma_ok = decode_mfma_supports(p);
     if (variant == VECINFER_VARIANT_MFMA && !mfma_ok) return VECINFER_EUNSUPPORTED;
-    const bool use_mfma = (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
+    const bool use_roles = variant == VECINFER_VARIANT_ROLES;
+    if (use_roles && !(mfma_ok && decode_roles_supports(p))) return VECINFER_EUNSUPPORTED;
+    const bool use_mfma = use_roles || (variant == VECINFER_VARIANT_MFMA) || (variant == VECINFER_VARIANT_AUTO && mfma_ok);
     // the lookup-table kernel reads one byte per code, from rows
     if (!use_mfma && (wide(cfg) || cfg->v_tiled)) return VECINFER_EUNSUPPORTED;
     int rc = 0;
@@ -255,8 +258,9 @@ int decode_common(const vecinfer_cfg *cfg, const void *q_f16, const float *lambd
         if (rc != 0) return launch_status(rc);
     }
     if (N > 0)
-        rc = use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
-                      : launch_decode_lut(p, static_cast<hipStream_t>(stream));
+        rc = use_roles  ? launch_decode_roles(p, static_cast<hipStream_t>(stream))
+             : use_mfma ? launch_decode_mfma(p, static_cast<hipStream_t>(stream))
+                        : launch_decode_lut(p, static_cast<hipStream_t>(stream));
     else
         p.S = 0;                        // nothing but the window: the merge kernel sees no split partial
     // log-sum-exp merge of the splits and of the window (single split, no window: done in-kernel)

@@ -192,6 +192,8 @@ int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma_wide(const DecodeParams &p, hipStream_t stream);   // 10- / 12-bit codes
 int launch_decode_mfma_tiled(const DecodeParams &p, hipStream_t stream);  // 8-bit codes, tiled value codes
 bool decode_mfma_supports(const DecodeParams &p);
+bool decode_roles_supports(const DecodeParams &p);                        // score / value wavefront kernel
+int launch_decode_roles(const DecodeParams &p, hipStream_t stream);
 
 struct EncodeParams {
     const __half *x;      // [B, Hkv, T, D]

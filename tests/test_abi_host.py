@@ -103,6 +103,11 @@ def test_decode_argument_errors():
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
     # the matrix-core variant does not cover d_v = 8 at head dim 64
     assert _decode(cfg=vb.Config(64, 8, 1, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # the score / value wavefront kernel: D = 128, G <= 4, d in {2, 4}, 8-bit codes
+    for bad in (vb.Config(64, 8, 2, 4, 4), vb.Config(128, 16, 2, 4, 4), vb.Config(128, 8, 2, 8, 4),
+                vb.Config(128, 8, 2, 4, 4, 12, 8)):
+        assert _decode(cfg=bad, variant=vb.VARIANT_ROLES, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert _decode(variant=4) == vb.EINVAL
     # more KV heads (or sequences) than a grid dimension holds
     assert _decode(cfg=vb.Config(128, 70000, 70000, 4, 4), ws=FAKE, ws_bytes=1 << 40) == vb.EUNSUPPORTED
     assert _decode(B=70000, ws=FAKE, ws_bytes=1 << 40) == vb.EUNSUPPORTED

@@ -12,10 +12,12 @@ from helpers import (assert_decode_close, assert_indices_match, cfg_of, dev, gpu
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA}
+VARIANTS = {"lut": vb.VARIANT_LUT, "mfma": vb.VARIANT_MFMA, "roles": vb.VARIANT_ROLES}
 
 
 def _supported(shape, variant):
+    if variant == vb.VARIANT_ROLES:       # score / value wavefront kernel: 8-bit codes, D = 128, G <= 4, d in {2, 4}
+        return shape.D == 128 and shape.G <= 4 and shape.d_k in (2, 4) and shape.d_v in (2, 4)
     return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G <= 8 and shape.d_k in (2, 4, 8)
                                          and (shape.d_v in (2, 4) or (shape.d_v == 8 and shape.D == 128)))
 

@@ -67,6 +67,23 @@ def test_decode_tiled(shape, splits):
     np.testing.assert_array_equal(got[1], rows[1])
 
 
+@pytest.mark.parametrize("shape", [synth.Shape(2, 8, 2, 128, 777, 4, 4), synth.Shape(1, 4, 1, 128, 4099, 2, 2),
+                                   synth.Shape(1, 6, 2, 128, 1500, 4, 2), synth.Shape(2, 4, 2, 128, 900, 2, 4)], ids=_id)
+@pytest.mark.parametrize("splits", [1, 3, 0])
+def test_decode_tiled_roles_variant(shape, splits):
+    """The score / value wavefront kernel reads the tiled value codes too: bit-identical to its own
+    result on rows, and within the bar of the oracle."""
+    x = synth.decode_inputs(shape, seed=shape.N + splits + 100, n_cap=_cap(shape.N))
+    ref = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"][:, :, :shape.N],
+                                  x["v_idx"][:, :, :shape.N])
+    rows = gpu_decode(shape, x, N=shape.N, num_splits=splits, variant=vb.VARIANT_ROLES)
+    got = gpu_decode(shape, dict(x, v_idx=tile_value_codes(x["v_idx"])), N=shape.N, num_splits=splits, v_tiled=1,
+                     variant=vb.VARIANT_ROLES)
+    assert_decode_close(*got, *ref, what=f"tiled roles {_id(shape)} S={splits}")
+    np.testing.assert_array_equal(got[0], rows[0])
+    np.testing.assert_array_equal(got[1], rows[1])
+
+
 def test_decode_tiled_ragged_and_degenerate_lengths():
     shape = synth.Shape(4, 8, 2, 128, 900, 4, 4)
     x = synth.decode_inputs(shape, seed=5, n_cap=1024)
