@@ -306,16 +306,16 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             if constexpr (WK) {
 #pragma unroll
                 for (int j = 0; j < WIN_K; ++j)
-                    cd.kc[st][j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * ROWB_K + 4 * j, 0, 0);
+                    cd.kc[st][j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * ROWB_K + 4 * j, 0, kStreamPolicy);
             } else if constexpr (MK / 4 == 2) {
-                cd.kc[st][0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_k, ko + 16 * st * MK, 0, 0);
+                cd.kc[st][0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
             } else if constexpr (MK / 4 == 4) {
-                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * MK, 0, 0);
+                cd.kc[st][0] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
             } else if constexpr (MK / 4 == 8) {
-                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, 0);
+                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1];
             } else {
-                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, 0);
+                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
                 cd.kc[st][0] = w[0]; cd.kc[st][1] = w[1]; cd.kc[st][2] = w[2]; cd.kc[st][3] = w[3];
             }
         }
@@ -328,7 +328,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             unsigned w[4 * NROUND_V];
 #pragma unroll
             for (int j = 0; j < NROUND_V; ++j) {
-                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, vo + 1024 * j, 0, 0);
+                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, vo + 1024 * j, 0, kStreamPolicy);
                 w[4 * j] = x[0]; w[4 * j + 1] = x[1]; w[4 * j + 2] = x[2]; w[4 * j + 3] = x[3];
             }
 #pragma unroll
@@ -345,25 +345,25 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                 // the window of token 4 (col & 3) + kg: quarter col / 4 of its row
 #pragma unroll
                 for (int j = 0; j < WIN_V; ++j)
-                    cd.vc[st][j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + 16 * st * ROWB_V + 4 * j, 0, 0);
+                    cd.vc[st][j] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + 16 * st * ROWB_V + 4 * j, 0, kStreamPolicy);
             } else if constexpr (NROUND_V == 1) {
                 unsigned w = 0;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0) << (8 * v);
+                    w |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, kStreamPolicy) << (8 * v);
                 cd.vc[st][0] = w;
             } else if constexpr (NROUND_V == 2) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     ushortx2 t;
-                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, 0);
-                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, 0);
+                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, kStreamPolicy);
+                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, kStreamPolicy);
                     cd.vc[st][u] = __builtin_bit_cast(unsigned, t);
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0);
+                    cd.vc[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, kStreamPolicy);
             }
         }
     };
@@ -909,22 +909,25 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         unsigned pp[HG][4];                      // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
 #pragma unroll
         for (int hg = 0; hg < HG; ++hg) {
-            if (SPLITQ) {
-                // columns t0 < 2 carry q~_hi . k, columns t0 >= 2 carry q~_lo . k: add the two halves
-                // of the quad so that all four lanes hold the full-precision score again
-#pragma unroll
-                for (int st = 0; st < 4; ++st)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) sacc[hg][st][v] += quad_xor<2>(sacc[hg][st][v]);
-            }
+            // Branch-free per-lane pick with bit masks (exactly one of sel[] is all ones; v_bfi_b32 /
+            // v_cndmask).  With the split query, columns t0 < 2 carry q~_hi . k and columns t0 >= 2
+            // carry q~_lo . k: a lane keeps its own part of sub-tile t0 (`mine`) and hands its part of
+            // sub-tile t0 ^ 2 - the one the lane two further on keeps - across the quad (`theirs`), so
+            // that one DPP add per score restores the full precision: 7 operations per score in
+            // place of the 4 adds over all sub-tiles and a 7-operation pick.
+            auto bfi = [](unsigned m, unsigned a, unsigned b) -> unsigned { return (m & a) | (~m & b); };
             float sc[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                // branch-free per-lane pick of sacc[t0][v] (bit masks: exactly one of sel[] is all ones)
-                const float s0 = sacc[hg][0][v], s1 = sacc[hg][1][v], s2 = sacc[hg][2][v], s3 = sacc[hg][3][v];
-                const unsigned u = (__float_as_uint(s0) & sel[0]) | (__float_as_uint(s1) & sel[1]) |
-                                   (__float_as_uint(s2) & sel[2]) | (__float_as_uint(s3) & sel[3]);
-                sc[v] = __uint_as_float(u);
+                const unsigned s0 = __float_as_uint(sacc[hg][0][v]), s1 = __float_as_uint(sacc[hg][1][v]);
+                const unsigned s2 = __float_as_uint(sacc[hg][2][v]), s3 = __float_as_uint(sacc[hg][3][v]);
+                const unsigned mine = bfi(sel[3], s3, bfi(sel[2], s2, bfi(sel[1], s1, s0)));
+                if (SPLITQ) {
+                    const unsigned theirs = bfi(sel[1], s3, bfi(sel[0], s2, bfi(sel[3], s1, s0)));
+                    sc[v] = __uint_as_float(mine) + quad_xor<2>(__uint_as_float(theirs));
+                } else {
+                    sc[v] = __uint_as_float(mine);
+                }
             }
             if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
 #pragma unroll
@@ -948,7 +951,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             for (int v = 0; v < 4; ++v) {
                 const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run[hg]);
                 l_part[hg] += pr;
-                pp[hg][v] = pack_dup_f16(pr);
+                pp[hg][v] = pack_dup_f16(pr);          // (p, p) as two fp16, round-to-nearest-even: one v_cvt_pk_f16_f32
             }
         }
 

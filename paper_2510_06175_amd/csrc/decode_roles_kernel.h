@@ -183,10 +183,10 @@ void decode_roles_kernel(const __half *q_arg, const float *lam_arg, const __half
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             if constexpr (MK / 4 == 8) {
-                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, 0);
+                const uintx2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
                 cd.c[st][0] = w[0]; cd.c[st][1] = w[1];
             } else {
-                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, 0);
+                const uintx4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc_k, ko + 16 * st * MK, 0, kStreamPolicy);
                 cd.c[st][0] = w[0]; cd.c[st][1] = w[1]; cd.c[st][2] = w[2]; cd.c[st][3] = w[3];
             }
         }
@@ -199,7 +199,7 @@ void decode_roles_kernel(const __half *q_arg, const float *lam_arg, const __half
             unsigned w[4 * NROUND_V];
 #pragma unroll
             for (int j = 0; j < NROUND_V; ++j) {
-                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, vo + 1024 * j, 0, 0);
+                const uintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_v, vo + 1024 * j, 0, kStreamPolicy);
                 w[4 * j] = x[0]; w[4 * j + 1] = x[1]; w[4 * j + 2] = x[2]; w[4 * j + 3] = x[3];
             }
 #pragma unroll
@@ -216,14 +216,14 @@ void decode_roles_kernel(const __half *q_arg, const float *lam_arg, const __half
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     ushortx2 t;
-                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, 0);
-                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, 0);
+                    t[0] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u) * MV, 0, kStreamPolicy);
+                    t[1] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rsrc_v, vo + (16 * st + 8 * u + 4) * MV, 0, kStreamPolicy);
                     cd.c[st][u] = __builtin_bit_cast(unsigned, t);
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    cd.c[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, 0);
+                    cd.c[st][v] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_v, vo + (16 * st + 4 * v) * MV, 0, kStreamPolicy);
             }
         }
     };
