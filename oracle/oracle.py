@@ -23,8 +23,17 @@ _LIB = os.path.join(_HERE, "libvecinfer_oracle.so")
 _lib = None
 
 
+_SAN_LIB = os.path.join(_HERE, "libvecinfer_oracle_san.so")
+# VECINFER_ORACLE_SANITIZED=1 (set before the first call): load the AddressSanitizer +
+# UndefinedBehaviorSanitizer build instead.  The process must then have been started with the
+# sanitizer runtime preloaded (see build_sanitized); the CPU test tier does that in a child process.
+_SANITIZED = os.environ.get("VECINFER_ORACLE_SANITIZED") == "1"
+
+
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (``-O2``, OpenMP, no fast-math)."""
+    if _SANITIZED:
+        return build_sanitized(force)
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
                "-ffp-contract=off", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
@@ -32,11 +41,28 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime, to be preloaded into a process that loads the sanitized build."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
+
+
+def build_sanitized(force: bool = False) -> str:
+    """The same source with -fsanitize=address,undefined (-O1, frame pointers kept, no OpenMP so that
+    every report points into the oracle): out-of-bounds accesses, misaligned or overflowing
+    arithmetic and the like abort the process instead of passing silently."""
+    if force or not os.path.exists(_SAN_LIB) or os.path.getmtime(_SAN_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-ffp-contract=off", "-Wall", "-Wextra",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+               "-Wno-unknown-pragmas", "-o", _SAN_LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SAN_LIB
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = C.CDLL(_LIB)
+        lib = C.CDLL(build())
         dp, u8p, i64p = C.POINTER(C.c_double), C.POINTER(C.c_uint8), C.POINTER(C.c_int64)
         lib.vo_num_threads.restype = C.c_int
         lib.vo_set_num_threads.argtypes = [C.c_int]

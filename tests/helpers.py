@@ -1,4 +1,14 @@
-"""Helpers of the GPU parity tests: run the library on numpy inputs, compare with the oracle."""
+"""Helpers of the GPU parity tests: run the library on numpy inputs, compare with the oracle.
+
+A failing seeded case can be kept and replayed: with ``pytest --dump-case DIR`` the inputs of the
+last decode call of every failing test are written as ``DIR/<test>.bin`` (the arrays, flat, one
+after the other) plus ``DIR/<test>.json`` (names, dtypes, shapes, byte offsets, the shape and call
+arguments); ``pytest tests/test_replay_case.py --load-case DIR/<test>`` runs that case alone, GPU
+against oracle.  The method's persistent state is just these arrays (smoothing factors, codebooks,
+code caches, query)."""
+import json
+import os
+
 import numpy as np
 import torch
 
@@ -53,9 +63,48 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+DECODE_KEYS = ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx")
+last_case = None          # (kind, shape, arrays, call arguments) of the most recent decode call
+
+
+def dump_case(prefix, kind, shape, arrays, args):
+    """Write a case as prefix.bin (flat arrays) + prefix.json (header)."""
+    os.makedirs(os.path.dirname(os.path.abspath(prefix)), exist_ok=True)
+    import dataclasses
+    header = {"kind": kind, "shape": list(dataclasses.astuple(shape)), "args": args, "arrays": []}
+    off = 0
+    with open(prefix + ".bin", "wb") as f:
+        for name, a in arrays.items():
+            a = np.ascontiguousarray(a.cpu().numpy() if isinstance(a, torch.Tensor) else a)
+            f.write(a.tobytes())
+            header["arrays"].append({"name": name, "dtype": str(a.dtype), "shape": list(a.shape), "offset": off,
+                                     "nbytes": a.nbytes})
+            off += a.nbytes
+    with open(prefix + ".json", "w") as f:
+        json.dump(header, f, indent=1)
+
+
+def load_case(prefix):
+    """-> (kind, synth.Shape, {name: numpy array}, call arguments) of a dumped case."""
+    from paper_2510_06175_amd import synth
+    with open(prefix + ".json") as f:
+        header = json.load(f)
+    blob = np.fromfile(prefix + ".bin", dtype=np.uint8)
+    arrays = {}
+    for e in header["arrays"]:
+        raw = blob[e["offset"]:e["offset"] + e["nbytes"]]
+        arrays[e["name"]] = raw.view(np.dtype(e["dtype"])).reshape(e["shape"]).copy()
+    return header["kind"], synth.Shape(*header["shape"]), arrays, header["args"]
+
+
 def gpu_decode(shape, x, seq_lens=None, N=None, num_splits=0, variant=vb.VARIANT_AUTO, ws=None, want_lse=True,
                v_tiled=0):
     """x: dict of numpy arrays (q, lam, cb_k, cb_v, k_idx, v_idx) -> (out fp16 as f64, lse f64)."""
+    global last_case
+    last_case = ("decode", shape, {k: x[k] for k in DECODE_KEYS},
+                 {"seq_lens": None if seq_lens is None else [int(v) for v in np.asarray(seq_lens)],
+                  "N": None if N is None else int(N), "num_splits": int(num_splits), "variant": int(variant),
+                  "v_tiled": int(v_tiled)})
     cfg = cfg_of(shape, v_tiled)
     t = {k: (v if isinstance(v, torch.Tensor) else dev(v)) for k, v in x.items()
          if k in ("q", "lam", "cb_k", "cb_v", "k_idx", "v_idx")}
