@@ -450,3 +450,42 @@ def kmeans_step(x_f16, lam, cb):
             rows = transform_keys(rows, _f64(lam)[g])
         cb_new[g], counts[g] = kmeans_update(rows, idx[:, g].reshape(B * T, -1), cb[g])
     return cb_new, counts, idx
+
+
+def quantization_error(x_f16, lam, cb, idx):
+    """Sum over all sub-vectors of the squared distance to the centroid they are coded with (the
+    K-Means objective, Sec. 2.2): x_f16 [B, Hkv, T, D]; lam [Hkv, D] or None (values); cb
+    [Hkv, M, C, d] (or [Hkv, 1, C, d], shared); idx [B, Hkv, T, M].  Returns one float per KV head."""
+    x = _f64(x_f16)
+    cb = _f64(cb)
+    B, Hkv, T, D = x.shape
+    err = np.zeros(Hkv)
+    for g in range(Hkv):
+        rows = x[:, g].reshape(B * T, D)
+        if lam is not None:
+            rows = transform_keys(rows, _f64(lam)[g])
+        err[g] = ((rows - vq_dequantize(idx[:, g].reshape(B * T, -1), cb[g])) ** 2).sum()
+    return err
+
+
+def kmeans_train(x_f16, lam, cb0, max_iters=30, tol=1e-4, round_f16=True):
+    """K-Means codebook training (Sec. 2.2; Sec. 3.2: on the transformed keys / the original values;
+    Sec. 4.1: at most 30 iterations), Lloyd's algorithm as a loop of kmeans_step.
+    Iteration t assigns every sub-vector to its nearest centroid of cb_t (Eq. 2), records the
+    quantization error E_t of that assignment (all KV heads together), and replaces every centroid
+    by the mean of its cluster (an empty cluster keeps its centroid) -> cb_{t+1}.  The loop stops
+    after the update of iteration t when t = max_iters - 1, or when t >= 1 and
+    E_{t-1} - E_t <= tol * E_{t-1} (the improvement has died down; a negative tol never stops early).
+    round_f16: the codebook is stored in fp16 (2 bytes per element, Sec. 2.2), so each cb_{t+1} is
+    rounded to fp16 before the next assignment.
+    Returns (cb [like cb0, f64], counts and idx of the last assignment, errors [iterations run])."""
+    cb = _f64(cb0)
+    errors = []
+    counts = idx = None
+    for t in range(max_iters):
+        cb_new, counts, idx = kmeans_step(x_f16, lam, cb)
+        errors.append(float(quantization_error(x_f16, lam, cb, idx).sum()))
+        cb = _f64(cb_new.astype(np.float16)) if round_f16 else cb_new
+        if t >= 1 and errors[t - 1] - errors[t] <= tol * errors[t - 1]:
+            break
+    return cb, counts, idx, np.array(errors)

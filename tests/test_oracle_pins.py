@@ -736,3 +736,79 @@ def test_tiny_config_end_to_end_quantization_is_sane(oracle):
     s_q = oracle.vq_dequantize(k_idx[0, 0], cb_k[0]) @ oracle.transform_query(q, lam[0]) / np.sqrt(sh.D)
     assert np.corrcoef(s_q, K @ q / np.sqrt(sh.D))[0, 1] > 0.9
     assert np.abs(out[0, 0] - full).max() < 0.5 * np.abs(V).max()
+
+
+# --------------------------------------------------------------------------- K-Means training loop (Sec. 2.2, 4.1)
+
+def test_kmeans_train_matches_scipy_kmeans2_over_k_iterations(oracle):
+    """The training loop with no early stop and no fp16 rounding is scipy's kmeans2 started from the
+    same centroids and run for the same number of iterations (values: no transform; one KV head,
+    one sub-space per column block), labels and centroids; the error it reports for an iteration is
+    the distortion of that iteration's assignment."""
+    import warnings
+    from scipy.cluster.vq import kmeans2
+    g = synth.rng(91)
+    for d, iters in ((4, 5), (2, 3), (8, 4)):
+        D, T = 2 * d, 1500
+        v = (g.standard_normal((1, 1, T, D)) * np.array([1.0, 0.3] * d)).astype(np.float16)
+        init = (g.standard_normal((1, D // d, 256, d)) * 0.8).astype(np.float16).astype(np.float64)
+        init[0, 0, 9] = 40.0                                  # stays empty in every iteration
+        cb, counts, idx, errs = oracle.kmeans_train(v, None, init, max_iters=iters, tol=-1.0, round_f16=False)
+        assert len(errs) == iters and counts[0, 0, 9] == 0 and (cb[0, 0, 9] == 40.0).all()
+        X = v[0, 0].astype(np.float64)
+        for m in range(D // d):
+            with warnings.catch_warnings():
+                warnings.simplefilter("ignore")
+                ref, _ = kmeans2(X[:, m * d:(m + 1) * d], init[0, m].copy(), iter=iters, minit="matrix")
+                # the labels scipy returns belong to the centroids BEFORE its last update: the loop's idx
+                before, lab = kmeans2(X[:, m * d:(m + 1) * d], init[0, m].copy(), iter=iters - 1, minit="matrix") \
+                    if iters > 1 else (init[0, m], None)
+            np.testing.assert_allclose(cb[0, m], ref, rtol=1e-10, atol=1e-12)
+            dist = ((X[:, None, m * d:(m + 1) * d] - before[None]) ** 2).sum(-1)
+            np.testing.assert_array_equal(idx[0, 0, :, m], dist.argmin(1))
+        # errors: distortion of each iteration's assignment, by brute force on the first and the last
+        cb1, _, idx1, e1 = oracle.kmeans_train(v, None, init, max_iters=1, tol=-1.0, round_f16=False)
+        want = sum(((X[:, None, m * d:(m + 1) * d] - init[0, m][None]) ** 2).sum(-1).min(1).sum() for m in range(D // d))
+        np.testing.assert_allclose(e1[0], want, rtol=1e-12)
+        np.testing.assert_allclose(errs[0], want, rtol=1e-12)
+        assert all(b <= a * (1 + 1e-12) for a, b in zip(errs, errs[1:]))
+
+
+def test_kmeans_train_stopping_rule_and_fp16_storage(oracle):
+    """Well separated clusters: the error stops improving after a few iterations and the loop ends
+    there (far before 30); tol < 0 runs all iterations; with fp16 storage every returned centroid is
+    an fp16 number and the trajectory equals stepping by hand with the rounding in between."""
+    g = synth.rng(92)
+    B, Hkv, T, D, d = 1, 2, 1200, 16, 4
+    centers = g.standard_normal((Hkv, D // d, 8, d)) * 4.0
+    pick = g.integers(0, 8, size=(B, Hkv, T, D // d))
+    k = np.empty((B, Hkv, T, D))
+    for h in range(Hkv):
+        for m in range(D // d):
+            k[:, h, :, m * d:(m + 1) * d] = centers[h, m][pick[:, h, :, m]] + 0.05 * g.standard_normal((B, T, d))
+    k = k.astype(np.float16)
+    cb0 = synth.codebooks(g, Hkv, D // d, d)
+    cb, counts, idx, errs = oracle.kmeans_train(k, None, cb0, max_iters=30, tol=1e-4)
+    assert 2 <= len(errs) < 30
+    assert errs[-2] - errs[-1] <= 1e-4 * errs[-2] and all(a - b > 1e-4 * a for a, b in zip(errs[:-2], errs[1:-1]))
+    np.testing.assert_array_equal(cb, cb.astype(np.float16).astype(np.float64))
+    # by hand
+    c = cb0.astype(np.float64)
+    for t in range(len(errs)):
+        new, cnt, ix = oracle.kmeans_step(k, None, c)
+        np.testing.assert_allclose(oracle.quantization_error(k, None, c, ix).sum(), errs[t], rtol=1e-13)
+        c = new.astype(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(c, cb)
+    np.testing.assert_array_equal(ix, idx)
+    np.testing.assert_array_equal(cnt, counts)
+    full = oracle.kmeans_train(k, None, cb0, max_iters=7, tol=-1.0)
+    assert len(full[3]) == 7
+    # keys: trained on the transformed keys (Sec. 3.2); the error is measured there too
+    lam = np.stack([oracle.smoothing_factors(k[:, h]) for h in range(Hkv)])
+    cbk, _, ixk, ek = oracle.kmeans_train(k, lam, cb0, max_iters=3, tol=-1.0)
+    rows = oracle.transform_keys(k[0, 0].astype(np.float64), lam[0])
+    first = oracle.encode_keys(k, lam, cb0.astype(np.float64))
+    e0 = oracle.quantization_error(k, lam, cb0.astype(np.float64), first)
+    np.testing.assert_allclose(e0.sum(), ek[0], rtol=1e-13)
+    np.testing.assert_allclose(e0[0], ((rows - oracle.vq_dequantize(first[0, 0], cb0[0].astype(np.float64))) ** 2).sum(),
+                               rtol=1e-13)
