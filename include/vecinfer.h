@@ -54,11 +54,12 @@
 extern "C" {
 #endif
 
-#define VECINFER_VERSION 200          /* major*10000 + minor*100 + patch */
+#define VECINFER_VERSION 300          /* major*10000 + minor*100 + patch */
 #define VECINFER_MAX_SPLITS 256       /* upper bound of num_splits */
 #define VECINFER_MAX_APPEND 16        /* most tokens vecinfer_append_kv takes per call */
 #define VECINFER_MAX_RESIDUAL 128     /* most rows of the full-precision residual window */
 #define VECINFER_STATIC_SCRATCH_BYTES (4u << 20) /* workspace limit of vecinfer_decode_attention_static */
+#define VECINFER_KMEANS_MAX_ITERS 30   /* most iterations of vecinfer_kmeans_train (Sec. 4.1) */
 #define VECINFER_LAMBDA_FLOOR 1e-5f    /* smallest smoothing factor vecinfer_calibrate_lambda returns */
 
 enum {
@@ -187,7 +188,7 @@ int vecinfer_calibrate_lambda(const vecinfer_cfg *cfg, const void *k_f16, float 
  *               (lambda == NULL) would write with cb_in
  *   update      cb_out[g, m, c, :] = fp16(mean of the sub-vectors assigned to c), summed in fp32;
  *               a centroid nobody was assigned to keeps its cb_in value
- * The sums are formed with hardware fp32 atomics, so their last bits (and rarely the fp16
+ * The sums are formed with fp32 atomics, so their last bits (and rarely the fp16
  * rounding of a centroid) may differ between runs.
  *   x_f16  [B, H_kv, T, D] fp16       cb_in_f16, cb_out_f16 [H_kv, M, 256, d] (may not alias)
  *   codes  [B, H_kv, T, M] uint8 (written)    counts int32 [H_kv, M, 256] or NULL: cluster sizes
@@ -202,6 +203,37 @@ size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys);
 int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda,
                          const void *cb_in_f16, void *cb_out_f16, uint8_t *codes, int32_t *counts,
                          int32_t B, int64_t T, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * K-Means codebook training: Lloyd's algorithm, at most max_iters <= VECINFER_KMEANS_MAX_ITERS = 30
+ * iterations (Sec. 2.2: the codebook is built by K-Means; Sec. 3.2: on the transformed keys and the
+ * original values; Sec. 4.1: maximum number of iterations 30), with the quantization error
+ * computed on the device and a stopping rule there.  8-bit codes on the trained side.
+ * Iteration t = 0, 1, ..:
+ *   assignment  as vecinfer_kmeans_step, with the centroids cb_t (cb_0 = what cb_f16 holds on entry)
+ *   error       E_t = sum over all KV heads, sub-spaces and tokens of |x - cb_t[code]|^2 (fp32 per
+ *               sub-vector, summed in fp64): the quantization error of that assignment
+ *   update      cb_{t+1} = fp16(cluster means), in place in cb_f16; empty clusters keep their centroid
+ *   stop        after the update of iteration t when t = max_iters - 1, or when t >= 1 and
+ *               E_{t-1} - E_t <= tol * E_{t-1}  (tol < 0: never before max_iters)
+ * All max_iters iterations are enqueued; those after the stop return at once (a flag in the
+ * workspace), so the call never synchronises.  Initial centroids are the caller's (e.g. a sample
+ * of the training vectors).
+ *   cb_f16     [H_kv, M, 256, d] fp16, read and overwritten
+ *   codes      [B, H_kv, T, M] uint8: the assignment of the last iteration run
+ *   counts     int32 [H_kv, M, 256] or NULL: its cluster sizes
+ *   iters_run  int32 on the device or NULL: iterations run
+ *   errors     fp64 [max_iters] on the device or NULL: E_0 .. E_{iters_run - 1}; the rest untouched
+ *   workspace  vecinfer_kmeans_workspace_bytes(cfg, lambda != NULL) bytes, 256-byte aligned
+ * The cluster sums are formed with fp32 atomics (in LDS, then one per workgroup and centroid in
+ * memory), so their last bits, and rarely the fp16 rounding of a centroid, may differ between runs.
+ * Errors: as vecinfer_kmeans_step; EINVAL for max_iters outside 1 .. 30 or tol = NaN; EUNSUPPORTED
+ * for 10- / 12-bit codes on the trained side (vecinfer_kmeans_step covers one iteration of those).
+ */
+int vecinfer_kmeans_train(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, void *cb_f16,
+                          uint8_t *codes, int32_t *counts, int32_t B, int64_t T, int32_t max_iters,
+                          float tol, int32_t *iters_run, double *errors, void *workspace,
+                          size_t workspace_bytes, void *stream);
 
 /*
  * Number of sequence splits the library would pick for (B, N) when num_splits = 0

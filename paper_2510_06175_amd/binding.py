@@ -26,7 +26,7 @@ EXPORTS = [
     "vecinfer_decode_workspace_bytes",
     "vecinfer_decode_attention", "vecinfer_decode_attention_residual", "vecinfer_decode_step",
     "vecinfer_decode_attention_static",
-    "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step",
+    "vecinfer_kmeans_workspace_bytes", "vecinfer_kmeans_step", "vecinfer_kmeans_train",
     "vecinfer_index_row_bytes", "vecinfer_codebook_elems", "vecinfer_calibrate_lambda", "vecinfer_read_probe",
     "vecinfer_export_value_codes",
     "vecinfer_strerror", "vecinfer_version",
@@ -114,6 +114,8 @@ def lib() -> C.CDLL:
         L.vecinfer_kmeans_workspace_bytes.restype = sz
         L.vecinfer_kmeans_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, i32, i64, vp, sz, vp]
         L.vecinfer_kmeans_step.restype = C.c_int
+        L.vecinfer_kmeans_train.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i64, i32, C.c_float, vp, vp, vp, sz, vp]
+        L.vecinfer_kmeans_train.restype = C.c_int
         L.vecinfer_calibrate_lambda.argtypes = [cfgp, vp, vp, i32, i64, vp]
         L.vecinfer_calibrate_lambda.restype = C.c_int
         L.vecinfer_read_probe.argtypes = [vp, sz, vp, vp]
@@ -369,3 +371,25 @@ def vecinfer_kmeans_step(cfg: Config, x_f16, lam, cb_in, cb_out, codes, workspac
         _dev(codes, torch.uint8, (B, cfg.num_kv_heads, T, cfg.row_bytes(keys)), "codes"),
         None if counts is None else _dev(counts, torch.int32, cb_shape[:-1], "counts"),
         B, T, ws.data_ptr(), ws.numel(), _stream(stream)))
+
+
+KMEANS_MAX_ITERS = 30
+
+
+def vecinfer_kmeans_train(cfg: Config, x_f16, lam, cb, codes, workspace, counts=None, max_iters: int = 30,
+                          tol: float = 1e-4, iters_run=None, errors=None, stream=None) -> None:
+    """K-Means training in place on cb (at most max_iters Lloyd iterations, stopping rule on the device).
+    iters_run: int32 device tensor [1] or None; errors: float64 device tensor [max_iters] or None."""
+    B, Hkv, T, D = x_f16.shape
+    keys = lam is not None
+    cb_shape = cfg.cb_shape(keys)
+    _check(lib().vecinfer_kmeans_train(
+        C.byref(cfg.c()), _dev(x_f16, torch.float16, (B, cfg.num_kv_heads, T, cfg.head_dim), "x_f16"),
+        None if lam is None else _dev(lam, torch.float32, (cfg.num_kv_heads, cfg.head_dim), "lambda"),
+        _dev(cb, torch.float16, cb_shape, "cb"),
+        _dev(codes, torch.uint8, (B, cfg.num_kv_heads, T, cfg.row_bytes(keys)), "codes"),
+        None if counts is None else _dev(counts, torch.int32, cb_shape[:-1], "counts"),
+        B, T, max_iters, tol,
+        None if iters_run is None else _dev(iters_run, torch.int32, (1,), "iters_run"),
+        None if errors is None else _dev(errors, torch.float64, (max_iters,), "errors"),
+        workspace.data_ptr(), workspace.numel(), _stream(stream)))

@@ -317,12 +317,18 @@ size_t vecinfer_kmeans_workspace_bytes(const vecinfer_cfg *cfg, int32_t keys)
     if (!cfg_ok(cfg)) return 0;
     const size_t d = keys ? cfg->k_sub_dim : cfg->v_sub_dim;
     const size_t cen = vecinfer_codebook_elems(cfg, keys) / d;     // centroids of the whole tensor
-    return (cen * d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
+    // fp32 sums, int32 counts, the training state (error accumulators, stopping flag)
+    return (cen * d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256 +
+           (kmeans_state_bytes() + 255) / 256 * 256;
 }
 
-int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, const void *cb_in_f16,
-                         void *cb_out_f16, uint8_t *codes, int32_t *counts, int32_t B, int64_t T, void *workspace,
-                         size_t workspace_bytes, void *stream)
+namespace {
+
+// Shared body of vecinfer_kmeans_step (one iteration, cb_in -> cb_out) and vecinfer_kmeans_train
+// (up to max_iters iterations in place, every one enqueued; iterations after the stop do nothing).
+int kmeans_common(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, const void *cb_in_f16,
+                  void *cb_out_f16, uint8_t *codes, int32_t *counts, int32_t B, int64_t T, int32_t max_iters,
+                  float tol, int32_t *iters_run, double *errors, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!cfg || !cb_out_f16 || !aligned(cb_out_f16, 16)) return VECINFER_EINVAL;
     vecinfer_cfg rows_cfg = *cfg;
@@ -330,20 +336,63 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
     cfg = &rows_cfg;
     EncodeParams p;
     const bool keys = lambda != nullptr;
+    const bool in_place = cb_in_f16 == cb_out_f16;
     const int rc = encode_args(cfg, x_f16, lambda, keys, cb_in_f16, codes, B, T, 0, T, p);
     if (rc != VECINFER_OK) return rc;
     const size_t need = vecinfer_kmeans_workspace_bytes(cfg, keys ? 1 : 0);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) return VECINFER_EWORKSPACE;
     const size_t cen = vecinfer_codebook_elems(cfg, keys ? 1 : 0) / p.d;
-    p.km_sums = static_cast<float *>(workspace);
-    p.km_counts = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(workspace) +
-                                              (cen * p.d * sizeof(float) + 255) / 256 * 256);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    p.km_sums = reinterpret_cast<float *>(ws);
+    p.km_counts = reinterpret_cast<int32_t *>(ws + (cen * p.d * sizeof(float) + 255) / 256 * 256);
+    void *state = ws + (cen * p.d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int lr = launch_kmeans_zero(p.km_sums, p.km_counts, cen * p.d, cen, st);
-    if (lr == 0) lr = launch_encode(p, st);
-    if (lr == 0)
-        lr = launch_kmeans_finalize(p.km_sums, p.km_counts, p.cb, static_cast<__half *>(cb_out_f16), counts, cen, p.d, st);
+    if (p.bits != 8) {
+        // 10- / 12-bit codes (one shared table per KV head): a single iteration through the tiled
+        // wide cache-fill kernel with its accumulation epilogue
+        if (max_iters != 1) return VECINFER_EUNSUPPORTED;
+        int lr = launch_kmeans_zero(p.km_sums, p.km_counts, cen * p.d, cen, st);
+        if (lr == 0) lr = launch_encode(p, st);
+        if (lr == 0)
+            lr = launch_kmeans_finalize(p.km_sums, p.km_counts, p.cb, static_cast<__half *>(cb_out_f16), counts, cen,
+                                        p.d, st);
+        return launch_status(lr);
+    }
+    int lr = 0;
+    if (!in_place)       // the update works in place on cb_out: start it from cb_in
+        lr = hipMemcpyAsync(cb_out_f16, cb_in_f16, cen * p.d * sizeof(__half), hipMemcpyDeviceToDevice, st) == hipSuccess
+                 ? 0 : -4;
+    p.cb = static_cast<const __half *>(cb_out_f16);
+    for (int it = 0; it < max_iters && lr == 0; ++it) {
+        lr = launch_kmeans_begin(p.km_sums, p.km_counts, cen * p.d, cen, it, state, st);
+        if (lr == 0) lr = launch_kmeans_assign(p, it, state, num_cus(), st);
+        if (lr == 0)
+            lr = launch_kmeans_end(p.km_sums, p.km_counts, static_cast<__half *>(cb_out_f16), counts, cen, p.d, it, tol,
+                                   state, iters_run, errors, st);
+    }
     return launch_status(lr);
+}
+
+} // namespace
+
+int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, const void *cb_in_f16,
+                         void *cb_out_f16, uint8_t *codes, int32_t *counts, int32_t B, int64_t T, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    return kmeans_common(cfg, x_f16, lambda, cb_in_f16, cb_out_f16, codes, counts, B, T, 1, -1.0f, nullptr, nullptr,
+                         workspace, workspace_bytes, stream);
+}
+
+int vecinfer_kmeans_train(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, void *cb_f16, uint8_t *codes,
+                          int32_t *counts, int32_t B, int64_t T, int32_t max_iters, float tol, int32_t *iters_run,
+                          double *errors, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (max_iters < 1 || max_iters > VECINFER_KMEANS_MAX_ITERS || !(tol == tol)) return VECINFER_EINVAL;
+    if (errors && !aligned(errors, 8)) return VECINFER_EINVAL;
+    if (iters_run && !aligned(iters_run, 4)) return VECINFER_EINVAL;
+    if (cfg && cfg_ok(cfg) && (lambda ? cfg->k_bits : cfg->v_bits) != 8) return VECINFER_EUNSUPPORTED;
+    return kmeans_common(cfg, x_f16, lambda, cb_f16, cb_f16, codes, counts, B, T, max_iters, tol, iters_run, errors,
+                         workspace, workspace_bytes, stream);
 }
 
 int32_t vecinfer_decode_auto_splits(const vecinfer_cfg *cfg, int32_t B, int64_t N)

@@ -216,6 +216,14 @@ struct EncodeParams {
 int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, hipStream_t stream);
 int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
                            int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream);
+// K-Means training iteration, 8-bit codes: begin (clear), assign + accumulate, end (update in place,
+// error, stopping rule); `state` is kmeans_state_bytes() of device memory
+size_t kmeans_state_bytes();
+int launch_kmeans_begin(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter, void *state,
+                        hipStream_t stream);
+int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream);
+int launch_kmeans_end(const float *sums, const int32_t *counts, __half *cb, int32_t *counts_out, size_t n_centroids,
+                      int d, int iter, float tol, void *state, int32_t *iters_run, double *errors, hipStream_t stream);
 int launch_encode(const EncodeParams &p, hipStream_t stream);
 int launch_export_value_codes(const uint8_t *tiled, uint8_t *rows, int BH, int M, long long N, long long n_cap,
                               hipStream_t stream);

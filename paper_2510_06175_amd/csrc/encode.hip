@@ -234,6 +234,173 @@ __global__ void kmeans_finalize_kernel(const float *sums, const int32_t *counts,
         cb_out[c * d + j] = n > 0 ? __float2half(sums[c * d + j] / (float)n) : cb_in[c * d + j];
 }
 
+// ---------------------------------------------------------------------------------------------
+// K-Means training (Sec. 2.2, 3.2, 4.1), 8-bit codes: assignment + accumulation in one kernel.
+//
+// A workgroup takes one chunk of four sub-spaces (one per wavefront) of one (sequence, KV head) and
+// walks over a run of `tiles_per_wg` 64-token tiles.  Per tile it transforms the rows exactly as the
+// cache-fill kernel does (same function, so k~ is bit-identical), keeps the chunk's 4 d channels,
+// searches the four codebooks (same arithmetic and tie rule as encode_kernel: the codes are the
+// ones vecinfer_encode_* would write), and adds every sub-vector to the sum of its centroid in
+// LDS (ds_add_f32: fast, and a long run of tokens meets each of the 256 centroids many times).
+// Only at the end of the run do the 4 x 256 x (d + 1) partial sums go to memory, one atomic each.
+// The rows are read M / 4 times in all (once per chunk); the search, which dominates, is not repeated.
+// The squared distance of every sub-vector to its centroid is summed on the way: the
+// quantization error of the assignment.
+struct KmeansState {
+    double err_cur;       // quantization error of the assignment being accumulated
+    double err_prev;      // .. of the iteration before
+    int32_t stop_at;      // iteration after whose update the training stopped (INT32_MAX: not yet)
+    int32_t pad;
+};
+
+template <int D, int d, bool kTransform>
+__global__ __launch_bounds__(kEncBlock) void kmeans_assign_kernel(EncodeParams p, int tiles_per_wg, int iter,
+                                                                  KmeansState *state)
+{
+    constexpr int M = D / d;
+    constexpr int MS = kChunkSub;
+    constexpr int CH = MS * d;                 // channels of the chunk
+    constexpr int XS = D + 4;                  // row stride of the transformed tile
+    extern __shared__ __align__(16) unsigned char km_smem[];
+    float *const cb_s = reinterpret_cast<float *>(km_smem);                 // [MS][256][d] fp32 centroids
+    float *const x_s = cb_s + MS * kCentroids * d;                          // [64][XS] transformed tile
+    float *const acc_s = x_s + kEncTokens * XS;                             // [MS][256][d + 1] sums and counts
+    uint8_t *const idx_s = reinterpret_cast<uint8_t *>(acc_s + MS * kCentroids * (d + 1));   // [64][MS]
+
+    if (iter > 0 && iter > state->stop_at) return;     // training already stopped (same for every thread)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.y;
+    const int bg = blockIdx.z, g = bg % p.Hkv;
+    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
+
+    {   // the chunk's centroids, widened once (exact); accumulators cleared
+        const uint2 *src = reinterpret_cast<const uint2 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
+        float4 *dst = reinterpret_cast<float4 *>(cb_s);
+        for (int e = tid; e < MS * kCentroids * d / 4; e += kEncBlock) {
+            const uint2 raw = src[e];
+            const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
+            const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
+            float4 w; w.x = __low2float(h01); w.y = __high2float(h01); w.z = __low2float(h23); w.w = __high2float(h23);
+            dst[e] = w;
+        }
+        for (int e = tid; e < MS * kCentroids * (d + 1); e += kEncBlock) acc_s[e] = 0.f;
+    }
+    auto dist_bits = [&](const float (&x)[d], const float *cen) -> unsigned {
+        float dist = 0.f;
+#pragma unroll
+        for (int j = 0; j < d; ++j) {
+            const float t = x[j] - cen[j];
+            dist = fmaf(t, t, dist);
+        }
+        return __float_as_uint(dist);
+    };
+    float err = 0.f;
+    for (int ti = 0; ti < tiles_per_wg; ++ti) {
+        const long long t0 = (tile0 + ti) * kEncTokens;
+        if (t0 >= p.T) break;
+        __syncthreads();                       // previous tile's x_s, idx_s consumed; tables ready
+        load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
+        __syncthreads();
+        {   // wavefront `wave` searches sub-space chunk * MS + wave; a lane owns a token
+            const int ms = wave;
+            float x[d];
+#pragma unroll
+            for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + chunk * CH + ms * d + j];
+            const float *cen = cb_s + (size_t)ms * kCentroids * d;
+            unsigned best = 0x7f800000u;            // +inf
+            int best_group = 0;
+#pragma unroll 2
+            for (int c0 = 0; c0 < kCentroids; c0 += 8) {
+                unsigned gmin = dist_bits(x, cen + c0 * d);
+#pragma unroll
+                for (int k = 1; k < 8; ++k) {
+                    const unsigned v = dist_bits(x, cen + (c0 + k) * d);
+                    gmin = v < gmin ? v : gmin;
+                }
+                if (gmin < best) {
+                    best = gmin;
+                    best_group = c0;
+                }
+            }
+            int arg = best_group;
+#pragma unroll
+            for (int k = 7; k >= 0; --k)
+                if (dist_bits(x, cen + (best_group + k) * d) == best) arg = best_group + k;
+            idx_s[lane * MS + ms] = (uint8_t)arg;
+            if (t0 + lane < p.T) {
+                float *a = acc_s + ((size_t)ms * kCentroids + arg) * (d + 1);
+#pragma unroll
+                for (int j = 0; j < d; ++j) atomicAdd(a + j, x[j]);
+                atomicAdd(a + d, 1.0f);             // (counts stay exact in fp32: far below 2^24 per run)
+                err += __uint_as_float(best);
+            }
+        }
+        __syncthreads();
+        // the chunk's MS = 4 code bytes of each token: one 32-bit word of its row
+        if (tid < kEncTokens && t0 + tid < p.T)
+            *reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t0 + tid) * M + chunk * MS) =
+                reinterpret_cast<const uint32_t *>(idx_s)[tid];
+    }
+    __syncthreads();
+    // the run's partial sums -> memory
+    for (int e = tid; e < MS * kCentroids; e += kEncBlock) {
+        const float *a = acc_s + (size_t)e * (d + 1);
+        const int n = (int)a[d];
+        if (n > 0) {
+            const size_t cen = ((size_t)g * M + (size_t)chunk * MS) * kCentroids + e;
+#pragma unroll
+            for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, a[j]);
+            atomicAdd(p.km_counts + cen, n);
+        }
+    }
+    double e64 = (double)err;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
+    if (lane == 0 && state) unsafeAtomicAdd(&state->err_cur, e64);
+}
+
+// Start of a training iteration: sums and counts cleared, the error accumulator reset (and, before
+// the first iteration, the whole state).
+__global__ void kmeans_begin_kernel(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter,
+                                    KmeansState *state)
+{
+    if (iter > 0 && iter > state->stop_at) return;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_sums) sums[i] = 0.f;
+    if (i < n_counts) counts[i] = 0;
+    if (i == 0) {
+        state->err_cur = 0.0;
+        if (iter == 0) {
+            state->err_prev = 0.0;
+            state->stop_at = 0x7fffffff;
+        }
+    }
+}
+
+// End of a training iteration: the centroid update in place (an empty cluster keeps its centroid),
+// the cluster sizes, the iteration's error, and the stopping rule: the training stops after this
+// update when the error improved by no more than tol times the error of the iteration before.
+__global__ void kmeans_end_kernel(const float *sums, const int32_t *counts, __half *cb, int32_t *counts_out,
+                                  size_t n_centroids, int d, int iter, float tol, KmeansState *state,
+                                  int32_t *iters_run, double *errors)
+{
+    if (iter > 0 && iter > state->stop_at) return;
+    const size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c == 0) {
+        const double e = state->err_cur, prev = state->err_prev;
+        if (errors) errors[iter] = e;
+        if (iters_run) *iters_run = iter + 1;
+        if (iter >= 1 && prev - e <= (double)tol * prev) state->stop_at = iter;
+        state->err_prev = e;
+    }
+    if (c >= n_centroids) return;
+    const int n = counts[c];
+    if (counts_out) counts_out[c] = n;
+    if (n > 0)
+        for (int j = 0; j < d; ++j) cb[c * d + j] = __float2half(sums[c * d + j] / (float)n);
+}
+
 // Decode-time append (Eq. 9) and other short inputs: one workgroup per (token, batch, KV head).
 // The token is transformed in LDS with the same butterfly order as the tiled kernel (so both
 // produce bit-identical k~).  Then, 32 sub-spaces at a time: thread c writes the distance of
@@ -779,6 +946,76 @@ int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __hal
 {
     hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)((n_centroids + 255) / 256)), dim3(256), 0, stream,
                        sums, counts, cb_in, cb_out, counts_out, n_centroids, d);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+namespace {
+
+template <int D, int d>
+int launch_kmeans_assign_typed(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream)
+{
+    constexpr int M = D / d;
+    constexpr size_t smem = sizeof(float) * ((size_t)kChunkSub * kCentroids * d + (size_t)kEncTokens * (D + 4) +
+                                             (size_t)kChunkSub * kCentroids * (d + 1)) + kEncTokens * kChunkSub;
+    static const bool configured =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kmeans_assign_kernel<D, d, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kmeans_assign_kernel<D, d, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!configured) return -4;
+    // runs long enough that a workgroup meets each centroid many times, short enough that the
+    // grid still fills the chip several times over
+    const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
+    const long long groups = (long long)(M / kChunkSub) * p.B * p.Hkv;
+    long long per = tiles * groups / (8LL * num_cus);
+    if (per < 1) per = 1;
+    if (per > 256) per = 256;
+    dim3 grid((unsigned)((tiles + per - 1) / per), M / kChunkSub, p.B * p.Hkv);
+    if (p.lam)
+        hipLaunchKernelGGL((kmeans_assign_kernel<D, d, true>), grid, dim3(kEncBlock), smem, stream, p, (int)per, iter,
+                           static_cast<KmeansState *>(state));
+    else
+        hipLaunchKernelGGL((kmeans_assign_kernel<D, d, false>), grid, dim3(kEncBlock), smem, stream, p, (int)per, iter,
+                           static_cast<KmeansState *>(state));
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+} // namespace
+
+size_t kmeans_state_bytes() { return sizeof(KmeansState); }
+
+// Assignment + accumulation of one training iteration for 8-bit codes (rows layout of the codes).
+int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream)
+{
+    if (p.bits != 8 || !p.km_sums || p.tiled) return -2;
+    if ((p.T + kEncTokens - 1) / kEncTokens > 0x7fffffffLL || p.B * p.Hkv > 65535) return -2;
+    const int key = p.D * 10 + p.d;
+    switch (key) {
+    case 1282: return launch_kmeans_assign_typed<128, 2>(p, iter, state, num_cus, stream);
+    case 1284: return launch_kmeans_assign_typed<128, 4>(p, iter, state, num_cus, stream);
+    case 1288: return launch_kmeans_assign_typed<128, 8>(p, iter, state, num_cus, stream);
+    case 642: return launch_kmeans_assign_typed<64, 2>(p, iter, state, num_cus, stream);
+    case 644: return launch_kmeans_assign_typed<64, 4>(p, iter, state, num_cus, stream);
+    case 648: return launch_kmeans_assign_typed<64, 8>(p, iter, state, num_cus, stream);
+    default: return -2;
+    }
+}
+
+int launch_kmeans_begin(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter, void *state,
+                        hipStream_t stream)
+{
+    const size_t n = n_sums > n_counts ? n_sums : n_counts;
+    hipLaunchKernelGGL(kmeans_begin_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, sums, counts,
+                       n_sums, n_counts, iter, static_cast<KmeansState *>(state));
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+int launch_kmeans_end(const float *sums, const int32_t *counts, __half *cb, int32_t *counts_out, size_t n_centroids,
+                      int d, int iter, float tol, void *state, int32_t *iters_run, double *errors, hipStream_t stream)
+{
+    hipLaunchKernelGGL(kmeans_end_kernel, dim3((unsigned)((n_centroids + 255) / 256)), dim3(256), 0, stream, sums,
+                       counts, cb, counts_out, n_centroids, d, iter, tol, static_cast<KmeansState *>(state), iters_run,
+                       errors);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_strerror():
-    assert vb.vecinfer_version() == 200
+    assert vb.vecinfer_version() == 300
     assert vb.strerror(0) == "ok"
     for code in (vb.EINVAL, vb.EUNSUPPORTED, vb.EWORKSPACE, vb.ELAUNCH):
         assert vb.strerror(code) not in ("ok", "unknown error code")
@@ -204,7 +204,7 @@ def test_wide_code_sizes_and_argument_errors():
     # wide codes on one side need d = 4 or 8 on the other side too
     assert _decode(cfg=vb.Config(128, 32, 8, 8, 2, 12, 8), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     # the training step: fp32 sums and int32 counts for the head's one table
-    assert vb.vecinfer_kmeans_workspace_bytes(d8b12, True) == 8 * 4096 * (8 * 4 + 4)
+    assert vb.vecinfer_kmeans_workspace_bytes(d8b12, True) == 8 * 4096 * (8 * 4 + 4) + 256   # sums, counts, training state
     assert vb.lib().vecinfer_kmeans_step(C.byref(d8b12.c()), FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, 64, FAKE, 1024,
                                          None) == vb.EWORKSPACE
     assert _enc_keys(cfg=d8b12, k=None) == vb.EINVAL
