@@ -78,8 +78,7 @@ enum {
                                     configuration                                            */
     VECINFER_VARIANT_MFMA = 2    /* codebooks in LDS, dequantized tiles fed to the matrix
                                     cores for both q.K and P.V; D in {64,128}, d_k and d_v
-                                    in {2,4,8} (d_v = 8 only with D = 128), any G the cfg
-                                    allows; the only variant for 10- / 12-bit codes, which
+                                    in {2,4,8}, any G the cfg allows; the only variant for 10- / 12-bit codes, which
                                     need d = 4 or 8 on BOTH sides.  Code rows are addressed
                                     with 32-bit byte offsets: N * D / 2 < 2^31 (N < 33 554 432
                                     tokens at D = 128); longer caches fall to the lookup-table
@@ -113,7 +112,8 @@ typedef struct vecinfer_cfg {
 } vecinfer_cfg;
 
 /*
- * Tiled value codes (cfg.v_tiled = 1; v_bits = 8; n_cap a multiple of 64).
+ * Tiled value codes (cfg.v_tiled = 1; v_bits = 8; M_v >= 16, i.e. not d_v = 8 at D = 64;
+ * n_cap a multiple of 64).
  * The cache holds the same N x M_v code matrix of a (sequence, KV head), stored in blocks of
  * 64 tokens (64 M_v bytes each, block t / 64 of token t) in the order in which the lanes of the
  * matrix-core attention kernel consume them, so that a lane fetches its share of a block with

@@ -30,8 +30,8 @@ bool cfg_ok(const vecinfer_cfg *c)
         return bits == 8 || ((bits == 10 || bits == 12) && c->head_dim == 128 && (d == 4 || d == 8));
     };
     if (!bits_ok(c->k_bits, c->k_sub_dim) || !bits_ok(c->v_bits, c->v_sub_dim)) return false;
-    // tiled value codes: one byte per code
-    return c->v_tiled == 0 || (c->v_tiled == 1 && c->v_bits == 8);
+    // tiled value codes: one byte per code, and at least the 16 sub-spaces the block order is made of
+    return c->v_tiled == 0 || (c->v_tiled == 1 && c->v_bits == 8 && c->head_dim / c->v_sub_dim >= 16);
 }
 
 bool wide(const vecinfer_cfg *c) { return c->k_bits != 8 || c->v_bits != 8; }

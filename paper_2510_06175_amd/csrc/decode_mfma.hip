@@ -6,7 +6,7 @@ namespace vecinfer {
 bool decode_mfma_supports(const DecodeParams &p)
 {
     const bool dk_ok = p.dk == 8 || p.dk == 4 || p.dk == 2;
-    const bool dv_ok = p.dv == 4 || p.dv == 2 || (p.dv == 8 && p.D == 128);
+    const bool dv_ok = p.dv == 8 || p.dv == 4 || p.dv == 2;
     // 10- and 12-bit codes: D = 128 and d = 4 or 8 on that side, d = 4 or 8 on the other side too
     auto wide = [](int b) { return b == 10 || b == 12; };
     bool bits_ok = p.bk == 8 && p.bv == 8;
@@ -14,7 +14,8 @@ bool decode_mfma_supports(const DecodeParams &p)
         bits_ok = p.D == 128 && (wide(p.bk) || p.bk == 8) && (wide(p.bv) || p.bv == 8) && p.dk >= 4 && p.dv >= 4;
     // code rows are addressed with 32-bit byte offsets (a row is at most D / 2 bytes)
     // tiled value codes: 8-bit codes on both sides (the instantiations built)
-    const bool tiled_ok = !p.v_tiled || (p.bk == 8 && p.bv == 8 && p.n_cap % 64 == 0);
+    // (and not d_v = 8 at D = 64: fewer than the 16 sub-spaces the block order is made of)
+    const bool tiled_ok = !p.v_tiled || (p.bk == 8 && p.bv == 8 && p.n_cap % 64 == 0 && !(p.D == 64 && p.dv == 8));
     return (p.D == 128 || p.D == 64) && p.G >= 1 && p.G <= 8 && dk_ok && dv_ok && bits_ok && tiled_ok &&
            (p.v_tiled ? (p.N + 63) / 64 * 64 : p.N) * (long long)(p.D / 2) < (1LL << 31);
 }
@@ -36,6 +37,9 @@ int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
     case 12882: return launch_typed<128, 8, 2, 8, true>(p, stream);
     case 12848: return launch_typed<128, 4, 8, 8, true>(p, stream);
     case 12828: return launch_typed<128, 2, 8, 8, true>(p, stream);
+    case 6488: return launch_typed<64, 8, 8, 8, true>(p, stream);
+    case 6448: return launch_typed<64, 4, 8, 8, true>(p, stream);
+    case 6428: return launch_typed<64, 2, 8, 8, true>(p, stream);
     case 6484: return launch_typed<64, 8, 4, 8, true>(p, stream);
     case 6482: return launch_typed<64, 8, 2, 8, true>(p, stream);
     case 6444: return launch_typed<64, 4, 4, 8, true>(p, stream);

@@ -51,22 +51,29 @@ namespace {
 // codes packed end to end in the token's row, one table of 2^b centroids for all sub-spaces.
 // VT: 8-bit value codes stored in tiles of 64 tokens (v_tiled_offset): a lane's share of a tile is
 // 16 NROUND_V bytes, fetched with NROUND_V 16-byte loads.
-template <int kD, int DK, int DV, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8, bool VT = false>
+template <int kD, int DK, int DVR, int HG, int NW, bool SPLITQ, int BK = 8, int BV = 8, bool VT = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, kD == 128 ? NW / 4 : NW / 2)))
 void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half *cb_k_arg, const __half *cb_v_arg,
                         const __half *k_new_arg, const __half *v_new_arg, unsigned hkv_g_arg, int S_, DecodeParams p)
 {
     constexpr int KG = kG * HG;                        // head slots of the workgroup
-    static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DV == 8 || DV == 4 || DV == 2) &&
-                      (DV != 8 || kD == 128),
-                  "shapes this kernel is laid out for (d_v = 8 needs 16 value sub-spaces: D = 128)");
+    // d_v = 8 needs 16 value sub-spaces (one per MFMA column): D = 128.  At D = 64 each of the 8
+    // sub-spaces is therefore handled as two of 4 channels that share the code byte (VSPLIT): the
+    // gather, the P.V operands and the accumulators are those of d_v = 4 (DV below), only the
+    // addressing of the code rows, the staging of the table and the search for a fused new token
+    // know the real sub-vector (DVR).
+    constexpr bool VSPLIT = kD == 64 && DVR == 8;
+    constexpr int DV = VSPLIT ? 4 : DVR;
+    static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DVR == 8 || DVR == 4 || DVR == 2),
+                  "shapes this kernel is laid out for");
+    static_assert(!VSPLIT || (!VT && BV == 8), "split value sub-spaces: 8-bit codes in rows");
     constexpr bool WK = BK > 8, WV = BV > 8;           // wide codes: shared table, packed rows
     static_assert(!VT || !WV, "tiled value codes are 8-bit codes");
     static_assert((BK == 8 || ((BK == 10 || BK == 12) && kD == 128 && DK >= 4)) &&
                       (BV == 8 || ((BV == 10 || BV == 12) && kD == 128 && DV >= 4)),
                   "wide codes: 10 or 12 bits, D = 128, d = 4 or 8");
     constexpr int BLOCK = NW * 64;
-    constexpr int MK = kD / DK, MV = kD / DV;          // sub-spaces: 16, 32 or 64
+    constexpr int MK = kD / DK, MV = kD / DVR;         // sub-spaces: 8, 16, 32 or 64
     // bytes of the key / value tables of a KV head in LDS
     constexpr int CBK_BYTES = WK ? (1 << BK) * DK * 2 : kCentroids * kD * 2;
     constexpr int CBV_BYTES = WV ? (1 << BV) * DV * 2 : kCentroids * kD * 2;
@@ -77,7 +84,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     constexpr int NR = kD / 32;                        // score MFMA rounds (32 channels each): 4 or 2;
                                                        // also the P.V operands (and MFMAs) per sub-tile
     constexpr int H = NR / 2;                          // rounds per pipeline stage
-    constexpr int NROUND_V = MV / 16;                  // value sub-spaces per MFMA column: 1, 2 or 4
+    constexpr int NROUND_V = (kD / DV) / 16;           // value sub-spaces per MFMA column: 1, 2 or 4
     // Wide codes.  A lane's key operand needs the MK / 4 consecutive codes of quarter kg of its
     // token's row; the four lanes of a quad (columns 4a .. 4a+3) need, of each of their four
     // tokens, the MV / 4 consecutive codes of quarter a of its row.  Either way that is a run of
@@ -170,12 +177,15 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         // the four quarters take adjacent 16-byte pieces, so an instruction reads 64 contiguous
         // bytes of 16 tables.  Item it serves r = it % NROUND_V and the 4 * CPL codes of code
         // group it / NROUND_V.
+        // (VSPLIT: a lane's 16 bytes are the whole centroid `8 it + lane / 8` of sub-space lane % 8, i.e.
+        // the entries of that code for columns 2 (lane % 8) and 2 (lane % 8) + 1: one 16-byte write.)
 #pragma unroll
         for (int j = 0; j < kStageVPerWave; ++j) {
             const int it = wave + NW * j;
             const int r = it % NROUND_V, code = (it / NROUND_V) * 4 * CPL + vq * CPL;
             if (kStageV % NW == 0 || it < kStageV)
                 vreg[j] = WV ? *reinterpret_cast<const uintx4 *>(srcv + it * 1024 + lane * 16)   // shared table: as is
+                          : VSPLIT ? *reinterpret_cast<const uintx4 *>(srcv + (lane & 7) * (kCentroids * 16) + (8 * it + (lane >> 3)) * 16)
                              : *reinterpret_cast<const uintx4 *>(srcv + (NROUND_V * vcol + r) * SUB_V + code * ENTRY_V);
         }
     }
@@ -296,6 +306,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                                   : (unsigned)(krow_tok * MK + kg * (MK / 4));
     const unsigned voff_lane = WV ? (unsigned)((4 * (col & 3) + kg) * ROWB_V + 4 * (((col >> 2) * (MV / 4) * BV) >> 5))
                                : VT ? (unsigned)(lane * 16)
+                               : VSPLIT ? (unsigned)(kg * MV + (col >> 1))
                                     : (unsigned)(kg * MV + col * NROUND_V);
 
     auto load_codes_k = [&](Codes &cd, long long tb) {
@@ -478,6 +489,9 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         if constexpr (WV) {
             if (kStageV % NW == 0 || it < kStageV)
                 *reinterpret_cast<uintx4 *>(sm_v + it * 1024 + lane * 16) = vreg[j];
+        } else if constexpr (VSPLIT) {
+            if (kStageV % NW == 0 || it < kStageV)
+                *reinterpret_cast<uintx4 *>(sm_v + (8 * it + (lane >> 3)) * ROW_V + (lane & 7) * 16) = vreg[j];
         } else if (kStageV % NW == 0 || it < kStageV) {
 #pragma unroll
             for (int e = 0; e < CPL; ++e) {
@@ -528,7 +542,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     auto new_items = [&](auto kv_c, auto nb_c, int i0) {
         constexpr int kv = decltype(kv_c)::value;          // 0: key sub-spaces, 1: value sub-spaces
         constexpr int NB = decltype(nb_c)::value;          // items taken at a time
-        constexpr int DS = kv == 0 ? DK : DV, EN = 2 * DS, MX = kv == 0 ? MK : MV;
+        constexpr int DS = kv == 0 ? DK : DVR, EN = 2 * DS, MX = kv == 0 ? MK : MV;
         // entry c of a sub-space sits at tab + c * stride (value tables are transposed)
         constexpr int stride = kv == 0 ? ENTRY_K : ROW_V;
         int m[NB];
@@ -542,6 +556,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
             ok[b4] = mm < MX;
             m[b4] = ok[b4] ? mm : 0;                        // a surplus slot redoes sub-space 0 and writes nothing
             tab[b4] = kv == 0 ? sm_k + m[b4] * SUB_K
+                      : VSPLIT ? sm_v + m[b4] * 2 * ENTRY_V        // columns 2 m and 2 m + 1 side by side
                               : sm_v + (m[b4] % NROUND_V) * PLANE_V + (m[b4] / NROUND_V) * ENTRY_V;
             best[b4] = INFINITY;
             arg[b4] = 0;

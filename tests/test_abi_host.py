@@ -101,8 +101,8 @@ def test_decode_argument_errors():
     assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
     assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
-    # the matrix-core variant does not cover d_v = 8 at head dim 64
-    assert _decode(cfg=vb.Config(64, 8, 1, 8, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # the matrix-core variant does not cover 10- / 12-bit codes at head dim 64
+    assert _decode(cfg=vb.Config(64, 8, 1, 8, 8, 12, 12), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     # the score / value wavefront kernel: D = 128, G <= 4, d in {2, 4}, 8-bit codes
     for bad in (vb.Config(64, 8, 2, 4, 4), vb.Config(128, 16, 2, 4, 4), vb.Config(128, 8, 2, 8, 4),
                 vb.Config(128, 8, 2, 4, 4, 12, 8)):
@@ -144,7 +144,7 @@ def test_decode_step_argument_errors():
     assert step(N=0) == vb.EINVAL                               # the new token itself makes N >= 1
     assert step(N=2048) == vb.EINVAL
     assert step(cfg=vb.Config(128, 32, 8, 4, 4, k_bits=4)) == vb.EUNSUPPORTED
-    assert step(cfg=vb.Config(64, 8, 8, 4, 8), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert step(cfg=vb.Config(64, 8, 8, 4, 8, 8, 10), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     need = vb.vecinfer_decode_workspace_bytes(CFG, 1, 1024, 4)
     assert step(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
 
@@ -238,6 +238,9 @@ def test_tiled_value_codes_argument_errors():
     # tiled value codes are one byte per code
     assert _decode(cfg=vb.Config(128, 32, 8, 8, 8, 12, 12, 1), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     assert _decode(cfg=vb.Config(128, 32, 8, 4, 4, v_tiled=2), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # .. and need the 16 value sub-spaces the block order is made of
+    assert _decode(cfg=vb.Config(64, 8, 8, 4, 8, v_tiled=1), ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    assert _enc_vals(cfg=vb.Config(64, 8, 8, 4, 8, v_tiled=1), T=64, n_cap=64) == vb.EUNSUPPORTED
     # whole 64-token blocks
     assert _decode(cfg=tiled, N=1000, n_cap=1000, ws=FAKE, ws_bytes=1 << 30) == vb.EINVAL
     assert _enc_vals(cfg=tiled, T=4, n_cap=100) == vb.EINVAL

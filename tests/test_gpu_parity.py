@@ -19,7 +19,7 @@ def _supported(shape, variant):
     if variant == vb.VARIANT_ROLES:       # score / value wavefront kernel: 8-bit codes, D = 128, G <= 4, d in {2, 4}
         return shape.D == 128 and shape.G <= 4 and shape.d_k in (2, 4) and shape.d_v in (2, 4)
     return variant == vb.VARIANT_LUT or (shape.D in (64, 128) and shape.G <= 8 and shape.d_k in (2, 4, 8)
-                                         and (shape.d_v in (2, 4) or (shape.d_v == 8 and shape.D == 128)))
+                                         and shape.d_v in (2, 4, 8))
 
 
 # ------------------------------------------------------------------ decode, small shapes
@@ -505,6 +505,30 @@ def test_decode_head_dim_64_long():
     k_new, v_new = _new_token(shape, seed=65)
     step = _gpu_step(shape, x, k_new, v_new, variant=vb.VARIANT_MFMA)
     _check_step(shape, x, k_new, v_new, step, [shape.N], "step D=64, 64k tokens")
+
+
+D64_DV8 = [synth.Shape(2, 8, 2, 64, 5000, 8, 8), synth.Shape(1, 6, 2, 64, 3333, 4, 8), synth.Shape(1, 16, 2, 64, 1111, 2, 8),
+           synth.Shape(3, 2, 2, 64, 70, 8, 8)]
+
+
+@pytest.mark.parametrize("shape", D64_DV8, ids=lambda s: f"B{s.B}h{s.Hq}-{s.Hkv}N{s.N}k{s.d_k}")
+@pytest.mark.parametrize("splits", [1, 7, 0])
+def test_decode_head_dim_64_value_sub_vectors_of_8(shape, splits):
+    """D = 64 with d_v = 8 has 8 value sub-spaces for 16 matrix-core columns: the kernel handles each
+    as two halves of 4 channels that share the code byte.  Attention, ragged lengths and the fused
+    step against the oracle (Eq. 10, Eq. 9)."""
+    x = synth.decode_inputs(shape, seed=shape.N + shape.d_k)
+    ref = oracle.decode_attention(x["q"], x["lam"], x["cb_k"], x["cb_v"], x["k_idx"], x["v_idx"])
+    got = gpu_decode(shape, x, num_splits=splits, variant=vb.VARIANT_MFMA)
+    assert_decode_close(*got, *ref, what=f"D=64 d_v=8 S={splits}")
+    k_new, v_new = _new_token(shape, seed=shape.N + 9)
+    step = _gpu_step(shape, x, k_new, v_new, num_splits=splits, variant=vb.VARIANT_MFMA)
+    _check_step(shape, x, k_new, v_new, step, [shape.N] * shape.B, f"step D=64 d_v=8 S={splits}")
+    if shape.B > 1:
+        lens = [shape.N // 3, 0, 1][:shape.B]
+        k_new, v_new = _new_token(shape, seed=shape.N + 10)
+        step = _gpu_step(shape, x, k_new, v_new, seq_lens=lens, N=shape.N, num_splits=splits, variant=vb.VARIANT_MFMA)
+        _check_step(shape, x, k_new, v_new, step, lens, f"ragged step D=64 d_v=8 S={splits}")
 
 
 # ------------------------------------------------------------------ K-Means codebook training step

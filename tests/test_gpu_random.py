@@ -36,8 +36,6 @@ def _random_cases(n, seed):
         wide = bk != 8 or bv != 8
         if wide and (D != 128 or dk < 4 or dv < 4):
             continue
-        if dv == 8 and D != 128:
-            continue
         G = int(g.choice([1, 2, 3, 4, 5, 8]))
         Hkv = int(g.choice([1, 2, 3]))
         B = int(g.choice([1, 2, 3]))
@@ -63,7 +61,7 @@ def test_decode_random_configurations(case):
         sub = {k: (v[keep] if k in ("q", "k_idx", "v_idx") else v) for k, v in x.items()}
         ref_o, ref_l = _oracle_decode(shape, sub, lens_a[keep])
         assert_decode_close(got_o[keep], got_l[keep], ref_o, ref_l, what=f"random {_id(shape)} S={S}")
-    if shape.b_k == 8 and shape.b_v == 8:
+    if shape.b_k == 8 and shape.b_v == 8 and shape.Mv >= 16:
         # the tiled layout of the value codes feeds the same arithmetic: same bits out
         cap = (shape.N + 63) // 64 * 64
         x2 = synth.decode_inputs(shape, seed=seed + 1, n_cap=cap)
