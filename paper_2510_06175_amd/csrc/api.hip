@@ -365,7 +365,7 @@ int kmeans_common(const vecinfer_cfg *cfg, const void *x_f16, const float *lambd
     p.cb = static_cast<const __half *>(cb_out_f16);
     for (int it = 0; it < max_iters && lr == 0; ++it) {
         lr = launch_kmeans_begin(p.km_sums, p.km_counts, cen * p.d, cen, it, state, st);
-        if (lr == 0) lr = launch_kmeans_assign(p, it, state, num_cus(), st);
+        if (lr == 0) lr = launch_kmeans_assign(p, it, state, st);
         if (lr == 0)
             lr = launch_kmeans_end(p.km_sums, p.km_counts, static_cast<__half *>(cb_out_f16), counts, cen, p.d, it, tol,
                                    state, iters_run, errors, st);

@@ -221,7 +221,7 @@ int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __hal
 size_t kmeans_state_bytes();
 int launch_kmeans_begin(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter, void *state,
                         hipStream_t stream);
-int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream);
+int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, hipStream_t stream);
 int launch_kmeans_end(const float *sums, const int32_t *counts, __half *cb, int32_t *counts_out, size_t n_centroids,
                       int d, int iter, float tol, void *state, int32_t *iters_run, double *errors, hipStream_t stream);
 int launch_encode(const EncodeParams &p, hipStream_t stream);

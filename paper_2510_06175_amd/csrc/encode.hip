@@ -18,6 +18,7 @@
 //            taken on the bits (integer min: no NaN canonicalisation on the way).
 //   phase 3  the 64 x M code bytes go out through LDS as whole 32-bit words.
 #include "common.h"
+#include "encode_screen.h"
 
 namespace vecinfer {
 
@@ -25,13 +26,12 @@ namespace {
 
 constexpr int kEncBlock = 256;
 constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
-constexpr int kChunkSub = 4;       // sub-spaces searched per pass: one per wavefront
 
 // Phase 1 of the tiled kernels: the 64 tokens of the tile, smoothed and Hadamard-transformed
 // (kTransform) or just widened (values), as fp32 rows of x_s (row stride D + 4 floats).  A lane
 // owns 4 consecutive channels of one token; the first two butterfly stages run inside the lane,
 // the others across lanes with wavefront shuffles.
-template <int D, bool kTransform>
+template <int D, bool kTransform, int BLOCK = kEncBlock>
 __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float *x_s, long long t0, int bg, int g)
 {
     constexpr int LPT = D / 4;                 // lanes per token
@@ -47,13 +47,13 @@ __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float
             rl[0] = l4.x; rl[1] = l4.y; rl[2] = l4.z; rl[3] = l4.w;
         }
         const float hs = 1.0f / sqrtf((float)D);
-        constexpr int NP = kEncTokens / TPW / (kEncBlock / 64);   // passes per wavefront
+        constexpr int NP = kEncTokens / TPW / (BLOCK / 64);   // passes per wavefront
         // All passes of the wavefront advance stage by stage, so that a stage's shuffles (NP x 4
         // independent ones) are in flight together instead of one LDS round trip at a time.
         float v[NP][4];
 #pragma unroll
         for (int pi = 0; pi < NP; ++pi) {
-            const int tl = (wave + pi * (kEncBlock / 64)) * TPW + tw;   // token within the tile
+            const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;   // token within the tile
             long long t = t0 + tl;
             if (t >= p.T) t = p.T - 1;                                  // tail: harmless duplicate
             const uint2 raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
@@ -93,126 +93,142 @@ __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float
         }
 #pragma unroll
         for (int pi = 0; pi < NP; ++pi) {
-            const int tl = (wave + pi * (kEncBlock / 64)) * TPW + tw;
+            const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;
             float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
             *reinterpret_cast<float4 *>(&x_s[tl * XS + c0]) = w;
         }
 }
 
-template <int D, int d, bool kTransform>
-__global__ __launch_bounds__(kEncBlock) void encode_kernel(EncodeParams p)
+// Cache fill (Eq. 2, 3, 6, 8) and K-Means assignment (Sec. 2.2), 8-bit codes: one kernel.
+//
+// A workgroup (8 wavefronts) takes a group of MSW sub-spaces of one (sequence, KV head) and walks
+// over a run of `tiles_per_wg` 64-token tiles, so that the group's search tables are built once
+// per run: per sub-space the fp16 centroids and -sigma |c|^2 / 2 (encode_screen.h), 3 to 5 KB.
+// Per tile: the rows are transformed into LDS (phase 1 above; once per group of sub-spaces, so
+// M / MSW times in all), every wavefront searches MSW / 8 sub-spaces for the 64 tokens (a lane
+// owns a token at the end), and the group's MSW code bytes per token go out as 8- or 16-byte
+// stores (tiled value codes: byte by byte, each to its place in the token's 64-token block).
+// kAccumulate (K-Means): every sub-vector is also added to the sum of its centroid in LDS
+// (ds_add_f32; a run meets each centroid many times) and its squared distance to the run's error;
+// at the end of the run the partial sums go to memory, one atomic per non-empty centroid, and the
+// error to the training state.
+constexpr int kVqBlock = 512;
+
+// Sub-spaces per workgroup: all of them for the cache fill (32 at most: d = 2 at D = 128 takes two
+// workgroups per tile), 8 for K-Means, whose sums need 256 (d + 1) floats per sub-space.
+template <int d, bool kAccumulate>
+constexpr int vq_group(int M) { return M < (kAccumulate ? 8 : 32) ? M : (kAccumulate ? 8 : 32); }
+
+template <int D, int d, bool kAccumulate>
+constexpr size_t vq_smem_bytes()
+{
+    constexpr int MSW = vq_group<d, kAccumulate>(D / d);
+    return (size_t)MSW * ScreenTab<d>::kBytes + sizeof(float) * kEncTokens * (D + 4) + (size_t)kEncTokens * MSW +
+           (kAccumulate ? sizeof(float) * MSW * kCentroids * (d + 1) : 0);
+}
+
+struct KmeansState {
+    double err_cur;       // quantization error of the assignment being accumulated
+    double err_prev;      // .. of the iteration before
+    int32_t stop_at;      // iteration after whose update the training stopped (INT32_MAX: not yet)
+    int32_t pad;
+};
+
+template <int D, int d, bool kTransform, bool kAccumulate>
+__global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int tiles_per_wg, int iter, KmeansState *state)
 {
     constexpr int M = D / d;
-    constexpr int MS = kChunkSub;              // sub-spaces per chunk
-    constexpr int kChunkCh = MS * d;           // channels per chunk
-    constexpr int NCHUNK = M / MS;             // chunks per token row
-    constexpr int LPT = D / 4;                 // lanes per token in phase 1
-    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass in phase 1
-    constexpr int XS = D + 4;                  // padded row stride of the LDS tile (floats)
+    constexpr int MSW = vq_group<d, kAccumulate>(M);       // sub-spaces of the workgroup
+    constexpr int NW = kVqBlock / 64;
+    constexpr int SPW = (MSW + NW - 1) / NW;               // sub-spaces per wavefront: 1, 2 or 4
+    static_assert(MSW % NW == 0 && M % MSW == 0, "whole groups, dealt evenly to the wavefronts");
+    constexpr int XS = D + 4;                              // row stride of the transformed tile
+    constexpr int TB = ScreenTab<d>::kBytes;
+    extern __shared__ __align__(16) unsigned char vq_smem[];
+    unsigned char *const tab_s = vq_smem;                                          // [MSW] search tables
+    float *const x_s = reinterpret_cast<float *>(tab_s + MSW * TB);                // [64][XS] transformed tile
+    uint8_t *const idx_s = reinterpret_cast<uint8_t *>(x_s + kEncTokens * XS);     // [64][MSW] codes of the tile
+    float *const acc_s = reinterpret_cast<float *>(idx_s + kEncTokens * MSW);      // [MSW][256][d + 1] sums, counts
 
-    __shared__ __align__(16) float cb_s[MS * kCentroids * d];      // 4096 d bytes: fp32 copies of one chunk's centroids
-    __shared__ __align__(16) float x_s[kEncTokens * XS];           // 33 KB (D = 128): the transformed tile
-    __shared__ __align__(16) uint8_t idx_s[kEncTokens * M];        // codes of the tile
-
+    if (kAccumulate && iter > 0 && iter > state->stop_at) return;     // training already stopped (every thread alike)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long t0 = (long long)blockIdx.x * kEncTokens;
-    const int bg = blockIdx.z;
-    const int g = bg % p.Hkv;
+    const int grp = blockIdx.y;
+    const int bg = blockIdx.z, g = bg % p.Hkv;
+    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
 
-    // ---- phase 1: the whole transformed tile -> LDS (once per workgroup)
-    load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
-
-    auto dist_bits = [&](const float (&x)[d], const float *cen) -> unsigned {
-        float dist = 0.f;
+    // ---- the search tables of this wavefront's sub-spaces (nobody else reads them)
+    ScreenConsts sc[SPW];
 #pragma unroll
-        for (int j = 0; j < d; ++j) {
-            const float t = x[j] - cen[j];
-            dist = fmaf(t, t, dist);
-        }
-        return __float_as_uint(dist);
-    };
+    for (int i = 0; i < SPW; ++i) {
+        const int ms = wave + NW * i;
+        sc[i] = screen_prepare<d>(p.cb + ((size_t)g * M + (size_t)grp * MSW + ms) * kCentroids * d, tab_s + ms * TB, lane);
+    }
+    if (kAccumulate)
+        for (int e = tid; e < MSW * kCentroids * (d + 1); e += kVqBlock) acc_s[e] = 0.f;
 
-    for (int chunk = 0; chunk < NCHUNK; ++chunk) {
-        __syncthreads();                       // x_s complete / previous chunk's search done with cb_s
-        // ---- this chunk's centroids -> LDS, widened to fp32 once (exact)
-        {
-            const uint2 *src = reinterpret_cast<const uint2 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
-            float4 *dst = reinterpret_cast<float4 *>(cb_s);
-            for (int e = tid; e < MS * kCentroids * d / 4; e += kEncBlock) {
-                const uint2 raw = src[e];
-                const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
-                const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
-                float4 w; w.x = __low2float(h01); w.y = __high2float(h01); w.z = __low2float(h23); w.w = __high2float(h23);
-                dst[e] = w;
+    float err = 0.f;
+    for (int ti = 0; ti < tiles_per_wg; ++ti) {
+        const long long t0 = (tile0 + ti) * kEncTokens;
+        if (t0 >= p.T) break;
+        __syncthreads();                       // previous tile's x_s and idx_s consumed (first tile: accumulators cleared)
+        load_transform_tile<D, kTransform, kVqBlock>(p, x_s, t0, bg, g);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int ms = wave + NW * i;
+            const int ch0 = (grp * MSW + ms) * d;
+            int arg;
+            unsigned best;
+            search_tile<d>(x_s, XS, ch0, tab_s + ms * TB, sc[i], lane, arg, best);
+            idx_s[lane * MSW + ms] = (uint8_t)arg;
+            if (kAccumulate && t0 + lane < p.T) {
+                float *a = acc_s + ((size_t)ms * kCentroids + arg) * (d + 1);
+#pragma unroll
+                for (int j = 0; j < d; ++j) atomicAdd(a + j, x_s[lane * XS + ch0 + j]);
+                atomicAdd(a + d, 1.0f);             // (counts stay exact in fp32: far below 2^24 per run)
+                err += __uint_as_float(best);
             }
         }
         __syncthreads();
-
-        // ---- phase 2: search
-        for (int ms = wave; ms < MS; ms += kEncBlock / 64) {
-            float x[d];
-#pragma unroll
-            for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + chunk * kChunkCh + ms * d + j];
-            const float *cen = cb_s + (size_t)ms * kCentroids * d;
-            unsigned best = 0x7f800000u;            // +inf
-            int best_group = 0;
-#pragma unroll 2
-            for (int c0 = 0; c0 < kCentroids; c0 += 8) {
-                unsigned gmin = dist_bits(x, cen + c0 * d);
-#pragma unroll
-                for (int k = 1; k < 8; ++k) {
-                    const unsigned v = dist_bits(x, cen + (c0 + k) * d);
-                    gmin = v < gmin ? v : gmin;
-                }
-                if (gmin < best) {
-                    best = gmin;
-                    best_group = c0;
-                }
+        // ---- the group's MSW code bytes of each token
+        if (!kAccumulate && p.tiled) {
+            for (int e = tid; e < kEncTokens * MSW; e += kVqBlock) {
+                const int tl = e / MSW, m = grp * MSW + (e - tl * MSW);
+                const long long t = t0 + tl;
+                if (t < p.T) p.idx[(size_t)bg * p.n_cap * M + v_tiled_offset(p.pos0 + t, m, M)] = idx_s[e];
             }
-            int arg = best_group;
-#pragma unroll
-            for (int k = 7; k >= 0; --k)
-                if (dist_bits(x, cen + (best_group + k) * d) == best) arg = best_group + k;
-            idx_s[lane * M + chunk * MS + ms] = (uint8_t)arg;
+        } else if constexpr (MSW == 8) {
+            if (tid < kEncTokens && t0 + tid < p.T)
+                *reinterpret_cast<uint2 *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t0 + tid) * M + grp * MSW) =
+                    reinterpret_cast<const uint2 *>(idx_s)[tid];
+        } else {
+            constexpr int QPT = MSW / 16;      // 16-byte pieces per token
+            const int tl = tid / QPT, q = tid % QPT;
+            if (tid < kEncTokens * QPT && t0 + tl < p.T)
+                *reinterpret_cast<uint4 *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t0 + tl) * M + grp * MSW + 16 * q) =
+                    reinterpret_cast<const uint4 *>(idx_s)[tid];
         }
     }
-    __syncthreads();
-
-    // ---- phase 3: M bytes per token, written as 32-bit words (whole rows: coalesced); tiled value
-    // codes byte by byte, each at its place in the token's 64-token block
-    if (p.tiled) {
-        for (int e = tid; e < kEncTokens * M; e += kEncBlock) {
-            const int tl = e / M, m = e - tl * M;
-            const long long t = t0 + tl;
-            if (t < p.T) p.idx[(size_t)bg * p.n_cap * M + v_tiled_offset(p.pos0 + t, m, M)] = idx_s[tl * M + m];
-        }
-    } else {
-        constexpr int WPT = M / 4;             // words per token
-        for (int e = tid; e < kEncTokens * WPT; e += kEncBlock) {
-            const int tl = e / WPT, w = e - tl * WPT;
-            const long long t = t0 + tl;
-            if (t < p.T) {
-                uint32_t *dst = reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t) * M);
-                dst[w] = reinterpret_cast<const uint32_t *>(idx_s)[tl * WPT + w];
-            }
-        }
-    }
-
-    // ---- K-Means training only: every sub-vector of the tile joins the sum of its centroid
-    // (fp32 hardware atomics; the order of the additions, and with it the last bits of the sums,
-    // varies from run to run)
-    if (p.km_sums) {
-        for (int e = tid; e < kEncTokens * M; e += kEncBlock) {
-            const int tl = e / M, m = e - tl * M;
-            if (t0 + tl < p.T) {
-                const size_t cen = ((size_t)g * M + m) * kCentroids + idx_s[tl * M + m];
+    if constexpr (kAccumulate) {
+        __syncthreads();
+        // the run's partial sums -> memory
+        for (int e = tid; e < MSW * kCentroids; e += kVqBlock) {
+            const float *a = acc_s + (size_t)e * (d + 1);
+            const int n = (int)a[d];
+            if (n > 0) {
+                const size_t cen = ((size_t)g * M + (size_t)grp * MSW) * kCentroids + e;
 #pragma unroll
-                for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
-                atomicAdd(p.km_counts + cen, 1);
+                for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, a[j]);
+                atomicAdd(p.km_counts + cen, n);
             }
         }
+        double e64 = (double)err;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
+        if (lane == 0 && state) unsafeAtomicAdd(&state->err_cur, e64);
     }
 }
+
 
 __global__ void kmeans_zero_kernel(float *sums, int32_t *counts, size_t n_sums, size_t n_counts)
 {
@@ -232,132 +248,6 @@ __global__ void kmeans_finalize_kernel(const float *sums, const int32_t *counts,
     if (counts_out) counts_out[c] = n;
     for (int j = 0; j < d; ++j)
         cb_out[c * d + j] = n > 0 ? __float2half(sums[c * d + j] / (float)n) : cb_in[c * d + j];
-}
-
-// ---------------------------------------------------------------------------------------------
-// K-Means training (Sec. 2.2, 3.2, 4.1), 8-bit codes: assignment + accumulation in one kernel.
-//
-// A workgroup takes one chunk of four sub-spaces (one per wavefront) of one (sequence, KV head) and
-// walks over a run of `tiles_per_wg` 64-token tiles.  Per tile it transforms the rows exactly as the
-// cache-fill kernel does (same function, so k~ is bit-identical), keeps the chunk's 4 d channels,
-// searches the four codebooks (same arithmetic and tie rule as encode_kernel: the codes are the
-// ones vecinfer_encode_* would write), and adds every sub-vector to the sum of its centroid in
-// LDS (ds_add_f32: fast, and a long run of tokens meets each of the 256 centroids many times).
-// Only at the end of the run do the 4 x 256 x (d + 1) partial sums go to memory, one atomic each.
-// The rows are read M / 4 times in all (once per chunk); the search, which dominates, is not repeated.
-// The squared distance of every sub-vector to its centroid is summed on the way: the
-// quantization error of the assignment.
-struct KmeansState {
-    double err_cur;       // quantization error of the assignment being accumulated
-    double err_prev;      // .. of the iteration before
-    int32_t stop_at;      // iteration after whose update the training stopped (INT32_MAX: not yet)
-    int32_t pad;
-};
-
-template <int D, int d, bool kTransform>
-__global__ __launch_bounds__(kEncBlock) void kmeans_assign_kernel(EncodeParams p, int tiles_per_wg, int iter,
-                                                                  KmeansState *state)
-{
-    constexpr int M = D / d;
-    constexpr int MS = kChunkSub;
-    constexpr int CH = MS * d;                 // channels of the chunk
-    constexpr int XS = D + 4;                  // row stride of the transformed tile
-    extern __shared__ __align__(16) unsigned char km_smem[];
-    float *const cb_s = reinterpret_cast<float *>(km_smem);                 // [MS][256][d] fp32 centroids
-    float *const x_s = cb_s + MS * kCentroids * d;                          // [64][XS] transformed tile
-    float *const acc_s = x_s + kEncTokens * XS;                             // [MS][256][d + 1] sums and counts
-    uint8_t *const idx_s = reinterpret_cast<uint8_t *>(acc_s + MS * kCentroids * (d + 1));   // [64][MS]
-
-    if (iter > 0 && iter > state->stop_at) return;     // training already stopped (same for every thread)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = blockIdx.y;
-    const int bg = blockIdx.z, g = bg % p.Hkv;
-    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
-
-    {   // the chunk's centroids, widened once (exact); accumulators cleared
-        const uint2 *src = reinterpret_cast<const uint2 *>(p.cb + ((size_t)g * M + (size_t)chunk * MS) * kCentroids * d);
-        float4 *dst = reinterpret_cast<float4 *>(cb_s);
-        for (int e = tid; e < MS * kCentroids * d / 4; e += kEncBlock) {
-            const uint2 raw = src[e];
-            const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
-            const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
-            float4 w; w.x = __low2float(h01); w.y = __high2float(h01); w.z = __low2float(h23); w.w = __high2float(h23);
-            dst[e] = w;
-        }
-        for (int e = tid; e < MS * kCentroids * (d + 1); e += kEncBlock) acc_s[e] = 0.f;
-    }
-    auto dist_bits = [&](const float (&x)[d], const float *cen) -> unsigned {
-        float dist = 0.f;
-#pragma unroll
-        for (int j = 0; j < d; ++j) {
-            const float t = x[j] - cen[j];
-            dist = fmaf(t, t, dist);
-        }
-        return __float_as_uint(dist);
-    };
-    float err = 0.f;
-    for (int ti = 0; ti < tiles_per_wg; ++ti) {
-        const long long t0 = (tile0 + ti) * kEncTokens;
-        if (t0 >= p.T) break;
-        __syncthreads();                       // previous tile's x_s, idx_s consumed; tables ready
-        load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
-        __syncthreads();
-        {   // wavefront `wave` searches sub-space chunk * MS + wave; a lane owns a token
-            const int ms = wave;
-            float x[d];
-#pragma unroll
-            for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + chunk * CH + ms * d + j];
-            const float *cen = cb_s + (size_t)ms * kCentroids * d;
-            unsigned best = 0x7f800000u;            // +inf
-            int best_group = 0;
-#pragma unroll 2
-            for (int c0 = 0; c0 < kCentroids; c0 += 8) {
-                unsigned gmin = dist_bits(x, cen + c0 * d);
-#pragma unroll
-                for (int k = 1; k < 8; ++k) {
-                    const unsigned v = dist_bits(x, cen + (c0 + k) * d);
-                    gmin = v < gmin ? v : gmin;
-                }
-                if (gmin < best) {
-                    best = gmin;
-                    best_group = c0;
-                }
-            }
-            int arg = best_group;
-#pragma unroll
-            for (int k = 7; k >= 0; --k)
-                if (dist_bits(x, cen + (best_group + k) * d) == best) arg = best_group + k;
-            idx_s[lane * MS + ms] = (uint8_t)arg;
-            if (t0 + lane < p.T) {
-                float *a = acc_s + ((size_t)ms * kCentroids + arg) * (d + 1);
-#pragma unroll
-                for (int j = 0; j < d; ++j) atomicAdd(a + j, x[j]);
-                atomicAdd(a + d, 1.0f);             // (counts stay exact in fp32: far below 2^24 per run)
-                err += __uint_as_float(best);
-            }
-        }
-        __syncthreads();
-        // the chunk's MS = 4 code bytes of each token: one 32-bit word of its row
-        if (tid < kEncTokens && t0 + tid < p.T)
-            *reinterpret_cast<uint32_t *>(p.idx + ((size_t)bg * p.n_cap + p.pos0 + t0 + tid) * M + chunk * MS) =
-                reinterpret_cast<const uint32_t *>(idx_s)[tid];
-    }
-    __syncthreads();
-    // the run's partial sums -> memory
-    for (int e = tid; e < MS * kCentroids; e += kEncBlock) {
-        const float *a = acc_s + (size_t)e * (d + 1);
-        const int n = (int)a[d];
-        if (n > 0) {
-            const size_t cen = ((size_t)g * M + (size_t)chunk * MS) * kCentroids + e;
-#pragma unroll
-            for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, a[j]);
-            atomicAdd(p.km_counts + cen, n);
-        }
-    }
-    double e64 = (double)err;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
-    if (lane == 0 && state) unsafeAtomicAdd(&state->err_cur, e64);
 }
 
 // Start of a training iteration: sums and counts cleared, the error accumulator reset (and, before
@@ -864,6 +754,48 @@ int launch_encode_wide(const EncodeParams &p, hipStream_t stream)
     }
 }
 
+int device_cus()
+{
+    static const int cached = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;                     // MI355X; used only to size the grid
+        return n;
+    }();
+    return cached;
+}
+
+// vq_tile_kernel over the T tokens of p: runs long enough that the tables are built a few times per
+// compute unit only (and, for K-Means, that a workgroup meets each centroid many times), short
+// enough that the grid still fills the chip several times over.
+template <int D, int d, bool kAccumulate>
+int launch_vq_tiles(const EncodeParams &p, int iter, void *state, hipStream_t stream)
+{
+    constexpr int M = D / d, MSW = vq_group<d, kAccumulate>(M);
+    constexpr size_t smem = vq_smem_bytes<D, d, kAccumulate>();
+    static_assert(smem <= 160 * 1024, "LDS of a compute unit");
+    static const bool configured =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(vq_tile_kernel<D, d, true, kAccumulate>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(vq_tile_kernel<D, d, false, kAccumulate>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    if (!configured) return -4;
+    const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
+    const long long groups = (long long)(M / MSW) * p.B * p.Hkv;
+    long long per = tiles * groups / (4LL * device_cus());
+    if (per < 1) per = 1;
+    if (per > 256) per = 256;
+    dim3 grid((unsigned)((tiles + per - 1) / per), M / MSW, p.B * p.Hkv);
+    if (p.lam)
+        hipLaunchKernelGGL((vq_tile_kernel<D, d, true, kAccumulate>), grid, dim3(kVqBlock), smem, stream, p, (int)per, iter,
+                           static_cast<KmeansState *>(state));
+    else
+        hipLaunchKernelGGL((vq_tile_kernel<D, d, false, kAccumulate>), grid, dim3(kVqBlock), smem, stream, p, (int)per, iter,
+                           static_cast<KmeansState *>(state));
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
 template <int D, int d>
 int launch_typed(const EncodeParams &p, hipStream_t stream)
 {
@@ -875,12 +807,7 @@ int launch_typed(const EncodeParams &p, hipStream_t stream)
             hipLaunchKernelGGL((encode_token_kernel<D, d, false>), tgrid, dim3(kCentroids), 0, stream, p);
         return hipGetLastError() == hipSuccess ? 0 : -4;
     }
-    dim3 grid((unsigned)((p.T + kEncTokens - 1) / kEncTokens), 1, p.B * p.Hkv);
-    if (p.lam)
-        hipLaunchKernelGGL((encode_kernel<D, d, true>), grid, dim3(kEncBlock), 0, stream, p);
-    else
-        hipLaunchKernelGGL((encode_kernel<D, d, false>), grid, dim3(kEncBlock), 0, stream, p);
-    return hipGetLastError() == hipSuccess ? 0 : -4;
+    return launch_vq_tiles<D, d, false>(p, 0, nullptr, stream);
 }
 
 template <int D, int dk>
@@ -951,52 +878,23 @@ int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __hal
 
 namespace {
 
-template <int D, int d>
-int launch_kmeans_assign_typed(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream)
-{
-    constexpr int M = D / d;
-    constexpr size_t smem = sizeof(float) * ((size_t)kChunkSub * kCentroids * d + (size_t)kEncTokens * (D + 4) +
-                                             (size_t)kChunkSub * kCentroids * (d + 1)) + kEncTokens * kChunkSub;
-    static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kmeans_assign_kernel<D, d, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(kmeans_assign_kernel<D, d, false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
-    if (!configured) return -4;
-    // runs long enough that a workgroup meets each centroid many times, short enough that the
-    // grid still fills the chip several times over
-    const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
-    const long long groups = (long long)(M / kChunkSub) * p.B * p.Hkv;
-    long long per = tiles * groups / (8LL * num_cus);
-    if (per < 1) per = 1;
-    if (per > 256) per = 256;
-    dim3 grid((unsigned)((tiles + per - 1) / per), M / kChunkSub, p.B * p.Hkv);
-    if (p.lam)
-        hipLaunchKernelGGL((kmeans_assign_kernel<D, d, true>), grid, dim3(kEncBlock), smem, stream, p, (int)per, iter,
-                           static_cast<KmeansState *>(state));
-    else
-        hipLaunchKernelGGL((kmeans_assign_kernel<D, d, false>), grid, dim3(kEncBlock), smem, stream, p, (int)per, iter,
-                           static_cast<KmeansState *>(state));
-    return hipGetLastError() == hipSuccess ? 0 : -4;
-}
-
 } // namespace
 
 size_t kmeans_state_bytes() { return sizeof(KmeansState); }
 
 // Assignment + accumulation of one training iteration for 8-bit codes (rows layout of the codes).
-int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, int num_cus, hipStream_t stream)
+int launch_kmeans_assign(const EncodeParams &p, int iter, void *state, hipStream_t stream)
 {
     if (p.bits != 8 || !p.km_sums || p.tiled) return -2;
     if ((p.T + kEncTokens - 1) / kEncTokens > 0x7fffffffLL || p.B * p.Hkv > 65535) return -2;
     const int key = p.D * 10 + p.d;
     switch (key) {
-    case 1282: return launch_kmeans_assign_typed<128, 2>(p, iter, state, num_cus, stream);
-    case 1284: return launch_kmeans_assign_typed<128, 4>(p, iter, state, num_cus, stream);
-    case 1288: return launch_kmeans_assign_typed<128, 8>(p, iter, state, num_cus, stream);
-    case 642: return launch_kmeans_assign_typed<64, 2>(p, iter, state, num_cus, stream);
-    case 644: return launch_kmeans_assign_typed<64, 4>(p, iter, state, num_cus, stream);
-    case 648: return launch_kmeans_assign_typed<64, 8>(p, iter, state, num_cus, stream);
+    case 1282: return launch_vq_tiles<128, 2, true>(p, iter, state, stream);
+    case 1284: return launch_vq_tiles<128, 4, true>(p, iter, state, stream);
+    case 1288: return launch_vq_tiles<128, 8, true>(p, iter, state, stream);
+    case 642: return launch_vq_tiles<64, 2, true>(p, iter, state, stream);
+    case 644: return launch_vq_tiles<64, 4, true>(p, iter, state, stream);
+    case 648: return launch_vq_tiles<64, 8, true>(p, iter, state, stream);
     default: return -2;
     }
 }

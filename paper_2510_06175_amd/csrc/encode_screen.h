@@ -1,0 +1,340 @@
+// Nearest-centroid search (Eq. 2) of the tiled cache-fill and K-Means kernels: a matrix-core screen
+// followed by the exact comparison.
+//
+// What is written is, bit for bit, what the plain search writes: the centroid with the smallest
+// squared distance, summed directly in fp32 in channel order, lowest index among equals.  The
+// matrix cores only tell which centroids can possibly be that one:
+//   score(c) = sigma (x . c - |c|^2 / 2)      (largest score <=> smallest distance)
+// for the 64 tokens of a tile against the 256 centroids of a sub-space, as
+// v_mfma_f32_32x32x16_f16 products: rows = 32 centroids, columns = 32 tokens, and along k
+//   [ c          | c          | -sigma |c|^2 / 2 as two fp16 parts ]   (A)
+//   [ hi(sigma x)| lo(sigma x)| 1 1                               ]   (B)
+// (hi + lo: sigma x to 22 bits; the centroids are fp16 already; sigma, a power of two per
+// sub-space, keeps the low parts out of the fp16 denormal range).  The screen's error is bounded
+// (below), so every centroid that can win or tie has a score within `margin` of the best one.
+// A lane keeps, of the 128 scores it sees per token, only their maxima over the 16 registers of
+// each MFMA (8 "blocks") and over the 8 MFMAs for each register (16 "groups"): a score within the
+// margin marks its block and its group, so the (few, normally one) marked pairs are a superset
+// of the centroids that matter, and only those get the exact distance.
+//
+// Error bound, in score units (T = sum_j |x_j| max|c_j| + max|c|^2 / 2 bounds the sum of the
+// magnitudes of a score's terms):
+//   split of sigma x          <= 2^-22 sigma T        fp32 |c|^2 and its two parts   <= 2^-20.2 sigma T
+//   fp32 accumulation of <= 18 products, taken as truncating                          <= 2^-19 sigma T
+//   fp16 parts below 2^-14 taken as flushed to zero: <= 2^-14 (d max|c_j| + 3), whatever sigma
+//   two scores compared: twice that, < 2^-17 sigma T + 2^-13 (d max|c_j| + 3)
+//   the exact distances themselves carry (d + 2) 2^-24 relative rounding each; a centroid is
+//   safely worse when its true distance exceeds the best's by 2^-18.9 times the best distance
+//   (<= 2 (|x|^2 + max|c|^2)), i.e. by 2^-18 sigma (|x|^2 + max|c|^2) in score units.
+// margin = sigma (2^-17 T + 2^-18 (|x|^2 + max|c|^2)) + 2^-13 (d max|c_j| + 3).
+// A token whose scaled sub-vector leaves the fp16 range (or holds an infinity or a NaN) has no
+// finite best score, a sub-space whose |c|^2 does not fit gets a NaN sigma: either way the
+// wavefront falls back to the plain search for that tile.
+#pragma once
+#include "common.h"
+
+namespace vecinfer {
+
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// LDS tables of one sub-space: plane 0 = the fp16 centroids as MFMA A operands want them (d = 2:
+// each twice, d = 4: 8 bytes, d = 8: 16 bytes), plane 1 = -sigma |c|^2 / 2 as {hi, lo}; 16 spare
+// bytes, so that an 8-byte read of the last plane-1 entry stays inside.
+template <int d>
+struct ScreenTab {
+    static constexpr int kCenBytes = d == 8 ? 16 : 8;
+    static constexpr int kPlane0 = kCentroids * kCenBytes;
+    static constexpr int kBytes = kPlane0 + kCentroids * 4 + 16;
+};
+
+struct ScreenConsts {
+    float sigma, cmax, nmax;
+};
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// Built by one wavefront (the one that searches the sub-space) from the sub-space's codebook
+// `src` [256][d] fp16 in memory.
+template <int d>
+__device__ __forceinline__ ScreenConsts screen_prepare(const __half *src, unsigned char *tab, int lane)
+{
+    float n[4], cm = 0.f, nm = 0.f;
+    typedef _Float16 f16xd __attribute__((ext_vector_type(d)));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        const f16xd raw = *reinterpret_cast<const f16xd *>(src + c * d);
+        float v[d];
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < d; ++j) {
+            v[j] = (float)raw[j];
+            s = fmaf(v[j], v[j], s);
+            cm = fmaxf(cm, fabsf(v[j]));
+        }
+        n[i] = s;
+        nm = fmaxf(nm, s);
+        if constexpr (d == 8) {
+            f16x8 h;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (_Float16)v[j];
+            *reinterpret_cast<f16x8 *>(tab + c * 16) = h;
+        } else if constexpr (d == 4) {
+            const f16x4 h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+            *reinterpret_cast<f16x4 *>(tab + c * 8) = h;
+        } else {
+            const f16x4 h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[0], (_Float16)v[1]};
+            *reinterpret_cast<f16x4 *>(tab + c * 8) = h;
+        }
+    }
+    cm = wave_max(cm);
+    nm = wave_max(nm);
+    // sigma: the power of two that brings max |c|^2 / 2 to about 2^10 (within 2^-14 .. 2^14)
+    int e = 9 - ilogbf(fmaxf(0.5f * nm, 1e-30f));
+    e = e < -14 ? -14 : (e > 14 ? 14 : e);
+    float sigma = ldexpf(1.0f, e);
+    // centroids too large for the fp16 parts of -sigma |c|^2 / 2 (or not finite): no screen for this
+    // sub-space; a NaN sigma makes every margin NaN, which sends every tile to the plain search
+    if (!(0.5f * sigma * nm < 60000.0f)) sigma = __builtin_nanf("");
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        const float v = -0.5f * sigma * n[i];
+        const _Float16 hi = (_Float16)v;
+        const f16x2 h = {hi, (_Float16)(v - (float)hi)};
+        *reinterpret_cast<f16x2 *>(tab + ScreenTab<d>::kPlane0 + c * 4) = h;
+    }
+    return ScreenConsts{sigma, cm, nm};
+}
+
+// Bits of the squared distance of x to centroid c of the sub-space whose tables are `tab`: the
+// fp16 centroid widened (exact), differences squared and summed in channel order in fp32.
+template <int d>
+__device__ __forceinline__ unsigned screen_dist_bits(const float (&x)[d], const unsigned char *tab, int c)
+{
+    typedef _Float16 f16xd __attribute__((ext_vector_type(d)));
+    const f16xd cen = *reinterpret_cast<const f16xd *>(tab + c * ScreenTab<d>::kCenBytes);
+    float dist = 0.f;
+#pragma unroll
+    for (int j = 0; j < d; ++j) {
+        const float t = x[j] - (float)cen[j];
+        dist = fmaf(t, t, dist);
+    }
+    return __float_as_uint(dist);
+}
+
+// The plain search of one token's sub-vector x over the 256 centroids (the same address in every
+// lane: broadcast reads): groups of 8, the group minimum against the running best (strict "<":
+// the earliest group wins), the winning group re-evaluated for the lowest index at the minimum.
+template <int d>
+__device__ __forceinline__ void plain_search(const float (&x)[d], const unsigned char *tab, int &arg_out,
+                                             unsigned &best_out)
+{
+    unsigned best = 0x7f800000u;            // +inf
+    int best_group = 0;
+#pragma unroll 2
+    for (int c0 = 0; c0 < kCentroids; c0 += 8) {
+        unsigned gmin = screen_dist_bits<d>(x, tab, c0);
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            const unsigned v = screen_dist_bits<d>(x, tab, c0 + k);
+            gmin = v < gmin ? v : gmin;
+        }
+        if (gmin < best) {
+            best = gmin;
+            best_group = c0;
+        }
+    }
+    int arg = best_group;
+#pragma unroll
+    for (int k = 7; k >= 0; --k)
+        if (screen_dist_bits<d>(x, tab, best_group + k) == best) arg = best_group + k;
+    arg_out = arg;
+    best_out = best;
+}
+
+// The wavefront's 64 tokens (rows of x_s, channels ch0 .. ch0 + d) against the sub-space whose
+// tables are `tab`.  Returns the code of token `lane` and the bits of its squared distance; false
+// if the screen marked nothing for some token of the wavefront (the caller then runs the plain
+// search; same for every lane).
+template <int d>
+__device__ __forceinline__ bool screen_search(const float *x_s, int XS, int ch0, const unsigned char *tab,
+                                              const ScreenConsts &k, int lane, int &arg_out, unsigned &best_out)
+{
+    using Tab = ScreenTab<d>;
+    const int h = lane >> 5, col = lane & 31;
+    const _Float16 one = (_Float16)1.0f, zero = (_Float16)0.0f;
+    const f16x8 ones = {one, one, zero, zero, zero, zero, zero, zero};
+    const f16x8 zeros = {zero, zero, zero, zero, zero, zero, zero, zero};
+    // ---- B operands and margins of tokens col (cb = 0) and 32 + col (cb = 1)
+    f16x8 b1[2], b2[2];
+    float mg[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        float x[d], l1 = 0.f, l2 = 0.f;
+        _Float16 hi[d], lo[d];
+#pragma unroll
+        for (int j = 0; j < d; ++j) {
+            x[j] = x_s[(32 * cb + col) * XS + ch0 + j];
+            l1 += fabsf(x[j]);
+            l2 = fmaf(x[j], x[j], l2);
+            const float xs = x[j] * k.sigma;
+            hi[j] = (_Float16)xs;
+            lo[j] = (_Float16)(xs - (float)hi[j]);
+        }
+        mg[cb] = k.sigma * (0x1p-17f * (l1 * k.cmax + 0.5f * k.nmax) + 0x1p-18f * (l2 + k.nmax)) +
+                 0x1p-13f * ((float)d * k.cmax + 3.0f);
+        f16x8 v;
+        if constexpr (d == 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = h ? lo[j] : hi[j];
+            b2[cb] = h ? zeros : ones;
+        } else if constexpr (d == 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[j] = h ? ones[j] : hi[j];
+                v[4 + j] = h ? zero : lo[j];
+            }
+        } else {
+            v = zeros;
+            v[0] = h ? one : hi[0];
+            v[1] = h ? one : hi[1];
+            v[2] = h ? zero : lo[0];
+            v[3] = h ? zero : lo[1];
+        }
+        b1[cb] = v;
+    }
+    // ---- scores, 2 x 32 centroids at a time; maxima per block (MFMA) and per group (register)
+    float bm[2][8], gm[2][16];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) gm[cb][r] = -INFINITY;
+    const f32x16 z16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rp = 0; rp < 4; ++rp) {
+        f16x8 a1[2], a2[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int row = 32 * (2 * rp + u) + col;
+            if constexpr (d == 8) {
+                a1[u] = *reinterpret_cast<const f16x8 *>(tab + row * 16);
+                const f16x2 nn = *reinterpret_cast<const f16x2 *>(tab + Tab::kPlane0 + row * 4);
+                a2[u] = zeros;
+                a2[u][0] = nn[0];
+                a2[u][1] = nn[1];
+            } else {
+                // lanes 0-31: the centroid (8 bytes); lanes 32-63: the 4 bytes of plane 1 (read as 8)
+                const f16x4 rd = *reinterpret_cast<const f16x4 *>(tab + (h ? Tab::kPlane0 + row * 4 : row * 8));
+                a1[u] = zeros;
+                a1[u][0] = rd[0];
+                a1[u][1] = rd[1];
+                a1[u][2] = h ? zero : rd[2];
+                a1[u][3] = h ? zero : rd[3];
+                if constexpr (d == 4) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) a1[u][4 + j] = h ? zero : rd[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            f32x16 v[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                v[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[u], b1[cb], z16, 0, 0, 0);
+                if constexpr (d == 8) v[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2[u], b2[cb], v[u], 0, 0, 0);
+                float m = fmaxf(v[u][0], v[u][1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2) m = fmaxf(fmaxf(m, v[u][r]), v[u][r + 1]);
+                bm[cb][2 * rp + u] = m;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gm[cb][r] = fmaxf(fmaxf(gm[cb][r], v[0][r]), v[1][r]);
+        }
+    }
+    // ---- blocks and groups within the margin of the token's best score (both halves of the wavefront)
+    unsigned mask[2];
+    bool finite[2];                        // the token's scores are numbers: the marks mean something
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        float best = fmaxf(bm[cb][0], bm[cb][1]);
+#pragma unroll
+        for (int r = 2; r < 8; r += 2) best = fmaxf(fmaxf(best, bm[cb][r]), bm[cb][r + 1]);
+        best = fmaxf(best, __shfl_xor(best, 32));
+        const float thr = best - mg[cb];
+        finite[cb] = fabsf(thr) < INFINITY;
+        // a maximum above thr marks its block / group: the sign bit of thr - maximum, shifted into
+        // the mask (one subtraction and one v_alignbit each)
+        unsigned m = 0;
+#pragma unroll
+        for (int r = 15; r >= 0; --r) m = __builtin_amdgcn_alignbit(m, __float_as_uint(thr - gm[cb][r]), 31);
+#pragma unroll
+        for (int r = 7; r >= 0; --r) m = __builtin_amdgcn_alignbit(m, __float_as_uint(thr - bm[cb][r]), 31);
+        mask[cb] = m;                      // bits 0-7: blocks, bits 8-23: groups
+    }
+    // token `lane`: the marks of its own half of the rows, and those of the other half
+    const unsigned mine = h ? mask[1] : mask[0];
+    const unsigned other = __shfl_xor(h ? mask[0] : mask[1], 32);
+    // ---- exact distances of the marked centroids
+    float x[d];
+#pragma unroll
+    for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + ch0 + j];
+    unsigned best = 0x7f800000u;
+    int arg = 0;
+#pragma unroll
+    for (int side = 0; side < 2; ++side) {
+        const unsigned m = side == 0 ? mine : other;
+        const int hh = side == 0 ? h : (h ^ 1);
+        unsigned mb = m & 0xffu;
+        const unsigned mgp = m >> 8;
+        while (mb) {
+            const int rb = __builtin_ctz(mb);
+            mb &= mb - 1;
+            unsigned gg = mgp;
+            while (gg) {
+                const int r = __builtin_ctz(gg);
+                gg &= gg - 1;
+                const int c = 32 * rb + 8 * (r >> 2) + 4 * hh + (r & 3);   // row of register r of block rb
+                const unsigned dist = screen_dist_bits<d>(x, tab, c);
+                if (dist < best || (dist == best && c < arg)) {
+                    best = dist;
+                    arg = c;
+                }
+            }
+        }
+    }
+    arg_out = arg;
+    best_out = best;
+    // no screen result for a token whose scaled operands left the fp16 range (infinite or NaN
+    // scores), and none where nothing finite was found
+    const bool mine_ok = h ? finite[1] : finite[0];
+    return !__any(best == 0x7f800000u || !mine_ok);
+}
+
+// One wavefront, one sub-space, the 64 tokens of the tile in x_s: the screen and the exact
+// distances of what it marks; the plain search when the screen marks nothing.
+template <int d>
+__device__ __forceinline__ void search_tile(const float *x_s, int XS, int ch0, const unsigned char *tab,
+                                            const ScreenConsts &k, int lane, int &arg, unsigned &best)
+{
+    if (screen_search<d>(x_s, XS, ch0, tab, k, lane, arg, best)) return;
+    float x[d];
+#pragma unroll
+    for (int j = 0; j < d; ++j) x[j] = x_s[lane * XS + ch0 + j];
+    plain_search<d>(x, tab, arg, best);
+}
+
+} // namespace
+
+} // namespace vecinfer
