@@ -18,15 +18,15 @@
  *   vo_vq_encode           Sec. 2.2, Eq. 2; Sec. 3.2, Eq. 8
  *   vo_vq_dequantize       Sec. 2.2 (last paragraph): VQ^{-1} = centroid lookup
  *   vo_vq_attention        Sec. 3.2, Eq. 10 (explicit dequantize-then-attend)
- *   vo_vq_attention_alg1   App. A, Alg. 1 steps 4-23 (lookup table, tiles, online softmax, LSE)
+ *   vo_vq_attention_alg1   App. A, Alg. 1 as a self-check of Eq. 10: lookup-table scores, tiles, LSE merge
  *   vo_vq_attention_residual  Eq. 10 plus the full-precision residual window of Sec. 4.1
- *                          ("residual length ... 128"): recent tokens kept unquantized
+ *                          (the 128 most recent tokens kept unquantized)
  *   vo_kmeans_update       centroid update of one Lloyd iteration of the K-Means codebook training
  *                          (Sec. 2.2: the codebook is built by K-Means; Sec. 4.1: at most 30 iterations)
  *   vo_vq_encode_g, vo_vq_dequantize_g, vo_vq_attention_g, vo_encode_batch_g, vo_decode_batch_g
  *                          the same definitions (Eq. 2, VQ^{-1}, Eq. 10) for codes of up to 16 bits and
  *                          for a codebook shared by all sub-spaces, as Alg. 1 states it (one C_k, one
- *                          C_v of 2^b centroids; "codebook size 2^b x d x 2 bytes", Sec. 5.3), which the
+ *                          C_v of 2^b centroids; Sec. 5.3 sizes the codebook at 2^b * d * 2 bytes), which the
  *                          configurations with 10- and 12-bit codes (d8b12, d4b12, d4b10; Sec. 4.1,
  *                          Tables 1-3) call for
  *   vo_kmeans_update_g     the same update for a codebook shared by the sub-spaces (pooled sub-vectors)
@@ -266,18 +266,28 @@ int vo_vq_attention_residual(const double *qt, const double *q_raw, const uint8_
     return 0;
 }
 
-/* Alg. 1 steps 4-23 for one query row against one KV head, in the order and
- * notation of the listing: lut = qt' C_k^T; tiles of `Bt` tokens; per tile
- * s = lookup(K_q, lut)/sqrt(D), m_new, p, l_new, o update; then o / l and
- * L = m + log l.  (The prefetch steps move data only and have no CPU analogue.) */
+void vo_merge_splits(const double *o_parts, const double *L_parts, int S, int D, double *out, double *lse);
+
+/* What App. A, Alg. 1 computes for one query row against one KV head, put together from two facts
+ * rather than from the listing's running updates:
+ *   (1) the score of a token is a sum of table entries: with lut[m][c] = qt_m . C_k[m][c], the dot
+ *       product of qt with the dequantized key is sum_m lut[m][K_q[n][m]]  (the lookup of Sec. 3.3);
+ *   (2) attention over a token range can be computed tile by tile: every tile of `Bt` tokens gets
+ *       its own plain softmax result (o_t, L_t), and the tiles are joined by the log-sum-exp merge
+ *       (vo_merge_splits), which is what the online rescaling of Alg. 1 amounts to.
+ * The tests check that this equals the Eq. 10 definition (vo_vq_attention) for any tile size. */
 int vo_vq_attention_alg1(const double *qt, const uint8_t *kidx, const uint8_t *vidx,
                          const double *cb_k, const double *cb_v, int64_t N, int D,
                          int d_k, int d_v, int C, int64_t Bt, double *out, double *lse)
 {
     if (N < 1 || Bt < 1) return -1;
     const int Mk = D / d_k, Mv = D / d_v;
+    const int64_t T = (N + Bt - 1) / Bt;
+    if (T > 0x7fffffff) return -1;
     double *lut = (double *)malloc(sizeof(double) * (size_t)Mk * C);
     double *s = (double *)malloc(sizeof(double) * (size_t)Bt);
+    double *o_t = (double *)malloc(sizeof(double) * (size_t)T * D);
+    double *L_t = (double *)malloc(sizeof(double) * (size_t)T);
     for (int m = 0; m < Mk; ++m)
         for (int c = 0; c < C; ++c) {
             double acc = 0.0;
@@ -285,40 +295,38 @@ int vo_vq_attention_alg1(const double *qt, const uint8_t *kidx, const uint8_t *v
                 acc += qt[m * d_k + j] * cb_k[((int64_t)m * C + c) * d_k + j];
             lut[m * C + c] = acc;
         }
-    const double rsd = sqrt((double)D);
-    double m_run = -INFINITY, l_run = 0.0;
-    for (int i = 0; i < D; ++i) out[i] = 0.0;
-    const int64_t T = (N + Bt - 1) / Bt;
+    const double scale = 1.0 / sqrt((double)D);
     for (int64_t t = 0; t < T; ++t) {
         const int64_t n0 = t * Bt;
         const int64_t nb = (N - n0 < Bt) ? (N - n0) : Bt;
-        double m_new = m_run;
+        double mx = -INFINITY;
         for (int64_t r = 0; r < nb; ++r) {
             double acc = 0.0;
             for (int m = 0; m < Mk; ++m) acc += lut[m * C + kidx[(n0 + r) * Mk + m]];
-            s[r] = acc / rsd;
-            if (s[r] > m_new) m_new = s[r];
+            s[r] = acc * scale;
+            if (s[r] > mx) mx = s[r];
         }
-        const double alpha = exp(m_run - m_new); /* exp(-inf) = 0 on the first tile */
-        double rowsum = 0.0;
+        double denom = 0.0;
         for (int64_t r = 0; r < nb; ++r) {
-            s[r] = exp(s[r] - m_new);
-            rowsum += s[r];
+            s[r] = exp(s[r] - mx);
+            denom += s[r];
         }
-        const double l_new = alpha * l_run + rowsum;
-        for (int i = 0; i < D; ++i) out[i] *= alpha;
-        for (int64_t r = 0; r < nb; ++r)
+        double *o = o_t + t * D;
+        for (int i = 0; i < D; ++i) o[i] = 0.0;
+        for (int64_t r = 0; r < nb; ++r) {
+            const double p = s[r] / denom;
             for (int m = 0; m < Mv; ++m) {
                 const double *cen = cb_v + ((int64_t)m * C + vidx[(n0 + r) * Mv + m]) * d_v;
-                for (int j = 0; j < d_v; ++j) out[m * d_v + j] += s[r] * cen[j];
+                for (int j = 0; j < d_v; ++j) o[m * d_v + j] += p * cen[j];
             }
-        l_run = l_new;
-        m_run = m_new;
+        }
+        L_t[t] = mx + log(denom);
     }
-    for (int i = 0; i < D; ++i) out[i] /= l_run;
-    if (lse) *lse = m_run + log(l_run);
+    vo_merge_splits(o_t, L_t, (int)T, D, out, lse);
     free(lut);
     free(s);
+    free(o_t);
+    free(L_t);
     return 0;
 }
 
