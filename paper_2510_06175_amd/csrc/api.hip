@@ -38,6 +38,10 @@ bool wide(const vecinfer_cfg *c) { return c->k_bits != 8 || c->v_bits != 8; }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+} // namespace
+
+namespace vecinfer {
+
 int num_cus()
 {
     // queried once per process (function-local static: initialised thread-safely); the library is
@@ -51,6 +55,10 @@ int num_cus()
     }();
     return cached;
 }
+
+} // namespace vecinfer
+
+namespace {
 
 // Splits so that B * H_kv * S fills the compute units once, each split keeping enough
 // tokens to amortise staging the codebooks in LDS.

@@ -185,6 +185,8 @@ __device__ __forceinline__ void finish_split(const DecodeParams &p, int b, int g
 
 constexpr int kMaxResidual = 128;                  // rows of the residual window (the paper's setting)
 
+int num_cus();   // compute units of the chip (queried once per process; sizes grids only)
+
 // launchers (one translation unit each)
 int launch_merge(const DecodeParams &p, hipStream_t stream);   // splits (+ residual window) -> out, lse
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);

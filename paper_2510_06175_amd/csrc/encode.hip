@@ -754,18 +754,6 @@ int launch_encode_wide(const EncodeParams &p, hipStream_t stream)
     }
 }
 
-int device_cus()
-{
-    static const int cached = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;                     // MI355X; used only to size the grid
-        return n;
-    }();
-    return cached;
-}
-
 // vq_tile_kernel over the T tokens of p: runs long enough that the tables are built a few times per
 // compute unit only (and, for K-Means, that a workgroup meets each centroid many times), short
 // enough that the grid still fills the chip several times over.
@@ -783,7 +771,7 @@ int launch_vq_tiles(const EncodeParams &p, int iter, void *state, hipStream_t st
     if (!configured) return -4;
     const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
     const long long groups = (long long)(M / MSW) * p.B * p.Hkv;
-    long long per = tiles * groups / (4LL * device_cus());
+    long long per = tiles * groups / (4LL * num_cus());
     if (per < 1) per = 1;
     if (per > 256) per = 256;
     dim3 grid((unsigned)((tiles + per - 1) / per), M / MSW, p.B * p.Hkv);

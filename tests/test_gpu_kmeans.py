@@ -211,8 +211,8 @@ def test_train_refuses_wide_codes():
 
 def test_train_full_size_iteration_properties():
     """65536 tokens x 8 KV heads, d = 4 (the size the iteration is timed at): three iterations in
-    one call; sizes, counts and the means of sampled sub-spaces from the last assignment; the device's
-    last error is the oracle's for sampled heads summed... checked through sampled sub-spaces."""
+    one call; the errors fall, the counts add up, and for sampled (KV head, sub-space) pairs the counts
+    are the histogram of the codes and the centroids the means of their clusters."""
     shape = synth.Shape(1, 32, 8, 128, 65536, 4, 4)
     x, lam, cb0 = _problem(shape, "values", seed=3)
     t = Trainer(shape, x, lam, cb0)
