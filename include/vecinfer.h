@@ -31,7 +31,8 @@
  *   codebooks          fp16  [H_kv, M, 256, d]  one codebook per (KV head, sub-space)
  *   code cache         uint8 [B, H_kv, n_cap, M] one byte per (token, sub-space): the
  *                                               paper's N x M code matrix per head
- *  10- and 12-bit codes (d8b12, d4b12, d4b10, ... of Sec. 4.1; D = 128, d = 4 or 8)
+ *  10- and 12-bit codes (d8b12, d4b12, d4b10, ... of Sec. 4.1; d = 4 or 8; a row must be a whole
+ *  number of 32-bit words, which rules out only d = 8 with 10-bit codes at D = 64)
  *   codebooks          fp16  [H_kv, 2^b, d]     one codebook per KV head, shared by its M
  *                                               sub-spaces: the single codebook of Sec. 2.2
  *                                               and Alg. 1 (2^b x d x 2 bytes; 64 KB at d8b12,
@@ -104,7 +105,8 @@ typedef struct vecinfer_cfg {
     int32_t v_sub_dim;     /* d for values: 2, 4 or 8 (keys and values may differ, Sec. 3.2)  */
     int32_t k_bits;        /* code width b for keys: 8 (one byte per code, 256 centroids per
                               sub-space), or 10 / 12 (packed rows, one shared codebook of 2^b
-                              centroids per KV head; needs D = 128 and d_k = 4 or 8)          */
+                              centroids per KV head; needs d_k = 4 or 8 and (D / d_k) b a
+                              multiple of 32)                                                  */
     int32_t v_bits;        /* code width for values: 8, 10 or 12, same rules with d_v        */
     int32_t v_tiled;       /* physical layout of the value code cache (8-bit value codes only):
                               0 = rows, [B, H_kv, n_cap, M_v] as above;

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvecinfer.so")
-SOURCES = ["api.hip", "merge.hip", "encode.hip", "calibrate.hip", "probe.hip", "decode_lut.hip", "decode_mfma.hip", "decode_mfma_wide.hip", "decode_mfma_tiled.hip", "decode_roles.hip"]
+SOURCES = ["api.hip", "merge.hip", "encode.hip", "calibrate.hip", "probe.hip", "decode_lut.hip", "decode_mfma.hip", "decode_mfma_wide.hip", "decode_mfma_wide64.hip", "decode_mfma_tiled.hip", "decode_roles.hip"]
 
 # Packed-fp32 VALU forms are switched off for the device pass: hipcc otherwise forms them
 # from plain float code.

@@ -25,9 +25,10 @@ bool cfg_ok(const vecinfer_cfg *c)
     if (G > 8) return false;
     auto sub_ok = [](int d) { return d == 2 || d == 4 || d == 8; };
     if (!sub_ok(c->k_sub_dim) || !sub_ok(c->v_sub_dim)) return false;
-    // 10- and 12-bit codes (shared codebook, packed rows): D = 128 and d = 4 or 8 on that side
+    // 10- and 12-bit codes (shared codebook, packed rows): d = 4 or 8 on that side and rows of whole
+    // 32-bit words (all but d = 8 with 10 bits at D = 64)
     auto bits_ok = [&](int bits, int d) {
-        return bits == 8 || ((bits == 10 || bits == 12) && c->head_dim == 128 && (d == 4 || d == 8));
+        return bits == 8 || ((bits == 10 || bits == 12) && (d == 4 || d == 8) && (c->head_dim / d * bits) % 32 == 0);
     };
     if (!bits_ok(c->k_bits, c->k_sub_dim) || !bits_ok(c->v_bits, c->v_sub_dim)) return false;
     // tiled value codes: one byte per code, and at least the 16 sub-spaces the block order is made of

@@ -191,7 +191,8 @@ int num_cus();   // compute units of the chip (queried once per process; sizes g
 int launch_merge(const DecodeParams &p, hipStream_t stream);   // splits (+ residual window) -> out, lse
 int launch_decode_lut(const DecodeParams &p, hipStream_t stream);
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream);
-int launch_decode_mfma_wide(const DecodeParams &p, hipStream_t stream);   // 10- / 12-bit codes
+int launch_decode_mfma_wide128(const DecodeParams &p, hipStream_t stream);   // 10- / 12-bit codes, D = 128
+int launch_decode_mfma_wide64(const DecodeParams &p, hipStream_t stream);    // 10- / 12-bit codes, D = 64
 int launch_decode_mfma_tiled(const DecodeParams &p, hipStream_t stream);  // 8-bit codes, tiled value codes
 bool decode_mfma_supports(const DecodeParams &p);
 bool decode_roles_supports(const DecodeParams &p);                        // score / value wavefront kernel

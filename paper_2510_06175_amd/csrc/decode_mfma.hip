@@ -7,11 +7,12 @@ bool decode_mfma_supports(const DecodeParams &p)
 {
     const bool dk_ok = p.dk == 8 || p.dk == 4 || p.dk == 2;
     const bool dv_ok = p.dv == 8 || p.dv == 4 || p.dv == 2;
-    // 10- and 12-bit codes: D = 128 and d = 4 or 8 on that side, d = 4 or 8 on the other side too
+    // 10- and 12-bit codes: d = 4 or 8 on that side (rows of whole 32-bit words: not d = 8 with 10 bits
+    // at D = 64), d = 4 or 8 on the other side too
     auto wide = [](int b) { return b == 10 || b == 12; };
+    auto row_ok = [&](int d, int b) { return b == 8 || (wide(b) && (p.D / d * b) % 32 == 0); };
     bool bits_ok = p.bk == 8 && p.bv == 8;
-    if (wide(p.bk) || wide(p.bv))
-        bits_ok = p.D == 128 && (wide(p.bk) || p.bk == 8) && (wide(p.bv) || p.bv == 8) && p.dk >= 4 && p.dv >= 4;
+    if (wide(p.bk) || wide(p.bv)) bits_ok = row_ok(p.dk, p.bk) && row_ok(p.dv, p.bv) && p.dk >= 4 && p.dv >= 4;
     // code rows are addressed with 32-bit byte offsets (a row is at most D / 2 bytes)
     // tiled value codes: 8-bit codes on both sides (the instantiations built)
     // (and not d_v = 8 at D = 64: fewer than the 16 sub-spaces the block order is made of)
@@ -23,7 +24,7 @@ bool decode_mfma_supports(const DecodeParams &p)
 int launch_decode_mfma(const DecodeParams &p, hipStream_t stream)
 {
     if (!decode_mfma_supports(p)) return -2;
-    if (p.bk != 8 || p.bv != 8) return launch_decode_mfma_wide(p, stream);
+    if (p.bk != 8 || p.bv != 8) return p.D == 128 ? launch_decode_mfma_wide128(p, stream) : launch_decode_mfma_wide64(p, stream);
     if (p.v_tiled) return launch_decode_mfma_tiled(p, stream);
     // 8 wavefronts per workgroup (2 per SIMD): 12 measured slower, 4 is latency-bound
     const int key = p.D * 100 + p.dk * 10 + p.dv;

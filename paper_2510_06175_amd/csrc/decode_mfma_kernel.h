@@ -66,17 +66,17 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     constexpr int DV = VSPLIT ? 4 : DVR;
     static_assert((kD == 128 || kD == 64) && (DK == 8 || DK == 4 || DK == 2) && (DVR == 8 || DVR == 4 || DVR == 2),
                   "shapes this kernel is laid out for");
-    static_assert(!VSPLIT || (!VT && BV == 8), "split value sub-spaces: 8-bit codes in rows");
+    static_assert(!VSPLIT || !VT, "split value sub-spaces: codes in rows");
     constexpr bool WK = BK > 8, WV = BV > 8;           // wide codes: shared table, packed rows
     static_assert(!VT || !WV, "tiled value codes are 8-bit codes");
-    static_assert((BK == 8 || ((BK == 10 || BK == 12) && kD == 128 && DK >= 4)) &&
-                      (BV == 8 || ((BV == 10 || BV == 12) && kD == 128 && DV >= 4)),
-                  "wide codes: 10 or 12 bits, D = 128, d = 4 or 8");
+    static_assert((BK == 8 || ((BK == 10 || BK == 12) && DK >= 4 && (kD / DK * BK) % 32 == 0)) &&
+                      (BV == 8 || ((BV == 10 || BV == 12) && DVR >= 4 && (kD / DVR * BV) % 32 == 0)),
+                  "wide codes: 10 or 12 bits, d = 4 or 8, rows of whole 32-bit words (not d = 8 with 10 bits at D = 64)");
     constexpr int BLOCK = NW * 64;
     constexpr int MK = kD / DK, MV = kD / DVR;         // sub-spaces: 8, 16, 32 or 64
     // bytes of the key / value tables of a KV head in LDS
     constexpr int CBK_BYTES = WK ? (1 << BK) * DK * 2 : kCentroids * kD * 2;
-    constexpr int CBV_BYTES = WV ? (1 << BV) * DV * 2 : kCentroids * kD * 2;
+    constexpr int CBV_BYTES = WV ? (1 << BV) * DVR * 2 : kCentroids * kD * 2;
     constexpr int ROWB_K = MK * BK / 8, ROWB_V = MV * BV / 8;    // bytes of a token's code row
     constexpr int ENTRY_K = DK * 2, ENTRY_V = DV * 2;  // bytes per centroid: 8 or 4
     constexpr int SUB_K = kCentroids * ENTRY_K;        // one sub-space table: 2048 or 1024 bytes
@@ -92,7 +92,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // dwords that contain it, and a code is cut out of that window when its gather is issued.
     // For values quad lane t0 fetches the window of token t0 of the k-group, and the others read
     // it with DPP.
-    constexpr int WIN_K = DK == 8 ? 2 : 3, WIN_V = DV == 8 ? 2 : 3;
+    constexpr int WIN_K = DK == 8 ? 2 : 3, WIN_V = DVR == 8 ? 2 : 3;
     constexpr int KW = WK ? WIN_K : (MK / 4 + 3) / 4;  // key-code dwords per lane per sub-tile (MK / 4 bytes)
     constexpr int VW = WV ? WIN_V : NROUND_V;          // value-code dwords per lane per sub-tile (4 tokens x NROUND_V bytes)
     // P.V accumulators per head group: one per value sub-space of the lane's column, except at
@@ -221,7 +221,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         // (weights in tiles, from timing four configurations at 196608 tokens: 5 + 14 C / 4096 at
         // d = 8, 5 + 2 C / 4096 at d = 4; the step is within 0.3 us of its best over a wide range)
         constexpr long long wK = WK ? kTile * (((1 << BK) * (DK == 8 ? 14 : 2)) / 4096 + 5) : 0;
-        constexpr long long wV = WV ? kTile * (((1 << BV) * (DV == 8 ? 14 : 2)) / 4096 + 5) : 0;
+        constexpr long long wV = WV ? kTile * (((1 << BV) * (DVR == 8 ? 14 : 2)) / 4096 + 5) : 0;
         constexpr int IK = WK ? ITEMS_K : 0, IV = WV ? ITEMS_V : 0;
         if (fused && S_ >= IK && S_ >= IV) {
             const long long total = len - 1 + wK * IK + wV * IV;
@@ -273,11 +273,14 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     //                   values sub-space NROUND_V*col + r
     const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
     const unsigned lds_k = lds_base + (WK ? 0u : (unsigned)(kg * (MK / 4) * SUB_K));
-    const unsigned lds_v = lds_base + (unsigned)CBK_BYTES + (WV ? 0u : (unsigned)(col * ENTRY_V));
+    // (wide codes with split value sub-spaces: column col reads half col & 1 of its 16-byte centroid)
+    const unsigned lds_v = lds_base + (unsigned)CBK_BYTES +
+                           (WV ? (VSPLIT ? (unsigned)((col & 1) * ENTRY_V) : 0u) : (unsigned)(col * ENTRY_V));
     // wide codes: first bit of the lane's run of codes inside its window, and of its own code(s)
     // inside the quad's window
     const unsigned pos_k = (unsigned)(kg * (MK / 4) * BK) & 31u;
-    const unsigned pos_v = ((unsigned)((col >> 2) * (MV / 4) * BV) & 31u) + (unsigned)((col & 3) * NROUND_V * BV);
+    const unsigned pos_v = ((unsigned)((col >> 2) * (MV / 4) * BV) & 31u) +
+                           (unsigned)((VSPLIT ? (col & 3) >> 1 : (col & 3) * NROUND_V) * BV);
 
     const uint8_t *krow = p.k_idx + bg * p.n_cap * ROWB_K;
     const uint8_t *vrow = p.v_idx + bg * p.n_cap * ROWB_V;
@@ -627,7 +630,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // lowest index at the minimum distance.  Same distance arithmetic as the append kernels.
     auto wide_item = [&](auto kv_c, int grp) {
         constexpr int kv = decltype(kv_c)::value;
-        constexpr int DS = kv == 0 ? DK : DV, BITS = kv == 0 ? BK : BV, MX = kv == 0 ? MK : MV;
+        constexpr int DS = kv == 0 ? DK : DVR, BITS = kv == 0 ? BK : BV, MX = kv == 0 ? MK : MV;
         constexpr int C = 1 << BITS, PER_WAVE = C / NW, EN = 2 * DS;
         const unsigned char *const tab = kv == 0 ? sm_k : sm_v;
         float x[4][DS];
@@ -815,7 +818,7 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     };
     auto win_field_v = [&](const unsigned (&w)[VW], int v, unsigned pos) -> unsigned {
         constexpr auto bits_c = std::integral_constant<int, BV>{};
-        constexpr auto log2e_c = std::integral_constant<int, DV == 8 ? 4 : 3>{};
+        constexpr auto log2e_c = std::integral_constant<int, DVR == 8 ? 4 : 3>{};   // bytes of a table entry
         if constexpr (!WV) return 0u;
         else if constexpr (WIN_V == 2) return field2(quad_get(w[0], v), quad_get(w[1], v), pos, bits_c, log2e_c);
         else return field3(quad_get(w[0], v), quad_get(w[1], v), quad_get(w[2], v), pos, bits_c, log2e_c);

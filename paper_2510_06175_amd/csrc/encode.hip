@@ -410,7 +410,8 @@ constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b,
 // ---------------------------------------------------------------------------------------------
 // Codes wider than 8 bits (10 or 12; d8b12, d4b12, d4b10 of Sec. 4.1): one table of C = 2^b
 // centroids per KV head, shared by its sub-spaces (the codebook of Sec. 2.2 and Alg. 1), and a
-// token's M codes packed end to end, b bits each, in M b / 8 bytes.  D = 128.
+// token's M codes packed end to end, b bits each, in M b / 8 bytes.  D = 128, or D = 64 where a row
+// is a whole number of 32-bit words (not d = 8 with 10-bit codes).
 //
 // Tiled kernel: 64 tokens of one (batch, KV head) per workgroup.  The whole table stays in LDS as
 // fp16 (up to 64 KB) next to the transformed tile.  A lane owns one token, a wavefront M / 4
@@ -473,12 +474,13 @@ __device__ __forceinline__ void store_packed_rows(const EncodeParams &p, const u
     }
 }
 
-template <int d, int BITS, bool kTransform>
+template <int D, int d, int BITS, bool kTransform>
 __global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
 {
-    constexpr int D = 128, M = D / d, C = 1 << BITS;
+    constexpr int M = D / d, C = 1 << BITS;
+    static_assert(M * BITS % 32 == 0, "rows of whole 32-bit words");
     constexpr int XS = D + 4;
-    constexpr int SPW = M / (kEncBlock / 64);      // sub-spaces per wavefront: 4 (d = 8) or 8 (d = 4)
+    constexpr int SPW = M / (kEncBlock / 64);      // sub-spaces per wavefront: 4 (d = 8) or 8 (d = 4) at D = 128, half at D = 64
     extern __shared__ __align__(16) unsigned char smem_w[];
     __half *const tab = reinterpret_cast<__half *>(smem_w);                          // [C][d] fp16
     float *const x_s = reinterpret_cast<float *>(smem_w + (size_t)C * d * 2);        // [64][XS]
@@ -564,11 +566,11 @@ __global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
 // (distance bits, index) keys, and the group's 4 b bits (a whole number of bytes) go out as bytes.
 constexpr int kTokWideSub = 4;
 
-template <int d, int BITS, bool kTransform>
+template <int D, int d, int BITS, bool kTransform>
 __device__ __forceinline__ void encode_token_wide(const EncodeParams &p, int group, float *x_s,
                                                   unsigned long long (*key_s)[kTokWideSub], unsigned *code_s)
 {
-    constexpr int D = 128, M = D / d, C = 1 << BITS, MS = kTokWideSub;
+    constexpr int M = D / d, C = 1 << BITS, MS = kTokWideSub;
     const int tid = threadIdx.x;
     const long long t = blockIdx.x;
     const int m0 = group * MS;
@@ -657,99 +659,112 @@ __device__ __forceinline__ void encode_token_wide(const EncodeParams &p, int gro
     }
 }
 
-template <int d, int BITS, bool kTransform>
+template <int D, int d, int BITS, bool kTransform>
 __global__ __launch_bounds__(kCentroids) void encode_token_wide_kernel(EncodeParams p)
 {
-    __shared__ float x_s[128];
+    __shared__ float x_s[D];
     __shared__ unsigned long long key_s[kCentroids / 64][kTokWideSub];
     __shared__ unsigned code_s[kTokWideSub];
-    encode_token_wide<d, BITS, kTransform>(p, blockIdx.y, x_s, key_s, code_s);
+    encode_token_wide<D, d, BITS, kTransform>(p, blockIdx.y, x_s, key_s, code_s);
 }
 
 // Eq. 9 with wide codes on both sides in one launch: the first M_k / 4 workgroups along y take the
 // key's sub-space groups, the others the value's.
-template <int dk, int BK, int dv, int BV>
+template <int D, int dk, int BK, int dv, int BV>
 __global__ __launch_bounds__(kCentroids) void append_wide_kernel(EncodeParams pk, EncodeParams pv)
 {
-    __shared__ float x_s[128];
+    __shared__ float x_s[D];
     __shared__ unsigned long long key_s[kCentroids / 64][kTokWideSub];
     __shared__ unsigned code_s[kTokWideSub];
-    constexpr int GK = 128 / dk / kTokWideSub;
+    constexpr int GK = D / dk / kTokWideSub;
     if (blockIdx.y < GK)
-        encode_token_wide<dk, BK, true>(pk, blockIdx.y, x_s, key_s, code_s);
+        encode_token_wide<D, dk, BK, true>(pk, blockIdx.y, x_s, key_s, code_s);
     else
-        encode_token_wide<dv, BV, false>(pv, blockIdx.y - GK, x_s, key_s, code_s);
+        encode_token_wide<D, dv, BV, false>(pv, blockIdx.y - GK, x_s, key_s, code_s);
 }
 
-template <int dk, int BK, int dv, int BV>
+template <int D, int dk, int BK, int dv, int BV>
 int launch_append_wide_typed(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
 {
-    dim3 grid((unsigned)pk.T, (128 / dk + 128 / dv) / kTokWideSub, pk.B * pk.Hkv);
-    hipLaunchKernelGGL((append_wide_kernel<dk, BK, dv, BV>), grid, dim3(kCentroids), 0, stream, pk, pv);
+    dim3 grid((unsigned)pk.T, (D / dk + D / dv) / kTokWideSub, pk.B * pk.Hkv);
+    hipLaunchKernelGGL((append_wide_kernel<D, dk, BK, dv, BV>), grid, dim3(kCentroids), 0, stream, pk, pv);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
-template <int dk, int BK>
+template <int D, int dk, int BK>
 int launch_append_wide_v(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
 {
     switch (pv.d * 100 + pv.bits) {
-    case 810: return launch_append_wide_typed<dk, BK, 8, 10>(pk, pv, stream);
-    case 812: return launch_append_wide_typed<dk, BK, 8, 12>(pk, pv, stream);
-    case 410: return launch_append_wide_typed<dk, BK, 4, 10>(pk, pv, stream);
-    case 412: return launch_append_wide_typed<dk, BK, 4, 12>(pk, pv, stream);
+    case 810:
+        if constexpr (D == 128) return launch_append_wide_typed<D, dk, BK, 8, 10>(pk, pv, stream);
+        else return -2;
+    case 812: return launch_append_wide_typed<D, dk, BK, 8, 12>(pk, pv, stream);
+    case 410: return launch_append_wide_typed<D, dk, BK, 4, 10>(pk, pv, stream);
+    case 412: return launch_append_wide_typed<D, dk, BK, 4, 12>(pk, pv, stream);
     default: return -2;
     }
 }
 
-// both sides wide (D = 128): one launch
+template <int D>
+int launch_append_wide_d(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
+{
+    switch (pk.d * 100 + pk.bits) {
+    case 810:
+        if constexpr (D == 128) return launch_append_wide_v<D, 8, 10>(pk, pv, stream);
+        else return -2;
+    case 812: return launch_append_wide_v<D, 8, 12>(pk, pv, stream);
+    case 410: return launch_append_wide_v<D, 4, 10>(pk, pv, stream);
+    case 412: return launch_append_wide_v<D, 4, 12>(pk, pv, stream);
+    default: return -2;
+    }
+}
+
+// both sides wide: one launch
 int launch_append_wide(const EncodeParams &pk, const EncodeParams &pv, hipStream_t stream)
 {
-    if (pk.D != 128) return -2;
-    switch (pk.d * 100 + pk.bits) {
-    case 810: return launch_append_wide_v<8, 10>(pk, pv, stream);
-    case 812: return launch_append_wide_v<8, 12>(pk, pv, stream);
-    case 410: return launch_append_wide_v<4, 10>(pk, pv, stream);
-    case 412: return launch_append_wide_v<4, 12>(pk, pv, stream);
-    default: return -2;
-    }
+    if (pk.D == 128) return launch_append_wide_d<128>(pk, pv, stream);
+    if (pk.D == 64) return launch_append_wide_d<64>(pk, pv, stream);
+    return -2;
 }
 
-template <int d, int BITS>
+template <int D, int d, int BITS>
 int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
 {
-    constexpr int M = 128 / d;
+    constexpr int M = D / d;
     if (p.T <= kTokenKernelMaxT && !p.km_sums) {
         dim3 tgrid((unsigned)p.T, M / kTokWideSub, p.B * p.Hkv);
         if (p.lam)
-            hipLaunchKernelGGL((encode_token_wide_kernel<d, BITS, true>), tgrid, dim3(kCentroids), 0, stream, p);
+            hipLaunchKernelGGL((encode_token_wide_kernel<D, d, BITS, true>), tgrid, dim3(kCentroids), 0, stream, p);
         else
-            hipLaunchKernelGGL((encode_token_wide_kernel<d, BITS, false>), tgrid, dim3(kCentroids), 0, stream, p);
+            hipLaunchKernelGGL((encode_token_wide_kernel<D, d, BITS, false>), tgrid, dim3(kCentroids), 0, stream, p);
         return hipGetLastError() == hipSuccess ? 0 : -4;
     }
-    constexpr size_t smem = ((size_t)1 << BITS) * d * 2 + sizeof(float) * kWideTokens * (128 + 4) + 2 * kWideTokens * M;
+    constexpr size_t smem = ((size_t)1 << BITS) * d * 2 + sizeof(float) * kWideTokens * (D + 4) + 2 * kWideTokens * M;
     static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<d, BITS, true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<D, d, BITS, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<d, BITS, false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<D, d, BITS, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
     if (!configured) return -4;
     dim3 grid((unsigned)((p.T + kWideTokens - 1) / kWideTokens), 1, p.B * p.Hkv);
     if (p.lam)
-        hipLaunchKernelGGL((encode_wide_kernel<d, BITS, true>), grid, dim3(kEncBlock), smem, stream, p);
+        hipLaunchKernelGGL((encode_wide_kernel<D, d, BITS, true>), grid, dim3(kEncBlock), smem, stream, p);
     else
-        hipLaunchKernelGGL((encode_wide_kernel<d, BITS, false>), grid, dim3(kEncBlock), smem, stream, p);
+        hipLaunchKernelGGL((encode_wide_kernel<D, d, BITS, false>), grid, dim3(kEncBlock), smem, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
 int launch_encode_wide(const EncodeParams &p, hipStream_t stream)
 {
-    if (p.D != 128) return -2;
-    const int key = p.d * 100 + p.bits;
+    const int key = p.D * 1000 + p.d * 100 + p.bits;
     switch (key) {
-    case 810: return launch_wide_typed<8, 10>(p, stream);
-    case 812: return launch_wide_typed<8, 12>(p, stream);
-    case 410: return launch_wide_typed<4, 10>(p, stream);
-    case 412: return launch_wide_typed<4, 12>(p, stream);
+    case 128810: return launch_wide_typed<128, 8, 10>(p, stream);
+    case 128812: return launch_wide_typed<128, 8, 12>(p, stream);
+    case 128410: return launch_wide_typed<128, 4, 10>(p, stream);
+    case 128412: return launch_wide_typed<128, 4, 12>(p, stream);
+    case 64812: return launch_wide_typed<64, 8, 12>(p, stream);     // (d = 8 with 10-bit codes: 10-byte rows, not built)
+    case 64410: return launch_wide_typed<64, 4, 10>(p, stream);
+    case 64412: return launch_wide_typed<64, 4, 12>(p, stream);
     default: return -2;
     }
 }

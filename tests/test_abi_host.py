@@ -59,7 +59,7 @@ def test_encode_argument_errors():
     assert _enc_vals(T=9) == vb.EINVAL
     for bad in (vb.Config(96, 32, 8, 4, 4), vb.Config(128, 32, 5, 4, 4), vb.Config(128, 32, 8, 3, 4),
                 vb.Config(128, 32, 8, 4, 4, k_bits=16), vb.Config(128, 32, 8, 2, 4, k_bits=12),
-                vb.Config(64, 32, 8, 4, 4, v_bits=10), vb.Config(128, 32, 8, 4, 4, k_bits=9), vb.Config(128, 128, 8, 4, 4),
+                vb.Config(64, 32, 8, 4, 8, v_bits=10), vb.Config(64, 32, 8, 8, 4, k_bits=10), vb.Config(128, 32, 8, 4, 4, k_bits=9), vb.Config(128, 128, 8, 4, 4),
                 vb.Config(128, 32, 8, 4, 16)):
         assert _enc_keys(cfg=bad) == vb.EUNSUPPORTED
         assert _enc_vals(cfg=bad) == vb.EUNSUPPORTED
@@ -101,8 +101,8 @@ def test_decode_argument_errors():
     assert _decode(ws=None, ws_bytes=need) == vb.EWORKSPACE
     assert _decode(ws=FAKE, ws_bytes=need - 1) == vb.EWORKSPACE
     assert _decode(ws=FAKE + 64, ws_bytes=need) == vb.EWORKSPACE
-    # the matrix-core variant does not cover 10- / 12-bit codes at head dim 64
-    assert _decode(cfg=vb.Config(64, 8, 1, 8, 8, 12, 12), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
+    # no packed rows of 10 bytes: d = 8 with 10-bit codes at head dim 64
+    assert _decode(cfg=vb.Config(64, 8, 1, 8, 8, 10, 10), variant=vb.VARIANT_MFMA, ws=FAKE, ws_bytes=1 << 30) == vb.EUNSUPPORTED
     # the score / value wavefront kernel: D = 128, G <= 4, d in {2, 4}, 8-bit codes
     for bad in (vb.Config(64, 8, 2, 4, 4), vb.Config(128, 16, 2, 4, 4), vb.Config(128, 8, 2, 8, 4),
                 vb.Config(128, 8, 2, 4, 4, 12, 8)):

@@ -42,6 +42,15 @@ WIDE = [
     synth.Shape(1, 8, 2, 128, 700, 4, 4, 8, 12),          # 8-bit d4 keys, d4b12 values
     synth.Shape(1, 8, 2, 128, 700, 8, 4, 12, 8),          # d8b12 keys, 8-bit d4 values
     synth.Shape(1, 8, 2, 128, 500, 8, 4, 10, 10),
+    # head dim 64 (the second shape of the kernel sweep, App. B.2): d_v = 8 runs as two halves per code
+    synth.Shape(2, 8, 2, 64, 777, 8, 8, 12, 12),          # d8b12
+    synth.Shape(1, 16, 2, 64, 1300, 8, 8, 12, 12),        # G = 8
+    synth.Shape(1, 8, 2, 64, 900, 4, 4, 12, 12),          # d4b12
+    synth.Shape(2, 6, 2, 64, 650, 4, 4, 10, 10),          # d4b10, G = 3
+    synth.Shape(1, 8, 2, 64, 1000, 4, 8, 10, 12),         # K-d4b10 / V-d8b12
+    synth.Shape(1, 8, 2, 64, 800, 8, 8, 12, 8),           # K-d8b12 / V-d8b8
+    synth.Shape(1, 4, 1, 64, 4099, 8, 4, 8, 12),          # K-d8b8 / V-d4b12
+    synth.Shape(1, 8, 2, 64, 700, 4, 8, 8, 12),           # 8-bit d4 keys, d8b12 values
 ]
 
 
@@ -115,6 +124,10 @@ ENC_WIDE = [
     synth.Shape(2, 2, 2, 128, 3, 8, 8, 12, 12),       # per-token kernel
     synth.Shape(1, 2, 2, 128, 16, 4, 4, 10, 12),
     synth.Shape(1, 1, 1, 128, 65, 8, 8, 12, 8),       # one side wide, the other 8-bit
+    synth.Shape(2, 2, 2, 64, 200, 8, 8, 12, 12),      # head dim 64
+    synth.Shape(1, 2, 1, 64, 130, 4, 4, 10, 12),
+    synth.Shape(1, 2, 2, 64, 5, 4, 8, 12, 12),        # per-token kernel
+    synth.Shape(1, 1, 1, 64, 70, 8, 4, 12, 8),
 ]
 
 
@@ -279,6 +292,11 @@ STEP_WIDE = [
     synth.Shape(2, 8, 2, 128, 800, 8, 8, 12, 8),         # keys wide, values 8-bit
     synth.Shape(1, 6, 2, 128, 650, 4, 8, 8, 12),         # keys 8-bit, values wide, G = 3
     synth.Shape(1, 8, 2, 128, 1, 8, 8, 12, 12),          # the new token is the only one
+    synth.Shape(2, 8, 2, 64, 1200, 8, 8, 12, 12),        # head dim 64
+    synth.Shape(1, 8, 2, 64, 900, 4, 8, 10, 12),
+    synth.Shape(1, 16, 2, 64, 700, 4, 4, 12, 10),        # G = 8
+    synth.Shape(2, 4, 2, 64, 650, 8, 4, 12, 8),
+    synth.Shape(1, 6, 2, 64, 500, 4, 8, 8, 12),
 ]
 
 
@@ -288,7 +306,7 @@ def test_decode_step_wide_fused_equals_append_then_attend(shape, splits):
     """The whole step with wide codes encodes the new token inside the attention launch: the
     packed rows must be bit-identical to what vecinfer_append_kv writes, and the output equal to
     vecinfer_decode_attention on the result (and to the oracle)."""
-    x = synth.decode_inputs(shape, seed=shape.N + 5, n_cap=shape.N + 3)
+    x = synth.decode_inputs(shape, seed=shape.N + 5, n_cap=shape.N + 4)   # (+ 4: per-sequence slices of 12-byte rows stay 16-byte aligned)
     g = synth.rng(shape.N + 6)
     k_new, _ = synth.keys_with_outlier_channels(g, shape.B, shape.Hkv, 1, shape.D, 3)
     v_new = synth.values(g, shape.B, shape.Hkv, 1, shape.D)
