@@ -210,7 +210,9 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
  * K-Means codebook training: Lloyd's algorithm, at most max_iters <= VECINFER_KMEANS_MAX_ITERS = 30
  * iterations (Sec. 2.2: the codebook is built by K-Means; Sec. 3.2: on the transformed keys and the
  * original values; Sec. 4.1: maximum number of iterations 30), with the quantization error
- * computed on the device and a stopping rule there.  8-bit codes on the trained side.
+ * computed on the device and a stopping rule there.  Any supported code width: with 10- or 12-bit
+ * codes the KV head's one shared codebook is trained on the sub-vectors of all its sub-spaces, as
+ * for vecinfer_kmeans_step.
  * Iteration t = 0, 1, ..:
  *   assignment  as vecinfer_kmeans_step, with the centroids cb_t (cb_0 = what cb_f16 holds on entry)
  *   error       E_t = sum over all KV heads, sub-spaces and tokens of |x - cb_t[code]|^2 (fp32 per
@@ -221,16 +223,16 @@ int vecinfer_kmeans_step(const vecinfer_cfg *cfg, const void *x_f16, const float
  * All max_iters iterations are enqueued; those after the stop return at once (a flag in the
  * workspace), so the call never synchronises.  Initial centroids are the caller's (e.g. a sample
  * of the training vectors).
- *   cb_f16     [H_kv, M, 256, d] fp16, read and overwritten
- *   codes      [B, H_kv, T, M] uint8: the assignment of the last iteration run
- *   counts     int32 [H_kv, M, 256] or NULL: its cluster sizes
+ *   cb_f16     [H_kv, M, 256, d] fp16 (10- / 12-bit codes: [H_kv, 2^b, d]), read and overwritten
+ *   codes      [B, H_kv, T, row bytes] uint8 (rows as vecinfer_encode_* writes them): the assignment
+ *              of the last iteration run
+ *   counts     int32, one per centroid ([H_kv, M, 256] or [H_kv, 2^b]), or NULL: its cluster sizes
  *   iters_run  int32 on the device or NULL: iterations run
  *   errors     fp64 [max_iters] on the device or NULL: E_0 .. E_{iters_run - 1}; the rest untouched
  *   workspace  vecinfer_kmeans_workspace_bytes(cfg, lambda != NULL) bytes, 256-byte aligned
  * The cluster sums are formed with fp32 atomics (in LDS, then one per workgroup and centroid in
  * memory), so their last bits, and rarely the fp16 rounding of a centroid, may differ between runs.
- * Errors: as vecinfer_kmeans_step; EINVAL for max_iters outside 1 .. 30 or tol = NaN; EUNSUPPORTED
- * for 10- / 12-bit codes on the trained side (vecinfer_kmeans_step covers one iteration of those).
+ * Errors: as vecinfer_kmeans_step; EINVAL for max_iters outside 1 .. 30 or tol = NaN.
  */
 int vecinfer_kmeans_train(const vecinfer_cfg *cfg, const void *x_f16, const float *lambda, void *cb_f16,
                           uint8_t *codes, int32_t *counts, int32_t B, int64_t T, int32_t max_iters,

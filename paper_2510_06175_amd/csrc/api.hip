@@ -152,6 +152,8 @@ int encode_args(const vecinfer_cfg *cfg, const void *x, const float *lambda, boo
     p.len_max = 0;
     p.km_sums = nullptr;
     p.km_counts = nullptr;
+    p.km_state = nullptr;
+    p.km_iter = 0;
     return VECINFER_OK;
 }
 
@@ -356,17 +358,6 @@ int kmeans_common(const vecinfer_cfg *cfg, const void *x_f16, const float *lambd
     p.km_counts = reinterpret_cast<int32_t *>(ws + (cen * p.d * sizeof(float) + 255) / 256 * 256);
     void *state = ws + (cen * p.d * sizeof(float) + 255) / 256 * 256 + (cen * sizeof(int32_t) + 255) / 256 * 256;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (p.bits != 8) {
-        // 10- / 12-bit codes (one shared table per KV head): a single iteration through the tiled
-        // wide cache-fill kernel with its accumulation epilogue
-        if (max_iters != 1) return VECINFER_EUNSUPPORTED;
-        int lr = launch_kmeans_zero(p.km_sums, p.km_counts, cen * p.d, cen, st);
-        if (lr == 0) lr = launch_encode(p, st);
-        if (lr == 0)
-            lr = launch_kmeans_finalize(p.km_sums, p.km_counts, p.cb, static_cast<__half *>(cb_out_f16), counts, cen,
-                                        p.d, st);
-        return launch_status(lr);
-    }
     int lr = 0;
     if (!in_place)       // the update works in place on cb_out: start it from cb_in
         lr = hipMemcpyAsync(cb_out_f16, cb_in_f16, cen * p.d * sizeof(__half), hipMemcpyDeviceToDevice, st) == hipSuccess
@@ -374,7 +365,15 @@ int kmeans_common(const vecinfer_cfg *cfg, const void *x_f16, const float *lambd
     p.cb = static_cast<const __half *>(cb_out_f16);
     for (int it = 0; it < max_iters && lr == 0; ++it) {
         lr = launch_kmeans_begin(p.km_sums, p.km_counts, cen * p.d, cen, it, state, st);
-        if (lr == 0) lr = launch_kmeans_assign(p, it, state, st);
+        if (lr == 0) {
+            if (p.bits == 8) {
+                lr = launch_kmeans_assign(p, it, state, st);
+            } else {           // 10- / 12-bit codes: the tiled wide cache-fill kernel with its accumulation epilogue
+                p.km_state = state;
+                p.km_iter = it;
+                lr = launch_encode(p, st);
+            }
+        }
         if (lr == 0)
             lr = launch_kmeans_end(p.km_sums, p.km_counts, static_cast<__half *>(cb_out_f16), counts, cen, p.d, it, tol,
                                    state, iters_run, errors, st);
@@ -399,7 +398,6 @@ int vecinfer_kmeans_train(const vecinfer_cfg *cfg, const void *x_f16, const floa
     if (max_iters < 1 || max_iters > VECINFER_KMEANS_MAX_ITERS || !(tol == tol)) return VECINFER_EINVAL;
     if (errors && !aligned(errors, 8)) return VECINFER_EINVAL;
     if (iters_run && !aligned(iters_run, 4)) return VECINFER_EINVAL;
-    if (cfg && cfg_ok(cfg) && (lambda ? cfg->k_bits : cfg->v_bits) != 8) return VECINFER_EUNSUPPORTED;
     return kmeans_common(cfg, x_f16, lambda, cb_f16, cb_f16, codes, counts, B, T, max_iters, tol, iters_run, errors,
                          workspace, workspace_bytes, stream);
 }

@@ -211,16 +211,17 @@ struct EncodeParams {
     // goes to row clamp(seq_lens[b], 0, len_max) - 1, and a sequence of length 0 is skipped
     const int32_t *seq_lens;
     long long len_max;
-    // K-Means training (one Lloyd iteration): when km_sums != nullptr the tiled kernel also adds
-    // every (transformed) sub-vector into the sum of the centroid it was assigned to
-    float *km_sums;       // [Hkv, M, 256, d] fp32, zeroed beforehand
-    int32_t *km_counts;   // [Hkv, M, 256]
+    // K-Means training: when km_sums != nullptr the wide tiled kernel also adds every (transformed)
+    // sub-vector into the sum of the centroid it was assigned to and its squared distance to the
+    // iteration's error in km_state (8-bit codes: launch_kmeans_assign)
+    float *km_sums;       // [Hkv, M, 256, d] fp32 (wide codes: [Hkv, 2^b, d]), cleared by launch_kmeans_begin
+    int32_t *km_counts;   // [Hkv, M, 256]         (wide codes: [Hkv, 2^b])
+    void *km_state;       // kmeans_state_bytes() of device memory
+    int km_iter;          // iteration the launch belongs to (a launch behind the stop does nothing)
 };
-int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, hipStream_t stream);
-int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
-                           int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream);
-// K-Means training iteration, 8-bit codes: begin (clear), assign + accumulate, end (update in place,
-// error, stopping rule); `state` is kmeans_state_bytes() of device memory
+// K-Means training iteration: begin (clear), assign + accumulate (8-bit codes: launch_kmeans_assign; wide
+// codes: launch_encode with km_sums set), end (update in place, error, stopping rule); `state` is
+// kmeans_state_bytes() of device memory
 size_t kmeans_state_bytes();
 int launch_kmeans_begin(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter, void *state,
                         hipStream_t stream);

@@ -230,26 +230,6 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int t
 }
 
 
-__global__ void kmeans_zero_kernel(float *sums, int32_t *counts, size_t n_sums, size_t n_counts)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_sums) sums[i] = 0.f;
-    if (i < n_counts) counts[i] = 0;
-}
-
-// New centroid = sum / count (fp32), rounded to fp16; a centroid nobody was assigned to keeps its
-// old value.
-__global__ void kmeans_finalize_kernel(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
-                                       int32_t *counts_out, size_t n_centroids, int d)
-{
-    const size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= n_centroids) return;
-    const int n = counts[c];
-    if (counts_out) counts_out[c] = n;
-    for (int j = 0; j < d; ++j)
-        cb_out[c * d + j] = n > 0 ? __float2half(sums[c * d + j] / (float)n) : cb_in[c * d + j];
-}
-
 // Start of a training iteration: sums and counts cleared, the error accumulator reset (and, before
 // the first iteration, the whole state).
 __global__ void kmeans_begin_kernel(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, int iter,
@@ -490,6 +470,8 @@ __global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
     const long long t0 = (long long)blockIdx.x * kWideTokens;
     const int bg = blockIdx.z;
     const int g = bg % p.Hkv;
+    KmeansState *const state = static_cast<KmeansState *>(p.km_state);
+    if (p.km_sums && p.km_iter > 0 && p.km_iter > state->stop_at) return;   // training already stopped
 
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(p.cb + (size_t)g * C * d);
@@ -540,6 +522,18 @@ __global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
             if (dist_bits_of<d>(x[i], cen) == best[i]) arg = best_group[i] + k;
         }
         idx_s[lane * M + wave * SPW + i] = (unsigned short)arg;
+    }
+    if (p.km_sums) {
+        // K-Means: the squared distances of this wavefront's sub-vectors join the iteration's error
+        float err = 0.f;
+        if (t0 + lane < p.T) {
+#pragma unroll
+            for (int i = 0; i < SPW; ++i) err += __uint_as_float(best[i]);
+        }
+        double e64 = (double)err;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
+        if (lane == 0) unsafeAtomicAdd(&state->err_cur, e64);
     }
     __syncthreads();
     store_packed_rows<M, BITS>(p, idx_s, t0, kWideTokens, bg, kEncBlock);
@@ -862,26 +856,6 @@ int launch_export_value_codes(const uint8_t *tiled, uint8_t *rows, int BH, int M
 }
 
 int append_max_tokens() { return (int)kTokenKernelMaxT; }
-
-int launch_kmeans_zero(float *sums, int32_t *counts, size_t n_sums, size_t n_counts, hipStream_t stream)
-{
-    const size_t n = n_sums > n_counts ? n_sums : n_counts;
-    hipLaunchKernelGGL(kmeans_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, sums, counts,
-                       n_sums, n_counts);
-    return hipGetLastError() == hipSuccess ? 0 : -4;
-}
-
-int launch_kmeans_finalize(const float *sums, const int32_t *counts, const __half *cb_in, __half *cb_out,
-                           int32_t *counts_out, size_t n_centroids, int d, hipStream_t stream)
-{
-    hipLaunchKernelGGL(kmeans_finalize_kernel, dim3((unsigned)((n_centroids + 255) / 256)), dim3(256), 0, stream,
-                       sums, counts, cb_in, cb_out, counts_out, n_centroids, d);
-    return hipGetLastError() == hipSuccess ? 0 : -4;
-}
-
-namespace {
-
-} // namespace
 
 size_t kmeans_state_bytes() { return sizeof(KmeansState); }
 

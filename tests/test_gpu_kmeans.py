@@ -34,13 +34,13 @@ class Trainer:
     def __init__(self, shape, x, lam, cb0):
         self.cfg = cfg_of(shape)
         self.keys = lam is not None
-        d = shape.d_k if self.keys else shape.d_v
         B, Hkv, T, D = x.shape
-        M = D // d
+        self.bits = shape.b_k if self.keys else shape.b_v
+        self.M = shape.Mk if self.keys else shape.Mv
         self.x, self.lam = dev(x), None if lam is None else dev(lam)
         self.cb = dev(cb0).clone()
-        self.codes = torch.full((B, Hkv, T, M), 0xEE, dtype=torch.uint8, device="cuda")
-        self.counts = torch.full((Hkv, M, 256), -1, dtype=torch.int32, device="cuda")
+        self.codes = torch.full((B, Hkv, T, self.cfg.row_bytes(self.keys)), 0xEE, dtype=torch.uint8, device="cuda")
+        self.counts = torch.full(tuple(cb0.shape[:-1]), -1, dtype=torch.int32, device="cuda")
         self.ws = vb.new_kmeans_workspace(self.cfg, self.keys)
         self.ws.fill_(0xA5)                      # the library clears what must start at zero
 
@@ -53,7 +53,12 @@ class Trainer:
         return int(iters.item()), errors.cpu().numpy()
 
     def state(self):
-        return self.cb.cpu().numpy(), self.codes.cpu().numpy(), self.counts.cpu().numpy()
+        """(codebook, codes unpacked to [B, Hkv, T, M], counts); a shared table as [Hkv, 1, C, d] / [Hkv, 1, C],
+        the oracle's form."""
+        cb, counts = self.cb.cpu().numpy(), self.counts.cpu().numpy()
+        if self.bits != 8:
+            cb, counts = cb[:, None], counts[:, None]
+        return cb, oracle.unpack_codes(self.codes.cpu().numpy(), self.bits, self.M), counts
 
 
 def _rows(x, lam, g):
@@ -78,20 +83,22 @@ def _check_means(x, lam, cb_after, codes, counts, what, cb_before=None):
 
 
 SHAPES = [synth.Shape(2, 4, 2, 128, 1000, 4, 4), synth.Shape(1, 2, 2, 64, 777, 2, 8),
-          synth.Shape(3, 1, 1, 128, 70, 8, 2)]
+          synth.Shape(3, 1, 1, 128, 70, 8, 2),
+          # 10- / 12-bit codes: one shared codebook per KV head, trained on the pooled sub-vectors
+          synth.Shape(2, 2, 2, 128, 300, 8, 4, 12, 10), synth.Shape(1, 2, 2, 64, 330, 4, 8, 10, 12)]
 
 
 @pytest.mark.parametrize("kind", ["keys", "values"])
-@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s.B}g{s.Hkv}D{s.D}T{s.N}k{s.d_k}v{s.d_v}")
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"B{s.B}g{s.Hkv}D{s.D}T{s.N}k{s.d_k}b{s.b_k}v{s.d_v}b{s.b_v}")
 def test_train_iteration_by_iteration(shape, kind):
     """Five calls of one iteration each, in place.  Every call: the assignment is the oracle's for
     the codebook the call started from (Eq. 2, near-ties logged), the error is the oracle's for that
     codebook and the GPU's assignment, the new centroids are the means within one fp16 ulp."""
     x, lam, cb0 = _problem(shape, kind, seed=shape.N + 11)
     cb0 = cb0.copy()
-    cb0[:, :, 9] = 300.0                                   # a centroid nobody is assigned to
+    cb0[..., 9, :] = 300.0                                 # a centroid nobody is assigned to
     t = Trainer(shape, x, lam, cb0)
-    before = cb0
+    before = cb0 if t.bits == 8 else cb0[:, None]
     errs = []
     for it in range(5):
         n, e = t.train(1, 1e-4)
@@ -197,16 +204,20 @@ def test_train_one_iteration_equals_kmeans_step():
     np.testing.assert_allclose(got.astype(np.float64), cb.astype(np.float64), rtol=1e-3, atol=1e-6)
 
 
-def test_train_refuses_wide_codes():
-    shape = synth.Shape(1, 2, 1, 128, 256, 8, 8, 12, 12)
-    cfg = cfg_of(shape)
-    x = torch.zeros((1, 1, 256, 128), dtype=torch.float16, device="cuda")
-    cb = torch.zeros(cfg.cb_shape(False), dtype=torch.float16, device="cuda")
-    codes = torch.zeros((1, 1, 256, cfg.row_bytes(False)), dtype=torch.uint8, device="cuda")
-    ws = vb.new_kmeans_workspace(cfg, False)
-    with pytest.raises(vb.VecInferError) as ei:
-        vb.vecinfer_kmeans_train(cfg, x, None, cb, codes, ws, max_iters=3)
-    assert ei.value.code == vb.EUNSUPPORTED
+def test_train_wide_codes_against_the_oracle_loop():
+    """12-bit codes on sub-vectors of 8 (the 1.5-bit configuration): six iterations in one call against the
+    oracle's loop on the shared codebook: errors, final means, counts."""
+    shape = synth.Shape(2, 2, 2, 128, 400, 8, 8, 12, 12)
+    x, lam, cb0 = _problem(shape, "keys", seed=23)
+    ref_cb, ref_counts, ref_idx, ref_err = oracle.kmeans_train(x, lam, cb0[:, None], max_iters=6, tol=-1.0)
+    t = Trainer(shape, x, lam, cb0)
+    n, e = t.train(6, -1.0)
+    assert n == 6
+    np.testing.assert_allclose(e, ref_err, rtol=1e-3)
+    cb, codes, counts = t.state()
+    _check_means(x, lam, cb, codes, counts, "train d8b12")
+    assert counts.sum() == codes.size
+    assert (codes == ref_idx).mean() > 0.97
 
 
 def test_train_full_size_iteration_properties():
