@@ -20,9 +20,10 @@
 // Error bound, in score units (T = sum_j |x_j| max|c_j| + max|c|^2 / 2 bounds the sum of the
 // magnitudes of a score's terms):
 //   split of sigma x          <= 2^-22 sigma T        fp32 |c|^2 and its two parts   <= 2^-20.2 sigma T
-//   fp32 accumulation of <= 18 products, taken as truncating                          <= 2^-19 sigma T
+//   fp32 accumulation of <= 18 products, every addition taken as truncating (2^-23): <= 2^-18.8 sigma T
+//   (10 products and 2^-19.7 at d = 4; a matrix core that rounds once per instruction is far below this)
 //   fp16 parts below 2^-14 taken as flushed to zero: <= 2^-14 (d max|c_j| + 3), whatever sigma
-//   two scores compared: twice that, < 2^-17 sigma T + 2^-13 (d max|c_j| + 3)
+//   two scores compared: twice the sum, 2^-17.25 sigma T + 2^-13 (d max|c_j| + 3) < the margin's first terms
 //   the exact distances themselves carry (d + 2) 2^-24 relative rounding each; a centroid is
 //   safely worse when its true distance exceeds the best's by 2^-18.9 times the best distance
 //   (<= 2 (|x|^2 + max|c|^2)), i.e. by 2^-18 sigma (|x|^2 + max|c|^2) in score units.
