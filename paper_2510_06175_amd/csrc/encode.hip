@@ -393,13 +393,8 @@ constexpr long long kTokenKernelMaxT = 16;     // below this many tokens per (b,
 // token's M codes packed end to end, b bits each, in M b / 8 bytes.  D = 128, or D = 64 where a row
 // is a whole number of 32-bit words (not d = 8 with 10-bit codes).
 //
-// Tiled kernel: 64 tokens of one (batch, KV head) per workgroup.  The whole table stays in LDS as
-// fp16 (up to 64 KB) next to the transformed tile.  A lane owns one token, a wavefront M / 4
-// sub-spaces of it, so a centroid is read once (an LDS broadcast), widened to fp32 and tried
-// against all of the wavefront's sub-vectors.  The search is the one of the 8-bit kernel:
-// squared distances summed directly in channel order in fp32, group minima on the bit patterns,
-// strict "<" between groups, and the winning group looked at again for the lowest index.
-constexpr int kWideTokens = 64;
+// What is written is the centroid at the smallest squared distance, summed directly in channel order
+// in fp32, lowest index among equals: the rule of the 8-bit kernels.
 
 template <int d>
 __device__ __forceinline__ void load_centroid(const __half *tab, unsigned c, float (&cen)[d])
@@ -454,102 +449,79 @@ __device__ __forceinline__ void store_packed_rows(const EncodeParams &p, const u
     }
 }
 
+// Tiled kernel: as vq_tile_kernel, with one table for all sub-spaces.  A workgroup (8 wavefronts)
+// builds the search tables of its KV head's codebook once (the fp16 table as it is, 8 - 64 KB, and
+// -sigma |c|^2 / 2, 4 - 16 KB) and walks over a run of 64-token tiles; per tile every wavefront
+// searches M / 8 sub-spaces, 256 centroids at a time (screen_search_shared: matrix-core screen,
+// exact fp32 distances of what it keeps, the plain search where it gives up), and the tile's codes
+// are packed into rows.  K-Means (km_sums set): every sub-vector also joins the sum of its centroid
+// in the head's one table (fp32 hardware atomics, order of the additions not fixed) and its squared
+// distance the iteration's error.
+template <int D, int d, int BITS>
+constexpr size_t vq_wide_smem_bytes()
+{
+    return (size_t)ScreenTab<d, (1 << BITS)>::kBytes + sizeof(float) * kEncTokens * (D + 4) +
+           sizeof(unsigned short) * kEncTokens * (D / d);
+}
+
 template <int D, int d, int BITS, bool kTransform>
-__global__ __launch_bounds__(kEncBlock) void encode_wide_kernel(EncodeParams p)
+__global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, int tiles_per_wg)
 {
     constexpr int M = D / d, C = 1 << BITS;
     static_assert(M * BITS % 32 == 0, "rows of whole 32-bit words");
+    constexpr int NW = kVqBlock / 64;
+    constexpr int SPW = M / NW;                            // sub-spaces per wavefront: 1, 2 or 4
+    static_assert(M % NW == 0, "sub-spaces dealt evenly to the wavefronts");
     constexpr int XS = D + 4;
-    constexpr int SPW = M / (kEncBlock / 64);      // sub-spaces per wavefront: 4 (d = 8) or 8 (d = 4) at D = 128, half at D = 64
-    extern __shared__ __align__(16) unsigned char smem_w[];
-    __half *const tab = reinterpret_cast<__half *>(smem_w);                          // [C][d] fp16
-    float *const x_s = reinterpret_cast<float *>(smem_w + (size_t)C * d * 2);        // [64][XS]
-    unsigned short *const idx_s = reinterpret_cast<unsigned short *>(x_s + kWideTokens * XS);   // [64][M]
+    using Tab = ScreenTab<d, C>;
+    extern __shared__ __align__(16) unsigned char vqw_smem[];
+    unsigned char *const tab_s = vqw_smem;                                                  // the head's search tables
+    float *const x_s = reinterpret_cast<float *>(tab_s + Tab::kBytes);                      // [64][XS] transformed tile
+    unsigned short *const idx_s = reinterpret_cast<unsigned short *>(x_s + kEncTokens * XS);   // [64][M] codes of the tile
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long t0 = (long long)blockIdx.x * kWideTokens;
-    const int bg = blockIdx.z;
-    const int g = bg % p.Hkv;
     KmeansState *const state = static_cast<KmeansState *>(p.km_state);
     if (p.km_sums && p.km_iter > 0 && p.km_iter > state->stop_at) return;   // training already stopped
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bg = blockIdx.z, g = bg % p.Hkv;
+    const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
 
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(p.cb + (size_t)g * C * d);
-        uint4 *dst = reinterpret_cast<uint4 *>(tab);
-        for (int e = tid; e < C * d / 8; e += kEncBlock) dst[e] = src[e];
-    }
-    load_transform_tile<D, kTransform>(p, x_s, t0, bg, g);
-    __syncthreads();
+    const ScreenConsts sc = screen_prepare_shared<d, C, kVqBlock>(p.cb + (size_t)g * C * d, tab_s, x_s);
 
-    float x[SPW][d];
+    float err = 0.f;
+    for (int ti = 0; ti < tiles_per_wg; ++ti) {
+        const long long t0 = (tile0 + ti) * kEncTokens;
+        if (t0 >= p.T) break;
+        if (ti > 0) __syncthreads();           // previous tile's x_s and idx_s consumed
+        load_transform_tile<D, kTransform, kVqBlock>(p, x_s, t0, bg, g);
+        __syncthreads();
+#pragma unroll 1
+        for (int i = 0; i < SPW; ++i) {        // (not unrolled: the searches are long and share nothing but the tables)
+            const int m = wave + NW * i;
+            int arg;
+            unsigned best;
+            search_tile<d, C>(x_s, XS, m * d, tab_s, sc, lane, arg, best);
+            idx_s[lane * M + m] = (unsigned short)arg;
+            if (t0 + lane < p.T) err += __uint_as_float(best);
+        }
+        __syncthreads();
+        store_packed_rows<M, BITS>(p, idx_s, t0, kEncTokens, bg, kVqBlock);
+        if (p.km_sums) {
+            for (int e = tid; e < kEncTokens * M; e += kVqBlock) {
+                const int tl = e / M, m = e - tl * M;
+                if (t0 + tl < p.T) {
+                    const size_t cen = (size_t)g * C + idx_s[tl * M + m];
 #pragma unroll
-    for (int i = 0; i < SPW; ++i)
-#pragma unroll
-        for (int j = 0; j < d; ++j) x[i][j] = x_s[lane * XS + (wave * SPW + i) * d + j];
-    unsigned best[SPW];
-    int best_group[SPW];
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-        best[i] = 0x7f800000u;                     // +inf
-        best_group[i] = 0;
-    }
-    for (int c0 = 0; c0 < C; c0 += 8) {
-        unsigned gmin[SPW];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            float cen[d];
-            load_centroid<d>(tab, c0 + k, cen);    // same address in every lane: broadcast
-#pragma unroll
-            for (int i = 0; i < SPW; ++i) {
-                const unsigned v = dist_bits_of<d>(x[i], cen);
-                gmin[i] = k == 0 ? v : (v < gmin[i] ? v : gmin[i]);
+                    for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
+                    atomicAdd(p.km_counts + cen, 1);
+                }
             }
         }
-#pragma unroll
-        for (int i = 0; i < SPW; ++i)
-            if (gmin[i] < best[i]) {
-                best[i] = gmin[i];
-                best_group[i] = c0;
-            }
-    }
-#pragma unroll
-    for (int i = 0; i < SPW; ++i) {
-        int arg = best_group[i];
-#pragma unroll
-        for (int k = 7; k >= 0; --k) {
-            float cen[d];
-            load_centroid<d>(tab, best_group[i] + k, cen);
-            if (dist_bits_of<d>(x[i], cen) == best[i]) arg = best_group[i] + k;
-        }
-        idx_s[lane * M + wave * SPW + i] = (unsigned short)arg;
     }
     if (p.km_sums) {
-        // K-Means: the squared distances of this wavefront's sub-vectors join the iteration's error
-        float err = 0.f;
-        if (t0 + lane < p.T) {
-#pragma unroll
-            for (int i = 0; i < SPW; ++i) err += __uint_as_float(best[i]);
-        }
         double e64 = (double)err;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
         if (lane == 0) unsafeAtomicAdd(&state->err_cur, e64);
-    }
-    __syncthreads();
-    store_packed_rows<M, BITS>(p, idx_s, t0, kWideTokens, bg, kEncBlock);
-
-    // ---- K-Means training only: every sub-vector of the tile joins the sum of its centroid in the
-    // head's one table (fp32 hardware atomics, order of the additions not fixed)
-    if (p.km_sums) {
-        for (int e = tid; e < kWideTokens * M; e += kEncBlock) {
-            const int tl = e / M, m = e - tl * M;
-            if (t0 + tl < p.T) {
-                const size_t cen = (size_t)g * C + idx_s[tl * M + m];
-#pragma unroll
-                for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
-                atomicAdd(p.km_counts + cen, 1);
-            }
-        }
     }
 }
 
@@ -733,18 +705,24 @@ int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
             hipLaunchKernelGGL((encode_token_wide_kernel<D, d, BITS, false>), tgrid, dim3(kCentroids), 0, stream, p);
         return hipGetLastError() == hipSuccess ? 0 : -4;
     }
-    constexpr size_t smem = ((size_t)1 << BITS) * d * 2 + sizeof(float) * kWideTokens * (D + 4) + 2 * kWideTokens * M;
+    constexpr size_t smem = vq_wide_smem_bytes<D, d, BITS>();
+    static_assert(smem <= 160 * 1024, "LDS of a compute unit");
     static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<D, d, BITS, true>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(vq_tile_wide_kernel<D, d, BITS, true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(encode_wide_kernel<D, d, BITS, false>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(vq_tile_wide_kernel<D, d, BITS, false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
     if (!configured) return -4;
-    dim3 grid((unsigned)((p.T + kWideTokens - 1) / kWideTokens), 1, p.B * p.Hkv);
+    // runs: the tables are built a few times per compute unit only, the grid still fills the chip
+    const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
+    long long per = tiles * p.B * p.Hkv / (4LL * num_cus());
+    if (per < 1) per = 1;
+    if (per > 256) per = 256;
+    dim3 grid((unsigned)((tiles + per - 1) / per), 1, p.B * p.Hkv);
     if (p.lam)
-        hipLaunchKernelGGL((encode_wide_kernel<D, d, BITS, true>), grid, dim3(kEncBlock), smem, stream, p);
+        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, true>), grid, dim3(kVqBlock), smem, stream, p, (int)per);
     else
-        hipLaunchKernelGGL((encode_wide_kernel<D, d, BITS, false>), grid, dim3(kEncBlock), smem, stream, p);
+        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, false>), grid, dim3(kVqBlock), smem, stream, p, (int)per);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

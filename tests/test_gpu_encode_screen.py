@@ -111,3 +111,59 @@ def test_keys_with_outliers_full_tile_mix():
     got, = gpu_encode(shape, k=e["k"], lam=lam, cb_k=e["cb_k"])
     ref, gap = oracle.encode_keys(e["k"], lam, e["cb_k"], want_gap=True)
     assert_indices_match(got, ref, gap, "keys with outliers")
+
+
+# ------------------------------------------------------------------ shared codebooks (10- / 12-bit codes)
+
+def _wide_values_case(D, d, bits, x, cb):
+    """x [T, D] fp16, cb [2^bits, d] fp16 -> (GPU codes [T, M], oracle codes, oracle gap)."""
+    shape = synth.Shape(1, 1, 1, D, x.shape[0], d, d, bits, bits)
+    got, = gpu_encode(shape, v=x[None, None], cb_v=cb[None])
+    ref, gap = oracle.encode_values(x[None, None], cb[None, None], want_gap=True)
+    return oracle.unpack_codes(got, bits, D // d)[0, 0], ref[0, 0], gap[0, 0]
+
+
+@pytest.mark.parametrize("D,d,bits", [(128, 8, 12), (128, 4, 12), (128, 4, 10), (64, 8, 12), (64, 4, 10)])
+def test_shared_codebook_exact_ties_across_chunks(D, d, bits):
+    """A table of 2^b centroids that holds only 40 different vectors on a grid of halves: every
+    token's nearest centroid occurs about 2^b / 40 times, spread over all 256-centroid chunks of the
+    search, all at exactly the same distance.  More than two chunks tie, so the screen gives up and
+    the plain search must return the lowest index."""
+    g = synth.rng(D + d + bits)
+    C = 1 << bits
+    M = D // d
+    base = (g.integers(-6, 7, size=(40, d)) / 2).astype(np.float16)
+    cb = base[g.integers(0, 40, size=C)]
+    x = (base[g.integers(0, 40, size=(T, M))].astype(np.float32)
+         + g.integers(-1, 2, size=(T, M, d)).astype(np.float32) / 4).astype(np.float16).reshape(T, D)
+    got, ref, gap = _wide_values_case(D, d, bits, x, cb)
+    dist = ((x.reshape(T, M, 1, d).astype(np.float64) - cb[None, None].astype(np.float64)) ** 2).sum(-1)   # exact
+    np.testing.assert_array_equal(got, dist.argmin(-1))
+    assert ((dist == dist.min(-1, keepdims=True)).sum(-1) > 2).mean() > 0.9
+
+
+@pytest.mark.parametrize("scale", [1e-3, 1.0, 100.0])
+@pytest.mark.parametrize("D,d,bits", [(128, 8, 12), (128, 4, 10), (64, 4, 12)])
+def test_shared_codebook_scales_and_near_ties(D, d, bits, scale):
+    """Random shared tables at three scales with a block of centroids one fp16 ulp above others (in
+    other chunks), tokens near centroids, and tokens at the largest fp16 values."""
+    g = synth.rng(int(scale * 1000) + D + d + bits)
+    C = 1 << bits
+    M = D // d
+    cb = (g.standard_normal((C, d)) * scale).astype(np.float16)
+    cb[C // 2:C // 2 + 300] = np.nextafter(cb[:300], np.float16(np.inf)).astype(np.float16)
+    a = g.integers(0, C, size=(T, M))
+    x = cb[a].astype(np.float32) * (1 + g.standard_normal((T, M, d)).astype(np.float32) * 1e-3)
+    x = x.astype(np.float16).reshape(T, D)
+    x[11] = 65504.0
+    x[12, ::3] = -60000.0
+    got, ref, gap = _wide_values_case(D, d, bits, x, cb)
+    keep = np.ones(T, bool)
+    keep[[11, 12]] = False                                  # (fp64 gaps far below fp32 resolution there)
+    assert_indices_match(got[keep], ref[keep], gap[keep], f"shared table d{d}b{bits} x{scale}")
+    cb32 = cb.astype(np.float32)
+    for t in (11, 12):
+        xs = x[t].astype(np.float32).reshape(M, 1, d)
+        dist = ((xs - cb32[None]) ** 2).sum(-1, dtype=np.float32)
+        best = dist.min(-1, keepdims=True)
+        assert (dist[np.arange(M), got[t]] <= best[:, 0] * (1 + 1e-6)).all()

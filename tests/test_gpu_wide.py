@@ -182,6 +182,21 @@ def test_encode_wide_token_and_tiled_kernels_agree_and_append_equals_encodes():
     assert (ak.cpu().numpy()[:, :, :5] == 0xEE).all() and (av.cpu().numpy()[:, :, 21:] == 0xEE).all()
 
 
+def test_encode_wide_full_size_d8b12_sampled():
+    """65536 tokens x 8 KV heads with 12-bit codes on sub-vectors of 8 (the size the cache fill is timed
+    at): keys and values, 96 sampled tokens per head against the oracle (Eq. 2 over 4096 centroids)."""
+    shape = synth.Shape(1, 8, 8, 128, 65536, 8, 8, 12, 12)
+    e = synth.encode_inputs(shape, seed=5, n_outlier=3)
+    lam = np.stack([oracle.smoothing_factors(e["k"][:, h]) for h in range(shape.Hkv)]).astype(np.float32)
+    got_k, got_v = gpu_encode(shape, k=e["k"], lam=lam, cb_k=e["cb_k"], v=e["v"], cb_v=e["cb_v"])
+    rows = np.sort(synth.rng(6).choice(shape.N, size=96, replace=False))
+    rows[-1] = shape.N - 1
+    ref_k, gap_k = oracle.encode_keys(e["k"][:, :, rows], lam, e["cb_k"][:, None], want_gap=True)
+    ref_v, gap_v = oracle.encode_values(e["v"][:, :, rows], e["cb_v"][:, None], want_gap=True)
+    assert_indices_match(oracle.unpack_codes(got_k[:, :, rows], 12, shape.Mk), ref_k, gap_k, "d8b12 keys, 65536 tokens")
+    assert_indices_match(oracle.unpack_codes(got_v[:, :, rows], 12, shape.Mv), ref_v, gap_v, "d8b12 values, 65536 tokens")
+
+
 def test_encode_wide_planted_codes_and_ties():
     """Vectors built from centroids come back as those codes; a duplicated centroid resolves to
     its lowest index (Eq. 2 with the lowest-index rule)."""
