@@ -31,16 +31,20 @@ constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
 // (kTransform) or just widened (values), as fp32 rows of x_s (row stride D + 4 floats).  A lane
 // owns 4 consecutive channels of one token; the first two butterfly stages run inside the lane,
 // the others across lanes with wavefront shuffles.
-template <int D, bool kTransform, int BLOCK = kEncBlock>
-__device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float *x_s, long long t0, int bg, int g)
+// NCH < D: only channels ch0 .. ch0 + NCH - 1 are kept (row stride NCH + 4), for a workgroup that
+// searches a group of sub-spaces; values outside the window are then not even loaded.
+template <int D, bool kTransform, int BLOCK = kEncBlock, int NCH = D>
+__device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float *x_s, long long t0, int bg, int g,
+                                                    int ch0 = 0)
 {
     constexpr int LPT = D / 4;                 // lanes per token
     constexpr int TPW = 64 / LPT;              // tokens per wavefront pass
-    constexpr int XS = D + 4;                  // padded row stride of the LDS tile (floats)
+    constexpr int XS = NCH + 4;                // padded row stride of the LDS tile (floats)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
         const int sub = lane % LPT;            // which 4 channels of the token
         const int tw = lane / LPT;             // which token of this pass
         const int c0 = 4 * sub;
+        const bool kept = NCH == D || (c0 >= ch0 && c0 < ch0 + NCH);
         float rl[4] = {1.f, 1.f, 1.f, 1.f};
         if (kTransform) {
             const float4 l4 = *reinterpret_cast<const float4 *>(p.lam + (size_t)g * D + c0);
@@ -56,7 +60,8 @@ __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float
             const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;   // token within the tile
             long long t = t0 + tl;
             if (t >= p.T) t = p.T - 1;                                  // tail: harmless duplicate
-            const uint2 raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
+            uint2 raw = make_uint2(0u, 0u);
+            if (kTransform || kept) raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
             const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
             const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
             v[pi][0] = __low2float(h01); v[pi][1] = __high2float(h01);
@@ -95,7 +100,7 @@ __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float
         for (int pi = 0; pi < NP; ++pi) {
             const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;
             float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
-            *reinterpret_cast<float4 *>(&x_s[tl * XS + c0]) = w;
+            if (kept) *reinterpret_cast<float4 *>(&x_s[tl * XS + c0 - ch0]) = w;
         }
 }
 
@@ -115,16 +120,21 @@ __device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float
 constexpr int kVqBlock = 512;
 
 // Sub-spaces per workgroup: all of them for the cache fill (32 at most: d = 2 at D = 128 takes two
-// workgroups per tile), 8 for K-Means, whose sums need 256 (d + 1) floats per sub-space.
+// workgroups per tile), 16 (d = 8: 8) for K-Means, whose sums need 256 (d + 1) floats per sub-space.
 template <int d, bool kAccumulate>
-constexpr int vq_group(int M) { return M < (kAccumulate ? 8 : 32) ? M : (kAccumulate ? 8 : 32); }
+constexpr int vq_group(int M)
+{
+    const int most = !kAccumulate ? 32 : (d == 8 ? 8 : 16);
+    return M < most ? M : most;
+}
 
 template <int D, int d, bool kAccumulate>
 constexpr size_t vq_smem_bytes()
 {
     constexpr int MSW = vq_group<d, kAccumulate>(D / d);
-    return (size_t)MSW * ScreenTab<d>::kBytes + sizeof(float) * kEncTokens * (D + 4) + (size_t)kEncTokens * MSW +
-           (kAccumulate ? sizeof(float) * MSW * kCentroids * (d + 1) : 0);
+    constexpr int NCH = kAccumulate ? MSW * d : D;         // channels of the tile kept in LDS
+    return (size_t)MSW * ScreenTab<d>::kBytes + sizeof(float) * kEncTokens * (NCH + 4) + (size_t)kEncTokens * MSW +
+           (kAccumulate ? (sizeof(float) * (d + 1) + 1) * MSW * kCentroids : 0);
 }
 
 struct KmeansState {
@@ -142,13 +152,16 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int t
     constexpr int NW = kVqBlock / 64;
     constexpr int SPW = (MSW + NW - 1) / NW;               // sub-spaces per wavefront: 1, 2 or 4
     static_assert(MSW % NW == 0 && M % MSW == 0, "whole groups, dealt evenly to the wavefronts");
-    constexpr int XS = D + 4;                              // row stride of the transformed tile
+    // K-Means keeps only its group's channels of the tile (the sums need the room)
+    constexpr int NCH = kAccumulate ? MSW * d : D;
+    constexpr int XS = NCH + 4;                            // row stride of the transformed tile
     constexpr int TB = ScreenTab<d>::kBytes;
     extern __shared__ __align__(16) unsigned char vq_smem[];
     unsigned char *const tab_s = vq_smem;                                          // [MSW] search tables
     float *const x_s = reinterpret_cast<float *>(tab_s + MSW * TB);                // [64][XS] transformed tile
     uint8_t *const idx_s = reinterpret_cast<uint8_t *>(x_s + kEncTokens * XS);     // [64][MSW] codes of the tile
     float *const acc_s = reinterpret_cast<float *>(idx_s + kEncTokens * MSW);      // [MSW][256][d + 1] sums, counts
+    volatile uint8_t *const tag_s = reinterpret_cast<volatile uint8_t *>(acc_s + MSW * kCentroids * (d + 1));   // [MSW][256]
 
     if (kAccumulate && iter > 0 && iter > state->stop_at) return;     // training already stopped (every thread alike)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -171,21 +184,38 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int t
         const long long t0 = (tile0 + ti) * kEncTokens;
         if (t0 >= p.T) break;
         __syncthreads();                       // previous tile's x_s and idx_s consumed (first tile: accumulators cleared)
-        load_transform_tile<D, kTransform, kVqBlock>(p, x_s, t0, bg, g);
+        load_transform_tile<D, kTransform, kVqBlock, NCH>(p, x_s, t0, bg, g, grp * MSW * d);
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
             const int ms = wave + NW * i;
-            const int ch0 = (grp * MSW + ms) * d;
+            const int ch0 = (NCH == D ? grp * MSW + ms : ms) * d;
             int arg;
             unsigned best;
             search_tile<d>(x_s, XS, ch0, tab_s + ms * TB, sc[i], lane, arg, best);
             idx_s[lane * MSW + ms] = (uint8_t)arg;
             if (kAccumulate && t0 + lane < p.T) {
+                // The accumulators of a sub-space belong to this wavefront alone, and its LDS
+                // operations execute in order, so only lanes of the same instruction can collide.
+                // One lane per distinct code (the last to write its number into the code's tag)
+                // adds its sub-vector with plain loads and stores; the others, about a fifth of the
+                // lanes for evenly used codes, follow with atomics (ds_add_f32 costs roughly two
+                // cycles per active lane: 0.35 ms of a 0.82 ms iteration when every lane used it).
                 float *a = acc_s + ((size_t)ms * kCentroids + arg) * (d + 1);
+                volatile uint8_t *tag = tag_s + ms * kCentroids + arg;
+                *tag = (uint8_t)lane;
+                if (*tag == (uint8_t)lane) {
+                    float row[d + 1];
 #pragma unroll
-                for (int j = 0; j < d; ++j) atomicAdd(a + j, x_s[lane * XS + ch0 + j]);
-                atomicAdd(a + d, 1.0f);             // (counts stay exact in fp32: far below 2^24 per run)
+                    for (int j = 0; j <= d; ++j) row[j] = a[j];
+#pragma unroll
+                    for (int j = 0; j < d; ++j) a[j] = row[j] + x_s[lane * XS + ch0 + j];
+                    a[d] = row[d] + 1.0f;           // (counts stay exact in fp32: far below 2^24 per run)
+                } else {
+#pragma unroll
+                    for (int j = 0; j < d; ++j) atomicAdd(a + j, x_s[lane * XS + ch0 + j]);
+                    atomicAdd(a + d, 1.0f);
+                }
                 err += __uint_as_float(best);
             }
         }
@@ -758,7 +788,9 @@ int launch_vq_tiles(const EncodeParams &p, int iter, void *state, hipStream_t st
     if (!configured) return -4;
     const long long tiles = (p.T + kEncTokens - 1) / kEncTokens;
     const long long groups = (long long)(M / MSW) * p.B * p.Hkv;
-    long long per = tiles * groups / (4LL * num_cus());
+    // (K-Means: one workgroup per compute unit where the input allows, so that the partial sums are
+    // flushed as rarely as possible: 21 M global atomics per iteration at 65536 x 8 tokens with four)
+    long long per = tiles * groups / ((kAccumulate ? 1LL : 4LL) * num_cus());
     if (per < 1) per = 1;
     if (per > 256) per = 256;
     dim3 grid((unsigned)((tiles + per - 1) / per), M / MSW, p.B * p.Hkv);

@@ -241,3 +241,24 @@ def test_train_full_size_iteration_properties():
         full = counts[g, m] > 0
         np.testing.assert_allclose(cb[g, m][full].astype(np.float64), sums[full] / counts[g, m][full, None],
                                    rtol=1.5e-3, atol=1e-6)
+
+
+@pytest.mark.parametrize("n_distinct", [1, 3, 40])
+def test_train_heavily_shared_codes(n_distinct):
+    """Tokens drawn from a handful of vectors: in every wavefront many lanes carry the same code, the
+    case the accumulation resolves with one plain update and atomics for the rest.  Counts exact,
+    means within one fp16 ulp, error against the oracle."""
+    shape = synth.Shape(2, 2, 2, 128, 700, 4, 4)
+    g = synth.rng(300 + n_distinct)
+    pool = g.standard_normal((n_distinct, shape.D)).astype(np.float16)
+    x = pool[g.integers(0, n_distinct, size=(shape.B, shape.Hkv, shape.N))]
+    cb0 = g.standard_normal((shape.Hkv, shape.Mv, 256, shape.d_v)).astype(np.float16)
+    t = Trainer(shape, x, None, cb0)
+    n, e = t.train(1, -1.0)
+    cb, codes, counts = t.state()
+    ref_idx, gap = oracle.encode_values(x, cb0, want_gap=True)
+    assert_indices_match(codes, ref_idx, gap, "shared codes: assignment")
+    ref_e = oracle.quantization_error(x, None, cb0, codes).sum()
+    assert abs(e[0] - ref_e) <= 2e-5 * ref_e
+    _check_means(x, None, cb, codes, counts, "shared codes", cb_before=cb0)
+    assert (counts > 0).sum(axis=2).max() <= n_distinct
