@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int t
         const long long t0 = (tile0 + ti) * kEncTokens;
         if (t0 >= p.T) break;
         __syncthreads();                       // previous tile's x_s and idx_s consumed (first tile: accumulators cleared)
-        load_transform_tile<D, kTransform, kVqBlock, NCH>(p, x_s, t0, bg, g, grp * MSW * d);
+        load_transform_tile<D, kTransform, kVqBlock, NCH>(p, x_s, t0, bg, g, NCH == D ? 0 : grp * MSW * d);
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
