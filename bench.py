@@ -59,7 +59,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="196k-b2d4",
-                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-d64-d8", "196k-kd2vd4", "196k-d8b12",
+                    choices=["196k-b2d4", "196k-b4d2", "32k", "batch32", "196k-d64", "196k-d64-d8", "196k-kd2vd4", "196k-d8b8", "196k-d8b12",
                              "196k-d4b12", "196k-kd4b10-vd8b12", "196k-kd8b12-vd8b8"])
     ap.add_argument("--tokens", type=int, default=0,
                     help="override the workload's cache length N (the 32k .. 196k ladder); a side measurement")
@@ -99,6 +99,7 @@ def main() -> int:
              "32k": synth.LLAMA8B_32K, "batch32": synth.LLAMA8B_BATCH32,
              "196k-d64": synth.HEADDIM64_196K, "196k-kd2vd4": synth.LLAMA8B_196K_KD2_VD4,
              "196k-d64-d8": synth.Shape(1, 32, 8, 64, 196608, 8, 8),      # head dim 64, 1-bit keys and values
+             "196k-d8b8": synth.Shape(1, 32, 8, 128, 196608, 8, 8),       # 1 bit per element (d8b8)
              # codes wider than 8 bits, one shared codebook per KV head (side measurements, not the metric)
              "196k-d8b12": synth.LLAMA8B_196K_D8B12,
              "196k-d4b12": synth.Shape(1, 32, 8, 128, 196608, 4, 4, 12, 12),
