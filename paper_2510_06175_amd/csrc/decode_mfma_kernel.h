@@ -271,7 +271,11 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     for (int i = 0; i < 4; ++i) sel[i] = t0 == i ? 0xffffffffu : 0u;
     // LDS byte offsets: keys  MK/4 sub-spaces per kg
     //                   values sub-space NROUND_V*col + r
-    const unsigned lds_base = (unsigned)(uintptr_t)smem;          // LDS offset of the dynamic segment
+    // LDS offset of the dynamic segment.  The kernel owns no static LDS, so the segment starts at
+    // 0 (the launcher checks the kernel's static LDS size and refuses to launch otherwise); read
+    // off the pointer, the compiler would learn that constant only after instruction selection
+    // and keep an add of it in front of every gather of the shared tables of wide codes.
+    const unsigned lds_base = 0u;
     const unsigned lds_k = lds_base + (WK ? 0u : (unsigned)(kg * (MK / 4) * SUB_K));
     // (wide codes with split value sub-spaces: column col reads half col & 1 of its 16-byte centroid)
     const unsigned lds_v = lds_base + (unsigned)CBK_BYTES +
@@ -760,28 +764,52 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         const unsigned long long w = ((unsigned long long)w1 << 32) | w0;
         return ((unsigned)(w >> pos) & ((1u << B) - 1u)) << LOG2E;
     };
-    auto field3 = [&](unsigned w0, unsigned w1, unsigned w2, unsigned pos, auto bits_c, auto log2e_c) -> unsigned {
-        const unsigned j = pos >> 5;         // dword the field starts in
-        const unsigned lo = j == 0 ? w0 : (j == 1 ? w1 : w2), hi = j == 0 ? w1 : (j == 1 ? w2 : 0u);
-        return field2(lo, hi, pos & 31u, bits_c, log2e_c);
+    // A window of three dwords moved down by the lane constant `pos`, so that the fields of the
+    // lane's run sit at the same bit positions in every lane (one funnel shift per dword and
+    // window instead of a dword select and a 64-bit shift per code).  `nd` = dwords of the result
+    // that are used.
+    auto align3 = [](unsigned w0, unsigned w1, unsigned w2, unsigned pos, unsigned (&o)[3], auto nd_c) {
+        constexpr int ND = decltype(nd_c)::value;
+        const unsigned j = pos >> 5, sh = pos & 31u;
+        const unsigned t0 = j == 0 ? w0 : (j == 1 ? w1 : w2), t1 = j == 0 ? w1 : (j == 1 ? w2 : 0u);
+        o[0] = __builtin_amdgcn_alignbit(t1, t0, sh);
+        if constexpr (ND > 1) {
+            const unsigned t2 = j == 0 ? w2 : 0u;
+            o[1] = __builtin_amdgcn_alignbit(t2, t1, sh);
+            o[2] = t2 >> sh;
+        } else {
+            o[1] = o[2] = 0u;
+        }
     };
-    auto win_field_k = [&](const unsigned (&w)[KW], unsigned pos) -> unsigned {
+    // the B-bit field at the constant bit `at` of an aligned window, as a table offset
+    auto const_field = [](const unsigned (&o)[3], int at, auto bits_c, auto log2e_c) -> unsigned {
+        constexpr int B = decltype(bits_c)::value, LOG2E = decltype(log2e_c)::value;
+        const int j = at >> 5, sh = at & 31;
+        const unsigned x = sh + B <= 32 ? o[j] >> sh : __builtin_amdgcn_alignbit(o[j + 1 < 3 ? j + 1 : 2], o[j], (unsigned)sh);
+        return (x & ((1u << B) - 1u)) << LOG2E;
+    };
+    // key code i of the lane's run in the window w
+    auto win_field_k = [&](const unsigned (&w)[KW], int i) -> unsigned {
         constexpr auto bits_c = std::integral_constant<int, BK>{};
         constexpr auto log2e_c = std::integral_constant<int, DK == 8 ? 4 : 3>{};
         if constexpr (!WK) return 0u;
-        else if constexpr (WIN_K == 2) return field2(w[0], w[1], pos, bits_c, log2e_c);
-        else return field3(w[0], w[1], w[2], pos, bits_c, log2e_c);
+        else if constexpr (WIN_K == 2) return field2(w[0], w[1], pos_k + BK * i, bits_c, log2e_c);
+        else {
+            unsigned o[3];
+            align3(w[0], w[1], w[2], pos_k, o, std::integral_constant<int, 3>{});
+            return const_field(o, BK * i, bits_c, log2e_c);
+        }
     };
     // A operand of the score MFMA for sub-tile st, round r: the centroids of 8/d consecutive
     // key sub-spaces of the lane's token (pure LDS gathers, no arithmetic on the values).
     auto gather_k = [&](const Codes &cd, int st, int r) -> half8 {
         if constexpr (WK && DK == 8) {
             // code r of the lane's four
-            return __builtin_bit_cast(half8, lds_load_b128(lds_k + win_field_k(cd.kc[st], pos_k + BK * r)));
+            return __builtin_bit_cast(half8, lds_load_b128(lds_k + win_field_k(cd.kc[st], r)));
         } else if constexpr (WK) {
             // codes 2r, 2r + 1 of the lane's eight
-            const uint2 x0 = lds_load_b64(lds_k + win_field_k(cd.kc[st], pos_k + BK * (2 * r)));
-            const uint2 x1 = lds_load_b64(lds_k + win_field_k(cd.kc[st], pos_k + BK * (2 * r + 1)));
+            const uint2 x0 = lds_load_b64(lds_k + win_field_k(cd.kc[st], 2 * r));
+            const uint2 x1 = lds_load_b64(lds_k + win_field_k(cd.kc[st], 2 * r + 1));
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else if constexpr (DK == 8) {
             // sub-space (MK/4) kg + r: one 16-byte entry is the whole operand
@@ -816,22 +844,28 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         default: return quad_bcast<3>(x);
         }
     };
-    auto win_field_v = [&](const unsigned (&w)[VW], int v, unsigned pos) -> unsigned {
+    // value code r (of the lane's NROUND_V) of token v of the k-group
+    auto win_field_v = [&](const unsigned (&w)[VW], int v, int r) -> unsigned {
         constexpr auto bits_c = std::integral_constant<int, BV>{};
         constexpr auto log2e_c = std::integral_constant<int, DVR == 8 ? 4 : 3>{};   // bytes of a table entry
         if constexpr (!WV) return 0u;
-        else if constexpr (WIN_V == 2) return field2(quad_get(w[0], v), quad_get(w[1], v), pos, bits_c, log2e_c);
-        else return field3(quad_get(w[0], v), quad_get(w[1], v), quad_get(w[2], v), pos, bits_c, log2e_c);
+        else if constexpr (WIN_V == 2) return field2(quad_get(w[0], v), quad_get(w[1], v), pos_v + BV * r, bits_c, log2e_c);
+        else {
+            // (the lane's run, NROUND_V codes, fits one dword)
+            unsigned o[3];
+            align3(quad_get(w[0], v), quad_get(w[1], v), quad_get(w[2], v), pos_v, o, std::integral_constant<int, 1>{});
+            return const_field(o, BV * r, bits_c, log2e_c);
+        }
     };
     auto gather_v = [&](const Codes &cd, int st, int q) -> half8 {
         if constexpr (WV && DV == 8) {
             // q = token v of the k-group: the 8 channels of sub-space col of that token
-            return __builtin_bit_cast(half8, lds_load_b128(lds_v + win_field_v(cd.vc[st], q, pos_v)));
+            return __builtin_bit_cast(half8, lds_load_b128(lds_v + win_field_v(cd.vc[st], q, 0)));
         } else if constexpr (WV) {
             // q = 2 u + r: sub-space 2 col + r of tokens 2u, 2u + 1
             const int u = q / NROUND_V, r = q % NROUND_V;
-            const uint2 x0 = lds_load_b64(lds_v + win_field_v(cd.vc[st], 2 * u, pos_v + BV * r));
-            const uint2 x1 = lds_load_b64(lds_v + win_field_v(cd.vc[st], 2 * u + 1, pos_v + BV * r));
+            const uint2 x0 = lds_load_b64(lds_v + win_field_v(cd.vc[st], 2 * u, r));
+            const uint2 x1 = lds_load_b64(lds_v + win_field_v(cd.vc[st], 2 * u + 1, r));
             return as_half8(x0.x, x0.y, x1.x, x1.y);
         } else if constexpr (DV == 8) {
             // q = token v of the k-group: the 8 channels of sub-space col of that token
@@ -982,7 +1016,10 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                 const unsigned p0 = quad_bcast<st>(pp[hg][0]), p1 = quad_bcast<st>(pp[hg][1]);
                 const unsigned p2 = quad_bcast<st>(pp[hg][2]), p3 = quad_bcast<st>(pp[hg][3]);
                 if constexpr (DV == 8) {
-                    // one token per step; channels t0 (first accumulator) and t0 + 4 (second)
+                    // one token per step; channels t0 (first accumulator) and t0 + 4 (second).
+                    // (Two tokens per MFMA as at d = 4, with the halves of a centroid gathered apart,
+                    // halve the MFMAs but double the LDS reads: 1.5 us slower per call with 8-bit
+                    // codes, 6 us with a shared table, whose reads meet at random banks.)
                     const unsigned pt[4] = {p0, p1, p2, p3};
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
@@ -1155,9 +1192,13 @@ int launch_hg(const DecodeParams &p, hipStream_t stream)
     constexpr size_t merge_bytes = sizeof(float) * (NW * KG * kD + 2 * NW * KG);
     constexpr size_t smem = loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
     // once per process and instantiation (function-local static: initialised thread-safely)
-    static const bool configured =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    static const bool configured = [] {
+        const void *fn = reinterpret_cast<const void *>(decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>);
+        // (the kernel takes the dynamic segment to start at LDS offset 0: no static LDS in front of it)
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, fn) != hipSuccess || attr.sharedSizeBytes != 0) return false;
+        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) == hipSuccess;
+    }();
     if (!configured) return -4;
     dim3 grid(p.S, p.Hkv, p.B);
     hipLaunchKernelGGL((decode_mfma_kernel<kD, DK, DV, HG, NW, SPLITQ, BK, BV, VT>), grid, dim3(NW * 64), smem, stream,
