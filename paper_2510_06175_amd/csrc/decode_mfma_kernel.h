@@ -517,7 +517,14 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     // ---- B operands of the score MFMAs: q~_h[(D/4) kg + 8r .. +8); columns with t0 < 2 take the
     // fp16 high part, columns with t0 >= 2 the low part (x - float(hi)).
     // fold = (1/sqrt D of H_D) * (1/sqrt D of the score) * log2 e
-    half8 bq[HG][NR];
+    // With the split query a head has four columns but only two parts, so a column can serve two
+    // sub-tiles: the operand exists in two copies, copy c zero outside the columns with t0 % 2 = c,
+    // sub-tile st multiplies copy st % 2, and sub-tiles 0, 1 (2, 3) accumulate in one register
+    // set.  Column t0 of that set then holds part t0 / 2 of sub-tile t0 % 2 (2 + t0 % 2) and nothing
+    // else, which leaves the softmax a two-way pick instead of two four-way picks per score.
+    // (One head group only: with two the copies cost 32 more registers than there are.)
+    constexpr int NQ = SPLITQ && HG == 1 ? 2 : 1;    // operand copies;  score register sets = 4 / NQ
+    half8 bq[HG][NQ][NR];
     {
         const float fold = kLog2e / (float)kD;
 #pragma unroll
@@ -530,7 +537,9 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
                     const float x = sm_qt[hh * kD + (kD / 4) * kg + 8 * r + e] * fold;
                     const _Float16 hi = (_Float16)x;
                     const _Float16 lo = (_Float16)(x - (float)hi);
-                    bq[hg][r][e] = (SPLITQ && (col & 2)) ? lo : hi;
+                    const _Float16 part = (SPLITQ && (col & 2)) ? lo : hi;
+#pragma unroll
+                    for (int c = 0; c < NQ; ++c) bq[hg][c][r][e] = (NQ == 1 || (col & 1) == c) ? part : (_Float16)0.f;
                 }
         }
     }
@@ -917,17 +926,20 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
     auto process_tile = [&](Codes &cd, const Codes &next, long long tb, long long tb_refill) {
         half8 kb[4 * H], va[2 * NR], vb[2 * NR];
         const floatx4 kZero4 = {0.f, 0.f, 0.f, 0.f};
-        floatx4 sacc[HG][4];
+        floatx4 sacc[HG][4 / NQ];              // split query: set a holds sub-tiles 2a, 2a + 1
+        // (sub-tiles in the order 0, 2, 1, 3: consecutive MFMAs accumulate in different sets)
+        auto st_of = [](int i) { return NQ == 2 ? (i & 1) * 2 + (i >> 1) : i; };
 
         // ---- stage 1
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int hr = 0; hr < H; ++hr)
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
+            for (int i = 0; i < 4; ++i) {
+                const int st = st_of(i), a = st / NQ, c = st % NQ;
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg)
-                    sacc[hg][st] = MFMA16(ka[H * st + hr], bq[hg][hr], hr == 0 ? kZero4 : sacc[hg][st], 0, 0, 0);
+                    sacc[hg][a] = MFMA16(ka[H * st + hr], bq[hg][c][hr], hr == 0 && c == 0 ? kZero4 : sacc[hg][a], 0, 0, 0);
                 kb[H * st + hr] = gather_k(cd, st, H + hr);
             }
         VI_GROUPS8(HG, kReadsK, 0)
@@ -938,11 +950,12 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
 #pragma unroll
         for (int hr = 0; hr < H; ++hr)
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
+            for (int i = 0; i < 4; ++i) {
+                const int st = st_of(i), a = st / NQ, c = st % NQ;
 #pragma unroll
                 for (int hg = 0; hg < HG; ++hg)
-                    sacc[hg][st] = MFMA16(kb[H * st + hr], bq[hg][H + hr], sacc[hg][st], 0, 0, 0);
-                va[4 * hr + st] = gather_v(cd, (4 * hr + st) / NR, (4 * hr + st) % NR);   // sub-tiles 0, 1
+                    sacc[hg][a] = MFMA16(kb[H * st + hr], bq[hg][c][H + hr], sacc[hg][a], 0, 0, 0);
+                va[4 * hr + i] = gather_v(cd, (4 * hr + i) / NR, (4 * hr + i) % NR);   // sub-tiles 0, 1
             }
         VI_GROUPS8(HG, kReadsV, 0)
         __builtin_amdgcn_sched_barrier(0);
@@ -961,24 +974,32 @@ void decode_mfma_kernel(const __half *q_arg, const float *lam_arg, const __half 
         unsigned pp[HG][4];                      // (p, p) as fp16 pairs, tokens 4v + kg of sub-tile t0
 #pragma unroll
         for (int hg = 0; hg < HG; ++hg) {
-            // Branch-free per-lane pick with bit masks (exactly one of sel[] is all ones; v_bfi_b32 /
-            // v_cndmask).  With the split query, columns t0 < 2 carry q~_hi . k and columns t0 >= 2
-            // carry q~_lo . k: a lane keeps its own part of sub-tile t0 (`mine`) and hands its part of
-            // sub-tile t0 ^ 2 - the one the lane two further on keeps - across the quad (`theirs`), so
-            // that one DPP add per score restores the full precision: 7 operations per score in
-            // place of the 4 adds over all sub-tiles and a 7-operation pick.
+            // Branch-free per-lane pick with bit masks (v_bfi_b32 / v_cndmask).  With the split query,
+            // columns t0 < 2 carry q~_hi . k and columns t0 >= 2 carry q~_lo . k, and a lane's two
+            // register sets hold its part of sub-tiles t0 % 2 and 2 + t0 % 2: it keeps the one of
+            // sub-tile t0 (`mine`) and hands the other - its part of sub-tile t0 ^ 2, which the lane
+            // two further on keeps - across the quad (`theirs`), so that one DPP add per score
+            // restores the full precision: 3 operations per score.  (Two head groups: one register
+            // set per sub-tile, `mine` and `theirs` picked among four.)
             auto bfi = [](unsigned m, unsigned a, unsigned b) -> unsigned { return (m & a) | (~m & b); };
             float sc[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const unsigned s0 = __float_as_uint(sacc[hg][0][v]), s1 = __float_as_uint(sacc[hg][1][v]);
-                const unsigned s2 = __float_as_uint(sacc[hg][2][v]), s3 = __float_as_uint(sacc[hg][3][v]);
-                const unsigned mine = bfi(sel[3], s3, bfi(sel[2], s2, bfi(sel[1], s1, s0)));
-                if (SPLITQ) {
-                    const unsigned theirs = bfi(sel[1], s3, bfi(sel[0], s2, bfi(sel[3], s1, s0)));
+                if constexpr (NQ == 2) {
+                    const unsigned lower = __float_as_uint(sacc[hg][0][v]), upper = __float_as_uint(sacc[hg][1][v]);
+                    const unsigned up = sel[2] | sel[3];                   // all ones iff t0 >= 2
+                    const unsigned mine = bfi(up, upper, lower), theirs = bfi(up, lower, upper);
                     sc[v] = __uint_as_float(mine) + quad_xor<2>(__uint_as_float(theirs));
                 } else {
-                    sc[v] = __uint_as_float(mine);
+                    const unsigned s0 = __float_as_uint(sacc[hg][0][v]), s1 = __float_as_uint(sacc[hg][1][v]);
+                    const unsigned s2 = __float_as_uint(sacc[hg][2 % (4 / NQ)][v]), s3 = __float_as_uint(sacc[hg][3 % (4 / NQ)][v]);
+                    const unsigned mine = bfi(sel[3], s3, bfi(sel[2], s2, bfi(sel[1], s1, s0)));
+                    if (SPLITQ) {
+                        const unsigned theirs = bfi(sel[1], s3, bfi(sel[0], s2, bfi(sel[3], s1, s0)));
+                        sc[v] = __uint_as_float(mine) + quad_xor<2>(__uint_as_float(theirs));
+                    } else {
+                        sc[v] = __uint_as_float(mine);
+                    }
                 }
             }
             if (tb + kTile > n1) {                  // tail tile: tokens past the end get p = 0
