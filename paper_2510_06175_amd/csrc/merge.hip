@@ -48,11 +48,23 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // value; the token joins as the partial (m = sum of the shares, l = 1, o = value).
 enum { kPlain = 0, kWindow = 1, kNewToken = 2 };
 
+//
+// Arguments.  The first 14 dwords of a kernel's arguments can reach the wavefront in scalar
+// registers (kernel-argument preloading), everything behind them costs a cold trip to the argument
+// buffer before the loads that need it can leave.  They are therefore exactly what the first
+// requests of each mode use: the three partial arrays; three mode pointers xa, xb, xc (window: q,
+// k_res, v_res; new token: its score shares, its value, seq_lens); one packed dword
+// S | G << 9 | min(Hkv, 2047) << 13 | i0 << 24 (i0: window rows R, or M_k of the new token; 2047
+// stands for "read the grid's x extent", which is Hkv); and i1 (window: r_cap; new token: N clamped
+// to an int).  `out`, `lse` and the window's own lengths are needed at the end and ride behind.
 template <int D, int HB, int MODE>
 __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, const float *part_m, const float *part_l,
-                                                         __half *out, float *lse, int S, int G, int Hq, int Hkv,
-                                                         DecodeParams p)
+                                                         const void *xa, const void *xb, const void *xc, unsigned packed,
+                                                         int i1, __half *out, float *lse, const int32_t *res_lens)
 {
+    const int S = (int)(packed & 0x1ffu), G = (int)(packed >> 9 & 0xfu);
+    const int Hkv = (packed >> 13 & 0x7ffu) < 0x7ffu ? (int)(packed >> 13 & 0x7ffu) : (int)gridDim.x;
+    const int i0 = (int)(packed >> 24), Hq = Hkv * G;
     constexpr bool WINDOW = MODE == kWindow;
     constexpr int kMaxM = D / 2;                                      // key sub-spaces at d = 2
     constexpr int kSteps = D / 32;                                   // MFMA k-steps over the head dimension
@@ -93,35 +105,24 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
         }
     }
 
-    // Every other argument is read here, in one batch of scalar loads (left to itself the compiler
-    // fetches them where they are first needed: several cold trips to the argument buffer in a
-    // kernel whose whole run is a few of them long).
-#define VECINFER_PIN(x) asm volatile("" ::"s"(x))
-    if (MODE == kWindow) {
-        VECINFER_PIN(p.q); VECINFER_PIN(p.k_res); VECINFER_PIN(p.v_res); VECINFER_PIN(p.res_lens);
-        VECINFER_PIN(p.R); VECINFER_PIN(p.r_cap);
-    }
-    if (MODE == kNewToken) {
-        VECINFER_PIN(p.new_sc); VECINFER_PIN(p.new_v); VECINFER_PIN(p.Mk); VECINFER_PIN(p.seq_lens); VECINFER_PIN(p.N);
-    }
-#undef VECINFER_PIN
     // ---- 2. window operands -> registers
     half8 qa[kSteps], kb[kSteps];
     unsigned vv[kRowsPerWave];
     const int row0 = w * kRowsPerWave;
-    const bool wave_loads = WINDOW && row0 < p.R;            // wave-uniform
+    const int R = WINDOW ? i0 : 0, r_cap = i1;
+    const bool wave_loads = WINDOW && row0 < R;              // wave-uniform
     int r_len = 0;
     if (WINDOW) {
-        r_len = p.R;
-        if (p.res_lens) {
-            const int v = p.res_lens[b];
-            r_len = v < 0 ? 0 : (v > p.R ? p.R : v);
+        r_len = R;
+        if (res_lens) {
+            const int v = res_lens[b];
+            r_len = v < 0 ? 0 : (v > R ? R : v);
         }
         if (wave_loads) {
-            const __half *kg = p.k_res + bg * p.r_cap * D;
-            const __half *vg = p.v_res + bg * p.r_cap * D;
-            const __half *qg = p.q + ((size_t)b * Hq + (size_t)g * G) * D;
-            const int last = p.R - 1;
+            const __half *kg = static_cast<const __half *>(xb) + bg * r_cap * D;
+            const __half *vg = static_cast<const __half *>(xc) + bg * r_cap * D;
+            const __half *qg = static_cast<const __half *>(xa) + ((size_t)b * Hq + (size_t)g * G) * D;
+            const int last = R - 1;
             const int qrow = (lane & 15) < G ? (lane & 15) : 0;
             const int krow = row0 + (lane & 15) < last ? row0 + (lane & 15) : last;
 #pragma unroll
@@ -140,11 +141,19 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
     }
 
     // new token: its shares and value (read unconditionally; ignored for an empty sequence)
-    const long long len_b = MODE == kNewToken ? seq_len_of(p, b) : 0;
+    const int Mk = MODE == kNewToken ? i0 : 0;
+    int len_b = MODE == kNewToken ? i1 : 0;                  // only its sign matters here
     float nsc = 0.f, nvv = 0.f;
     if (MODE == kNewToken) {
-        if (t < p.Mk * G) nsc = p.new_sc[bg * p.Mk * G + t];
-        if (t < D) nvv = p.new_v[bg * D + t];
+        if (xc) {
+            // b is the same for the whole workgroup: read through the constant address space, i.e. by
+            // a scalar load, which does not queue behind the wavefront's vector loads
+            typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+            const int v = ((const_i32_ptr)(uintptr_t)xc)[b];
+            len_b = v < len_b ? v : len_b;
+        }
+        if (t < Mk * G) nsc = static_cast<const float *>(xa)[bg * Mk * G + t];
+        if (t < D) nvv = static_cast<const float *>(xb)[bg * D + t];
     }
 
     // ---- 3. the wave's window partial -> LDS
@@ -193,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
     }
 
     if (MODE == kNewToken) {
-        if (t < p.Mk * G) ns_s[t] = nsc;
+        if (t < Mk * G) ns_s[t] = nsc;
         if (t < D) nv_s[t] = nvv;
     }
 
@@ -223,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
         float s_new = -INFINITY;
         if (new_tok) {
             s_new = 0.f;
-            for (int m = 0; m < p.Mk; ++m) s_new += ns_s[m * G + hh];
+            for (int m = 0; m < Mk; ++m) s_new += ns_s[m * G + hh];
             M = fmaxf(M, s_new);
         }
         const float Mc = M > -INFINITY ? M : 0.f;            // nothing to attend to: all weights 0
@@ -268,12 +277,19 @@ template <int D, int HB>
 int launch_for(const DecodeParams &p, hipStream_t stream)
 {
     const dim3 grid(p.Hkv, p.B), block(kThreads);
+    const unsigned base = (unsigned)p.S | (unsigned)p.G << 9 | (unsigned)(p.Hkv < 2047 ? p.Hkv : 2047) << 13;
     if (p.k_res)
-        hipLaunchKernelGGL((merge_kernel<D, HB, kWindow>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kWindow>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l,
+                           (const void *)p.q, (const void *)p.k_res, (const void *)p.v_res, base | (unsigned)p.R << 24, (int)p.r_cap,
+                           p.out, p.lse, p.res_lens);
     else if (p.k_new)
-        hipLaunchKernelGGL((merge_kernel<D, HB, kNewToken>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kNewToken>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l,
+                           (const void *)p.new_sc, (const void *)p.new_v, (const void *)p.seq_lens, base | (unsigned)p.Mk << 24,
+                           (int)(p.N < 0x7fffffffLL ? p.N : 0x7fffffffLL), p.out, p.lse, (const int32_t *)nullptr);
     else
-        hipLaunchKernelGGL((merge_kernel<D, HB, kPlain>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l, p.out, p.lse, p.S, p.G, p.Hq, p.Hkv, p);
+        hipLaunchKernelGGL((merge_kernel<D, HB, kPlain>), grid, block, 0, stream, p.part_o, p.part_m, p.part_l,
+                           (const void *)nullptr, (const void *)nullptr, (const void *)nullptr, base, 0, p.out, p.lse,
+                           (const int32_t *)nullptr);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -281,7 +297,10 @@ int launch_for(const DecodeParams &p, hipStream_t stream)
 
 int launch_merge(const DecodeParams &p, hipStream_t stream)
 {
-    if (p.S > kMaxSplits || p.G > 8 || (p.k_res && p.R > kMaxResidual)) return -2;
+    // (field widths of the kernel's packed argument)
+    if (p.S > kMaxSplits || p.G > 8 || p.Hq != p.Hkv * p.G || p.Mk > 255 ||
+        (p.k_res && (p.R > kMaxResidual || p.r_cap > 0x7fffffffLL))) return -2;
+    static_assert(kMaxSplits < 512 && kMaxResidual < 256, "packed merge argument");
     if (p.D == 128) return p.G <= 4 ? launch_for<128, 4>(p, stream) : launch_for<128, 8>(p, stream);
     if (p.D == 64) return p.G <= 4 ? launch_for<64, 4>(p, stream) : launch_for<64, 8>(p, stream);
     return -2;
