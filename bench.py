@@ -209,18 +209,21 @@ def main() -> int:
     # average duration over K back-to-back calls between two events on the launch stream, right
     # behind the step leg (the same clock state, and its own W warm-up calls), and the
     # spread from one event pair per call (a pair adds its own overhead to the call it brackets)
+    # (at least 400 calls whatever K is: an average over a 20-call window of 0.6 ms carries the
+    # ramp of its first launches, +-1 us per call)
+    kern_calls = max(args.steps, 400)
     for i in range(max(args.warmup, 50)):
         attend(i)
     torch.cuda.synchronize()
     e0.record()
-    for i in range(args.steps):
+    for i in range(kern_calls):
         attend(i)
     e1.record()
     torch.cuda.synchronize()
-    kern_avg_ms = e0.elapsed_time(e1) / args.steps
+    kern_avg_ms = e0.elapsed_time(e1) / kern_calls
     achieved = idx_bytes / (kern_avg_ms * 1e-3) / 1e9
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(min(args.steps, 400))]
+             for _ in range(400)]
     for i, (a, b) in enumerate(pairs):
         a.record()
         attend(i)
@@ -268,7 +271,7 @@ def main() -> int:
                      "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "traffic_kernel": traffic_kernel, "traffic_source": traffic_src,
-                     "algorithmic_bytes": idx_bytes, "kernel_us_avg": round(kern_avg_ms * 1e3, 3),
+                     "algorithmic_bytes": idx_bytes, "kernel_us_avg": round(kern_avg_ms * 1e3, 3), "kernel_calls_timed": kern_calls,
                      "event_pair_us_median": round(kern_ms[len(kern_ms) // 2] * 1e3, 3),
                      "event_pair_us_min": round(kern_ms[0] * 1e3, 3),
                      "plain_read_probe_gbs": round(probe_gbs, 1),
