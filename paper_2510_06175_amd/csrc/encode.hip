@@ -493,6 +493,15 @@ constexpr size_t vq_wide_smem_bytes()
     return (size_t)ScreenTab<d, (1 << BITS)>::kBytes + sizeof(float) * kEncTokens * (D + 4) +
            sizeof(unsigned short) * kEncTokens * (D / d);
 }
+// K-Means with a shared table: a run's partial sums and counts [C][d + 1] stay in LDS where that
+// fits beside the search tables (1024 centroids: 20 or 36 KB), and go to memory once per run with
+// one atomic per non-empty centroid and channel; with 4096 centroids every sub-vector adds to
+// memory directly.
+template <int D, int d, int BITS>
+constexpr bool vq_wide_lds_sums()
+{
+    return vq_wide_smem_bytes<D, d, BITS>() + sizeof(float) * (size_t)(1 << BITS) * (d + 1) <= 96 * 1024;
+}
 
 template <int D, int d, int BITS, bool kTransform>
 __global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, int tiles_per_wg)
@@ -508,6 +517,8 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, 
     unsigned char *const tab_s = vqw_smem;                                                  // the head's search tables
     float *const x_s = reinterpret_cast<float *>(tab_s + Tab::kBytes);                      // [64][XS] transformed tile
     unsigned short *const idx_s = reinterpret_cast<unsigned short *>(x_s + kEncTokens * XS);   // [64][M] codes of the tile
+    constexpr bool kLdsSums = vq_wide_lds_sums<D, d, BITS>();
+    float *const acc_s = reinterpret_cast<float *>(vqw_smem + vq_wide_smem_bytes<D, d, BITS>());   // [C][d + 1] (K-Means)
 
     KmeansState *const state = static_cast<KmeansState *>(p.km_state);
     if (p.km_sums && p.km_iter > 0 && p.km_iter > state->stop_at) return;   // training already stopped
@@ -515,6 +526,8 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, 
     const int bg = blockIdx.z, g = bg % p.Hkv;
     const long long tile0 = (long long)blockIdx.x * tiles_per_wg;
 
+    if (kLdsSums && p.km_sums)
+        for (int e = tid; e < C * (d + 1); e += kVqBlock) acc_s[e] = 0.f;     // (the barriers of the table set-up follow)
     const ScreenConsts sc = screen_prepare_shared<d, C, kVqBlock>(p.cb + (size_t)g * C * d, tab_s, x_s);
 
     float err = 0.f;
@@ -539,15 +552,36 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, 
             for (int e = tid; e < kEncTokens * M; e += kVqBlock) {
                 const int tl = e / M, m = e - tl * M;
                 if (t0 + tl < p.T) {
-                    const size_t cen = (size_t)g * C + idx_s[tl * M + m];
+                    if constexpr (kLdsSums) {
+                        float *a = acc_s + (size_t)idx_s[tl * M + m] * (d + 1);
 #pragma unroll
-                    for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
-                    atomicAdd(p.km_counts + cen, 1);
+                        for (int j = 0; j < d; ++j) atomicAdd(a + j, x_s[tl * XS + m * d + j]);
+                        atomicAdd(a + d, 1.0f);        // (counts stay exact in fp32: far below 2^24 per run)
+                    } else {
+                        const size_t cen = (size_t)g * C + idx_s[tl * M + m];
+#pragma unroll
+                        for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, x_s[tl * XS + m * d + j]);
+                        atomicAdd(p.km_counts + cen, 1);
+                    }
                 }
             }
         }
     }
     if (p.km_sums) {
+        if constexpr (kLdsSums) {
+            __syncthreads();
+            // the run's partial sums -> memory
+            for (int e = tid; e < C; e += kVqBlock) {
+                const float *a = acc_s + (size_t)e * (d + 1);
+                const int n = (int)a[d];
+                if (n > 0) {
+                    const size_t cen = (size_t)g * C + e;
+#pragma unroll
+                    for (int j = 0; j < d; ++j) unsafeAtomicAdd(p.km_sums + cen * d + j, a[j]);
+                    atomicAdd(p.km_counts + cen, n);
+                }
+            }
+        }
         double e64 = (double)err;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) e64 += __shfl_xor(e64, o);
@@ -735,7 +769,8 @@ int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
             hipLaunchKernelGGL((encode_token_wide_kernel<D, d, BITS, false>), tgrid, dim3(kCentroids), 0, stream, p);
         return hipGetLastError() == hipSuccess ? 0 : -4;
     }
-    constexpr size_t smem = vq_wide_smem_bytes<D, d, BITS>();
+    constexpr size_t smem_fill = vq_wide_smem_bytes<D, d, BITS>();
+    constexpr size_t smem = smem_fill + (vq_wide_lds_sums<D, d, BITS>() ? sizeof(float) * (size_t)(1 << BITS) * (d + 1) : 0);
     static_assert(smem <= 160 * 1024, "LDS of a compute unit");
     static const bool configured =
         hipFuncSetAttribute(reinterpret_cast<const void *>(vq_tile_wide_kernel<D, d, BITS, true>),
@@ -749,10 +784,11 @@ int launch_wide_typed(const EncodeParams &p, hipStream_t stream)
     if (per < 1) per = 1;
     if (per > 256) per = 256;
     dim3 grid((unsigned)((tiles + per - 1) / per), 1, p.B * p.Hkv);
+    const size_t smem_now = p.km_sums ? smem : smem_fill;     // (the partial sums only where they are used)
     if (p.lam)
-        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, true>), grid, dim3(kVqBlock), smem, stream, p, (int)per);
+        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, true>), grid, dim3(kVqBlock), smem_now, stream, p, (int)per);
     else
-        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, false>), grid, dim3(kVqBlock), smem, stream, p, (int)per);
+        hipLaunchKernelGGL((vq_tile_wide_kernel<D, d, BITS, false>), grid, dim3(kVqBlock), smem_now, stream, p, (int)per);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

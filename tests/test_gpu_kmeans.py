@@ -85,7 +85,8 @@ def _check_means(x, lam, cb_after, codes, counts, what, cb_before=None):
 SHAPES = [synth.Shape(2, 4, 2, 128, 1000, 4, 4), synth.Shape(1, 2, 2, 64, 777, 2, 8),
           synth.Shape(3, 1, 1, 128, 70, 8, 2),
           # 10- / 12-bit codes: one shared codebook per KV head, trained on the pooled sub-vectors
-          synth.Shape(2, 2, 2, 128, 300, 8, 4, 12, 10), synth.Shape(1, 2, 2, 64, 330, 4, 8, 10, 12)]
+          synth.Shape(2, 2, 2, 128, 300, 8, 4, 12, 10), synth.Shape(1, 2, 2, 64, 330, 4, 8, 10, 12),
+          synth.Shape(1, 2, 2, 128, 260, 8, 8, 10, 10)]
 
 
 @pytest.mark.parametrize("kind", ["keys", "values"])
