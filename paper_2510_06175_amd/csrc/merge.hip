@@ -20,6 +20,13 @@ static_assert(kRowsPerWave == 16, "a wave scores 16 window rows with 16x16x32 MF
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// x of the lane N places further on in its row of 16 lanes (DPP row_ror)
+template <int N>
+__device__ __forceinline__ float row_ror(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x120 + N, 0xf, 0xf, true));
+}
+
 // One workgroup per (KV head g, sequence b); D = head dim, HB = bound on G (4 or 8), MODE below.
 //
 // Merge (the paper returns L from each tile loop, Alg. 1 step 22, and leaves the merge to the reader):
@@ -37,7 +44,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 //           the query rows and the row-major window keys that is one 16-byte global load, so the
 //           operands come straight from memory.  The result lands with window row l % 16 in lane l
 //           and head 4 (l / 16) + v in register v.
-//   softmax over the 16 rows: xor-shuffles inside each 16-lane group.
+//   softmax over the 16 rows: DPP row rotations inside each 16-lane group.
 //   o[hh][c] = sum_r p[hh][r] v[r][c] on the vector ALU: a lane owns two adjacent channels, p comes
 //           from the owning lane by v_readlane.
 // Window loads are clamped to row R - 1 (always inside the allocation) and masked by the
@@ -167,13 +174,18 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float *part_o, co
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const float s2 = valid ? sc[v] * scale : -INFINITY;
+            // (all-reduce over the 16-lane row by DPP rotations: no trip through the LDS crossbar)
             float m = s2;
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+            m = fmaxf(m, row_ror<8>(m));
+            m = fmaxf(m, row_ror<4>(m));
+            m = fmaxf(m, row_ror<2>(m));
+            m = fmaxf(m, row_ror<1>(m));
             pr[v] = __builtin_amdgcn_exp2f(s2 - m);          // row row0 is valid, so m is finite
             float l = pr[v];
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) l += __shfl_xor(l, o);
+            l += row_ror<8>(l);
+            l += row_ror<4>(l);
+            l += row_ror<2>(l);
+            l += row_ror<1>(l);
             const int hh = 4 * (lane >> 4) + v;
             if ((lane & 15) == 0 && hh < HB) {               // heads G .. HB - 1 hold finite filler
                 wm_s[w * HB + hh] = m;
