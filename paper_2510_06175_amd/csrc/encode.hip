@@ -33,75 +33,98 @@ constexpr int kEncTokens = 64;     // tokens per workgroup = lanes per wavefront
 // the others across lanes with wavefront shuffles.
 // NCH < D: only channels ch0 .. ch0 + NCH - 1 are kept (row stride NCH + 4), for a workgroup that
 // searches a group of sub-spaces; values outside the window are then not even loaded.
+// The two halves are separate so that a kernel can request the next tile's rows before it searches
+// the present one (the workgroups of the tile kernels fill a compute unit's LDS alone, so nothing
+// else would cover the trip to memory): tile_request leaves the raw fp16 rows in registers
+// (2 dwords per pass and lane), tile_finish converts, transforms and writes x_s.
+template <int D, int BLOCK>
+struct TileRows {
+    static constexpr int LPT = D / 4;                           // lanes per token
+    static constexpr int TPW = 64 / LPT;                        // tokens per wavefront pass
+    static constexpr int NP = kEncTokens / TPW / (BLOCK / 64);  // passes per wavefront
+    uint2 raw[NP];
+};
+
 template <int D, bool kTransform, int BLOCK = kEncBlock, int NCH = D>
-__device__ __forceinline__ void load_transform_tile(const EncodeParams &p, float *x_s, long long t0, int bg, int g,
-                                                    int ch0 = 0)
+__device__ __forceinline__ void tile_request(const EncodeParams &p, TileRows<D, BLOCK> &rows, long long t0, int bg,
+                                             int ch0 = 0)
 {
-    constexpr int LPT = D / 4;                 // lanes per token
-    constexpr int TPW = 64 / LPT;              // tokens per wavefront pass
+    constexpr int LPT = TileRows<D, BLOCK>::LPT, TPW = TileRows<D, BLOCK>::TPW, NP = TileRows<D, BLOCK>::NP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = 4 * (lane % LPT), tw = lane / LPT;
+    const bool kept = NCH == D || (c0 >= ch0 && c0 < ch0 + NCH);
+#pragma unroll
+    for (int pi = 0; pi < NP; ++pi) {
+        const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;   // token within the tile
+        long long t = t0 + tl;
+        if (t >= p.T) t = p.T - 1;                                  // tail: harmless duplicate
+        rows.raw[pi] = make_uint2(0u, 0u);
+        if (kTransform || kept) rows.raw[pi] = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
+    }
+}
+
+template <int D, bool kTransform, int BLOCK = kEncBlock, int NCH = D>
+__device__ __forceinline__ void tile_finish(const EncodeParams &p, const TileRows<D, BLOCK> &rows, float *x_s, int g,
+                                            int ch0 = 0)
+{
+    constexpr int LPT = TileRows<D, BLOCK>::LPT, TPW = TileRows<D, BLOCK>::TPW, NP = TileRows<D, BLOCK>::NP;
     constexpr int XS = NCH + 4;                // padded row stride of the LDS tile (floats)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-        const int sub = lane % LPT;            // which 4 channels of the token
-        const int tw = lane / LPT;             // which token of this pass
-        const int c0 = 4 * sub;
-        const bool kept = NCH == D || (c0 >= ch0 && c0 < ch0 + NCH);
-        float rl[4] = {1.f, 1.f, 1.f, 1.f};
-        if (kTransform) {
-            const float4 l4 = *reinterpret_cast<const float4 *>(p.lam + (size_t)g * D + c0);
-            rl[0] = l4.x; rl[1] = l4.y; rl[2] = l4.z; rl[3] = l4.w;
-        }
-        const float hs = 1.0f / sqrtf((float)D);
-        constexpr int NP = kEncTokens / TPW / (BLOCK / 64);   // passes per wavefront
-        // All passes of the wavefront advance stage by stage, so that a stage's shuffles (NP x 4
-        // independent ones) are in flight together instead of one LDS round trip at a time.
-        float v[NP][4];
+    const int sub = lane % LPT;                // which 4 channels of the token
+    const int tw = lane / LPT;                 // which token of this pass
+    const int c0 = 4 * sub;
+    const bool kept = NCH == D || (c0 >= ch0 && c0 < ch0 + NCH);
+    float rl[4] = {1.f, 1.f, 1.f, 1.f};
+    if (kTransform) {
+        const float4 l4 = *reinterpret_cast<const float4 *>(p.lam + (size_t)g * D + c0);
+        rl[0] = l4.x; rl[1] = l4.y; rl[2] = l4.z; rl[3] = l4.w;
+    }
+    const float hs = 1.0f / sqrtf((float)D);
+    // All passes of the wavefront advance stage by stage, so that a stage's shuffles (NP x 4
+    // independent ones) are in flight together instead of one LDS round trip at a time.
+    float v[NP][4];
+#pragma unroll
+    for (int pi = 0; pi < NP; ++pi) {
+        const __half2 h01 = *reinterpret_cast<const __half2 *>(&rows.raw[pi].x);
+        const __half2 h23 = *reinterpret_cast<const __half2 *>(&rows.raw[pi].y);
+        v[pi][0] = __low2float(h01); v[pi][1] = __high2float(h01);
+        v[pi][2] = __low2float(h23); v[pi][3] = __high2float(h23);
+    }
+    if (kTransform) {
 #pragma unroll
         for (int pi = 0; pi < NP; ++pi) {
-            const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;   // token within the tile
-            long long t = t0 + tl;
-            if (t >= p.T) t = p.T - 1;                                  // tail: harmless duplicate
-            uint2 raw = make_uint2(0u, 0u);
-            if (kTransform || kept) raw = *reinterpret_cast<const uint2 *>(p.x + ((size_t)bg * p.T + t) * D + c0);
-            const __half2 h01 = *reinterpret_cast<const __half2 *>(&raw.x);
-            const __half2 h23 = *reinterpret_cast<const __half2 *>(&raw.y);
-            v[pi][0] = __low2float(h01); v[pi][1] = __high2float(h01);
-            v[pi][2] = __low2float(h23); v[pi][3] = __high2float(h23);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[pi][j] = v[pi][j] / rl[j];
+            // butterflies with partner distance 1 and 2 (inside the lane)
+            const float a0 = v[pi][0] + v[pi][1], a1 = v[pi][0] - v[pi][1];
+            const float a2 = v[pi][2] + v[pi][3], a3 = v[pi][2] - v[pi][3];
+            v[pi][0] = a0 + a2; v[pi][1] = a1 + a3; v[pi][2] = a0 - a2; v[pi][3] = a1 - a3;
         }
-        if (kTransform) {
+        // partner distance 4 .. D/2 (across lanes)
 #pragma unroll
-            for (int pi = 0; pi < NP; ++pi) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) v[pi][j] = v[pi][j] / rl[j];
-                // butterflies with partner distance 1 and 2 (inside the lane)
-                const float a0 = v[pi][0] + v[pi][1], a1 = v[pi][0] - v[pi][1];
-                const float a2 = v[pi][2] + v[pi][3], a3 = v[pi][2] - v[pi][3];
-                v[pi][0] = a0 + a2; v[pi][1] = a1 + a3; v[pi][2] = a0 - a2; v[pi][3] = a1 - a3;
-            }
-            // partner distance 4 .. D/2 (across lanes)
-#pragma unroll
-            for (int x = 1; x < LPT; x <<= 1) {
-                float o[NP][4];
-#pragma unroll
-                for (int pi = 0; pi < NP; ++pi)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) o[pi][j] = __shfl_xor(v[pi][j], x);
-                const bool up = (sub & x) != 0;
-#pragma unroll
-                for (int pi = 0; pi < NP; ++pi)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v[pi][j] = up ? (o[pi][j] - v[pi][j]) : (v[pi][j] + o[pi][j]);
-            }
+        for (int x = 1; x < LPT; x <<= 1) {
+            float o[NP][4];
 #pragma unroll
             for (int pi = 0; pi < NP; ++pi)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[pi][j] *= hs;
+                for (int j = 0; j < 4; ++j) o[pi][j] = __shfl_xor(v[pi][j], x);
+            const bool up = (sub & x) != 0;
+#pragma unroll
+            for (int pi = 0; pi < NP; ++pi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[pi][j] = up ? (o[pi][j] - v[pi][j]) : (v[pi][j] + o[pi][j]);
         }
 #pragma unroll
-        for (int pi = 0; pi < NP; ++pi) {
-            const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;
-            float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
-            if (kept) *reinterpret_cast<float4 *>(&x_s[tl * XS + c0 - ch0]) = w;
-        }
+        for (int pi = 0; pi < NP; ++pi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[pi][j] *= hs;
+    }
+#pragma unroll
+    for (int pi = 0; pi < NP; ++pi) {
+        const int tl = (wave + pi * (BLOCK / 64)) * TPW + tw;
+        float4 w; w.x = v[pi][0]; w.y = v[pi][1]; w.z = v[pi][2]; w.w = v[pi][3];
+        if (kept) *reinterpret_cast<float4 *>(&x_s[tl * XS + c0 - ch0]) = w;
+    }
 }
 
 // Cache fill (Eq. 2, 3, 6, 8) and K-Means assignment (Sec. 2.2), 8-bit codes: one kernel.
@@ -180,12 +203,18 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_kernel(EncodeParams p, int t
         for (int e = tid; e < MSW * kCentroids * (d + 1); e += kVqBlock) acc_s[e] = 0.f;
 
     float err = 0.f;
+    const int win0 = NCH == D ? 0 : grp * MSW * d;         // first channel of the tile that is kept
+    TileRows<D, kVqBlock> rows;
+    if (tile0 * kEncTokens < p.T) tile_request<D, kTransform, kVqBlock, NCH>(p, rows, tile0 * kEncTokens, bg, win0);
     for (int ti = 0; ti < tiles_per_wg; ++ti) {
         const long long t0 = (tile0 + ti) * kEncTokens;
         if (t0 >= p.T) break;
         __syncthreads();                       // previous tile's x_s and idx_s consumed (first tile: accumulators cleared)
-        load_transform_tile<D, kTransform, kVqBlock, NCH>(p, x_s, t0, bg, g, NCH == D ? 0 : grp * MSW * d);
+        tile_finish<D, kTransform, kVqBlock, NCH>(p, rows, x_s, g, win0);
         __syncthreads();
+        // the next tile's rows travel while this one is searched
+        if (ti + 1 < tiles_per_wg && t0 + kEncTokens < p.T)
+            tile_request<D, kTransform, kVqBlock, NCH>(p, rows, t0 + kEncTokens, bg, win0);
 #pragma unroll
         for (int i = 0; i < SPW; ++i) {
             const int ms = wave + NW * i;
@@ -531,12 +560,17 @@ __global__ __launch_bounds__(kVqBlock) void vq_tile_wide_kernel(EncodeParams p, 
     const ScreenConsts sc = screen_prepare_shared<d, C, kVqBlock>(p.cb + (size_t)g * C * d, tab_s, x_s);
 
     float err = 0.f;
+    TileRows<D, kVqBlock> rows;
+    if (tile0 * kEncTokens < p.T) tile_request<D, kTransform, kVqBlock>(p, rows, tile0 * kEncTokens, bg);
     for (int ti = 0; ti < tiles_per_wg; ++ti) {
         const long long t0 = (tile0 + ti) * kEncTokens;
         if (t0 >= p.T) break;
         if (ti > 0) __syncthreads();           // previous tile's x_s and idx_s consumed
-        load_transform_tile<D, kTransform, kVqBlock>(p, x_s, t0, bg, g);
+        tile_finish<D, kTransform, kVqBlock>(p, rows, x_s, g);
         __syncthreads();
+        // the next tile's rows travel while this one is searched
+        if (ti + 1 < tiles_per_wg && t0 + kEncTokens < p.T)
+            tile_request<D, kTransform, kVqBlock>(p, rows, t0 + kEncTokens, bg);
 #pragma unroll 1
         for (int i = 0; i < SPW; ++i) {        // (not unrolled: the searches are long and share nothing but the tables)
             const int m = wave + NW * i;
