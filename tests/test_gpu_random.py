@@ -110,3 +110,34 @@ def test_encode_random_configurations(case):
     assert_indices_match(oracle.unpack_codes(got_v[:, :, rows], shape.b_v, shape.Mv), ref_v, gap_v, "random values")
     for got in (got_k, got_v):
         assert (got[:, :, :pos0] == 0xEE).all() and (got[:, :, pos0 + shape.N:] == 0xEE).all()
+
+
+# ------------------------------------------------------------------ every instantiation of the attention kernel
+
+def _all_side_combinations():
+    """Every (head dim, key side, value side) the matrix-core kernel is built for, each with one
+    head group (G = 4) and with two (G = 8): 2 x the 8-bit mixes + the 10- / 12-bit ones."""
+    sides = [(2, 8), (4, 8), (8, 8), (4, 10), (4, 12), (8, 10), (8, 12)]
+    cases = []
+    for D in (64, 128):
+        for dk, bk in sides:
+            for dv, bv in sides:
+                wide = bk != 8 or bv != 8
+                if wide and (dk < 4 or dv < 4):
+                    continue
+                if D == 64 and ((dk, bk) == (8, 10) or (dv, bv) == (8, 10)):      # 10-byte rows: not supported
+                    continue
+                for G in (4, 8):
+                    cases.append(synth.Shape(1, G, 1, D, 200, dk, dv, bk, bv))
+    return cases
+
+
+@pytest.mark.parametrize("shape", _all_side_combinations(), ids=lambda s: f"D{s.D}G{s.Hq}k{s.d_k}b{s.b_k}v{s.d_v}b{s.b_v}")
+def test_every_side_combination(shape):
+    """One small decode (200 tokens: three tiles and a tail, two splits) per instantiation of the
+    attention kernel with value codes in rows, against the oracle."""
+    seed = 31 * shape.D + 7 * shape.d_k + 5 * shape.d_v + shape.b_k + 3 * shape.b_v + shape.Hq
+    x = synth.decode_inputs(shape, seed=seed)
+    got_o, got_l = gpu_decode(shape, x, num_splits=2)
+    ref_o, ref_l = _oracle_decode(shape, x)
+    assert_decode_close(got_o, got_l, ref_o, ref_l, what=f"every combination {_id(shape)} D{shape.D}")
