@@ -141,3 +141,34 @@ def test_every_side_combination(shape):
     got_o, got_l = gpu_decode(shape, x, num_splits=2)
     ref_o, ref_l = _oracle_decode(shape, x)
     assert_decode_close(got_o, got_l, ref_o, ref_l, what=f"every combination {_id(shape)} D{shape.D}")
+
+
+@pytest.mark.parametrize("shape", _all_side_combinations(), ids=lambda s: f"D{s.D}G{s.Hq}k{s.d_k}b{s.b_k}v{s.d_v}b{s.b_v}")
+def test_every_side_combination_fused_step(shape):
+    """The whole step (Eq. 9 + Eq. 10 in one call) per instantiation: the new token's codes must be
+    what vecinfer_append_kv writes, bit for bit, and the output the oracle's on the cache with them."""
+    import torch
+    from paper_2510_06175_amd import binding as vb
+    from helpers import cfg_of, dev
+    seed = 17 * shape.D + 3 * shape.d_k + 11 * shape.d_v + shape.b_k + 5 * shape.b_v + shape.Hq
+    N = shape.N
+    x = synth.decode_inputs(shape, seed=seed, n_cap=N + 4)
+    g = synth.rng(seed + 1)
+    k_new, _ = synth.keys_with_outlier_channels(g, shape.B, shape.Hkv, 1, shape.D, 3)
+    v_new = synth.values(g, shape.B, shape.Hkv, 1, shape.D)
+    cfg = cfg_of(shape)
+    t = {k: dev(v) for k, v in x.items()}
+    ws = vb.new_workspace(cfg, shape.B, N, 3)
+    out = torch.full((shape.B, shape.Hq, shape.D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((shape.B, shape.Hq), float("nan"), dtype=torch.float32, device="cuda")
+    vb.vecinfer_decode_step(cfg, t["q"], dev(k_new), dev(v_new), t["lam"], t["cb_k"], t["cb_v"], t["k_idx"],
+                            t["v_idx"], ws, out, lse=lse, N=N, num_splits=3)
+    torch.cuda.synchronize()
+    k2, v2 = dev(x["k_idx"]), dev(x["v_idx"])
+    vb.vecinfer_append_kv(cfg, dev(k_new), dev(v_new), t["lam"], t["cb_k"], t["cb_v"], k2, v2, pos0=N - 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t["k_idx"].cpu().numpy(), k2.cpu().numpy())
+    np.testing.assert_array_equal(t["v_idx"].cpu().numpy(), v2.cpu().numpy())
+    got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+    ref = _oracle_decode(shape, dict(x, k_idx=k2.cpu().numpy()[:, :, :N], v_idx=v2.cpu().numpy()[:, :, :N]))
+    assert_decode_close(*got, *ref, what=f"fused step, every combination {_id(shape)} D{shape.D}")
