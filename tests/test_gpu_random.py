@@ -172,3 +172,22 @@ def test_every_side_combination_fused_step(shape):
     got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
     ref = _oracle_decode(shape, dict(x, k_idx=k2.cpu().numpy()[:, :, :N], v_idx=v2.cpu().numpy()[:, :, :N]))
     assert_decode_close(*got, *ref, what=f"fused step, every combination {_id(shape)} D{shape.D}")
+
+
+def _all_tiled_combinations():
+    return [synth.Shape(1, G, 1, D, 200, dk, dv) for D in (64, 128) for dk in (2, 4, 8) for dv in (2, 4, 8)
+            if D // dv >= 16 for G in (4, 8)]
+
+
+@pytest.mark.parametrize("shape", _all_tiled_combinations(), ids=lambda s: f"D{s.D}G{s.Hq}k{s.d_k}v{s.d_v}")
+def test_every_tiled_instantiation(shape):
+    """Every instantiation of the attention kernel for tiled value codes: the same bits out as with
+    the codes in rows (which test_every_side_combination holds against the oracle)."""
+    seed = 13 * shape.D + 3 * shape.d_k + 7 * shape.d_v + shape.Hq
+    x = synth.decode_inputs(shape, seed=seed, n_cap=256)
+    rows = gpu_decode(shape, x, N=shape.N, num_splits=2)
+    tiled = gpu_decode(shape, dict(x, v_idx=tile_value_codes(x["v_idx"])), N=shape.N, num_splits=2, v_tiled=1)
+    np.testing.assert_array_equal(tiled[0], rows[0])
+    np.testing.assert_array_equal(tiled[1], rows[1])
+    ref_o, ref_l = _oracle_decode(shape, dict(x, k_idx=x["k_idx"][:, :, :shape.N], v_idx=x["v_idx"][:, :, :shape.N]))
+    assert_decode_close(*rows, ref_o, ref_l, what=f"tiled instantiation {_id(shape)} D{shape.D}")
