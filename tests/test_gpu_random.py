@@ -191,3 +191,17 @@ def test_every_tiled_instantiation(shape):
     np.testing.assert_array_equal(tiled[1], rows[1])
     ref_o, ref_l = _oracle_decode(shape, dict(x, k_idx=x["k_idx"][:, :, :shape.N], v_idx=x["v_idx"][:, :, :shape.N]))
     assert_decode_close(*rows, ref_o, ref_l, what=f"tiled instantiation {_id(shape)} D{shape.D}")
+
+
+def _all_encode_combinations():
+    sides = [(2, 8), (4, 8), (8, 8), (4, 10), (4, 12), (8, 10), (8, 12)]
+    return [(synth.Shape(1, 2, 1, D, T, d, d, b, b), 3, 1000 * D + 100 * d + b + T)
+            for D in (64, 128) for d, b in sides if not (D == 64 and (d, b) == (8, 10)) for T in (5, 200)]
+
+
+@pytest.mark.parametrize("case", _all_encode_combinations(),
+                         ids=lambda c: f"D{c[0].D}d{c[0].d_k}b{c[0].b_k}T{c[0].N}")
+def test_every_cache_fill_instantiation(case):
+    """Every (head dim, sub-vector dim, code width) of the cache fill, keys and values, by the
+    per-token kernel (5 tokens) and the tile kernel (200 tokens), against the oracle."""
+    test_encode_random_configurations(case)
